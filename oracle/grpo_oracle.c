@@ -1,0 +1,360 @@
+/*
+ * fp64 CPU oracle for the token-level GRPO policy objective with two-sided
+ * clipping (paper section 3.4, second displayed objective) and its analytic
+ * gradient with respect to the logits.
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It is the plain definition written out in
+ * double precision, one step after the other, in the paper's notation.  It
+ * shares no code, header, table or helper with the HIP library and must never
+ * be reached from the product path; only the tests, the smoke check and the
+ * benchmark's cpu_baseline leg call it.
+ *
+ * Notation (section 3.4): z = one row of policy logits over the vocabulary,
+ * y = the sampled token o_{i,t}, l = log pi_theta(y), l_old = log pi_theta_old(y),
+ * r = pi_theta / pi_theta_old = exp(l - l_old), A = advantage \hat A_{i,t},
+ * eps = clip threshold (kept as eps_low / eps_high), delta = upper bound on r
+ * for negative advantages (section 3.4, "delta should be higher than 1+eps").
+ *
+ * Readings of points the paper leaves open (all listed again in the design
+ * document):
+ *  - advantages: (R - mean_group) / (std_group + eps_std); the paper only says
+ *    "based on their relative rewards" (section 3.4) and that a group whose
+ *    rewards are all equal has zero advantages (section 3.3, online filtering).
+ *  - normalisation: token-level masked mean (section 4.1), not the sample-level
+ *    1/G 1/|o_i| printed in the objective.
+ *  - loss = -J (the paper maximises J).
+ *  - temperature T divides the logits before the softmax (not in the paper).
+ *  - ties: a ratio exactly on a clip boundary is "not clipped"; the gradient
+ *    follows the first argument of the outer min when both are equal.
+ *
+ * Stored inputs are widened exactly: bf16 -> fp64 and fp32 -> fp64 lose nothing.
+ * OpenMP is used only as "for each row, independently".
+ *
+ * Parity pins: every function below is pinned by tests/test_oracle_pins.py
+ * (closed forms, invariants, library log-softmax / cross-entropy special cases,
+ * finite differences, a hand-derived branch table).  None is "parity unpinned".
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORACLE_F32 0
+#define ORACLE_BF16 1
+#define ORACLE_F64 2 /* only for the finite-difference pin, which needs steps below fp32 resolution */
+
+/* indicator bits, same meaning as the counters of oracle_loss_fwd_bwd */
+#define FLAG_CLIP_HIGH 1   /* A > 0 and r > 1 + eps_high            */
+#define FLAG_CLIP_LOW 2    /* A < 0 and r < 1 - eps_low             */
+#define FLAG_DELTA 4       /* A < 0 and r > delta                   */
+#define FLAG_OUT_OF_BAND 8 /* r outside [1 - eps_low, 1 + eps_high] */
+
+/* Exact widening of one stored logit. bf16 is the upper 16 bits of an IEEE
+ * binary32, so shifting it back into place reproduces the value exactly. */
+static double logit_at(const void *base, int dtype, int64_t idx)
+{
+    if (dtype == ORACLE_BF16) {
+        uint32_t bits = (uint32_t)((const uint16_t *)base)[idx] << 16;
+        float f;
+        memcpy(&f, &bits, sizeof f);
+        return (double)f;
+    }
+    if (dtype == ORACLE_F64)
+        return ((const double *)base)[idx];
+    return (double)((const float *)base)[idx];
+}
+
+static size_t elem_size(int dtype)
+{
+    return dtype == ORACLE_BF16 ? 2 : (dtype == ORACLE_F64 ? 8 : 4);
+}
+
+/* Compensated (Neumaier) running sum: the result carries an error of a few
+ * ulp of the TRUE sum, whatever the order and spread of the terms.  Needed for
+ * near-one-hot rows, where 150 000 terms of size 1e-17 meet one term equal to 1
+ * and a plain running sum would drop every one of them. */
+typedef struct { double s, c; } csum;
+static void csum_add(csum *a, double x)
+{
+    double t = a->s + x;
+    if (fabs(a->s) >= fabs(x))
+        a->c += (a->s - t) + x;
+    else
+        a->c += (x - t) + a->s;
+    a->s = t;
+}
+static double csum_value(const csum *a) { return a->s + a->c; }
+
+/* ------------------------------------------------------------------ *
+ * Group-relative advantages (section 3.4: advantages from the relative
+ * rewards inside the group of G outputs sampled for one prompt).
+ * Group g owns rollouts [group_offsets[g], group_offsets[g+1]); when
+ * group_offsets is NULL every group has group_size rollouts.
+ * sigma = sqrt(sum (R - mu)^2 / (G - ddof)); a group with G - ddof <= 0 or
+ * with sigma + eps_std == 0 gets zero advantages (all-equal rewards carry no
+ * signal, section 3.3).
+ * ------------------------------------------------------------------ */
+int oracle_group_advantages(const float *rewards, int64_t n_rollouts,
+                            const int32_t *group_offsets, int64_t n_groups,
+                            int64_t group_size, double eps_std, int ddof,
+                            double *adv_out)
+{
+    for (int64_t g = 0; g < n_groups; ++g) {
+        int64_t b = group_offsets ? group_offsets[g] : g * group_size;
+        int64_t e = group_offsets ? group_offsets[g + 1] : (g + 1) * group_size;
+        if (b < 0 || e < b || e > n_rollouts)
+            return 1;
+        int64_t G = e - b;
+        if (G == 0)
+            continue;
+        double sum = 0.0;
+        for (int64_t i = b; i < e; ++i)
+            sum += (double)rewards[i];
+        double mu = sum / (double)G;
+        double ss = 0.0;
+        for (int64_t i = b; i < e; ++i) {
+            double d = (double)rewards[i] - mu;
+            ss += d * d;
+        }
+        double sigma = (G - ddof > 0) ? sqrt(ss / (double)(G - ddof)) : 0.0;
+        double den = sigma + eps_std;
+        for (int64_t i = b; i < e; ++i) {
+            double d = (double)rewards[i] - mu;
+            adv_out[i] = (den > 0.0) ? d / den : 0.0;
+        }
+    }
+    return 0;
+}
+
+/* Every token of rollout i carries that rollout's advantage (\hat A_{i,t}
+ * does not depend on t in the outcome-reward setting of section 3.1). */
+void oracle_broadcast_advantages(const double *adv, const int32_t *rollout_of_token,
+                                 int64_t n_tokens, double *adv_tok_out)
+{
+    for (int64_t t = 0; t < n_tokens; ++t)
+        adv_tok_out[t] = adv[rollout_of_token[t]];
+}
+
+/* ------------------------------------------------------------------ *
+ * log-softmax of one row at temperature T:  u = z / T,
+ * lse = max u + log sum exp(u - max u),  out_j = u_j - lse.
+ * This is pi_theta(. | q, o_<t) of section 3.4 in log space.
+ * Returns lse.
+ * ------------------------------------------------------------------ */
+double oracle_row_log_softmax(const void *row, int dtype, int64_t V, double T,
+                              double *logp_out /* [V] or NULL */)
+{
+    double mx = -INFINITY;
+    for (int64_t j = 0; j < V; ++j) {
+        double u = logit_at(row, dtype, j) / T;
+        if (u > mx)
+            mx = u;
+    }
+    csum acc = {0.0, 0.0};
+    for (int64_t j = 0; j < V; ++j)
+        csum_add(&acc, exp(logit_at(row, dtype, j) / T - mx));
+    double s = csum_value(&acc);
+    double lse = mx + log(s);
+    if (logp_out)
+        for (int64_t j = 0; j < V; ++j)
+            logp_out[j] = logit_at(row, dtype, j) / T - lse;
+    return lse;
+}
+
+/* l_t = log pi_theta(y_t) for every row with mask 1; masked rows give 0 and
+ * their inputs are not read.  mask NULL = all ones.  An out-of-range token id
+ * at an unmasked row is an error (return 2). */
+int oracle_logprobs(const void *logits, int dtype, int64_t n_tokens, int64_t V,
+                    int64_t row_stride, const int64_t *tokens, const uint8_t *mask,
+                    double T, double *logprobs_out)
+{
+    int bad = 0;
+    size_t esz = elem_size(dtype);
+#pragma omp parallel for schedule(dynamic, 8)
+    for (int64_t t = 0; t < n_tokens; ++t) {
+        if (mask && !mask[t]) {
+            logprobs_out[t] = 0.0;
+            continue;
+        }
+        int64_t y = tokens[t];
+        if (y < 0 || y >= V) {
+#pragma omp atomic write
+            bad = 1;
+            logprobs_out[t] = 0.0;
+            continue;
+        }
+        const char *row = (const char *)logits + (size_t)t * (size_t)row_stride * esz;
+        double lse = oracle_row_log_softmax(row, dtype, V, T, NULL);
+        logprobs_out[t] = logit_at(row, dtype, y) / T - lse;
+    }
+    return bad ? 2 : 0;
+}
+
+/* ------------------------------------------------------------------ *
+ * The bracketed term of the two-sided-clipping objective (section 3.4):
+ *   J = min( min(r, delta) * A ,  clip(r, 1 - eps_low, 1 + eps_high) * A )
+ * together with dJ/dl (l = log pi_theta(y), so dr/dl = r) and the indicator
+ * bits.  Defined for any delta; the library itself insists on
+ * delta > 1 + eps_high as the paper recommends.
+ * ------------------------------------------------------------------ */
+void oracle_surrogate_from_ratio(double r, double A, double eps_low, double eps_high,
+                                 double delta, double *J_out, double *dJ_dlogp_out,
+                                 int *flags_out)
+{
+    double lo = 1.0 - eps_low, hi = 1.0 + eps_high;
+    double r_capped = (r < delta) ? r : delta;         /* min(r, delta)  */
+    double r_clipped = r;                              /* clip(r, lo, hi) */
+    if (r_clipped < lo)
+        r_clipped = lo;
+    if (r_clipped > hi)
+        r_clipped = hi;
+    double s1 = r_capped * A;
+    double s2 = r_clipped * A;
+    double J, dJ_dr;
+    if (s1 <= s2) { /* outer min picks the delta-capped term (or a tie) */
+        J = s1;
+        dJ_dr = (r <= delta) ? A : 0.0;
+    } else { /* outer min picks the clipped term */
+        J = s2;
+        dJ_dr = (r >= lo && r <= hi) ? A : 0.0;
+    }
+    int flags = 0;
+    if (A > 0.0 && r > hi)
+        flags |= FLAG_CLIP_HIGH;
+    if (A < 0.0 && r < lo)
+        flags |= FLAG_CLIP_LOW;
+    if (A < 0.0 && r > delta)
+        flags |= FLAG_DELTA;
+    if (r < lo || r > hi)
+        flags |= FLAG_OUT_OF_BAND;
+    if (J_out)
+        *J_out = J;
+    if (dJ_dlogp_out)
+        *dJ_dlogp_out = dJ_dr * r;
+    if (flags_out)
+        *flags_out = flags;
+}
+
+/* ------------------------------------------------------------------ *
+ * Whole objective and gradient.
+ *
+ *   loss = -(1/D) sum_t m_t J_t,  D = denom if denom > 0 else M = sum_t m_t,
+ *   loss = 0 when D = 0                           (token-level, section 4.1)
+ *   dloss/dz_{t,j} = grad_scale * (-(m_t / D) dJ_t/dl_t) * (1/T) * (1[j = y_t] - p_{t,j})
+ *   with p_{t,j} = exp(u_{t,j} - lse_t).
+ *
+ * Outputs (any of the optional ones may be NULL):
+ *   loss_out       [1]
+ *   logprobs_out   [n_tokens]   l_t (0 at masked rows)
+ *   counts_out     [5]          M, n_clip_high, n_clip_low, n_delta, n_out_of_band
+ *                               (counted over rows with m_t = 1)
+ *   J_out          [n_tokens]   J_t (0 at masked rows)              optional
+ *   coeff_out      [n_tokens]   c_t = dloss/dl_t incl. grad_scale   optional
+ *   flags_out      [n_tokens]   indicator bits per row               optional
+ *   grad_out       [n_grad_rows, V] dense fp64: gradient rows for the row
+ *                               indices listed in grad_rows           optional
+ * Returns 0, or 2 if an unmasked row has a token id outside [0, V).
+ * ------------------------------------------------------------------ */
+int oracle_loss_fwd_bwd(const void *logits, int dtype, int64_t n_tokens, int64_t V,
+                        int64_t row_stride, const int64_t *tokens,
+                        const float *old_logprobs, const float *advantages,
+                        const uint8_t *mask, double eps_low, double eps_high,
+                        double delta, double T, double denom, double grad_scale,
+                        double *loss_out, double *logprobs_out, int64_t *counts_out,
+                        double *J_out, double *coeff_out, int32_t *flags_out,
+                        const int64_t *grad_rows, int64_t n_grad_rows, double *grad_out)
+{
+    size_t esz = elem_size(dtype);
+    double *lp = (double *)malloc(sizeof(double) * (size_t)(n_tokens > 0 ? n_tokens : 1));
+    if (!lp)
+        return 3;
+    int rc = oracle_logprobs(logits, dtype, n_tokens, V, row_stride, tokens, mask, T, lp);
+    if (rc) {
+        free(lp);
+        return rc;
+    }
+
+    int64_t M = 0;
+    for (int64_t t = 0; t < n_tokens; ++t)
+        M += (!mask || mask[t]) ? 1 : 0;
+    double D = (denom > 0.0) ? denom : (double)M;
+
+    int64_t n_hi = 0, n_lo = 0, n_de = 0, n_oob = 0;
+    double sumJ = 0.0;
+    for (int64_t t = 0; t < n_tokens; ++t) {
+        double J = 0.0, dJ = 0.0;
+        int fl = 0;
+        if (!mask || mask[t]) {
+            double r = exp(lp[t] - (double)old_logprobs[t]);
+            oracle_surrogate_from_ratio(r, (double)advantages[t], eps_low, eps_high,
+                                        delta, &J, &dJ, &fl);
+            sumJ += J;
+            n_hi += (fl & FLAG_CLIP_HIGH) ? 1 : 0;
+            n_lo += (fl & FLAG_CLIP_LOW) ? 1 : 0;
+            n_de += (fl & FLAG_DELTA) ? 1 : 0;
+            n_oob += (fl & FLAG_OUT_OF_BAND) ? 1 : 0;
+        }
+        if (logprobs_out)
+            logprobs_out[t] = lp[t];
+        if (J_out)
+            J_out[t] = J;
+        if (coeff_out)
+            coeff_out[t] = (D > 0.0) ? -grad_scale * dJ / D : 0.0;
+        if (flags_out)
+            flags_out[t] = fl;
+    }
+    if (loss_out)
+        *loss_out = (D > 0.0) ? -sumJ / D : 0.0;
+    if (counts_out) {
+        counts_out[0] = M;
+        counts_out[1] = n_hi;
+        counts_out[2] = n_lo;
+        counts_out[3] = n_de;
+        counts_out[4] = n_oob;
+    }
+
+    if (grad_out && grad_rows) {
+#pragma omp parallel for schedule(dynamic, 1)
+        for (int64_t k = 0; k < n_grad_rows; ++k) {
+            int64_t t = grad_rows[k];
+            double *g = grad_out + (size_t)k * (size_t)V;
+            if (mask && !mask[t]) {
+                for (int64_t j = 0; j < V; ++j)
+                    g[j] = 0.0;
+                continue;
+            }
+            const char *row = (const char *)logits + (size_t)t * (size_t)row_stride * esz;
+            double r = exp(lp[t] - (double)old_logprobs[t]);
+            double dJ;
+            oracle_surrogate_from_ratio(r, (double)advantages[t], eps_low, eps_high,
+                                        delta, NULL, &dJ, NULL);
+            double c = (D > 0.0) ? -grad_scale * dJ / D : 0.0; /* dloss/dl_t */
+            double lse = oracle_row_log_softmax(row, dtype, V, T, NULL);
+            int64_t y = tokens[t];
+            /* (1[j = y] - p_j): for j != y this is -p_j; for j = y it is
+             * 1 - p_y = sum_{j != y} p_j (the p_j sum to one).  The second form
+             * is used because 1 - p_y cancels to nothing in any fixed precision
+             * once p_y is within an ulp of 1, while the sum does not. */
+            csum others = {0.0, 0.0};
+            for (int64_t j = 0; j < V; ++j) {
+                if (j == y)
+                    continue;
+                double p = exp(logit_at(row, dtype, j) / T - lse);
+                csum_add(&others, p);
+                g[j] = -(c / T) * p;
+            }
+            g[y] = (c / T) * csum_value(&others);
+        }
+    }
+    free(lp);
+    return 0;
+}
+
+/* Number of OpenMP threads a parallel region would use (for the benchmark's
+ * cpu_baseline report). */
+#ifdef _OPENMP
+#include <omp.h>
+int oracle_num_threads(void) { return omp_get_max_threads(); }
+#else
+int oracle_num_threads(void) { return 1; }
+#endif

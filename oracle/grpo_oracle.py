@@ -1,0 +1,185 @@
+"""ctypes front end of the fp64 CPU oracle (``grpo_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: the tests, the smoke check and the benchmark's
+``cpu_baseline`` leg may import this module; the product package never does.
+Everything here is argument marshalling for numpy arrays; the arithmetic lives
+in the C file next to it, which follows section 3.4 of the paper step by step.
+
+bf16 logits are passed as ``uint16`` arrays holding the raw bit patterns.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "grpo_oracle.c")
+_LIB = os.path.join(_HERE, "libgrpo_oracle.so")
+
+F32, BF16, F64 = 0, 1, 2
+FLAG_CLIP_HIGH, FLAG_CLIP_LOW, FLAG_DELTA, FLAG_OUT_OF_BAND = 1, 2, 4, 8
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (about a second)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+             "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _p(a, ct):
+    return None if a is None else a.ctypes.data_as(ctypes.POINTER(ct))
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(build())
+        i64, dbl, i32 = ctypes.c_int64, ctypes.c_double, ctypes.c_int
+        vp = ctypes.c_void_p
+        L.oracle_group_advantages.restype = i32
+        L.oracle_group_advantages.argtypes = [vp, i64, vp, i64, i64, dbl, i32, vp]
+        L.oracle_broadcast_advantages.restype = None
+        L.oracle_broadcast_advantages.argtypes = [vp, vp, i64, vp]
+        L.oracle_row_log_softmax.restype = dbl
+        L.oracle_row_log_softmax.argtypes = [vp, i32, i64, dbl, vp]
+        L.oracle_logprobs.restype = i32
+        L.oracle_logprobs.argtypes = [vp, i32, i64, i64, i64, vp, vp, dbl, vp]
+        L.oracle_surrogate_from_ratio.restype = None
+        L.oracle_surrogate_from_ratio.argtypes = [dbl, dbl, dbl, dbl, dbl, vp, vp, vp]
+        L.oracle_loss_fwd_bwd.restype = i32
+        L.oracle_loss_fwd_bwd.argtypes = [vp, i32, i64, i64, i64, vp, vp, vp, vp,
+                                          dbl, dbl, dbl, dbl, dbl, dbl,
+                                          vp, vp, vp, vp, vp, vp, vp, i64, vp]
+        L.oracle_num_threads.restype = i32
+        L.oracle_num_threads.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else ctypes.c_void_p(a.ctypes.data)
+
+
+def _logits_view(logits):
+    """Accept float32, float64 or uint16 (bf16 bit patterns) [N, S] with contiguous rows."""
+    a = np.asarray(logits)
+    if a.ndim == 1:
+        a = a[None, :]
+    assert a.ndim == 2 and a.strides[1] == a.itemsize, "rows must be contiguous"
+    if a.dtype == np.float32:
+        dt = F32
+    elif a.dtype == np.uint16:
+        dt = BF16
+    elif a.dtype == np.float64:
+        dt = F64
+    else:
+        raise TypeError("logits must be float32, float64 or uint16 (bf16 bits), got %s" % a.dtype)
+    assert a.strides[0] % a.itemsize == 0
+    return a, dt, a.strides[0] // a.itemsize
+
+
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())
+
+
+def group_advantages(rewards, group_size=None, group_offsets=None, eps_std=1e-6, ddof=0):
+    rewards = np.ascontiguousarray(rewards, dtype=np.float32)
+    R = rewards.shape[0]
+    if group_offsets is not None:
+        off = np.ascontiguousarray(group_offsets, dtype=np.int32)
+        n_groups, gs = off.shape[0] - 1, 0
+    else:
+        off = None
+        assert group_size and R % group_size == 0
+        n_groups, gs = R // group_size, int(group_size)
+    out = np.zeros(R, dtype=np.float64)
+    rc = lib().oracle_group_advantages(_ptr(rewards), R, _ptr(off), n_groups, gs,
+                                       float(eps_std), int(ddof), _ptr(out))
+    if rc:
+        raise ValueError("oracle_group_advantages: bad group offsets")
+    return out
+
+
+def broadcast_advantages(adv, rollout_of_token):
+    adv = np.ascontiguousarray(adv, dtype=np.float64)
+    rot = np.ascontiguousarray(rollout_of_token, dtype=np.int32)
+    out = np.zeros(rot.shape[0], dtype=np.float64)
+    lib().oracle_broadcast_advantages(_ptr(adv), _ptr(rot), rot.shape[0], _ptr(out))
+    return out
+
+
+def row_log_softmax(row, V=None, temperature=1.0):
+    a, dt, _ = _logits_view(row)
+    V = a.shape[1] if V is None else V
+    out = np.zeros(V, dtype=np.float64)
+    lse = lib().oracle_row_log_softmax(_ptr(a), dt, V, float(temperature), _ptr(out))
+    return out, float(lse)
+
+
+def logprobs(logits, tokens, mask=None, temperature=1.0, vocab=None):
+    a, dt, stride = _logits_view(logits)
+    N = a.shape[0]
+    V = a.shape[1] if vocab is None else vocab
+    tokens = np.ascontiguousarray(tokens, dtype=np.int64)
+    m = None if mask is None else np.ascontiguousarray(mask, dtype=np.uint8)
+    out = np.zeros(N, dtype=np.float64)
+    rc = lib().oracle_logprobs(_ptr(a), dt, N, V, stride, _ptr(tokens), _ptr(m),
+                               float(temperature), _ptr(out))
+    if rc:
+        raise ValueError("oracle_logprobs: token id out of range (rc=%d)" % rc)
+    return out
+
+
+def surrogate_from_ratio(r, A, eps_low, eps_high, delta):
+    """Returns (J, dJ/dlogp, flags) for one exact ratio r and advantage A."""
+    J, dJ, fl = ctypes.c_double(), ctypes.c_double(), ctypes.c_int()
+    lib().oracle_surrogate_from_ratio(float(r), float(A), float(eps_low), float(eps_high),
+                                      float(delta), ctypes.byref(J), ctypes.byref(dJ),
+                                      ctypes.byref(fl))
+    return J.value, dJ.value, fl.value
+
+
+def loss_fwd_bwd(logits, tokens, old_logprobs, advantages, mask=None, *, eps_low=0.2,
+                 eps_high=0.2, delta=4.0, temperature=1.0, denom=0.0, grad_scale=1.0,
+                 grad_rows=None, vocab=None):
+    """Full objective.  Returns a dict with loss, logprobs, counts, J, coeff, flags and,
+    for the row indices in ``grad_rows`` ("all" = every row), dense fp64 gradient rows."""
+    a, dt, stride = _logits_view(logits)
+    N = a.shape[0]
+    V = a.shape[1] if vocab is None else vocab
+    tokens = np.ascontiguousarray(tokens, dtype=np.int64)
+    old = np.ascontiguousarray(old_logprobs, dtype=np.float32)
+    adv = np.ascontiguousarray(advantages, dtype=np.float32)
+    m = None if mask is None else np.ascontiguousarray(mask, dtype=np.uint8)
+    assert tokens.shape[0] == N and old.shape[0] == N and adv.shape[0] == N
+    if isinstance(grad_rows, str) and grad_rows == "all":
+        grad_rows = np.arange(N, dtype=np.int64)
+    gr = None if grad_rows is None else np.ascontiguousarray(grad_rows, dtype=np.int64)
+    n_gr = 0 if gr is None else gr.shape[0]
+    grad = None if gr is None else np.zeros((n_gr, V), dtype=np.float64)
+    loss = np.zeros(1, dtype=np.float64)
+    lp = np.zeros(N, dtype=np.float64)
+    counts = np.zeros(5, dtype=np.int64)
+    J = np.zeros(N, dtype=np.float64)
+    coeff = np.zeros(N, dtype=np.float64)
+    flags = np.zeros(N, dtype=np.int32)
+    rc = lib().oracle_loss_fwd_bwd(
+        _ptr(a), dt, N, V, stride, _ptr(tokens), _ptr(old), _ptr(adv), _ptr(m),
+        float(eps_low), float(eps_high), float(delta), float(temperature), float(denom),
+        float(grad_scale), _ptr(loss), _ptr(lp), _ptr(counts), _ptr(J), _ptr(coeff),
+        _ptr(flags), _ptr(gr), n_gr, _ptr(grad))
+    if rc:
+        raise ValueError("oracle_loss_fwd_bwd failed (rc=%d)" % rc)
+    return dict(loss=float(loss[0]), logprobs=lp, counts=counts, J=J, coeff=coeff,
+                flags=flags, grad=grad, grad_rows=gr)
