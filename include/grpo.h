@@ -1,0 +1,187 @@
+/*
+ * libgrpo - token-level GRPO policy objective with two-sided clipping,
+ * forward and fused backward, for AMD MI355X (gfx950).
+ *
+ * The operation is the objective of section 3.4 of the INTELLECT-2 paper
+ * (second displayed objective, the one that adds the bound delta):
+ *
+ *   J_t  = min( min(r_t, delta) A_t , clip(r_t, 1 - eps_low, 1 + eps_high) A_t )
+ *   r_t  = pi_theta(y_t) / pi_theta_old(y_t) = exp(l_t - l_old_t)
+ *   l_t  = log softmax(z_t / T)[y_t]
+ *   loss = -(1/D) sum_t m_t J_t          (token-level mean, section 4.1)
+ *
+ * with z_t the row of policy logits of token t, y_t the sampled token, A_t the
+ * group-relative advantage (section 3.4), m_t the response mask.  The paper uses
+ * eps_low = eps_high = 0.2 and delta = 4 (section 4.1).
+ *
+ * Conventions shared by every entry point
+ *  - All data pointers are DEVICE pointers owned by the caller.  The library
+ *    allocates nothing, frees nothing and keeps no per-call state; scratch comes
+ *    from the caller's workspace.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
+ *    work is enqueued on it; nothing synchronises with the host, so results are
+ *    device-resident and valid once the stream has reached that point.
+ *  - Arguments are validated on the host BEFORE any GPU call; a failed
+ *    validation returns a code below and launches nothing.  Problems that only
+ *    the data can reveal (a token id outside [0, vocab)) cannot be returned as a
+ *    code; see each function.
+ *  - NaN or Inf in the logits of an unmasked row propagate to that row's
+ *    outputs and to the loss; they are never hidden.
+ *  - Rows are independent; 64-bit indexing throughout (n_tokens * vocab may
+ *    exceed 2^31).
+ */
+#ifndef GRPO_H
+#define GRPO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    GRPO_OK = 0,
+    GRPO_ERR_NULL = 1,      /* a required pointer is NULL                              */
+    GRPO_ERR_SHAPE = 2,     /* a size is negative/zero where it may not be, stride < vocab */
+    GRPO_ERR_DTYPE = 3,     /* dtype is not one of grpo_dtype                          */
+    GRPO_ERR_ALIGN = 4,     /* logits/grad base or row pitch not 16-byte aligned       */
+    GRPO_ERR_PARAM = 5,     /* temperature <= 0, eps out of range, delta <= 1+eps_high */
+    GRPO_ERR_WORKSPACE = 6, /* workspace NULL, misaligned or too small                 */
+    GRPO_ERR_HIP = 7        /* the HIP runtime reported an error at launch             */
+} grpo_status;
+
+typedef enum {
+    GRPO_F32 = 0, /* IEEE binary32 logits and gradients            */
+    GRPO_BF16 = 1 /* bfloat16 logits and gradients (RNE on store)  */
+} grpo_dtype;
+
+/* Index of each counter in counts_out of grpo_loss_fwd_bwd. */
+enum {
+    GRPO_COUNT_TOKENS = 0,     /* M = number of rows with mask 1                       */
+    GRPO_COUNT_CLIP_HIGH = 1,  /* A > 0 and r > 1 + eps_high (gradient cut)            */
+    GRPO_COUNT_CLIP_LOW = 2,   /* A < 0 and r < 1 - eps_low  (gradient cut)            */
+    GRPO_COUNT_DELTA = 3,      /* A < 0 and r > delta        (gradient cut, sec. 3.4)  */
+    GRPO_COUNT_OUT_OF_BAND = 4 /* r outside [1-eps_low, 1+eps_high], any A: the "token
+                                  probability clip ratio" tracked in section 3.5       */
+};
+
+/* Static, human-readable text for a status code.  Never NULL. */
+const char *grpo_status_string(grpo_status status);
+
+/* Bytes of device workspace grpo_loss_fwd_bwd needs for n_tokens rows (a pure host
+ * function; returns 0 for n_tokens < 0).  The workspace must be 256-byte aligned. */
+size_t grpo_workspace_bytes(int64_t n_tokens);
+
+/*
+ * Group-relative advantages (section 3.4: each prompt's G sampled outputs are
+ * scored relative to one another; section 3.3: a group whose rewards are all
+ * equal has zero advantages).  The paper gives no formula; this library uses
+ *     A_i = (R_i - mean_g) / (std_g + eps_std),
+ *     std_g = sqrt( sum_{i in g} (R_i - mean_g)^2 / (G - ddof) ),
+ * and A_i = 0 when G - ddof <= 0 or std_g + eps_std == 0.
+ *
+ *  rewards          [n_rollouts] f32, device, read.
+ *  group_offsets    [n_groups+1] i32, device, read, or NULL.  Group g owns rollouts
+ *                   [group_offsets[g], group_offsets[g+1]).  Offsets outside
+ *                   [0, n_rollouts] or decreasing are clamped on the device (no
+ *                   out-of-bounds access; the affected advantages are unspecified).
+ *  group_size       used when group_offsets is NULL: every group has group_size
+ *                   rollouts and n_rollouts must equal n_groups * group_size.
+ *  eps_std >= 0, ddof in {0, 1}.
+ *  adv_out          [n_rollouts] f32, device, written (rollouts no group owns are
+ *                   left untouched).
+ *  rollout_of_token [n_tokens] i32, device, read, or NULL: rollout index of every
+ *                   token row.  With it, adv_tok_out[t] = adv_out[rollout_of_token[t]]
+ *                   (NaN if the index is outside [0, n_rollouts)).
+ *  adv_tok_out      [n_tokens] f32, device, written; required iff rollout_of_token
+ *                   is given.
+ * Accumulation is in fp64, so results are independent of launch shape.
+ * n_groups == 0 and n_tokens == 0 are legal and do nothing.
+ */
+grpo_status grpo_group_advantages(const float *rewards, int64_t n_rollouts,
+                                  const int32_t *group_offsets, int64_t n_groups,
+                                  int64_t group_size, float eps_std, int ddof,
+                                  float *adv_out, const int32_t *rollout_of_token,
+                                  int64_t n_tokens, float *adv_tok_out, void *stream);
+
+/*
+ * Per-token log-probabilities of the sampled tokens,
+ *     logprobs_out[t] = log softmax(logits[t, :] / temperature)[tokens[t]],
+ * i.e. log pi_theta(o_{i,t} | q, o_{i,<t}) of section 3.4.  This is how the trainer
+ * obtains the old-policy log-probs at the start of an optimisation step
+ * (section 4.1: recomputed with the policy weights rather than taken from the
+ * inference workers).  One streaming read of the logits.
+ *
+ *  logits      [n_tokens, vocab] row-major, device, read; row t starts
+ *              row_stride ELEMENTS after row t-1 (row_stride >= vocab).  The base
+ *              pointer and the row pitch in bytes must be multiples of 16.
+ *  tokens      [n_tokens] i64, device, read.
+ *  mask        [n_tokens] u8 (0 or non-zero), device, read, or NULL = all ones.
+ *              Rows with mask 0 give logprobs_out = 0 and none of their inputs
+ *              (logits, token) is read.
+ *  logprobs_out[n_tokens] f32, device, written.
+ * A token id outside [0, vocab) at an unmasked row gives logprobs_out = NaN there.
+ * n_tokens == 0 is legal and does nothing.
+ */
+grpo_status grpo_logprobs_fwd(const void *logits, grpo_dtype dtype, int64_t n_tokens,
+                              int64_t vocab, int64_t row_stride, const int64_t *tokens,
+                              const uint8_t *mask, float temperature, float *logprobs_out,
+                              void *stream);
+
+/*
+ * Objective forward and fused backward (section 3.4 objective with delta,
+ * token-level normalisation of section 4.1; see the top of this file).
+ *
+ *  logits, dtype, n_tokens, vocab, row_stride, tokens, mask: as above.
+ *  old_logprobs [n_tokens] f32, device, read: l_old_t.
+ *  advantages   [n_tokens] f32, device, read: A_t per token.
+ *  eps_low in [0, 1], eps_high >= 0, delta > 1 + eps_high (section 3.4 asks for
+ *               delta above 1 + eps), temperature > 0.
+ *  denom        D.  denom > 0: used as given (a caller that splits a batch over
+ *               micro-batches or GPUs passes the global token count).  denom <= 0:
+ *               D = M = number of rows with mask 1 in this call; if that is 0 the
+ *               loss and all gradients are 0.
+ *  grad_scale   upstream gradient dL/dloss; multiplies grad_logits only.
+ *  loss_out     [1] f32, device, written: -(1/D) sum_t m_t J_t.
+ *  logprobs_out [n_tokens] f32, device, written, or NULL: l_t (0 at masked rows).
+ *  counts_out   [5] i64, device, written, or NULL: see GRPO_COUNT_*; counted over
+ *               rows with mask 1.  Clip fractions are counts / M.
+ *  grad_logits  [n_tokens, vocab] same dtype and row_stride as logits, device,
+ *               written:  grad_scale * dloss/dlogits
+ *                 = c_t / T * (1[j = y_t] - softmax(z_t / T)_j),
+ *               c_t = -grad_scale * m_t * (dJ_t/dl_t) / D,
+ *               dJ_t/dl_t = r_t A_t where the objective is not clipped, else 0
+ *               (a ratio exactly on a boundary counts as not clipped).
+ *               Rows with c_t = 0 (masked, clipped, delta-capped, A_t = 0) are
+ *               zero-filled.  bf16 gradients are rounded to nearest even.  May be
+ *               the same buffer as logits (in-place); no other aliasing is allowed.
+ *               Padding elements [vocab, row_stride) are never read or written.
+ *  workspace    device, >= grpo_workspace_bytes(n_tokens) bytes, 256-byte aligned;
+ *               contents on entry are ignored; on return it holds a sticky error
+ *               word readable with grpo_workspace_error.
+ * A token id outside [0, vocab) at an unmasked row makes that row behave as a
+ * masked row (it still counts towards M) and sets the error word.
+ * The loss is reduced in fp64 in a fixed order: results are bitwise reproducible.
+ * n_tokens == 0 is legal: loss 0, counts 0.
+ */
+grpo_status grpo_loss_fwd_bwd(const void *logits, grpo_dtype dtype, int64_t n_tokens,
+                              int64_t vocab, int64_t row_stride, const int64_t *tokens,
+                              const float *old_logprobs, const float *advantages,
+                              const uint8_t *mask, float eps_low, float eps_high,
+                              float delta, float temperature, double denom,
+                              float grad_scale, float *loss_out, float *logprobs_out,
+                              int64_t *counts_out, void *grad_logits, void *workspace,
+                              size_t workspace_bytes, void *stream);
+
+/*
+ * Reads the sticky error word the last grpo_loss_fwd_bwd left in `workspace`:
+ * waits for `stream`, copies one int to *flag_out (HOST pointer).  0 = no data
+ * error, bit 0 = some unmasked row had a token id outside [0, vocab).
+ */
+grpo_status grpo_workspace_error(const void *workspace, int32_t *flag_out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GRPO_H */

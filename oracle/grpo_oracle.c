@@ -236,23 +236,114 @@ void oracle_surrogate_from_ratio(double r, double A, double eps_low, double eps_
 }
 
 /* ------------------------------------------------------------------ *
- * Whole objective and gradient.
- *
+ * Objective from per-token log-probs (steps after the softmax):
+ *   r_t = exp(l_t - l_old_t),  J_t as above,
  *   loss = -(1/D) sum_t m_t J_t,  D = denom if denom > 0 else M = sum_t m_t,
  *   loss = 0 when D = 0                           (token-level, section 4.1)
- *   dloss/dz_{t,j} = grad_scale * (-(m_t / D) dJ_t/dl_t) * (1/T) * (1[j = y_t] - p_{t,j})
- *   with p_{t,j} = exp(u_{t,j} - lse_t).
- *
- * Outputs (any of the optional ones may be NULL):
- *   loss_out       [1]
- *   logprobs_out   [n_tokens]   l_t (0 at masked rows)
- *   counts_out     [5]          M, n_clip_high, n_clip_low, n_delta, n_out_of_band
- *                               (counted over rows with m_t = 1)
- *   J_out          [n_tokens]   J_t (0 at masked rows)              optional
- *   coeff_out      [n_tokens]   c_t = dloss/dl_t incl. grad_scale   optional
- *   flags_out      [n_tokens]   indicator bits per row               optional
- *   grad_out       [n_grad_rows, V] dense fp64: gradient rows for the row
- *                               indices listed in grad_rows           optional
+ *   c_t = grad_scale * dloss/dl_t = -grad_scale * m_t * (dJ_t/dl_t) / D.
+ * Outputs (optional ones may be NULL):
+ *   loss_out [1]; counts_out [5] = M, n_clip_high, n_clip_low, n_delta,
+ *   n_out_of_band (over rows with m_t = 1); J_out, coeff_out [n_tokens] (0 at
+ *   masked rows); flags_out [n_tokens] indicator bits.
+ * ------------------------------------------------------------------ */
+void oracle_objective_from_logprobs(int64_t n_tokens, const double *logprobs,
+                                    const float *old_logprobs, const float *advantages,
+                                    const uint8_t *mask, double eps_low, double eps_high,
+                                    double delta, double denom, double grad_scale,
+                                    double *loss_out, int64_t *counts_out, double *J_out,
+                                    double *coeff_out, int32_t *flags_out)
+{
+    int64_t M = 0;
+    for (int64_t t = 0; t < n_tokens; ++t)
+        M += (!mask || mask[t]) ? 1 : 0;
+    double D = (denom > 0.0) ? denom : (double)M;
+
+    int64_t n_hi = 0, n_lo = 0, n_de = 0, n_oob = 0;
+    csum sumJ = {0.0, 0.0};
+    for (int64_t t = 0; t < n_tokens; ++t) {
+        double J = 0.0, dJ = 0.0;
+        int fl = 0;
+        if (!mask || mask[t]) {
+            double r = exp(logprobs[t] - (double)old_logprobs[t]);
+            oracle_surrogate_from_ratio(r, (double)advantages[t], eps_low, eps_high,
+                                        delta, &J, &dJ, &fl);
+            csum_add(&sumJ, J);
+            n_hi += (fl & FLAG_CLIP_HIGH) ? 1 : 0;
+            n_lo += (fl & FLAG_CLIP_LOW) ? 1 : 0;
+            n_de += (fl & FLAG_DELTA) ? 1 : 0;
+            n_oob += (fl & FLAG_OUT_OF_BAND) ? 1 : 0;
+        }
+        if (J_out)
+            J_out[t] = J;
+        if (coeff_out)
+            coeff_out[t] = (D > 0.0) ? -grad_scale * dJ / D : 0.0;
+        if (flags_out)
+            flags_out[t] = fl;
+    }
+    if (loss_out)
+        *loss_out = (D > 0.0) ? -csum_value(&sumJ) / D : 0.0;
+    if (counts_out) {
+        counts_out[0] = M;
+        counts_out[1] = n_hi;
+        counts_out[2] = n_lo;
+        counts_out[3] = n_de;
+        counts_out[4] = n_oob;
+    }
+}
+
+/* ------------------------------------------------------------------ *
+ * Gradient of one row with respect to its logits, given c = grad_scale *
+ * dloss/dl of that row:
+ *   g_j = (c / T) * (1[j = y] - p_j),   p_j = exp(z_j / T - lse).
+ * For j != y this is -(c/T) p_j; for j = y it is (c/T)(1 - p_y) with
+ * 1 - p_y = sum_{j != y} p_j (the p_j sum to one).  The second form is used
+ * because 1 - p_y cancels to nothing in any fixed precision once p_y is within
+ * an ulp of 1, while the sum does not.
+ * ------------------------------------------------------------------ */
+void oracle_grad_row(const void *row, int dtype, int64_t V, double T, int64_t y, double c,
+                     double *g /* [V] */)
+{
+    double lse = oracle_row_log_softmax(row, dtype, V, T, NULL);
+    csum others = {0.0, 0.0};
+    for (int64_t j = 0; j < V; ++j) {
+        if (j == y)
+            continue;
+        double p = exp(logit_at(row, dtype, j) / T - lse);
+        csum_add(&others, p);
+        g[j] = -(c / T) * p;
+    }
+    g[y] = (c / T) * csum_value(&others);
+}
+
+/* Gradient rows for a list of rows: grad_out[k, :] belongs to row grad_rows[k] of
+ * the logits; coeff[t] is c_t for every row t of the batch; rows with coeff 0
+ * (masked, clipped, zero advantage) are zero and their logits are not read. */
+void oracle_grad_rows(const void *logits, int dtype, int64_t V, int64_t row_stride,
+                      const int64_t *tokens, const double *coeff, double T,
+                      const int64_t *grad_rows, int64_t n_grad_rows, double *grad_out)
+{
+    size_t esz = elem_size(dtype);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t k = 0; k < n_grad_rows; ++k) {
+        int64_t t = grad_rows[k];
+        double *g = grad_out + (size_t)k * (size_t)V;
+        if (coeff[t] == 0.0) {
+            for (int64_t j = 0; j < V; ++j)
+                g[j] = 0.0;
+            continue;
+        }
+        const char *row = (const char *)logits + (size_t)t * (size_t)row_stride * esz;
+        oracle_grad_row(row, dtype, V, T, tokens[t], coeff[t], g);
+    }
+}
+
+/* ------------------------------------------------------------------ *
+ * Whole objective and gradient in one call: log-probs, then the objective,
+ * then the gradient rows asked for.
+ *   dloss/dz_{t,j} * grad_scale = c_t * (1/T) * (1[j = y_t] - p_{t,j}).
+ * logprobs_out [n_tokens] (0 at masked rows) and the outputs of
+ * oracle_objective_from_logprobs; grad_out [n_grad_rows, V] dense fp64 for the
+ * row indices listed in grad_rows (optional).
  * Returns 0, or 2 if an unmasked row has a token id outside [0, V).
  * ------------------------------------------------------------------ */
 int oracle_loss_fwd_bwd(const void *logits, int dtype, int64_t n_tokens, int64_t V,
@@ -264,90 +355,32 @@ int oracle_loss_fwd_bwd(const void *logits, int dtype, int64_t n_tokens, int64_t
                         double *J_out, double *coeff_out, int32_t *flags_out,
                         const int64_t *grad_rows, int64_t n_grad_rows, double *grad_out)
 {
-    size_t esz = elem_size(dtype);
-    double *lp = (double *)malloc(sizeof(double) * (size_t)(n_tokens > 0 ? n_tokens : 1));
-    if (!lp)
-        return 3;
-    int rc = oracle_logprobs(logits, dtype, n_tokens, V, row_stride, tokens, mask, T, lp);
-    if (rc) {
+    size_t n_alloc = (size_t)(n_tokens > 0 ? n_tokens : 1);
+    double *lp = (double *)malloc(sizeof(double) * n_alloc);
+    double *cf = (double *)malloc(sizeof(double) * n_alloc);
+    if (!lp || !cf) {
         free(lp);
-        return rc;
+        free(cf);
+        return 3;
     }
-
-    int64_t M = 0;
-    for (int64_t t = 0; t < n_tokens; ++t)
-        M += (!mask || mask[t]) ? 1 : 0;
-    double D = (denom > 0.0) ? denom : (double)M;
-
-    int64_t n_hi = 0, n_lo = 0, n_de = 0, n_oob = 0;
-    double sumJ = 0.0;
-    for (int64_t t = 0; t < n_tokens; ++t) {
-        double J = 0.0, dJ = 0.0;
-        int fl = 0;
-        if (!mask || mask[t]) {
-            double r = exp(lp[t] - (double)old_logprobs[t]);
-            oracle_surrogate_from_ratio(r, (double)advantages[t], eps_low, eps_high,
-                                        delta, &J, &dJ, &fl);
-            sumJ += J;
-            n_hi += (fl & FLAG_CLIP_HIGH) ? 1 : 0;
-            n_lo += (fl & FLAG_CLIP_LOW) ? 1 : 0;
-            n_de += (fl & FLAG_DELTA) ? 1 : 0;
-            n_oob += (fl & FLAG_OUT_OF_BAND) ? 1 : 0;
+    int rc = oracle_logprobs(logits, dtype, n_tokens, V, row_stride, tokens, mask, T, lp);
+    if (rc == 0) {
+        oracle_objective_from_logprobs(n_tokens, lp, old_logprobs, advantages, mask, eps_low,
+                                       eps_high, delta, denom, grad_scale, loss_out,
+                                       counts_out, J_out, cf, flags_out);
+        for (int64_t t = 0; t < n_tokens; ++t) {
+            if (logprobs_out)
+                logprobs_out[t] = lp[t];
+            if (coeff_out)
+                coeff_out[t] = cf[t];
         }
-        if (logprobs_out)
-            logprobs_out[t] = lp[t];
-        if (J_out)
-            J_out[t] = J;
-        if (coeff_out)
-            coeff_out[t] = (D > 0.0) ? -grad_scale * dJ / D : 0.0;
-        if (flags_out)
-            flags_out[t] = fl;
-    }
-    if (loss_out)
-        *loss_out = (D > 0.0) ? -sumJ / D : 0.0;
-    if (counts_out) {
-        counts_out[0] = M;
-        counts_out[1] = n_hi;
-        counts_out[2] = n_lo;
-        counts_out[3] = n_de;
-        counts_out[4] = n_oob;
-    }
-
-    if (grad_out && grad_rows) {
-#pragma omp parallel for schedule(dynamic, 1)
-        for (int64_t k = 0; k < n_grad_rows; ++k) {
-            int64_t t = grad_rows[k];
-            double *g = grad_out + (size_t)k * (size_t)V;
-            if (mask && !mask[t]) {
-                for (int64_t j = 0; j < V; ++j)
-                    g[j] = 0.0;
-                continue;
-            }
-            const char *row = (const char *)logits + (size_t)t * (size_t)row_stride * esz;
-            double r = exp(lp[t] - (double)old_logprobs[t]);
-            double dJ;
-            oracle_surrogate_from_ratio(r, (double)advantages[t], eps_low, eps_high,
-                                        delta, NULL, &dJ, NULL);
-            double c = (D > 0.0) ? -grad_scale * dJ / D : 0.0; /* dloss/dl_t */
-            double lse = oracle_row_log_softmax(row, dtype, V, T, NULL);
-            int64_t y = tokens[t];
-            /* (1[j = y] - p_j): for j != y this is -p_j; for j = y it is
-             * 1 - p_y = sum_{j != y} p_j (the p_j sum to one).  The second form
-             * is used because 1 - p_y cancels to nothing in any fixed precision
-             * once p_y is within an ulp of 1, while the sum does not. */
-            csum others = {0.0, 0.0};
-            for (int64_t j = 0; j < V; ++j) {
-                if (j == y)
-                    continue;
-                double p = exp(logit_at(row, dtype, j) / T - lse);
-                csum_add(&others, p);
-                g[j] = -(c / T) * p;
-            }
-            g[y] = (c / T) * csum_value(&others);
-        }
+        if (grad_out && grad_rows)
+            oracle_grad_rows(logits, dtype, V, row_stride, tokens, cf, T, grad_rows,
+                             n_grad_rows, grad_out);
     }
     free(lp);
-    return 0;
+    free(cf);
+    return rc;
 }
 
 /* Number of OpenMP threads a parallel region would use (for the benchmark's

@@ -61,6 +61,11 @@ def lib():
         L.oracle_loss_fwd_bwd.argtypes = [vp, i32, i64, i64, i64, vp, vp, vp, vp,
                                           dbl, dbl, dbl, dbl, dbl, dbl,
                                           vp, vp, vp, vp, vp, vp, vp, i64, vp]
+        L.oracle_objective_from_logprobs.restype = None
+        L.oracle_objective_from_logprobs.argtypes = [i64, vp, vp, vp, vp, dbl, dbl, dbl, dbl, dbl,
+                                                     vp, vp, vp, vp, vp]
+        L.oracle_grad_rows.restype = None
+        L.oracle_grad_rows.argtypes = [vp, i32, i64, i64, vp, vp, dbl, vp, i64, vp]
         L.oracle_num_threads.restype = i32
         L.oracle_num_threads.argtypes = []
         _lib = L
@@ -183,3 +188,38 @@ def loss_fwd_bwd(logits, tokens, old_logprobs, advantages, mask=None, *, eps_low
         raise ValueError("oracle_loss_fwd_bwd failed (rc=%d)" % rc)
     return dict(loss=float(loss[0]), logprobs=lp, counts=counts, J=J, coeff=coeff,
                 flags=flags, grad=grad, grad_rows=gr)
+
+
+def objective_from_logprobs(logprobs, old_logprobs, advantages, mask=None, *, eps_low=0.2,
+                            eps_high=0.2, delta=4.0, denom=0.0, grad_scale=1.0):
+    """Ratio, surrogate, masked token mean and counters from per-token log-probs."""
+    lp = np.ascontiguousarray(logprobs, dtype=np.float64)
+    N = lp.shape[0]
+    old = np.ascontiguousarray(old_logprobs, dtype=np.float32)
+    adv = np.ascontiguousarray(advantages, dtype=np.float32)
+    m = None if mask is None else np.ascontiguousarray(mask, dtype=np.uint8)
+    loss = np.zeros(1, dtype=np.float64)
+    counts = np.zeros(5, dtype=np.int64)
+    J = np.zeros(N, dtype=np.float64)
+    coeff = np.zeros(N, dtype=np.float64)
+    flags = np.zeros(N, dtype=np.int32)
+    lib().oracle_objective_from_logprobs(N, _ptr(lp), _ptr(old), _ptr(adv), _ptr(m),
+                                         float(eps_low), float(eps_high), float(delta),
+                                         float(denom), float(grad_scale), _ptr(loss),
+                                         _ptr(counts), _ptr(J), _ptr(coeff), _ptr(flags))
+    return dict(loss=float(loss[0]), counts=counts, J=J, coeff=coeff, flags=flags)
+
+
+def grad_rows(logits_rows, tokens_rows, coeff_rows, temperature=1.0, vocab=None):
+    """Dense fp64 gradient rows for the given logits rows, their sampled tokens and their
+    coefficients c_t (from objective_from_logprobs)."""
+    a, dt, stride = _logits_view(logits_rows)
+    K = a.shape[0]
+    V = a.shape[1] if vocab is None else vocab
+    tok = np.ascontiguousarray(tokens_rows, dtype=np.int64)
+    cf = np.ascontiguousarray(coeff_rows, dtype=np.float64)
+    idx = np.arange(K, dtype=np.int64)
+    out = np.zeros((K, V), dtype=np.float64)
+    lib().oracle_grad_rows(_ptr(a), dt, V, stride, _ptr(tok), _ptr(cf), float(temperature),
+                           _ptr(idx), K, _ptr(out))
+    return out

@@ -1,0 +1,192 @@
+"""Thin Python binding of libgrpo's C ABI (see include/grpo.h).
+
+Argument marshalling only: tensors become raw device pointers, sizes and the
+current HIP stream; every step of the computation runs in the library's kernels.
+There is no fallback: if the shared library cannot be loaded the call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch  # imported first so that the HIP runtime torch ships is the one in the process
+
+from . import build as _build
+
+GRPO_OK = 0
+GRPO_F32, GRPO_BF16 = 0, 1
+COUNT_NAMES = ("tokens", "clip_high", "clip_low", "delta", "out_of_band")
+
+_lib = None
+
+
+class GrpoError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = int(status)
+        super().__init__("%s failed: %s (status %d)" % (where, status_string(status), status))
+
+
+def lib():
+    """The loaded C library with argument types declared.  Builds it only if absent."""
+    global _lib
+    if _lib is None:
+        path = _build.LIB_PATH
+        if not os.path.exists(path):
+            path = _build.build_library()
+        L = ctypes.CDLL(path)
+        vp, i64, i32, f32, f64, sz = (ctypes.c_void_p, ctypes.c_int64, ctypes.c_int,
+                                      ctypes.c_float, ctypes.c_double, ctypes.c_size_t)
+        L.grpo_status_string.restype = ctypes.c_char_p
+        L.grpo_status_string.argtypes = [i32]
+        L.grpo_workspace_bytes.restype = sz
+        L.grpo_workspace_bytes.argtypes = [i64]
+        L.grpo_group_advantages.restype = i32
+        L.grpo_group_advantages.argtypes = [vp, i64, vp, i64, i64, f32, i32, vp, vp, i64, vp, vp]
+        L.grpo_logprobs_fwd.restype = i32
+        L.grpo_logprobs_fwd.argtypes = [vp, i32, i64, i64, i64, vp, vp, f32, vp, vp]
+        L.grpo_loss_fwd_bwd.restype = i32
+        L.grpo_loss_fwd_bwd.argtypes = [vp, i32, i64, i64, i64, vp, vp, vp, vp, f32, f32, f32, f32,
+                                        f64, f32, vp, vp, vp, vp, vp, sz, vp]
+        L.grpo_workspace_error.restype = i32
+        L.grpo_workspace_error.argtypes = [vp, vp, vp]
+        _lib = L
+    return _lib
+
+
+def status_string(status) -> str:
+    return lib().grpo_status_string(int(status)).decode()
+
+
+def grpo_workspace_bytes(n_tokens: int) -> int:
+    return int(lib().grpo_workspace_bytes(int(n_tokens)))
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _check(t, dtype, n, name, device):
+    if t.dtype != dtype or t.dim() != 1 or t.shape[0] != n or not t.is_contiguous():
+        raise ValueError("%s must be a contiguous %s tensor of length %d" % (name, dtype, n))
+    if t.device != device:
+        raise ValueError("%s must live on %s" % (name, device))
+
+
+def _logits_args(logits, vocab):
+    if logits.dim() != 2 or logits.stride(1) != 1:
+        raise ValueError("logits must be [n_tokens, vocab] with unit stride along the vocabulary")
+    if not logits.is_cuda:
+        raise ValueError("logits must be a device tensor: libgrpo has no CPU path")
+    if logits.dtype == torch.bfloat16:
+        dt = GRPO_BF16
+    elif logits.dtype == torch.float32:
+        dt = GRPO_F32
+    else:
+        raise ValueError("logits must be bfloat16 or float32")
+    n = logits.shape[0]
+    v = logits.shape[1] if vocab is None else int(vocab)
+    stride = logits.stride(0) if n > 1 else max(logits.stride(0), v)
+    return dt, n, v, stride
+
+
+def grpo_group_advantages(rewards, group_size=None, group_offsets=None, eps_std=1e-6, ddof=0,
+                          rollout_of_token=None, adv_out=None, adv_tok_out=None, stream=None):
+    """Returns (adv [n_rollouts], adv_tok [n_tokens] or None); see grpo_group_advantages in grpo.h."""
+    dev = rewards.device
+    R = rewards.shape[0]
+    _check(rewards, torch.float32, R, "rewards", dev)
+    if group_offsets is not None:
+        _check(group_offsets, torch.int32, group_offsets.shape[0], "group_offsets", dev)
+        n_groups, gs = group_offsets.shape[0] - 1, 0
+    else:
+        gs = int(group_size)
+        n_groups = R // gs if gs > 0 else 0
+    if adv_out is None:
+        adv_out = torch.empty(R, dtype=torch.float32, device=dev)
+    n_tok = 0
+    if rollout_of_token is not None:
+        n_tok = rollout_of_token.shape[0]
+        _check(rollout_of_token, torch.int32, n_tok, "rollout_of_token", dev)
+        if adv_tok_out is None:
+            adv_tok_out = torch.empty(n_tok, dtype=torch.float32, device=dev)
+    rc = lib().grpo_group_advantages(_ptr(rewards), R, _ptr(group_offsets), n_groups, gs,
+                                     float(eps_std), int(ddof), _ptr(adv_out),
+                                     _ptr(rollout_of_token), n_tok, _ptr(adv_tok_out),
+                                     _stream(stream))
+    if rc != GRPO_OK:
+        raise GrpoError(rc, "grpo_group_advantages")
+    return adv_out, adv_tok_out
+
+
+def grpo_logprobs_fwd(logits, tokens, mask=None, temperature=1.0, vocab=None, logprobs_out=None,
+                      stream=None):
+    """log softmax(logits / T)[tokens] per row; see grpo_logprobs_fwd in grpo.h."""
+    dt, n, v, stride = _logits_args(logits, vocab)
+    dev = logits.device
+    _check(tokens, torch.int64, n, "tokens", dev)
+    if mask is not None:
+        _check(mask, torch.uint8, n, "mask", dev)
+    if logprobs_out is None:
+        logprobs_out = torch.empty(n, dtype=torch.float32, device=dev)
+    rc = lib().grpo_logprobs_fwd(_ptr(logits), dt, n, v, stride, _ptr(tokens), _ptr(mask),
+                                 float(temperature), _ptr(logprobs_out), _stream(stream))
+    if rc != GRPO_OK:
+        raise GrpoError(rc, "grpo_logprobs_fwd")
+    return logprobs_out
+
+
+def grpo_loss_fwd_bwd(logits, tokens, old_logprobs, advantages, mask=None, eps_low=0.2,
+                      eps_high=0.2, delta=4.0, temperature=1.0, denom=0.0, grad_scale=1.0, *,
+                      vocab=None, grad_logits=None, inplace=False, loss_out=None,
+                      logprobs_out=None, counts_out=None, workspace=None, stream=None):
+    """Objective forward + fused backward; see grpo_loss_fwd_bwd in grpo.h.
+
+    Returns (loss [1] f32, logprobs [n] f32, counts [5] i64, grad_logits), all on the device and
+    valid once the stream has run.  ``inplace=True`` writes the gradient over the logits.
+    """
+    dt, n, v, stride = _logits_args(logits, vocab)
+    dev = logits.device
+    _check(tokens, torch.int64, n, "tokens", dev)
+    _check(old_logprobs, torch.float32, n, "old_logprobs", dev)
+    _check(advantages, torch.float32, n, "advantages", dev)
+    if mask is not None:
+        _check(mask, torch.uint8, n, "mask", dev)
+    if inplace:
+        grad_logits = logits
+    elif grad_logits is None:
+        grad_logits = torch.empty_strided(logits.shape, logits.stride(), dtype=logits.dtype, device=dev)
+    elif grad_logits.dtype != logits.dtype or grad_logits.shape != logits.shape or \
+            grad_logits.stride() != logits.stride():
+        raise ValueError("grad_logits must match logits in dtype, shape and strides")
+    if loss_out is None:
+        loss_out = torch.empty(1, dtype=torch.float32, device=dev)
+    if logprobs_out is None:
+        logprobs_out = torch.empty(n, dtype=torch.float32, device=dev)
+    if counts_out is None:
+        counts_out = torch.empty(5, dtype=torch.int64, device=dev)
+    need = grpo_workspace_bytes(n)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    rc = lib().grpo_loss_fwd_bwd(_ptr(logits), dt, n, v, stride, _ptr(tokens), _ptr(old_logprobs),
+                                 _ptr(advantages), _ptr(mask), float(eps_low), float(eps_high),
+                                 float(delta), float(temperature), float(denom), float(grad_scale),
+                                 _ptr(loss_out), _ptr(logprobs_out), _ptr(counts_out),
+                                 _ptr(grad_logits), _ptr(workspace), workspace.numel(),
+                                 _stream(stream))
+    if rc != GRPO_OK:
+        raise GrpoError(rc, "grpo_loss_fwd_bwd")
+    return loss_out, logprobs_out, counts_out, grad_logits
+
+
+def grpo_workspace_error(workspace, stream=None) -> int:
+    flag = ctypes.c_int32(0)
+    rc = lib().grpo_workspace_error(_ptr(workspace), ctypes.byref(flag), _stream(stream))
+    if rc != GRPO_OK:
+        raise GrpoError(rc, "grpo_workspace_error")
+    return int(flag.value)

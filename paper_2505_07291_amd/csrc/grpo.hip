@@ -1,0 +1,907 @@
+// libgrpo: token-level GRPO objective with two-sided clipping (INTELLECT-2 paper,
+// section 3.4, objective with the bound delta; token-level mean of section 4.1),
+// forward and fused backward, hand-written for gfx950 (MI355X).
+//
+// The path is a streaming reduction over rows of 152k logits: it is bound by HBM
+// bandwidth, not by arithmetic, so there is no MFMA here.  The design keeps one
+// whole row resident in the vector registers of a 1024-lane workgroup (304 KB of
+// the CU's 512 KB register file for a 152064-wide bf16 row), so that the row is
+// read from HBM once, reduced twice (max, sum of exponentials) out of registers,
+// and the gradient is produced from the same registers: 1 read + 1 write of HBM
+// traffic per row instead of 2 reads + 1 write.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+
+#include "grpo.h"
+
+namespace {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr unsigned kNegInfF32 = 0xff800000u;
+constexpr unsigned kNegInfBf16x2 = 0xff80ff80u;
+
+constexpr int kFlagClipHigh = 1, kFlagClipLow = 2, kFlagDelta = 4, kFlagOutOfBand = 8;
+
+// First 256 bytes of the caller's workspace.
+struct WsHeader {
+    double D;      // denominator of the token-level mean
+    double inv_D;  // 1 / D, or 0 when D == 0
+    long long M;   // rows with mask != 0
+    int error;     // sticky data-error word (bit 0: token id out of range)
+    int pad;
+};
+constexpr size_t kHeaderBytes = 256;
+constexpr long long kMaxVocab = 1ll << 28;  // byte offsets inside a row stay below 2^32
+
+struct RowParams {
+    const void *logits;
+    void *grad;  // may alias logits: deliberately no __restrict__ anywhere
+    const long long *tokens;
+    const float *old_lp;
+    const float *adv;
+    const unsigned char *mask;
+    float *logprobs_out;
+    float *J_ws;
+    unsigned char *flags_ws;
+    WsHeader *hdr;
+    long long n_tokens, vocab, row_stride;
+    float k;      // log2(e) / T: exponents are kept in base 2 for v_exp_f32
+    float inv_T;  // 1 / T
+    float lo, hi, delta, grad_scale;
+    int bwd;  // 0: log-probs only (grpo_logprobs_fwd), 1: objective + gradient
+};
+
+template <grpo_dtype DT>
+struct Elem;
+template <>
+struct Elem<GRPO_BF16> {
+    static constexpr int EPV = 8, BYTES = 2;
+};
+template <>
+struct Elem<GRPO_F32> {
+    static constexpr int EPV = 4, BYTES = 4;
+};
+
+__device__ __forceinline__ float as_f32(unsigned u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ unsigned as_u32(float f) { return __builtin_bit_cast(unsigned, f); }
+
+// 16-byte vector -> EPV floats.  A bf16 is the upper half of a binary32.
+template <grpo_dtype DT>
+__device__ __forceinline__ void unpack(const u32x4 &v, float (&f)[Elem<DT>::EPV])
+{
+    if constexpr (DT == GRPO_BF16) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f[2 * i] = as_f32(v[i] << 16);
+            f[2 * i + 1] = as_f32(v[i] & 0xffff0000u);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) f[i] = as_f32(v[i]);
+    }
+}
+
+// EPV floats -> 16-byte vector; bf16 rounds to nearest even (v_cvt_pk_bf16_f32).
+template <grpo_dtype DT>
+__device__ __forceinline__ u32x4 pack(const float (&f)[Elem<DT>::EPV])
+{
+    u32x4 v;
+    if constexpr (DT == GRPO_BF16) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f32x2 p = {f[2 * i], f[2 * i + 1]};
+            v[i] = __builtin_bit_cast(unsigned, __builtin_convertvector(p, bf16x2));
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = as_u32(f[i]);
+    }
+    return v;
+}
+
+template <grpo_dtype DT>
+__device__ __forceinline__ float load_elem(const char *row, long long j)
+{
+    if constexpr (DT == GRPO_BF16)
+        return as_f32((unsigned)((const unsigned short *)row)[j] << 16);
+    else
+        return ((const float *)row)[j];
+}
+
+template <grpo_dtype DT>
+__device__ __forceinline__ void store_elem(char *row, long long j, float x)
+{
+    if constexpr (DT == GRPO_BF16) {
+        f32x2 p = {x, 0.f};
+        unsigned u = __builtin_bit_cast(unsigned, __builtin_convertvector(p, bf16x2));
+        ((unsigned short *)row)[j] = (unsigned short)(u & 0xffffu);
+    } else {
+        ((float *)row)[j] = x;
+    }
+}
+
+template <grpo_dtype DT>
+__device__ __forceinline__ u32x4 neg_inf_vec()
+{
+    unsigned w = (DT == GRPO_BF16) ? kNegInfBf16x2 : kNegInfF32;
+    u32x4 v = {w, w, w, w};
+    return v;
+}
+
+// Vector number v of a row: full vectors come as one 16-byte load; the ragged last
+// vector (vocab not a multiple of EPV) is gathered element by element and padded
+// with -inf, which contributes exp2(-inf) = 0 and never wins the max; vectors past
+// the row are all -inf.
+template <grpo_dtype DT>
+__device__ __forceinline__ u32x4 load_vec(const char *row, int v, int nvec_full, int tail)
+{
+    constexpr int EPV = Elem<DT>::EPV;
+    if (v < nvec_full) return *(const u32x4 *)(row + (unsigned)v * 16u);
+    u32x4 out = neg_inf_vec<DT>();
+    if (v == nvec_full && tail) {
+        float f[EPV];
+#pragma unroll
+        for (int i = 0; i < EPV; ++i)
+            f[i] = (i < tail) ? load_elem<DT>(row, (long long)v * EPV + i) : -INFINITY;
+        out = pack<DT>(f);  // exact: the values are already representable
+    }
+    return out;
+}
+
+template <grpo_dtype DT>
+__device__ __forceinline__ void store_vec(char *row, int v, int nvec_full, int tail,
+                                          const float (&g)[Elem<DT>::EPV])
+{
+    constexpr int EPV = Elem<DT>::EPV;
+    if (v < nvec_full) {
+        *(u32x4 *)(row + (unsigned)v * 16u) = pack<DT>(g);
+    } else if (v == nvec_full && tail) {
+#pragma unroll
+        for (int i = 0; i < EPV; ++i)
+            if (i < tail) store_elem<DT>(row, (long long)v * EPV + i, g[i]);
+    }
+}
+
+template <grpo_dtype DT, int BLOCK>
+__device__ __forceinline__ void zero_row(char *row, int nvec_full, int tail, int tid)
+{
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    for (int v = tid; v < nvec_full; v += BLOCK) *(u32x4 *)(row + (unsigned)v * 16u) = z;
+    if (tail && tid < tail) store_elem<DT>(row, (long long)nvec_full * Elem<DT>::EPV + tid, 0.f);
+}
+
+// ---- reductions: butterflies inside the 64-lane wavefront, LDS across waves,
+// always in the same order, so results are bitwise reproducible ----
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ long long wave_sum(long long v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// The caller guarantees a __syncthreads() between the reads of one call and the
+// writes of the next call on the same LDS array (the other reduction sits between).
+template <int BLOCK>
+__device__ __forceinline__ float block_max(float v, float *lds)
+{
+    constexpr int NW = BLOCK / 64;
+    v = wave_max(v);
+    if constexpr (NW == 1) return v;
+    if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float r = lds[0];
+#pragma unroll
+    for (int i = 1; i < NW; ++i) r = fmaxf(r, lds[i]);
+    return r;
+}
+template <int BLOCK>
+__device__ __forceinline__ float block_sum(float v, float *lds)
+{
+    constexpr int NW = BLOCK / 64;
+    v = wave_sum(v);
+    if constexpr (NW == 1) return v;
+    if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float r = lds[0];
+#pragma unroll
+    for (int i = 1; i < NW; ++i) r += lds[i];
+    return r;
+}
+
+// Per-row scalars once the row statistics are known.
+//   mk     = (max_j z_j) * k                      (k = log2 e / T)
+//   s_excl = sum_{j != y} exp2(z_j k - mk)        (the sampled token is left out so that
+//            1 - p_y = s_excl / s keeps its precision on near-one-hot rows, where
+//            1 - p_y cancels to nothing in fp32)
+// Produces l = log pi(y), the bracketed surrogate term J of section 3.4, its
+// indicator bits, and c = grad_scale * dloss/dl.
+struct RowScalars {
+    float logp, J, c, shift, s, s_excl;
+    int flags;
+};
+
+__device__ __forceinline__ RowScalars row_scalars(const RowParams &p, long long row, float zy,
+                                                  float mk, float s_excl)
+{
+    RowScalars o;
+    const float ay = fmaf(zy, p.k, -mk);
+    const float s = s_excl + __builtin_amdgcn_exp2f(ay);
+    const float log2s = log2f(s);
+    o.s = s;
+    o.s_excl = s_excl;
+    o.shift = mk + log2s;
+    o.logp = (ay - log2s) * kLn2;
+    o.J = 0.f;
+    o.c = 0.f;
+    o.flags = 0;
+    if (!p.bwd) return o;
+
+    const float A = p.adv[row];
+    const float r = expf(o.logp - p.old_lp[row]);
+    // J = min( min(r, delta) A , clip(r, 1 - eps_low, 1 + eps_high) A )
+    const float s1 = fminf(r, p.delta) * A;
+    const float s2 = fminf(fmaxf(r, p.lo), p.hi) * A;
+    const bool first = s1 <= s2;
+    float J = first ? s1 : s2;
+    // dJ/dl = r dJ/dr; a ratio exactly on a boundary counts as not clipped
+    const bool open = first ? (r <= p.delta) : (r >= p.lo && r <= p.hi);
+    float dJ = open ? A * r : 0.f;
+    if (r != r || A != A) {  // fminf/fmaxf drop NaNs: put them back
+        J = NAN;
+        dJ = NAN;
+    }
+    int fl = 0;
+    if (A > 0.f && r > p.hi) fl |= kFlagClipHigh;
+    if (A < 0.f && r < p.lo) fl |= kFlagClipLow;
+    if (A < 0.f && r > p.delta) fl |= kFlagDelta;
+    if (r < p.lo || r > p.hi) fl |= kFlagOutOfBand;
+    o.J = J;
+    o.flags = fl;
+    o.c = -(p.grad_scale * dJ) * (float)p.hdr->inv_D;
+    return o;
+}
+
+// Overwrites element e of a resident vector with -inf.
+template <grpo_dtype DT>
+__device__ __forceinline__ void set_neg_inf(u32x4 &v, int e)
+{
+    if constexpr (DT == GRPO_BF16) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            if (d == (e >> 1))
+                v[d] = (e & 1) ? ((v[d] & 0x0000ffffu) | 0xff800000u) : ((v[d] & 0xffff0000u) | 0x0000ff80u);
+        }
+    } else {
+#pragma unroll
+        for (int d = 0; d < 4; ++d)
+            if (d == e) v[d] = kNegInfF32;
+    }
+}
+
+// sum_e exp2(z_e k - mk) over one vector.
+template <grpo_dtype DT>
+__device__ __forceinline__ float exp_sum_vec(const u32x4 &z, float k, float mk)
+{
+    constexpr int EPV = Elem<DT>::EPV;
+    float f[EPV];
+    unpack<DT>(z, f);
+    float part = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) part += __builtin_amdgcn_exp2f(fmaf(f[e], k, -mk));
+    return part;
+}
+
+// Gradient of one vector: g_j = -(c/T) p_j with p_j = exp2(z_j k - shift), and at
+// the sampled token g_y = (c/T) (1 - p_y) = (c/T) s_excl / s.
+template <grpo_dtype DT>
+__device__ __forceinline__ void grad_vec(const u32x4 &z, float k, float shift, float q, bool has_y,
+                                         int ey, float gy, float (&g)[Elem<DT>::EPV])
+{
+    constexpr int EPV = Elem<DT>::EPV;
+    float f[EPV];
+    unpack<DT>(z, f);
+#pragma unroll
+    for (int i = 0; i < EPV; ++i) g[i] = __builtin_amdgcn_exp2f(fmaf(f[i], k, -shift)) * q;
+    if (has_y) {
+#pragma unroll
+        for (int i = 0; i < EPV; ++i)
+            if (i == ey) g[i] = gy;
+    }
+}
+
+__device__ __forceinline__ void write_row_outputs(const RowParams &p, long long row, float logp,
+                                                  float J, int flags)
+{
+    if (p.logprobs_out) p.logprobs_out[row] = logp;
+    if (p.bwd) {
+        p.J_ws[row] = J;
+        p.flags_ws[row] = (unsigned char)flags;
+    }
+}
+
+// Decides whether a row takes part; handles the rows that do not (masked, or with a
+// token id outside the vocabulary).  Returns true when the row must be processed.
+template <grpo_dtype DT, int BLOCK>
+__device__ __forceinline__ bool row_is_live(const RowParams &p, long long row, int nvec_full,
+                                            int tail, long long &y)
+{
+    bool live = p.mask ? (p.mask[row] != 0) : true;
+    bool bad = false;
+    y = 0;
+    if (live) {
+        y = p.tokens[row];
+        if (y < 0 || y >= p.vocab) {
+            live = false;
+            bad = true;
+        }
+    }
+    if (live) return true;
+    if (threadIdx.x == 0) {
+        // log-probs-only mode has no error word: a bad token id shows up as NaN
+        write_row_outputs(p, row, (bad && !p.bwd) ? NAN : 0.f, 0.f, 0);
+        if (bad && p.bwd) atomicOr(&p.hdr->error, 1);
+    }
+    if (p.bwd)
+        zero_row<DT, BLOCK>((char *)p.grad + row * p.row_stride * Elem<DT>::BYTES, nvec_full, tail,
+                            threadIdx.x);
+    return false;
+}
+
+// Keeps the instruction scheduler from interleaving the work of different vectors of
+// the unrolled row loops: with 76 registers per lane holding the row, there is room
+// for the temporaries of one vector at a time, not of several.
+#define VECTOR_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// Makes the compiler forget what it knows about a resident vector.  Without this the
+// bf16 -> fp32 widening done in one pass over the row is kept alive for the next pass
+// (common-subexpression elimination), which turns 4 registers per vector into 12 and
+// spills the row to scratch memory.  Emits no instruction.
+__device__ __forceinline__ void forget(u32x4 &v) { asm volatile("" : "+v"(v)); }
+
+// ---------------------------------------------------------------------------
+// Register-resident row kernel: requires ceil(vocab / EPV) <= BLOCK * NV.
+// One workgroup per row at a time, rows strided over a persistent grid.
+// ---------------------------------------------------------------------------
+template <grpo_dtype DT, int BLOCK, int NV>
+__global__ void __launch_bounds__(BLOCK) grpo_rows_cached(RowParams p)
+{
+    constexpr int EPV = Elem<DT>::EPV;
+    constexpr int BYTES = Elem<DT>::BYTES;
+    constexpr unsigned SLAB = BLOCK * 16u;  // bytes one pass of the workgroup covers
+    __shared__ float lds_max[BLOCK / 64];
+    __shared__ float lds_sum[BLOCK / 64];
+    const int tid = threadIdx.x;
+    const unsigned toff = (unsigned)tid * 16u;
+    const int nvec_full = (int)(p.vocab / EPV);
+    const int tail = (int)(p.vocab % EPV);
+    // The ragged last vector (vocab not a multiple of EPV) lives in one extra slot
+    // that only the first wavefront carries: lane 0 holds the elements, padded with
+    // -inf.  Full rows never enter those branches.
+    const bool tail_wave = tail != 0 && tid < 64;
+
+    for (long long row = blockIdx.x; row < p.n_tokens; row += gridDim.x) {
+        long long y;
+        if (!row_is_live<DT, BLOCK>(p, row, nvec_full, tail, y)) continue;
+        const char *zrow = (const char *)p.logits + row * p.row_stride * BYTES;
+
+        // slot i of lane tid holds vector i * BLOCK + tid: consecutive lanes read
+        // consecutive 16-byte pieces; slots past the row hold -inf
+        u32x4 buf[NV];
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const char *slab = zrow + (size_t)i * SLAB;
+            buf[i] = neg_inf_vec<DT>();
+            if (i * BLOCK + tid < nvec_full) buf[i] = *(const u32x4 *)(slab + toff);
+        }
+        u32x4 tbuf = neg_inf_vec<DT>();
+        if (tail_wave && tid == 0) tbuf = load_vec<DT>(zrow, nvec_full, nvec_full, tail);
+        const float zy = load_elem<DT>(zrow, y);
+        const int vy = (int)(y / EPV);
+        const int ey = (int)(y % EPV);
+
+        // The sampled token's logit is taken out of the resident row (replaced by -inf):
+        // the sum below is then s_excl = sum_{j != y}, which keeps 1 - p_y = s_excl / s
+        // accurate on near-one-hot rows where it would cancel to 0 in fp32.  One lane
+        // of one wavefront does this once per row.
+        if (tid == (vy & (BLOCK - 1)) && vy < nvec_full) {
+#pragma unroll
+            for (int i = 0; i < NV; ++i)
+                if (i == vy / BLOCK) set_neg_inf<DT>(buf[i], ey);
+        }
+        if (tail_wave && tid == 0 && vy == nvec_full) set_neg_inf<DT>(tbuf, ey);
+
+        // row maximum (over j != y, then joined with z_y)
+        float mx = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            float f[EPV];
+            forget(buf[i]);
+            unpack<DT>(buf[i], f);
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) mx = fmaxf(mx, f[e]);
+            VECTOR_FENCE();
+        }
+        if (tail_wave) {
+            float f[EPV];
+            unpack<DT>(tbuf, f);
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) mx = fmaxf(mx, f[e]);
+        }
+        mx = fmaxf(block_max<BLOCK>(mx, lds_max), zy);
+        const float mk = mx * p.k;
+
+        // sum of exponentials over j != y
+        float acc = 0.f;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            forget(buf[i]);
+            acc += exp_sum_vec<DT>(buf[i], p.k, mk);
+            VECTOR_FENCE();
+        }
+        if (tail_wave) acc += exp_sum_vec<DT>(tbuf, p.k, mk);
+        const float s_excl = block_sum<BLOCK>(acc, lds_sum);
+
+        const RowScalars sc = row_scalars(p, row, zy, mk, s_excl);
+        if (tid == 0) write_row_outputs(p, row, sc.logp, sc.J, sc.flags);
+        if (!p.bwd) continue;
+
+        char *grow = (char *)p.grad + row * p.row_stride * BYTES;
+        if (sc.c == 0.f) {
+            zero_row<DT, BLOCK>(grow, nvec_full, tail, tid);
+            continue;
+        }
+        const float q = -sc.c * p.inv_T;
+        const float gy = (sc.c * p.inv_T) * (sc.s_excl / sc.s);
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int v = i * BLOCK + tid;
+            char *slab = grow + (size_t)i * SLAB;
+            float g[EPV];
+            forget(buf[i]);
+            grad_vec<DT>(buf[i], p.k, sc.shift, q, v == vy, ey, gy, g);
+            if (v < nvec_full) *(u32x4 *)(slab + toff) = pack<DT>(g);
+            VECTOR_FENCE();
+        }
+        if (tail_wave && tid == 0) {
+            float g[EPV];
+            grad_vec<DT>(tbuf, p.k, sc.shift, q, vy == nvec_full, ey, gy, g);
+            store_vec<DT>(grow, nvec_full, nvec_full, tail, g);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Streaming row kernel for rows too wide for the register file: an online
+// (max, sum) pass and a gradient pass, i.e. 2 reads + 1 write.
+// ---------------------------------------------------------------------------
+template <grpo_dtype DT, int BLOCK>
+__global__ void __launch_bounds__(BLOCK) grpo_rows_streamed(RowParams p)
+{
+    constexpr int EPV = Elem<DT>::EPV;
+    constexpr int BYTES = Elem<DT>::BYTES;
+    __shared__ float lds_max[BLOCK / 64];
+    __shared__ float lds_sum[BLOCK / 64];
+    const int tid = threadIdx.x;
+    const int nvec_full = (int)(p.vocab / EPV);
+    const int tail = (int)(p.vocab % EPV);
+    const int nvec = nvec_full + (tail ? 1 : 0);
+
+    for (long long row = blockIdx.x; row < p.n_tokens; row += gridDim.x) {
+        long long y;
+        if (!row_is_live<DT, BLOCK>(p, row, nvec_full, tail, y)) continue;
+        const char *zrow = (const char *)p.logits + row * p.row_stride * BYTES;
+        const float zy = load_elem<DT>(zrow, y);
+        const int vy = (int)(y / EPV);
+        const int ey = (int)(y % EPV);
+
+        // online pass: running maximum m (in logit units) and sum relative to it
+        float m = -INFINITY, s = 0.f;
+        for (int v = tid; v < nvec; v += BLOCK) {
+            const u32x4 z = load_vec<DT>(zrow, v, nvec_full, tail);
+            float f[EPV];
+            unpack<DT>(z, f);
+            float vm = f[0];
+#pragma unroll
+            for (int e = 1; e < EPV; ++e) vm = fmaxf(vm, f[e]);
+            if (vm > m) {
+                s *= __builtin_amdgcn_exp2f((m - vm) * p.k);  // m = -inf: s is 0 and stays 0
+                m = vm;
+            }
+            const float mk_t = m * p.k;
+            float part = 0.f;
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) {
+                float ex = __builtin_amdgcn_exp2f(fmaf(f[e], p.k, -mk_t));
+                if (v == vy && e == ey) ex = 0.f;
+                part += ex;
+            }
+            if (m > -INFINITY) s += part;  // all -inf so far: exponents would be NaN
+        }
+        const float mx = block_max<BLOCK>(m, lds_max);
+        const float mk = mx * p.k;
+        const float scaled = (m > -INFINITY) ? s * __builtin_amdgcn_exp2f((m - mx) * p.k) : 0.f;
+        float s_excl = block_sum<BLOCK>(scaled, lds_sum);
+        if (!(mx > -INFINITY)) s_excl = NAN;  // a row of -inf (or NaN) has no softmax
+
+        const RowScalars sc = row_scalars(p, row, zy, mk, s_excl);
+        if (tid == 0) write_row_outputs(p, row, sc.logp, sc.J, sc.flags);
+        // the LDS arrays are reused by the next row: one barrier separates this row's
+        // reads of lds_sum from the next row's writes of lds_max/lds_sum
+        __syncthreads();
+        if (!p.bwd) continue;
+
+        char *grow = (char *)p.grad + row * p.row_stride * BYTES;
+        if (sc.c == 0.f) {
+            zero_row<DT, BLOCK>(grow, nvec_full, tail, tid);
+            continue;
+        }
+        const float q = -sc.c * p.inv_T;
+        const float gy = (sc.c * p.inv_T) * (sc.s_excl / sc.s);
+        for (int v = tid; v < nvec; v += BLOCK) {
+            const u32x4 z = load_vec<DT>(zrow, v, nvec_full, tail);
+            float g[EPV];
+            grad_vec<DT>(z, p.k, sc.shift, q, v == vy, ey, gy, g);
+            store_vec<DT>(grow, v, nvec_full, tail, g);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Small kernels around the row kernel
+// ---------------------------------------------------------------------------
+
+// Counts the unmasked rows and fixes the denominator before any row is processed.
+__global__ void __launch_bounds__(1024) grpo_prepare(const unsigned char *mask, long long n,
+                                                     double denom, WsHeader *hdr)
+{
+    __shared__ long long lds[16];
+    long long cnt = 0;
+    if (mask) {
+        for (long long i = threadIdx.x; i < n; i += 1024) cnt += mask[i] ? 1 : 0;
+    }
+    cnt = wave_sum(cnt);
+    if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = cnt;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        long long M = 0;
+        for (int i = 0; i < 16; ++i) M += lds[i];
+        if (!mask) M = n;
+        const double D = denom > 0.0 ? denom : (double)M;
+        hdr->D = D;
+        hdr->inv_D = D > 0.0 ? 1.0 / D : 0.0;
+        hdr->M = M;
+        hdr->error = 0;
+        hdr->pad = 0;
+    }
+}
+
+// loss = -(1/D) sum_t J_t in fp64 and a fixed order; indicator counts.
+__global__ void __launch_bounds__(1024) grpo_finalize(const float *J_ws, const unsigned char *flags_ws,
+                                                      long long n, const WsHeader *hdr,
+                                                      float *loss_out, long long *counts_out)
+{
+    __shared__ double lds_j[16];
+    __shared__ long long lds_c[16][4];
+    double sj = 0.0;
+    long long c[4] = {0, 0, 0, 0};
+    for (long long i = threadIdx.x; i < n; i += 1024) {
+        sj += (double)J_ws[i];
+        const int fl = flags_ws[i];
+        c[0] += (fl & kFlagClipHigh) ? 1 : 0;
+        c[1] += (fl & kFlagClipLow) ? 1 : 0;
+        c[2] += (fl & kFlagDelta) ? 1 : 0;
+        c[3] += (fl & kFlagOutOfBand) ? 1 : 0;
+    }
+    sj = wave_sum(sj);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) c[q] = wave_sum(c[q]);
+    if ((threadIdx.x & 63) == 0) {
+        lds_j[threadIdx.x >> 6] = sj;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) lds_c[threadIdx.x >> 6][q] = c[q];
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double tot = 0.0;
+        long long t[4] = {0, 0, 0, 0};
+        for (int w = 0; w < 16; ++w) {
+            tot += lds_j[w];
+            for (int q = 0; q < 4; ++q) t[q] += lds_c[w][q];
+        }
+        *loss_out = (float)(0.0 - tot * hdr->inv_D);
+        if (counts_out) {
+            counts_out[GRPO_COUNT_TOKENS] = hdr->M;
+            counts_out[GRPO_COUNT_CLIP_HIGH] = t[0];
+            counts_out[GRPO_COUNT_CLIP_LOW] = t[1];
+            counts_out[GRPO_COUNT_DELTA] = t[2];
+            counts_out[GRPO_COUNT_OUT_OF_BAND] = t[3];
+        }
+    }
+}
+
+// One wavefront per group: mean, then spread around the mean, both in fp64.
+__global__ void __launch_bounds__(64) grpo_group_adv(const float *rewards, long long n_rollouts,
+                                                     const int *offsets, long long n_groups,
+                                                     long long group_size, double eps_std, int ddof,
+                                                     float *adv_out)
+{
+    const int lane = threadIdx.x;
+    for (long long g = blockIdx.x; g < n_groups; g += gridDim.x) {
+        long long b = offsets ? (long long)offsets[g] : g * group_size;
+        long long e = offsets ? (long long)offsets[g + 1] : (g + 1) * group_size;
+        b = b < 0 ? 0 : (b > n_rollouts ? n_rollouts : b);
+        e = e < b ? b : (e > n_rollouts ? n_rollouts : e);
+        const long long G = e - b;
+        if (G == 0) continue;
+        double sum = 0.0;
+        for (long long i = b + lane; i < e; i += 64) sum += (double)rewards[i];
+        const double mu = wave_sum(sum) / (double)G;
+        double ss = 0.0;
+        for (long long i = b + lane; i < e; i += 64) {
+            const double d = (double)rewards[i] - mu;
+            ss += d * d;
+        }
+        ss = wave_sum(ss);
+        const double sigma = (G - ddof > 0) ? sqrt(ss / (double)(G - ddof)) : 0.0;
+        const double den = sigma + eps_std;
+        for (long long i = b + lane; i < e; i += 64)
+            adv_out[i] = den > 0.0 ? (float)(((double)rewards[i] - mu) / den) : 0.f;
+    }
+}
+
+__global__ void __launch_bounds__(256) grpo_adv_to_tokens(const float *adv, long long n_rollouts,
+                                                          const int *rollout_of_token,
+                                                          long long n_tokens, float *adv_tok)
+{
+    for (long long t = (long long)blockIdx.x * 256 + threadIdx.x; t < n_tokens;
+         t += (long long)gridDim.x * 256) {
+        const int r = rollout_of_token[t];
+        adv_tok[t] = (r >= 0 && r < n_rollouts) ? adv[r] : NAN;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Host side
+// ---------------------------------------------------------------------------
+
+int cu_count()
+{
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
+template <grpo_dtype DT, int BLOCK, int NV>
+void launch_cached(const RowParams &p, int blocks_per_cu, hipStream_t st)
+{
+    long long grid = (long long)cu_count() * blocks_per_cu;
+    if (grid > p.n_tokens) grid = p.n_tokens;
+    hipLaunchKernelGGL((grpo_rows_cached<DT, BLOCK, NV>), dim3((unsigned)grid), dim3(BLOCK), 0, st, p);
+}
+
+template <grpo_dtype DT>
+void launch_rows(const RowParams &p, hipStream_t st)
+{
+    const long long nvec = (p.vocab + Elem<DT>::EPV - 1) / Elem<DT>::EPV;
+    if (nvec <= 256 * 1)
+        launch_cached<DT, 256, 1>(p, 8, st);
+    else if (nvec <= 256 * 4)
+        launch_cached<DT, 256, 4>(p, 8, st);
+    else if (nvec <= 1024 * 4)
+        launch_cached<DT, 1024, 4>(p, 2, st);
+    else if (nvec <= 1024 * 10)
+        launch_cached<DT, 1024, 10>(p, 1, st);
+    else if (nvec <= 1024 * 19)
+        launch_cached<DT, 1024, 19>(p, 1, st);
+    else {
+        long long grid = (long long)cu_count() * 2;
+        if (grid > p.n_tokens) grid = p.n_tokens;
+        hipLaunchKernelGGL((grpo_rows_streamed<DT, 1024>), dim3((unsigned)grid), dim3(1024), 0, st, p);
+    }
+}
+
+grpo_status check_logits_args(const void *logits, grpo_dtype dtype, int64_t n_tokens, int64_t vocab,
+                              int64_t row_stride, const int64_t *tokens, float temperature)
+{
+    if (dtype != GRPO_F32 && dtype != GRPO_BF16) return GRPO_ERR_DTYPE;
+    if (n_tokens < 0 || vocab <= 0 || vocab > kMaxVocab || row_stride < vocab) return GRPO_ERR_SHAPE;
+    if (!(temperature > 0.f) || !std::isfinite(temperature)) return GRPO_ERR_PARAM;
+    if (n_tokens == 0) return GRPO_OK;
+    if (!logits || !tokens) return GRPO_ERR_NULL;
+    const int64_t bytes = dtype == GRPO_BF16 ? 2 : 4;
+    if (((uintptr_t)logits & 15u) != 0 || ((row_stride * bytes) & 15) != 0) return GRPO_ERR_ALIGN;
+    return GRPO_OK;
+}
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+}  // namespace
+
+extern "C" {
+
+const char *grpo_status_string(grpo_status status)
+{
+    switch (status) {
+        case GRPO_OK: return "ok";
+        case GRPO_ERR_NULL: return "a required pointer is NULL";
+        case GRPO_ERR_SHAPE: return "bad shape: negative size, vocab outside [1, 2^28] or row_stride < vocab";
+        case GRPO_ERR_DTYPE: return "unknown dtype";
+        case GRPO_ERR_ALIGN: return "logits/grad base pointer or row pitch is not 16-byte aligned";
+        case GRPO_ERR_PARAM:
+            return "bad parameter: need temperature > 0, 0 <= eps_low <= 1, eps_high >= 0, "
+                   "delta > 1 + eps_high, eps_std >= 0, ddof in {0,1}";
+        case GRPO_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned or too small";
+        case GRPO_ERR_HIP: return "HIP runtime error at kernel launch";
+    }
+    return "unknown status";
+}
+
+size_t grpo_workspace_bytes(int64_t n_tokens)
+{
+    if (n_tokens < 0) return 0;
+    // header | J per row (f32) | indicator bits per row (u8)
+    return kHeaderBytes + align_up((size_t)n_tokens * 4, 256) + align_up((size_t)n_tokens, 256);
+}
+
+grpo_status grpo_group_advantages(const float *rewards, int64_t n_rollouts,
+                                  const int32_t *group_offsets, int64_t n_groups,
+                                  int64_t group_size, float eps_std, int ddof, float *adv_out,
+                                  const int32_t *rollout_of_token, int64_t n_tokens,
+                                  float *adv_tok_out, void *stream)
+{
+    if (n_rollouts < 0 || n_groups < 0 || n_tokens < 0) return GRPO_ERR_SHAPE;
+    if (!group_offsets && (group_size <= 0 || n_groups * group_size != n_rollouts) && n_groups > 0)
+        return GRPO_ERR_SHAPE;
+    if (!(eps_std >= 0.f) || !std::isfinite(eps_std) || (ddof != 0 && ddof != 1)) return GRPO_ERR_PARAM;
+    if (n_groups > 0 && n_rollouts > 0 && (!rewards || !adv_out)) return GRPO_ERR_NULL;
+    if (rollout_of_token && n_tokens > 0 && (!adv_tok_out || !adv_out)) return GRPO_ERR_NULL;
+    hipStream_t st = (hipStream_t)stream;
+    const bool any_work = (n_groups > 0 && n_rollouts > 0) || (rollout_of_token && n_tokens > 0);
+    if (!any_work) return GRPO_OK;
+    if (n_groups > 0 && n_rollouts > 0) {
+        const unsigned grid = (unsigned)(n_groups < 4096 ? n_groups : 4096);
+        hipLaunchKernelGGL(grpo_group_adv, dim3(grid), dim3(64), 0, st, rewards, (long long)n_rollouts,
+                           group_offsets, (long long)n_groups, (long long)group_size, (double)eps_std,
+                           ddof, adv_out);
+    }
+    if (rollout_of_token && n_tokens > 0) {
+        long long blocks = (n_tokens + 255) / 256;
+        if (blocks > 4096) blocks = 4096;
+        hipLaunchKernelGGL(grpo_adv_to_tokens, dim3((unsigned)blocks), dim3(256), 0, st, adv_out,
+                           (long long)n_rollouts, rollout_of_token, (long long)n_tokens, adv_tok_out);
+    }
+    return hipGetLastError() == hipSuccess ? GRPO_OK : GRPO_ERR_HIP;
+}
+
+grpo_status grpo_logprobs_fwd(const void *logits, grpo_dtype dtype, int64_t n_tokens, int64_t vocab,
+                              int64_t row_stride, const int64_t *tokens, const uint8_t *mask,
+                              float temperature, float *logprobs_out, void *stream)
+{
+    grpo_status rc = check_logits_args(logits, dtype, n_tokens, vocab, row_stride, tokens, temperature);
+    if (rc != GRPO_OK) return rc;
+    if (n_tokens == 0) return GRPO_OK;
+    if (!logprobs_out) return GRPO_ERR_NULL;
+    RowParams p = {};
+    p.logits = logits;
+    p.tokens = (const long long *)tokens;
+    p.mask = mask;
+    p.logprobs_out = logprobs_out;
+    p.n_tokens = n_tokens;
+    p.vocab = vocab;
+    p.row_stride = row_stride;
+    p.inv_T = 1.0f / temperature;
+    p.k = (float)((double)kLog2e / (double)temperature);
+    p.bwd = 0;
+    hipStream_t st = (hipStream_t)stream;
+    if (dtype == GRPO_BF16)
+        launch_rows<GRPO_BF16>(p, st);
+    else
+        launch_rows<GRPO_F32>(p, st);
+    return hipGetLastError() == hipSuccess ? GRPO_OK : GRPO_ERR_HIP;
+}
+
+grpo_status grpo_loss_fwd_bwd(const void *logits, grpo_dtype dtype, int64_t n_tokens, int64_t vocab,
+                              int64_t row_stride, const int64_t *tokens, const float *old_logprobs,
+                              const float *advantages, const uint8_t *mask, float eps_low,
+                              float eps_high, float delta, float temperature, double denom,
+                              float grad_scale, float *loss_out, float *logprobs_out,
+                              int64_t *counts_out, void *grad_logits, void *workspace,
+                              size_t workspace_bytes, void *stream)
+{
+    grpo_status rc = check_logits_args(logits, dtype, n_tokens, vocab, row_stride, tokens, temperature);
+    if (rc != GRPO_OK) return rc;
+    if (!(eps_low >= 0.f && eps_low <= 1.f) || !(eps_high >= 0.f) || !std::isfinite(eps_high) ||
+        !(delta > 1.f + eps_high) || std::isnan(denom) || std::isnan(grad_scale))
+        return GRPO_ERR_PARAM;
+    if (!loss_out) return GRPO_ERR_NULL;
+    if (n_tokens > 0 && (!old_logprobs || !advantages || !grad_logits)) return GRPO_ERR_NULL;
+    if (n_tokens > 0 && ((uintptr_t)grad_logits & 15u) != 0) return GRPO_ERR_ALIGN;
+    if (!workspace || ((uintptr_t)workspace & 255u) != 0 ||
+        workspace_bytes < grpo_workspace_bytes(n_tokens))
+        return GRPO_ERR_WORKSPACE;
+
+    char *ws = (char *)workspace;
+    WsHeader *hdr = (WsHeader *)ws;
+    float *J_ws = (float *)(ws + kHeaderBytes);
+    unsigned char *flags_ws =
+        (unsigned char *)(ws + kHeaderBytes + align_up((size_t)n_tokens * 4, 256));
+    hipStream_t st = (hipStream_t)stream;
+
+    hipLaunchKernelGGL(grpo_prepare, dim3(1), dim3(1024), 0, st, mask, (long long)n_tokens, denom, hdr);
+    if (n_tokens > 0) {
+        RowParams p = {};
+        p.logits = logits;
+        p.grad = grad_logits;
+        p.tokens = (const long long *)tokens;
+        p.old_lp = old_logprobs;
+        p.adv = advantages;
+        p.mask = mask;
+        p.logprobs_out = logprobs_out;
+        p.J_ws = J_ws;
+        p.flags_ws = flags_ws;
+        p.hdr = hdr;
+        p.n_tokens = n_tokens;
+        p.vocab = vocab;
+        p.row_stride = row_stride;
+        p.inv_T = 1.0f / temperature;
+        p.k = (float)((double)kLog2e / (double)temperature);
+        p.lo = 1.0f - eps_low;
+        p.hi = 1.0f + eps_high;
+        p.delta = delta;
+        p.grad_scale = grad_scale;
+        p.bwd = 1;
+        if (dtype == GRPO_BF16)
+            launch_rows<GRPO_BF16>(p, st);
+        else
+            launch_rows<GRPO_F32>(p, st);
+    }
+    hipLaunchKernelGGL(grpo_finalize, dim3(1), dim3(1024), 0, st, J_ws, flags_ws, (long long)n_tokens,
+                       hdr, loss_out, (long long *)counts_out);
+    return hipGetLastError() == hipSuccess ? GRPO_OK : GRPO_ERR_HIP;
+}
+
+grpo_status grpo_workspace_error(const void *workspace, int32_t *flag_out, void *stream)
+{
+    if (!workspace || !flag_out) return GRPO_ERR_NULL;
+    const WsHeader *hdr = (const WsHeader *)workspace;
+    int v = 0;
+    if (hipMemcpyAsync(&v, &hdr->error, sizeof(int), hipMemcpyDeviceToHost, (hipStream_t)stream) != hipSuccess)
+        return GRPO_ERR_HIP;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return GRPO_ERR_HIP;
+    *flag_out = v;
+    return GRPO_OK;
+}
+
+}  // extern "C"

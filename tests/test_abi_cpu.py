@@ -1,0 +1,101 @@
+"""The C-ABI library without a GPU: it loads, exports every declared symbol, and turns
+every bad argument into its status code before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2505_07291_amd as grpo
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+OK, NULL, SHAPE, DTYPE, ALIGN, PARAM, WORKSPACE, HIP = range(8)
+P = 0x7F0000001000  # a fake, 256-byte aligned, non-null "device pointer": validation never dereferences
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "grpo.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(grpo_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert {"grpo_group_advantages", "grpo_logprobs_fwd", "grpo_loss_fwd_bwd",
+            "grpo_workspace_bytes", "grpo_status_string", "grpo_workspace_error"} <= set(names)
+    L = grpo.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_status_strings_and_workspace_size():
+    for code in range(8):
+        assert len(grpo.status_string(code)) > 1
+    assert grpo.status_string(99) == "unknown status"
+    assert grpo.grpo_workspace_bytes(-1) == 0
+    assert grpo.grpo_workspace_bytes(0) == 256
+    for n in (1, 255, 256, 257, 131072):
+        b = grpo.grpo_workspace_bytes(n)
+        assert b % 256 == 0 and b >= 256 + 5 * n
+
+
+def loss_args(**over):
+    a = dict(logits=P, dtype=1, n=16, V=1024, stride=1024, tokens=P, old=P, adv=P, mask=P,
+             el=0.2, eh=0.2, delta=4.0, T=1.0, denom=0.0, gs=1.0, loss=P, lp=P, counts=P, grad=P,
+             ws=P, ws_bytes=1 << 20, stream=None)
+    a.update(over)
+    return [a[k] for k in ("logits", "dtype", "n", "V", "stride", "tokens", "old", "adv", "mask",
+                           "el", "eh", "delta", "T", "denom", "gs", "loss", "lp", "counts", "grad",
+                           "ws", "ws_bytes", "stream")]
+
+
+@pytest.mark.parametrize("over,expect", [
+    (dict(logits=None), NULL), (dict(tokens=None), NULL), (dict(old=None), NULL),
+    (dict(adv=None), NULL), (dict(loss=None), NULL), (dict(grad=None), NULL),
+    (dict(n=-1), SHAPE), (dict(V=0), SHAPE), (dict(stride=1000), SHAPE), (dict(V=(1 << 28) + 8, stride=(1 << 28) + 8), SHAPE),
+    (dict(dtype=2), DTYPE), (dict(dtype=-1), DTYPE),
+    (dict(logits=P + 8), ALIGN), (dict(grad=P + 2), ALIGN), (dict(V=1001, stride=1001), ALIGN),
+    (dict(dtype=0, V=1001, stride=1002), ALIGN),
+    (dict(T=0.0), PARAM), (dict(T=-1.0), PARAM), (dict(T=float("nan")), PARAM),
+    (dict(el=-0.1), PARAM), (dict(el=1.5), PARAM), (dict(eh=-0.2), PARAM),
+    (dict(delta=1.2), PARAM), (dict(delta=1.0), PARAM), (dict(delta=float("nan")), PARAM),
+    (dict(eh=float("inf")), PARAM), (dict(denom=float("nan")), PARAM),
+    (dict(ws=None), WORKSPACE), (dict(ws=P + 64), WORKSPACE), (dict(ws_bytes=100), WORKSPACE),
+])
+def test_loss_fwd_bwd_rejects_bad_arguments_before_any_launch(over, expect):
+    assert grpo.lib().grpo_loss_fwd_bwd(*loss_args(**over)) == expect
+
+
+def test_logprobs_and_advantages_reject_bad_arguments():
+    L = grpo.lib()
+    f = L.grpo_logprobs_fwd
+    assert f(None, 1, 4, 64, 64, P, None, 1.0, P, None) == NULL
+    assert f(P, 1, 4, 64, 64, None, None, 1.0, P, None) == NULL
+    assert f(P, 1, 4, 64, 64, P, None, 1.0, None, None) == NULL
+    assert f(P, 1, 4, 64, 60, P, None, 1.0, P, None) == SHAPE
+    assert f(P, 3, 4, 64, 64, P, None, 1.0, P, None) == DTYPE
+    assert f(P + 4, 1, 4, 64, 64, P, None, 1.0, P, None) == ALIGN
+    assert f(P, 1, 4, 63, 63, P, None, 1.0, P, None) == ALIGN     # 126-byte row pitch
+    assert f(P, 1, 4, 64, 64, P, None, 0.0, P, None) == PARAM
+    assert f(P, 1, 0, 64, 64, None, None, 1.0, None, None) == OK   # nothing to do
+    g = L.grpo_group_advantages
+    assert g(None, 8, None, 2, 4, 1e-6, 0, P, None, 0, None, None) == NULL
+    assert g(P, 8, None, 2, 4, 1e-6, 0, None, None, 0, None, None) == NULL
+    assert g(P, 8, None, 2, 3, 1e-6, 0, P, None, 0, None, None) == SHAPE   # 2*3 != 8
+    assert g(P, 8, None, 2, 0, 1e-6, 0, P, None, 0, None, None) == SHAPE
+    assert g(P, -1, None, 2, 4, 1e-6, 0, P, None, 0, None, None) == SHAPE
+    assert g(P, 8, None, 2, 4, -1.0, 0, P, None, 0, None, None) == PARAM
+    assert g(P, 8, None, 2, 4, 1e-6, 2, P, None, 0, None, None) == PARAM
+    assert g(P, 8, None, 2, 4, 1e-6, 0, P, P, 10, None, None) == NULL       # adv_tok_out missing
+    assert g(P, 0, None, 0, 4, 1e-6, 0, None, None, 0, None, None) == OK    # nothing to do
+    e = L.grpo_workspace_error
+    flag = ctypes.c_int32(7)
+    assert e(None, ctypes.byref(flag), None) == NULL
+    assert e(P, None, None) == NULL
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    z = torch.zeros(4, 64)
+    with pytest.raises(ValueError):
+        grpo.grpo_logprobs_fwd(z, torch.zeros(4, dtype=torch.int64))

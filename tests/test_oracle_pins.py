@@ -487,3 +487,24 @@ def test_advantages_ragged_groups_and_broadcast():
         orc.group_advantages(R, group_offsets=np.array([0, 40], np.int32))
     rot = rng.integers(0, len(R), 200).astype(np.int32)
     assert np.array_equal(orc.broadcast_advantages(adv, rot), adv[rot])
+
+
+# ----------------------------------------------------------------------------
+# the staged entry points are the same computation as the one-call form
+# ----------------------------------------------------------------------------
+
+def test_staged_entry_points_agree_with_one_call_form():
+    rng = np.random.default_rng(81)
+    N, V = 50, 37
+    z, tokens, adv, mask = _tiny_batch(rng, N, V, "bf16")
+    T = 0.7
+    lp = orc.logprobs(z, tokens, mask, temperature=T)
+    old = (lp + rng.uniform(-2, 2, N)).astype(np.float32)
+    kw = dict(eps_low=0.2, eps_high=0.3, delta=4.0, grad_scale=1.5)
+    one = orc.loss_fwd_bwd(z, tokens, old, adv, mask, temperature=T, grad_rows="all", **kw)
+    obj = orc.objective_from_logprobs(lp, old, adv, mask, **kw)
+    assert obj["loss"] == one["loss"] and np.array_equal(obj["counts"], one["counts"])
+    assert np.array_equal(obj["coeff"], one["coeff"]) and np.array_equal(obj["J"], one["J"])
+    pick = np.array([3, 0, 17, 49])
+    g = orc.grad_rows(z[pick], tokens[pick], obj["coeff"][pick], temperature=T)
+    assert np.array_equal(g, one["grad"][pick])
