@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Benchmark of the GRPO-loss hot path on one MI355X.
+
+One "step" is the whole hot path over one synthetic batch that is already resident
+in HBM: group advantages (+ broadcast to tokens), then the objective forward and the
+fused backward over the full vocabulary (grpo_group_advantages + grpo_loss_fwd_bwd).
+Prints ONE JSON line: whole-job tokens/s, the HBM roofline of the dominant (row)
+kernel measured with events on the launch stream, and the fp64 CPU oracle timed on a
+bounded sample of the same batch as a reported baseline.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak, 8 TB/s
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def traffic_from_profiles(workload):
+    """Measured HBM bytes per row-kernel launch, if a counter summary was committed for
+    this workload (profiles/hbm_traffic_<workload>.txt, line 'traffic_bytes_per_launch = N')."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % workload)
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(batch, old, adv_tok, budget_s=12.0, max_rows=32768, block=512):
+    """fp64 oracle, forward + backward, on the first rows of the same batch until the time
+    budget is used; returns tokens/s of that sample."""
+    import numpy as np
+    import torch
+    from oracle import grpo_oracle as orc
+    cfg = batch["cfg"]
+    done, t_used = 0, 0.0
+    tokens = batch["tokens"].cpu().numpy()
+    mask = batch["mask"].cpu().numpy()
+    oldn, advn = old.cpu().numpy(), adv_tok.cpu().numpy()
+    while done < min(max_rows, batch["n_tokens"]) and t_used < budget_s:
+        r0, r1 = done, min(done + block, batch["n_tokens"], max_rows)
+        z = batch["logits"][r0:r1].cpu()
+        z = z.view(torch.int16).numpy().view(np.uint16) if z.dtype == torch.bfloat16 else z.numpy()
+        t0 = time.perf_counter()
+        orc.loss_fwd_bwd(z, tokens[r0:r1], oldn[r0:r1], advn[r0:r1], mask[r0:r1],
+                         eps_low=cfg.eps_low, eps_high=cfg.eps_high, delta=cfg.delta,
+                         temperature=cfg.temperature, grad_rows="all")
+        t_used += time.perf_counter() - t0
+        done = r1
+    return dict(value=done / t_used, unit="tokens/s", cores=orc.num_threads(), kind="oracle",
+                sample="first %d rows of the batch (%d unmasked), fp64 forward+backward, %.1f s"
+                       % (done, int(mask[:done].sum()), t_used))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="qwen_short")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run plain 1 GiB device copies (reference for HBM counters)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (rows are independent; a multi-GPU run "
+              "would be this same kernel per rank plus a 40-byte all-reduce); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2505_07291_amd as grpo
+    from paper_2505_07291_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+    cfg = wl.CONFIGS[args.workload]
+    N, V = cfg.n_tokens, cfg.vocab
+    log("[bench] generating %s: N=%d V=%d %s (%.2f GB of logits)" %
+        (cfg.name, N, V, cfg.dtype, N * V * (2 if cfg.dtype == "bf16" else 4) / 1e9))
+    batch = wl.make_batch(cfg, dev)
+    esz = batch["logits"].element_size()
+    # old-policy log-probs: the library's own forward pass plus the recipe's staleness noise
+    new_lp = grpo.grpo_logprobs_fwd(batch["logits"], batch["tokens"], batch["mask"], cfg.temperature)
+    torch.cuda.synchronize()
+    old = wl.make_old_logprobs(cfg, new_lp).to(dev)
+
+    adv = torch.empty(cfg.n_rollouts, dtype=torch.float32, device=dev)
+    adv_tok = torch.empty(N, dtype=torch.float32, device=dev)
+    grad = torch.empty_like(batch["logits"])
+    loss = torch.empty(1, dtype=torch.float32, device=dev)
+    lp = torch.empty(N, dtype=torch.float32, device=dev)
+    counts = torch.empty(5, dtype=torch.int64, device=dev)
+    ws = torch.empty(grpo.grpo_workspace_bytes(N), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step(ev=None, mask=batch["mask"], oldlp=old, advantages=None):
+        a_tok = adv_tok
+        if advantages is None:
+            grpo.grpo_group_advantages(batch["rewards"], group_size=cfg.group_size, eps_std=1e-6,
+                                       ddof=0, rollout_of_token=batch["rollout_of_token"],
+                                       adv_out=adv, adv_tok_out=adv_tok, stream=stream)
+        else:
+            a_tok = advantages
+        if ev:
+            ev[0].record(stream)
+        grpo.grpo_loss_fwd_bwd(batch["logits"], batch["tokens"], oldlp, a_tok, mask,
+                               cfg.eps_low, cfg.eps_high, cfg.delta, cfg.temperature, 0.0, 1.0,
+                               grad_logits=grad, loss_out=loss, logprobs_out=lp,
+                               counts_out=counts, workspace=ws, stream=stream)
+        if ev:
+            ev[1].record(stream)
+
+    def timed(K, W, **kw):
+        for _ in range(W):
+            step(**kw)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in range(K)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(K):
+            step(ev=evs[i], **kw)
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) / K
+        kern = sum(a.elapsed_time(b) for a, b in evs) / K * 1e-3
+        return wall, kern
+
+    log("[bench] timing %d steps after %d warm-up steps" % (args.steps, args.warmup))
+    wall, kern = timed(args.steps, args.warmup)
+    assert grpo.grpo_workspace_error(ws) == 0
+    c = counts.cpu().tolist()
+    M = c[0]
+    zero_adv = int(((adv_tok == 0) & (batch["mask"] != 0)).sum())
+    n_zero_coeff = c[1] + c[2] + c[3] + zero_adv
+    n_full, n_masked = M - n_zero_coeff, N - M
+    row_bytes = V * esz
+    # algorithmic bytes by row class: live rows 2 reads + 1 write, rows whose gradient is
+    # cut 1 read + 1 zero-fill, masked rows 1 zero-fill; plus 29 B of per-token scalars
+    alg_bytes = row_bytes * (3 * n_full + 2 * n_zero_coeff + 1 * n_masked) + 29 * N
+    conv_bytes = 3 * N * row_bytes
+    # what this design has to move through HBM: live rows are read once (kept in registers)
+    design_bytes = row_bytes * (2 * n_full + 2 * n_zero_coeff + 1 * n_masked) + 29 * N
+
+    # worst case for the kernel: every row unmasked and live (ratio 1, non-zero advantage)
+    ones = torch.ones(N, dtype=torch.uint8, device=dev)
+    adv_ones = torch.full((N,), 0.5, dtype=torch.float32, device=dev)
+    wall_full, kern_full = timed(max(5, args.steps // 3), 2, mask=ones, oldlp=new_lp, advantages=adv_ones)
+    full_counts = counts.cpu().tolist()
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
+    out = {
+        "metric": "GRPO loss fwd+bwd tokens/s (V=152064 bf16)" if V == 152064 else "GRPO loss fwd+bwd tokens/s",
+        "value": N / wall, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": wall * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": cfg.name, "n_tokens": N, "vocab": V, "logits_dtype": cfg.dtype,
+                   "group_size": cfg.group_size, "n_rollouts": cfg.n_rollouts,
+                   "rows_live": n_full, "rows_zero_coeff": n_zero_coeff, "rows_masked": n_masked,
+                   "eps_low": cfg.eps_low, "eps_high": cfg.eps_high, "delta": cfg.delta,
+                   "temperature": cfg.temperature},
+        "counts": dict(zip(grpo.COUNT_NAMES, c)), "loss": float(loss.cpu()),
+        "roofline": {"bound": "hbm", "achieved": alg_bytes / kern / 1e9, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": alg_bytes / kern / 1e9 / HBM_PEAK_GBPS,
+                     "traffic": traffic_from_profiles(cfg.name),
+                     "kernel": "grpo_rows_cached (inside grpo_loss_fwd_bwd)",
+                     "kernel_ms": kern * 1e3, "algorithmic_bytes": alg_bytes,
+                     "gbps_2r1w_all_rows_convention": conv_bytes / kern / 1e9,
+                     "gbps_design_traffic_1r1w": design_bytes / kern / 1e9},
+        "full_rows": {"note": "same logits, every row unmasked and live: the kernel's worst case",
+                      "tokens_per_s": N / wall_full, "kernel_ms": kern_full * 1e3,
+                      "gbps_2r1w": conv_bytes / kern_full / 1e9,
+                      "frac_2r1w": conv_bytes / kern_full / 1e9 / HBM_PEAK_GBPS,
+                      "gbps_design_traffic_1r1w": 2 * N * row_bytes / kern_full / 1e9,
+                      "rows_live": full_counts[0]},
+    }
+    if not args.no_cpu_baseline:
+        log("[bench] timing the fp64 oracle on a sample of the batch (about 12 s)")
+        step()
+        torch.cuda.synchronize()
+        out["cpu_baseline"] = cpu_baseline(batch, old, adv_tok)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -346,7 +346,12 @@ def test_full_size_configs(name):
     expect = coeff / T * (-torch.expm1(torch.as_tensor(lp_orc, device=DEV)))
     live = ~zero_rows
     scale = expect[live].abs()
-    assert bool(((g_y[live] - expect[live]).abs() <= TOL_GRAD * scale).all())
-    assert bool(((rowmax[live].double() - scale).abs() <= TOL_GRAD * scale).all())
+    # 1 - p_y is taken from the oracle's l = z_y/T - lse, whose last bit is an ulp of lse
+    # (1.4e-14 below 64); on near-one-hot rows (1 - p_y ~ 1e-10) that is 1e-4 of the value,
+    # more than the 9e-5 the bound leaves beside bf16 rounding (2^-8): allow for it here.
+    # The element-by-element comparison above has no such term.
+    slack = (coeff[live] / T).abs() * 1.5e-14
+    assert bool(((g_y[live] - expect[live]).abs() <= TOL_GRAD * scale + slack).all())
+    assert bool(((rowmax[live].double() - scale).abs() <= TOL_GRAD * scale + slack).all())
     del batch, out, grad
     torch.cuda.empty_cache()
