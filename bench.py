@@ -162,6 +162,19 @@ def main():
     wall_full, kern_full = timed(max(5, args.steps // 3), 2, mask=ones, oldlp=new_lp, advantages=adv_ones)
     full_counts = counts.cpu().tolist()
 
+    # the old-policy log-probs pass (one read of the logits), every row unmasked
+    fwd_ws = torch.empty(256, dtype=torch.uint8, device=dev)
+    fwd_evs = []
+    for i in range(3 + max(5, args.steps // 3)):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        grpo.grpo_logprobs_fwd(batch["logits"], batch["tokens"], ones, cfg.temperature,
+                               logprobs_out=lp, workspace=fwd_ws, stream=stream)
+        b.record(stream)
+        fwd_evs.append((a, b))
+    torch.cuda.synchronize()
+    fwd_ms = sum(a.elapsed_time(b) for a, b in fwd_evs[3:]) / len(fwd_evs[3:])
+
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
@@ -193,6 +206,10 @@ def main():
                       "frac_2r1w": conv_bytes / kern_full / 1e9 / HBM_PEAK_GBPS,
                       "gbps_design_traffic_1r1w": 2 * N * row_bytes / kern_full / 1e9,
                       "rows_live": full_counts[0]},
+        "logprobs_fwd": {"note": "grpo_logprobs_fwd, every row unmasked: one read of the logits",
+                         "tokens_per_s": N / (fwd_ms * 1e-3), "kernel_ms": fwd_ms,
+                         "gbps": N * row_bytes / (fwd_ms * 1e-3) / 1e9,
+                         "frac": N * row_bytes / (fwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS},
     }
     if not args.no_cpu_baseline:
         log("[bench] timing the fp64 oracle on a sample of the batch (about 12 s)")

@@ -28,7 +28,7 @@
  *  - NaN or Inf in the logits of an unmasked row propagate to that row's
  *    outputs and to the loss; they are never hidden.
  *  - Rows are independent; 64-bit indexing throughout (n_tokens * vocab may
- *    exceed 2^31).
+ *    exceed 2^31).  vocab itself must lie in [1, 2^28].
  */
 #ifndef GRPO_H
 #define GRPO_H
@@ -121,13 +121,18 @@ grpo_status grpo_group_advantages(const float *rewards, int64_t n_rollouts,
  *              Rows with mask 0 give logprobs_out = 0 and none of their inputs
  *              (logits, token) is read.
  *  logprobs_out[n_tokens] f32, device, written.
+ *  workspace   device, optional (NULL allowed): at least 256 bytes, 256-byte aligned,
+ *              contents ignored on entry.  With it rows are handed to workgroups
+ *              through a queue, which keeps the GPU evenly loaded when many rows are
+ *              masked; without it rows are assigned in a fixed strided pattern.  The
+ *              results are identical either way.
  * A token id outside [0, vocab) at an unmasked row gives logprobs_out = NaN there.
  * n_tokens == 0 is legal and does nothing.
  */
 grpo_status grpo_logprobs_fwd(const void *logits, grpo_dtype dtype, int64_t n_tokens,
                               int64_t vocab, int64_t row_stride, const int64_t *tokens,
                               const uint8_t *mask, float temperature, float *logprobs_out,
-                              void *stream);
+                              void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Objective forward and fused backward (section 3.4 objective with delta,

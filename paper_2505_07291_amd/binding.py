@@ -43,7 +43,7 @@ def lib():
         L.grpo_group_advantages.restype = i32
         L.grpo_group_advantages.argtypes = [vp, i64, vp, i64, i64, f32, i32, vp, vp, i64, vp, vp]
         L.grpo_logprobs_fwd.restype = i32
-        L.grpo_logprobs_fwd.argtypes = [vp, i32, i64, i64, i64, vp, vp, f32, vp, vp]
+        L.grpo_logprobs_fwd.argtypes = [vp, i32, i64, i64, i64, vp, vp, f32, vp, vp, sz, vp]
         L.grpo_loss_fwd_bwd.restype = i32
         L.grpo_loss_fwd_bwd.argtypes = [vp, i32, i64, i64, i64, vp, vp, vp, vp, f32, f32, f32, f32,
                                         f64, f32, vp, vp, vp, vp, vp, sz, vp]
@@ -125,8 +125,10 @@ def grpo_group_advantages(rewards, group_size=None, group_offsets=None, eps_std=
 
 
 def grpo_logprobs_fwd(logits, tokens, mask=None, temperature=1.0, vocab=None, logprobs_out=None,
-                      stream=None):
-    """log softmax(logits / T)[tokens] per row; see grpo_logprobs_fwd in grpo.h."""
+                      workspace=None, use_queue=True, stream=None):
+    """log softmax(logits / T)[tokens] per row; see grpo_logprobs_fwd in grpo.h.
+    A 256-byte workspace for the row queue is allocated unless one is passed or
+    ``use_queue`` is False."""
     dt, n, v, stride = _logits_args(logits, vocab)
     dev = logits.device
     _check(tokens, torch.int64, n, "tokens", dev)
@@ -134,8 +136,11 @@ def grpo_logprobs_fwd(logits, tokens, mask=None, temperature=1.0, vocab=None, lo
         _check(mask, torch.uint8, n, "mask", dev)
     if logprobs_out is None:
         logprobs_out = torch.empty(n, dtype=torch.float32, device=dev)
+    if workspace is None and use_queue and n > 0:
+        workspace = torch.empty(256, dtype=torch.uint8, device=dev)
     rc = lib().grpo_logprobs_fwd(_ptr(logits), dt, n, v, stride, _ptr(tokens), _ptr(mask),
-                                 float(temperature), _ptr(logprobs_out), _stream(stream))
+                                 float(temperature), _ptr(logprobs_out), _ptr(workspace),
+                                 0 if workspace is None else workspace.numel(), _stream(stream))
     if rc != GRPO_OK:
         raise GrpoError(rc, "grpo_logprobs_fwd")
     return logprobs_out

@@ -36,6 +36,7 @@ struct WsHeader {
     long long M;   // rows with mask != 0
     int error;     // sticky data-error word (bit 0: token id out of range)
     int pad;
+    unsigned long long next_row;  // work queue of the row kernel: next row nobody has taken
 };
 constexpr size_t kHeaderBytes = 256;
 constexpr long long kMaxVocab = 1ll << 28;  // byte offsets inside a row stay below 2^32
@@ -68,6 +69,39 @@ template <>
 struct Elem<GRPO_F32> {
     static constexpr int EPV = 4, BYTES = 4;
 };
+
+// Tunables, with the settings measured best on MI355X (5 GB to 20 GB of logits):
+//  - non-temporal loads and stores for the two row streams: every byte is touched
+//    once, so nothing is gained by keeping it in L2 / Infinity Cache
+//    (log-probs pass 5.5 -> 6.3 TB/s, mixed batches about 4% faster);
+//  - the next row's loads are issued slot by slot behind the gradient stores of the
+//    current row rather than in one burst after them (within noise of each other).
+#ifndef GRPO_BWD_INTERLEAVE
+#define GRPO_BWD_INTERLEAVE 1
+#endif
+#ifndef GRPO_NT_LOAD
+#define GRPO_NT_LOAD 1
+#endif
+#ifndef GRPO_NT_STORE
+#define GRPO_NT_STORE 1
+#endif
+// 16-byte global accesses of the row streams.
+__device__ __forceinline__ u32x4 ld16(const char *p)
+{
+#if GRPO_NT_LOAD
+    return __builtin_nontemporal_load((const u32x4 *)p);
+#else
+    return *(const u32x4 *)p;
+#endif
+}
+__device__ __forceinline__ void st16(char *p, const u32x4 &v)
+{
+#if GRPO_NT_STORE
+    __builtin_nontemporal_store(v, (u32x4 *)p);
+#else
+    *(u32x4 *)p = v;
+#endif
+}
 
 __device__ __forceinline__ float as_f32(unsigned u) { return __builtin_bit_cast(float, u); }
 __device__ __forceinline__ unsigned as_u32(float f) { return __builtin_bit_cast(unsigned, f); }
@@ -143,7 +177,7 @@ template <grpo_dtype DT>
 __device__ __forceinline__ u32x4 load_vec(const char *row, int v, int nvec_full, int tail)
 {
     constexpr int EPV = Elem<DT>::EPV;
-    if (v < nvec_full) return *(const u32x4 *)(row + (unsigned)v * 16u);
+    if (v < nvec_full) return ld16(row + (unsigned)v * 16u);
     u32x4 out = neg_inf_vec<DT>();
     if (v == nvec_full && tail) {
         float f[EPV];
@@ -161,7 +195,7 @@ __device__ __forceinline__ void store_vec(char *row, int v, int nvec_full, int t
 {
     constexpr int EPV = Elem<DT>::EPV;
     if (v < nvec_full) {
-        *(u32x4 *)(row + (unsigned)v * 16u) = pack<DT>(g);
+        st16(row + (unsigned)v * 16u, pack<DT>(g));
     } else if (v == nvec_full && tail) {
 #pragma unroll
         for (int i = 0; i < EPV; ++i)
@@ -173,8 +207,20 @@ template <grpo_dtype DT, int BLOCK>
 __device__ __forceinline__ void zero_row(char *row, int nvec_full, int tail, int tid)
 {
     const u32x4 z = {0u, 0u, 0u, 0u};
-    for (int v = tid; v < nvec_full; v += BLOCK) *(u32x4 *)(row + (unsigned)v * 16u) = z;
+    for (int v = tid; v < nvec_full; v += BLOCK) st16(row + (unsigned)v * 16u, z);
     if (tail && tid < tail) store_elem<DT>(row, (long long)nvec_full * Elem<DT>::EPV + tid, 0.f);
+}
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
+// outstanding global load and store of the wavefront, which would drain the gradient
+// stores of the previous row and the prefetch of the next one at each of the three
+// barriers a row needs.  Nothing in the row kernels passes data between lanes through
+// global memory, so LDS ordering is all the barrier has to provide.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
 // ---- reductions: butterflies inside the 64-lane wavefront, LDS across waves,
@@ -213,7 +259,7 @@ __device__ __forceinline__ float block_max(float v, float *lds)
     v = wave_max(v);
     if constexpr (NW == 1) return v;
     if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = v;
-    __syncthreads();
+    lds_barrier();
     float r = lds[0];
 #pragma unroll
     for (int i = 1; i < NW; ++i) r = fmaxf(r, lds[i]);
@@ -226,7 +272,7 @@ __device__ __forceinline__ float block_sum(float v, float *lds)
     v = wave_sum(v);
     if constexpr (NW == 1) return v;
     if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = v;
-    __syncthreads();
+    lds_barrier();
     float r = lds[0];
 #pragma unroll
     for (int i = 1; i < NW; ++i) r += lds[i];
@@ -303,6 +349,25 @@ __device__ __forceinline__ void set_neg_inf(u32x4 &v, int e)
     }
 }
 
+// A reference maximum of one vector for the softmax shift.  For bf16 the upper
+// element of each 32-bit word is compared as the raw word, i.e. with the lower
+// element's bits as extra mantissa: that moves it by less than one bf16 ulp, which is
+// immaterial for a shift (any value near the maximum does) and saves the masking.
+// A raw word whose upper half is +-inf reads as NaN and is skipped by fmaxf.
+template <grpo_dtype DT>
+__device__ __forceinline__ float vec_max_ref(const u32x4 &z)
+{
+    float m;
+    if constexpr (DT == GRPO_BF16) {
+        m = fmaxf(as_f32(z[0]), as_f32(z[0] << 16));
+#pragma unroll
+        for (int d = 1; d < 4; ++d) m = fmaxf(m, fmaxf(as_f32(z[d]), as_f32(z[d] << 16)));
+    } else {
+        m = fmaxf(fmaxf(as_f32(z[0]), as_f32(z[1])), fmaxf(as_f32(z[2]), as_f32(z[3])));
+    }
+    return m;
+}
+
 // sum_e exp2(z_e k - mk) over one vector.
 template <grpo_dtype DT>
 __device__ __forceinline__ float exp_sum_vec(const u32x4 &z, float k, float mk)
@@ -377,6 +442,26 @@ __device__ __forceinline__ bool row_is_live(const RowParams &p, long long row, i
 // for the temporaries of one vector at a time, not of several.
 #define VECTOR_FENCE() __builtin_amdgcn_sched_barrier(0)
 
+// A value every lane holds alike, moved to scalar registers: what is derived from it
+// (row base addresses, loop conditions) then stays scalar too.
+__device__ __forceinline__ long long uniform(long long v)
+{
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)(unsigned long long)v);
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)((unsigned long long)v >> 32));
+    return (long long)(((unsigned long long)hi << 32) | lo);
+}
+
+// Pins program order: whatever is computed from `off` afterwards (the address of the
+// next row's load into a slot) cannot be moved above the point where `x` (the last
+// value computed from the slot's current contents) exists.  Otherwise the compiler
+// starts those loads early into fresh registers and the row no longer fits.  Emits no
+// instruction.
+template <typename X>
+__device__ __forceinline__ void order_after(unsigned &off, X &x)
+{
+    asm volatile("" : "+v"(off), "+v"(x));
+}
+
 // Makes the compiler forget what it knows about a resident vector.  Without this the
 // bf16 -> fp32 widening done in one pass over the row is kept alive for the next pass
 // (common-subexpression elimination), which turns 4 registers per vector into 12 and
@@ -395,6 +480,7 @@ __global__ void __launch_bounds__(BLOCK) grpo_rows_cached(RowParams p)
     constexpr unsigned SLAB = BLOCK * 16u;  // bytes one pass of the workgroup covers
     __shared__ float lds_max[BLOCK / 64];
     __shared__ float lds_sum[BLOCK / 64];
+    __shared__ long long lds_row[2];
     const int tid = threadIdx.x;
     const unsigned toff = (unsigned)tid * 16u;
     const int nvec_full = (int)(p.vocab / EPV);
@@ -404,26 +490,72 @@ __global__ void __launch_bounds__(BLOCK) grpo_rows_cached(RowParams p)
     // -inf.  Full rows never enter those branches.
     const bool tail_wave = tail != 0 && tid < 64;
 
-    for (long long row = blockIdx.x; row < p.n_tokens; row += gridDim.x) {
-        long long y;
-        if (!row_is_live<DT, BLOCK>(p, row, nvec_full, tail, y)) continue;
-        const char *zrow = (const char *)p.logits + row * p.row_stride * BYTES;
-
-        // slot i of lane tid holds vector i * BLOCK + tid: consecutive lanes read
-        // consecutive 16-byte pieces; slots past the row hold -inf
-        u32x4 buf[NV];
-#pragma unroll
-        for (int i = 0; i < NV; ++i) {
-            const char *slab = zrow + (size_t)i * SLAB;
-            buf[i] = neg_inf_vec<DT>();
-            if (i * BLOCK + tid < nvec_full) buf[i] = *(const u32x4 *)(slab + toff);
+    // ---- which row next ----
+    // With a workspace (objective + gradient) rows are handed out through a counter in
+    // it, one at a time, to whichever workgroup is free: masked rows cost a third of a
+    // live row, and a fixed assignment leaves some workgroups with all the live ones.
+    // Without a workspace (log-probs only) rows are strided over the grid.
+    const bool queued = p.hdr != nullptr;
+    long long strided_next = blockIdx.x;
+    unsigned grabs = 0;
+    auto grab = [&]() -> long long {
+        if (!queued) {
+            const long long r = strided_next;
+            strided_next += gridDim.x;
+            return r;
         }
-        u32x4 tbuf = neg_inf_vec<DT>();
+        // two LDS slots used alternately: the barrier of grab k+1 separates the reads
+        // of grab k from the write of grab k+2 into the same slot
+        const unsigned slot = grabs++ & 1u;
+        if (tid == 0) lds_row[slot] = (long long)atomicAdd(&p.hdr->next_row, 1ull);
+        lds_barrier();
+        return uniform(lds_row[slot]);
+    };
+    // next row that needs the full treatment; rows that do not (masked, bad token id)
+    // are finished on the way
+    auto acquire = [&](long long &y) -> long long {
+        for (;;) {
+            const long long r = grab();
+            if (r >= p.n_tokens) return p.n_tokens;
+            if (row_is_live<DT, BLOCK>(p, r, nvec_full, tail, y)) return r;
+        }
+    };
+
+    // slot i of lane tid holds vector i * BLOCK + tid of the resident row: consecutive
+    // lanes hold consecutive 16-byte pieces; slots past the end of the row stay -inf
+    u32x4 buf[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) buf[i] = neg_inf_vec<DT>();
+    u32x4 tbuf = neg_inf_vec<DT>();
+    float zy = 0.f;
+
+    unsigned noff = toff;  // byte offset of this lane inside a slab, as used by the refills
+    auto fetch_slot = [&](const char *zrow, int i) {
+        if (i * BLOCK + tid < nvec_full) buf[i] = ld16(zrow + (size_t)i * SLAB + noff);
+    };
+    auto fetch_rest = [&](const char *zrow, long long y) {
         if (tail_wave && tid == 0) tbuf = load_vec<DT>(zrow, nvec_full, nvec_full, tail);
-        const float zy = load_elem<DT>(zrow, y);
+        zy = load_elem<DT>(zrow, y);
+    };
+
+    long long y = 0, y_next = 0;
+    long long row = acquire(y);
+    if (row < p.n_tokens) {
+        const char *zrow = (const char *)p.logits + row * p.row_stride * BYTES;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) fetch_slot(zrow, i);
+        fetch_rest(zrow, y);
+    }
+
+    while (row < p.n_tokens) {
+        // Take the following row now: its loads are issued while this row's last pass
+        // still computes, into the registers that pass has just finished with.
+        const long long next = acquire(y_next);
+        const bool has_next = next < p.n_tokens;
+        const char *zrow_next = (const char *)p.logits + (has_next ? next : row) * p.row_stride * BYTES;
+
         const int vy = (int)(y / EPV);
         const int ey = (int)(y % EPV);
-
         // The sampled token's logit is taken out of the resident row (replaced by -inf):
         // the sum below is then s_excl = sum_{j != y}, which keeps 1 - p_y = s_excl / s
         // accurate on near-one-hot rows where it would cancel to 0 in fp32.  One lane
@@ -435,63 +567,82 @@ __global__ void __launch_bounds__(BLOCK) grpo_rows_cached(RowParams p)
         }
         if (tail_wave && tid == 0 && vy == nvec_full) set_neg_inf<DT>(tbuf, ey);
 
-        // row maximum (over j != y, then joined with z_y)
+        // reference maximum over j != y, then joined with z_y
         float mx = -INFINITY;
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
-            float f[EPV];
             forget(buf[i]);
-            unpack<DT>(buf[i], f);
-#pragma unroll
-            for (int e = 0; e < EPV; ++e) mx = fmaxf(mx, f[e]);
+            mx = fmaxf(mx, vec_max_ref<DT>(buf[i]));
             VECTOR_FENCE();
         }
-        if (tail_wave) {
-            float f[EPV];
-            unpack<DT>(tbuf, f);
-#pragma unroll
-            for (int e = 0; e < EPV; ++e) mx = fmaxf(mx, f[e]);
-        }
+        if (tail_wave) mx = fmaxf(mx, vec_max_ref<DT>(tbuf));
         mx = fmaxf(block_max<BLOCK>(mx, lds_max), zy);
         const float mk = mx * p.k;
 
-        // sum of exponentials over j != y
+        // sum of exponentials over j != y; in log-probs-only mode this is the last use
+        // of the row, so the next row is fetched slot by slot behind it
         float acc = 0.f;
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
             forget(buf[i]);
             acc += exp_sum_vec<DT>(buf[i], p.k, mk);
+            if (!p.bwd && has_next) {
+                order_after(noff, acc);
+                fetch_slot(zrow_next, i);
+            }
             VECTOR_FENCE();
         }
         if (tail_wave) acc += exp_sum_vec<DT>(tbuf, p.k, mk);
+        const float zy_row = zy;
+        if (!p.bwd && has_next) fetch_rest(zrow_next, y_next);
         const float s_excl = block_sum<BLOCK>(acc, lds_sum);
 
-        const RowScalars sc = row_scalars(p, row, zy, mk, s_excl);
+        const RowScalars sc = row_scalars(p, row, zy_row, mk, s_excl);
         if (tid == 0) write_row_outputs(p, row, sc.logp, sc.J, sc.flags);
-        if (!p.bwd) continue;
 
-        char *grow = (char *)p.grad + row * p.row_stride * BYTES;
-        if (sc.c == 0.f) {
-            zero_row<DT, BLOCK>(grow, nvec_full, tail, tid);
-            continue;
-        }
-        const float q = -sc.c * p.inv_T;
-        const float gy = (sc.c * p.inv_T) * (sc.s_excl / sc.s);
+        if (p.bwd) {
+            char *grow = (char *)p.grad + row * p.row_stride * BYTES;
+            if (sc.c == 0.f) {
+                // the gradient of this row is cut: fetch the next row, then zero-fill
+                if (has_next) {
 #pragma unroll
-        for (int i = 0; i < NV; ++i) {
-            const int v = i * BLOCK + tid;
-            char *slab = grow + (size_t)i * SLAB;
-            float g[EPV];
-            forget(buf[i]);
-            grad_vec<DT>(buf[i], p.k, sc.shift, q, v == vy, ey, gy, g);
-            if (v < nvec_full) *(u32x4 *)(slab + toff) = pack<DT>(g);
-            VECTOR_FENCE();
+                    for (int i = 0; i < NV; ++i) fetch_slot(zrow_next, i);
+                    fetch_rest(zrow_next, y_next);
+                }
+                zero_row<DT, BLOCK>(grow, nvec_full, tail, tid);
+            } else {
+                const float q = -sc.c * p.inv_T;
+                const float gy = (sc.c * p.inv_T) * (sc.s_excl / sc.s);
+#pragma unroll
+                for (int i = 0; i < NV; ++i) {
+                    const int v = i * BLOCK + tid;
+                    float g[EPV];
+                    forget(buf[i]);
+                    grad_vec<DT>(buf[i], p.k, sc.shift, q, v == vy, ey, gy, g);
+                    u32x4 packed = pack<DT>(g);
+                    order_after(noff, packed);
+                    if (v < nvec_full) st16(grow + (size_t)i * SLAB + toff, packed);
+#if GRPO_BWD_INTERLEAVE
+                    if (has_next) fetch_slot(zrow_next, i);
+#endif
+                    VECTOR_FENCE();
+                }
+                if (tail_wave && tid == 0) {
+                    float g[EPV];
+                    grad_vec<DT>(tbuf, p.k, sc.shift, q, vy == nvec_full, ey, gy, g);
+                    store_vec<DT>(grow, nvec_full, nvec_full, tail, g);
+                }
+#if !GRPO_BWD_INTERLEAVE
+                if (has_next) {
+#pragma unroll
+                    for (int i = 0; i < NV; ++i) fetch_slot(zrow_next, i);
+                }
+#endif
+                if (has_next) fetch_rest(zrow_next, y_next);
+            }
         }
-        if (tail_wave && tid == 0) {
-            float g[EPV];
-            grad_vec<DT>(tbuf, p.k, sc.shift, q, vy == nvec_full, ey, gy, g);
-            store_vec<DT>(grow, nvec_full, nvec_full, tail, g);
-        }
+        row = next;
+        y = y_next;
     }
 }
 
@@ -552,7 +703,7 @@ __global__ void __launch_bounds__(BLOCK) grpo_rows_streamed(RowParams p)
         if (tid == 0) write_row_outputs(p, row, sc.logp, sc.J, sc.flags);
         // the LDS arrays are reused by the next row: one barrier separates this row's
         // reads of lds_sum from the next row's writes of lds_max/lds_sum
-        __syncthreads();
+        lds_barrier();
         if (!p.bwd) continue;
 
         char *grow = (char *)p.grad + row * p.row_stride * BYTES;
@@ -597,6 +748,16 @@ __global__ void __launch_bounds__(1024) grpo_prepare(const unsigned char *mask, 
         hdr->M = M;
         hdr->error = 0;
         hdr->pad = 0;
+        hdr->next_row = 0ull;
+    }
+}
+
+// Log-probs-only calls that bring a workspace use it for the row queue alone.
+__global__ void grpo_reset_queue(WsHeader *hdr)
+{
+    if (threadIdx.x == 0) {
+        hdr->next_row = 0ull;
+        hdr->error = 0;
     }
 }
 
@@ -807,10 +968,13 @@ grpo_status grpo_group_advantages(const float *rewards, int64_t n_rollouts,
 
 grpo_status grpo_logprobs_fwd(const void *logits, grpo_dtype dtype, int64_t n_tokens, int64_t vocab,
                               int64_t row_stride, const int64_t *tokens, const uint8_t *mask,
-                              float temperature, float *logprobs_out, void *stream)
+                              float temperature, float *logprobs_out, void *workspace,
+                              size_t workspace_bytes, void *stream)
 {
     grpo_status rc = check_logits_args(logits, dtype, n_tokens, vocab, row_stride, tokens, temperature);
     if (rc != GRPO_OK) return rc;
+    if (workspace && (((uintptr_t)workspace & 255u) != 0 || workspace_bytes < kHeaderBytes))
+        return GRPO_ERR_WORKSPACE;
     if (n_tokens == 0) return GRPO_OK;
     if (!logprobs_out) return GRPO_ERR_NULL;
     RowParams p = {};
@@ -818,6 +982,7 @@ grpo_status grpo_logprobs_fwd(const void *logits, grpo_dtype dtype, int64_t n_to
     p.tokens = (const long long *)tokens;
     p.mask = mask;
     p.logprobs_out = logprobs_out;
+    p.hdr = (WsHeader *)workspace;  // NULL: rows are strided over the grid instead of queued
     p.n_tokens = n_tokens;
     p.vocab = vocab;
     p.row_stride = row_stride;
@@ -825,6 +990,7 @@ grpo_status grpo_logprobs_fwd(const void *logits, grpo_dtype dtype, int64_t n_to
     p.k = (float)((double)kLog2e / (double)temperature);
     p.bwd = 0;
     hipStream_t st = (hipStream_t)stream;
+    if (workspace) hipLaunchKernelGGL(grpo_reset_queue, dim3(1), dim3(64), 0, st, p.hdr);
     if (dtype == GRPO_BF16)
         launch_rows<GRPO_BF16>(p, st);
     else

@@ -69,15 +69,17 @@ def test_loss_fwd_bwd_rejects_bad_arguments_before_any_launch(over, expect):
 def test_logprobs_and_advantages_reject_bad_arguments():
     L = grpo.lib()
     f = L.grpo_logprobs_fwd
-    assert f(None, 1, 4, 64, 64, P, None, 1.0, P, None) == NULL
-    assert f(P, 1, 4, 64, 64, None, None, 1.0, P, None) == NULL
-    assert f(P, 1, 4, 64, 64, P, None, 1.0, None, None) == NULL
-    assert f(P, 1, 4, 64, 60, P, None, 1.0, P, None) == SHAPE
-    assert f(P, 3, 4, 64, 64, P, None, 1.0, P, None) == DTYPE
-    assert f(P + 4, 1, 4, 64, 64, P, None, 1.0, P, None) == ALIGN
-    assert f(P, 1, 4, 63, 63, P, None, 1.0, P, None) == ALIGN     # 126-byte row pitch
-    assert f(P, 1, 4, 64, 64, P, None, 0.0, P, None) == PARAM
-    assert f(P, 1, 0, 64, 64, None, None, 1.0, None, None) == OK   # nothing to do
+    assert f(None, 1, 4, 64, 64, P, None, 1.0, P, None, 0, None) == NULL
+    assert f(P, 1, 4, 64, 64, None, None, 1.0, P, None, 0, None) == NULL
+    assert f(P, 1, 4, 64, 64, P, None, 1.0, None, None, 0, None) == NULL
+    assert f(P, 1, 4, 64, 60, P, None, 1.0, P, None, 0, None) == SHAPE
+    assert f(P, 3, 4, 64, 64, P, None, 1.0, P, None, 0, None) == DTYPE
+    assert f(P + 4, 1, 4, 64, 64, P, None, 1.0, P, None, 0, None) == ALIGN
+    assert f(P, 1, 4, 63, 63, P, None, 1.0, P, None, 0, None) == ALIGN     # 126-byte row pitch
+    assert f(P, 1, 4, 64, 64, P, None, 0.0, P, None, 0, None) == PARAM
+    assert f(P, 1, 4, 64, 64, P, None, 1.0, P, P + 8, 256, None) == WORKSPACE   # misaligned
+    assert f(P, 1, 4, 64, 64, P, None, 1.0, P, P, 100, None) == WORKSPACE       # too small
+    assert f(P, 1, 0, 64, 64, None, None, 1.0, None, None, 0, None) == OK   # nothing to do
     g = L.grpo_group_advantages
     assert g(None, 8, None, 2, 4, 1e-6, 0, P, None, 0, None, None) == NULL
     assert g(P, 8, None, 2, 4, 1e-6, 0, None, None, 0, None, None) == NULL

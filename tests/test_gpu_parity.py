@@ -130,6 +130,11 @@ def test_reduced_configs_every_element(name):
     torch.cuda.synchronize()
     assert np.max(np.abs(lp_fwd.cpu().numpy() - lp_orc)) <= TOL_LOGP
     assert torch.equal(lp_fwd, out["logprobs"])
+    # ... and without the row queue (fixed strided assignment): same bits
+    lp_strided = grpo.grpo_logprobs_fwd(batch["logits"], batch["tokens"], batch["mask"],
+                                        temperature=f32(cfg.temperature), use_queue=False)
+    torch.cuda.synchronize()
+    assert torch.equal(lp_fwd, lp_strided)
     # every counter the recipe is meant to exercise is exercised
     if name in ("qwen_medium", "numerics_stress"):
         assert min(out["obj"]["counts"][1:].tolist()[0:2]) > 0
