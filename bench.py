@@ -40,19 +40,20 @@ def traffic_from_profiles(workload):
     return None
 
 
-def cpu_baseline(batch, old, adv_tok, budget_s=12.0, max_rows=32768, block=512):
-    """fp64 oracle, forward + backward, on the first rows of the same batch until the time
-    budget is used; returns tokens/s of that sample."""
+def cpu_baseline(batch, old, adv_tok, budget_s=10.0, block=512):
+    """fp64 oracle, forward + backward, over the rows of the same batch in blocks (wrapping
+    around if the batch is finished early) until the time budget is used; tokens/s of that."""
     import numpy as np
     import torch
     from oracle import grpo_oracle as orc
     cfg = batch["cfg"]
-    done, t_used = 0, 0.0
+    N = batch["n_tokens"]
+    done, live, t_used, r0 = 0, 0, 0.0, 0
     tokens = batch["tokens"].cpu().numpy()
     mask = batch["mask"].cpu().numpy()
     oldn, advn = old.cpu().numpy(), adv_tok.cpu().numpy()
-    while done < min(max_rows, batch["n_tokens"]) and t_used < budget_s:
-        r0, r1 = done, min(done + block, batch["n_tokens"], max_rows)
+    while t_used < budget_s:
+        r1 = min(r0 + block, N)
         z = batch["logits"][r0:r1].cpu()
         z = z.view(torch.int16).numpy().view(np.uint16) if z.dtype == torch.bfloat16 else z.numpy()
         t0 = time.perf_counter()
@@ -60,10 +61,12 @@ def cpu_baseline(batch, old, adv_tok, budget_s=12.0, max_rows=32768, block=512):
                          eps_low=cfg.eps_low, eps_high=cfg.eps_high, delta=cfg.delta,
                          temperature=cfg.temperature, grad_rows="all")
         t_used += time.perf_counter() - t0
-        done = r1
+        done += r1 - r0
+        live += int(mask[r0:r1].sum())
+        r0 = r1 % N
     return dict(value=done / t_used, unit="tokens/s", cores=orc.num_threads(), kind="oracle",
-                sample="first %d rows of the batch (%d unmasked), fp64 forward+backward, %.1f s"
-                       % (done, int(mask[:done].sum()), t_used))
+                sample="%d rows of the batch in order from row 0, wrapping (%d unmasked), fp64 "
+                       "forward+backward in blocks of %d rows, %.1f s" % (done, live, block, t_used))
 
 
 def main():
