@@ -32,7 +32,10 @@
  *
  * Parity pins: every function below is pinned by tests/test_oracle_pins.py
  * (closed forms, invariants, library log-softmax / cross-entropy special cases,
- * finite differences, a hand-derived branch table).  None is "parity unpinned".
+ * finite differences, a hand-derived branch table; for the auxiliary terms:
+ * library entropy, binary-entropy closed form, the identity
+ * sum_y pi(y) kl(y) = KL(pi || pi_ref), autograd and finite differences of the
+ * total).  None is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -381,6 +384,151 @@ int oracle_loss_fwd_bwd(const void *logits, int dtype, int64_t n_tokens, int64_t
     free(lp);
     free(cf);
     return rc;
+}
+
+/* ================================================================== *
+ * Auxiliary losses (section 2.1.1: the trainer implements GRPO "along with
+ * auxiliary KL and entropy losses"; section 4.1: KL coefficient 0.001,
+ * entropy coefficient 1e-4).  The paper prints neither estimator; the
+ * readings used here:
+ *   - KL: per sampled token, from the log-probs of a reference policy
+ *     (section 5 speaks of the "relative KL log-probability computation"),
+ *     with the estimator of the GRPO paper the objective is taken from:
+ *       kl_t = exp(d) - d - 1,  d = l_ref_t - l_t   (>= 0, 0 iff l = l_ref).
+ *     Summed over y ~ pi it equals KL(pi || pi_ref) exactly.
+ *   - entropy: H_t = - sum_j p_j log p_j of softmax(z_t / T), entering as a
+ *     bonus (minus sign), as in the PPO family the objective descends from.
+ *   total = -(1/D) sum m J + kl_coef (1/D) sum m kl - ent_coef (1/D) sum m H
+ * ================================================================== */
+
+/* Entropy (nats) of softmax(z / T) of one row. */
+double oracle_row_entropy(const void *row, int dtype, int64_t V, double T)
+{
+    double lse = oracle_row_log_softmax(row, dtype, V, T, NULL);
+    csum h = {0.0, 0.0};
+    for (int64_t j = 0; j < V; ++j) {
+        double lp = logit_at(row, dtype, j) / T - lse;
+        double p = exp(lp);
+        if (p > 0.0) /* p log p -> 0 as p -> 0, also for -inf logits */
+            csum_add(&h, -p * lp);
+    }
+    return csum_value(&h);
+}
+
+/* kl = exp(d) - d - 1 with d = l_ref - l, and its derivative with respect to l. */
+void oracle_kl_estimator(double l, double l_ref, double *kl_out, double *dkl_dl_out)
+{
+    double d = l_ref - l;
+    if (kl_out)
+        *kl_out = expm1(d) - d; /* exp(d) - 1 - d without cancellation for small d */
+    if (dkl_dl_out)
+        *dkl_dl_out = -expm1(d); /* d/dl [exp(d) - d - 1] = -exp(d) + 1 */
+}
+
+/* H_t for every unmasked row (0 at masked rows). */
+int oracle_entropies(const void *logits, int dtype, int64_t n_tokens, int64_t V,
+                     int64_t row_stride, const uint8_t *mask, double T, double *entropy_out)
+{
+    size_t esz = elem_size(dtype);
+#pragma omp parallel for schedule(dynamic, 8)
+    for (int64_t t = 0; t < n_tokens; ++t) {
+        if (mask && !mask[t]) {
+            entropy_out[t] = 0.0;
+            continue;
+        }
+        const char *row = (const char *)logits + (size_t)t * (size_t)row_stride * esz;
+        entropy_out[t] = oracle_row_entropy(row, dtype, V, T);
+    }
+    return 0;
+}
+
+/* Objective with the auxiliary terms, from per-token log-probs and entropies.
+ * aux_out[0] = policy loss -(1/D) sum m J, aux_out[1] = (1/D) sum m kl,
+ * aux_out[2] = (1/D) sum m H;  *total_out = aux0 + kl_coef aux1 - ent_coef aux2.
+ * coeff_out[t] = grad_scale * dtotal/dl_t through the ratio and the KL term;
+ * ent_coeff_out[t] = grad_scale * ent_coef * m_t / D, the weight of -H_t.
+ * ref_logprobs may be NULL when kl_coef == 0. */
+void oracle_aux_objective_from_logprobs(int64_t n_tokens, const double *logprobs,
+                                        const double *entropies, const float *old_logprobs,
+                                        const float *ref_logprobs, const float *advantages,
+                                        const uint8_t *mask, double eps_low, double eps_high,
+                                        double delta, double kl_coef, double ent_coef,
+                                        double denom, double grad_scale, double *total_out,
+                                        double *aux_out, int64_t *counts_out,
+                                        double *coeff_out, double *ent_coeff_out)
+{
+    double policy = 0.0;
+    oracle_objective_from_logprobs(n_tokens, logprobs, old_logprobs, advantages, mask, eps_low,
+                                   eps_high, delta, denom, grad_scale, &policy, counts_out,
+                                   NULL, coeff_out, NULL);
+    int64_t M = 0;
+    for (int64_t t = 0; t < n_tokens; ++t)
+        M += (!mask || mask[t]) ? 1 : 0;
+    double D = (denom > 0.0) ? denom : (double)M;
+    csum skl = {0.0, 0.0}, sh = {0.0, 0.0};
+    for (int64_t t = 0; t < n_tokens; ++t) {
+        int live = (!mask || mask[t]) && D > 0.0;
+        double kl = 0.0, dkl = 0.0;
+        if (live && ref_logprobs && kl_coef != 0.0)
+            oracle_kl_estimator(logprobs[t], (double)ref_logprobs[t], &kl, &dkl);
+        if (live) {
+            csum_add(&skl, kl);
+            csum_add(&sh, entropies[t]);
+        }
+        if (coeff_out)
+            coeff_out[t] += live ? grad_scale * kl_coef * dkl / D : 0.0;
+        if (ent_coeff_out)
+            ent_coeff_out[t] = live ? grad_scale * ent_coef / D : 0.0;
+    }
+    double klm = (D > 0.0) ? csum_value(&skl) / D : 0.0;
+    double hm = (D > 0.0) ? csum_value(&sh) / D : 0.0;
+    if (aux_out) {
+        aux_out[0] = policy;
+        aux_out[1] = klm;
+        aux_out[2] = hm;
+    }
+    if (total_out)
+        *total_out = policy + kl_coef * klm - ent_coef * hm;
+}
+
+/* Gradient of one row of the total with respect to its logits:
+ *   g_j = (c/T) (1[j = y] - p_j)  +  (b/T) p_j (log p_j + H),
+ * c = coeff (ratio and KL part), b = ent_coeff; the second term is the
+ * derivative of -b H, since dH/du_j = -p_j (log p_j + H). */
+void oracle_aux_grad_row(const void *row, int dtype, int64_t V, double T, int64_t y, double c,
+                         double b, double *g /* [V] */)
+{
+    oracle_grad_row(row, dtype, V, T, y, c, g);
+    if (b == 0.0)
+        return;
+    double lse = oracle_row_log_softmax(row, dtype, V, T, NULL);
+    double H = oracle_row_entropy(row, dtype, V, T);
+    for (int64_t j = 0; j < V; ++j) {
+        double lp = logit_at(row, dtype, j) / T - lse;
+        double p = exp(lp);
+        if (p > 0.0)
+            g[j] += (b / T) * p * (lp + H);
+    }
+}
+
+void oracle_aux_grad_rows(const void *logits, int dtype, int64_t V, int64_t row_stride,
+                          const int64_t *tokens, const double *coeff, const double *ent_coeff,
+                          double T, const int64_t *grad_rows, int64_t n_grad_rows,
+                          double *grad_out)
+{
+    size_t esz = elem_size(dtype);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t k = 0; k < n_grad_rows; ++k) {
+        int64_t t = grad_rows[k];
+        double *g = grad_out + (size_t)k * (size_t)V;
+        if (coeff[t] == 0.0 && ent_coeff[t] == 0.0) {
+            for (int64_t j = 0; j < V; ++j)
+                g[j] = 0.0;
+            continue;
+        }
+        const char *row = (const char *)logits + (size_t)t * (size_t)row_stride * esz;
+        oracle_aux_grad_row(row, dtype, V, T, tokens[t], coeff[t], ent_coeff[t], g);
+    }
 }
 
 /* Number of OpenMP threads a parallel region would use (for the benchmark's

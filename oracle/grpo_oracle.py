@@ -66,6 +66,17 @@ def lib():
                                                      vp, vp, vp, vp, vp]
         L.oracle_grad_rows.restype = None
         L.oracle_grad_rows.argtypes = [vp, i32, i64, i64, vp, vp, dbl, vp, i64, vp]
+        L.oracle_row_entropy.restype = dbl
+        L.oracle_row_entropy.argtypes = [vp, i32, i64, dbl]
+        L.oracle_kl_estimator.restype = None
+        L.oracle_kl_estimator.argtypes = [dbl, dbl, vp, vp]
+        L.oracle_entropies.restype = i32
+        L.oracle_entropies.argtypes = [vp, i32, i64, i64, i64, vp, dbl, vp]
+        L.oracle_aux_objective_from_logprobs.restype = None
+        L.oracle_aux_objective_from_logprobs.argtypes = [i64, vp, vp, vp, vp, vp, vp, dbl, dbl, dbl,
+                                                         dbl, dbl, dbl, dbl, vp, vp, vp, vp, vp]
+        L.oracle_aux_grad_rows.restype = None
+        L.oracle_aux_grad_rows.argtypes = [vp, i32, i64, i64, vp, vp, vp, dbl, vp, i64, vp]
         L.oracle_num_threads.restype = i32
         L.oracle_num_threads.argtypes = []
         _lib = L
@@ -223,3 +234,91 @@ def grad_rows(logits_rows, tokens_rows, coeff_rows, temperature=1.0, vocab=None)
     lib().oracle_grad_rows(_ptr(a), dt, V, stride, _ptr(tok), _ptr(cf), float(temperature),
                            _ptr(idx), K, _ptr(out))
     return out
+
+
+# ---------------------------------------------------------------------------
+# auxiliary KL and entropy terms
+# ---------------------------------------------------------------------------
+
+def row_entropy(row, V=None, temperature=1.0):
+    a, dt, _ = _logits_view(row)
+    V = a.shape[1] if V is None else V
+    return float(lib().oracle_row_entropy(_ptr(a), dt, V, float(temperature)))
+
+
+def kl_estimator(l, l_ref):
+    """(kl, dkl/dl) of the sampled-token estimator exp(d) - d - 1, d = l_ref - l."""
+    kl, dkl = ctypes.c_double(), ctypes.c_double()
+    lib().oracle_kl_estimator(float(l), float(l_ref), ctypes.byref(kl), ctypes.byref(dkl))
+    return kl.value, dkl.value
+
+
+def entropies(logits, mask=None, temperature=1.0, vocab=None):
+    a, dt, stride = _logits_view(logits)
+    N = a.shape[0]
+    V = a.shape[1] if vocab is None else vocab
+    m = None if mask is None else np.ascontiguousarray(mask, dtype=np.uint8)
+    out = np.zeros(N, dtype=np.float64)
+    lib().oracle_entropies(_ptr(a), dt, N, V, stride, _ptr(m), float(temperature), _ptr(out))
+    return out
+
+
+def aux_objective_from_logprobs(logprobs, entropies_, old_logprobs, ref_logprobs, advantages,
+                                mask=None, *, eps_low=0.2, eps_high=0.2, delta=4.0, kl_coef=0.0,
+                                ent_coef=0.0, denom=0.0, grad_scale=1.0):
+    lp = np.ascontiguousarray(logprobs, dtype=np.float64)
+    N = lp.shape[0]
+    H = np.ascontiguousarray(entropies_, dtype=np.float64)
+    old = np.ascontiguousarray(old_logprobs, dtype=np.float32)
+    ref = None if ref_logprobs is None else np.ascontiguousarray(ref_logprobs, dtype=np.float32)
+    adv = np.ascontiguousarray(advantages, dtype=np.float32)
+    m = None if mask is None else np.ascontiguousarray(mask, dtype=np.uint8)
+    total = np.zeros(1, dtype=np.float64)
+    aux = np.zeros(3, dtype=np.float64)
+    counts = np.zeros(5, dtype=np.int64)
+    coeff = np.zeros(N, dtype=np.float64)
+    ent_coeff = np.zeros(N, dtype=np.float64)
+    lib().oracle_aux_objective_from_logprobs(
+        N, _ptr(lp), _ptr(H), _ptr(old), _ptr(ref), _ptr(adv), _ptr(m), float(eps_low),
+        float(eps_high), float(delta), float(kl_coef), float(ent_coef), float(denom),
+        float(grad_scale), _ptr(total), _ptr(aux), _ptr(counts), _ptr(coeff), _ptr(ent_coeff))
+    return dict(total=float(total[0]), policy=float(aux[0]), kl=float(aux[1]),
+                entropy=float(aux[2]), counts=counts, coeff=coeff, ent_coeff=ent_coeff)
+
+
+def aux_grad_rows(logits_rows, tokens_rows, coeff_rows, ent_coeff_rows, temperature=1.0, vocab=None):
+    a, dt, stride = _logits_view(logits_rows)
+    K = a.shape[0]
+    V = a.shape[1] if vocab is None else vocab
+    tok = np.ascontiguousarray(tokens_rows, dtype=np.int64)
+    cf = np.ascontiguousarray(coeff_rows, dtype=np.float64)
+    ef = np.ascontiguousarray(ent_coeff_rows, dtype=np.float64)
+    idx = np.arange(K, dtype=np.int64)
+    out = np.zeros((K, V), dtype=np.float64)
+    lib().oracle_aux_grad_rows(_ptr(a), dt, V, stride, _ptr(tok), _ptr(cf), _ptr(ef),
+                               float(temperature), _ptr(idx), K, _ptr(out))
+    return out
+
+
+def aux_loss_fwd_bwd(logits, tokens, old_logprobs, ref_logprobs, advantages, mask=None, *,
+                     eps_low=0.2, eps_high=0.2, delta=4.0, temperature=1.0, kl_coef=0.0,
+                     ent_coef=0.0, denom=0.0, grad_scale=1.0, grad_rows=None, vocab=None):
+    """Total objective with the auxiliary terms in one call (composition of the stages)."""
+    a, dt, stride = _logits_view(logits)
+    N = a.shape[0]
+    V = a.shape[1] if vocab is None else vocab
+    lp = logprobs(a, tokens, mask, temperature, vocab=V)
+    H = entropies(a, mask, temperature, vocab=V)
+    obj = aux_objective_from_logprobs(lp, H, old_logprobs, ref_logprobs, advantages, mask,
+                                      eps_low=eps_low, eps_high=eps_high, delta=delta,
+                                      kl_coef=kl_coef, ent_coef=ent_coef, denom=denom,
+                                      grad_scale=grad_scale)
+    obj["logprobs"], obj["entropies"] = lp, H
+    if grad_rows is not None:
+        if isinstance(grad_rows, str):
+            grad_rows = np.arange(N)
+        gr = np.asarray(grad_rows, dtype=np.int64)
+        tok = np.ascontiguousarray(tokens, dtype=np.int64)
+        obj["grad"] = aux_grad_rows(a[gr], tok[gr], obj["coeff"][gr], obj["ent_coeff"][gr],
+                                    temperature, vocab=V)
+    return obj
