@@ -69,7 +69,7 @@ enum {
 /* Static, human-readable text for a status code.  Never NULL. */
 const char *grpo_status_string(grpo_status status);
 
-/* Bytes of device workspace grpo_loss_fwd_bwd needs for n_tokens rows (a pure host
+/* Bytes of device workspace grpo_loss_fwd_bwd / grpo_loss_aux_fwd_bwd need for n_tokens rows (a pure host
  * function; returns 0 for n_tokens < 0).  The workspace must be 256-byte aligned. */
 size_t grpo_workspace_bytes(int64_t n_tokens);
 
@@ -178,6 +178,43 @@ grpo_status grpo_loss_fwd_bwd(const void *logits, grpo_dtype dtype, int64_t n_to
                               float grad_scale, float *loss_out, float *logprobs_out,
                               int64_t *counts_out, void *grad_logits, void *workspace,
                               size_t workspace_bytes, void *stream);
+
+/*
+ * The same objective with the trainer's two auxiliary terms fused into the same pass
+ * over the logits (section 2.1.1: GRPO "along with auxiliary KL and entropy losses";
+ * section 4.1: KL coefficient 0.001, entropy coefficient 1e-4).  The paper prints
+ * neither estimator; this library uses
+ *   kl_t = exp(d_t) - d_t - 1,  d_t = ref_logprobs[t] - l_t    (sampled-token estimator
+ *          of KL(pi_theta || pi_ref), the one of the GRPO paper; >= 0),
+ *   H_t  = - sum_j p_j log p_j,  p = softmax(z_t / T)           (entropy, in nats),
+ *   total = -(1/D) sum m J  +  kl_coef (1/D) sum m kl  -  entropy_coef (1/D) sum m H
+ * (the entropy enters as a bonus; pass a negative coefficient to penalise it).
+ *
+ * Arguments as grpo_loss_fwd_bwd, plus
+ *  ref_logprobs [n_tokens] f32, device, read: log pi_ref(y_t); may be NULL iff
+ *               kl_coef == 0.
+ *  kl_coef, entropy_coef: finite.
+ *  loss_out     [4] f32, device, written: total, policy part -(1/D) sum m J,
+ *               mean kl, mean H (all with the same denominator D).
+ *  entropy_out  [n_tokens] f32, device, written, or NULL: H_t (0 at masked rows).
+ *  grad_logits  grad_scale * dtotal/dlogits
+ *                 = c_t/T (1[j = y_t] - p_j) + b_t/T p_j (log p_j + H_t),
+ *               c_t = grad_scale m_t (-dJ_t/dl_t + kl_coef (1 - exp(d_t))) / D,
+ *               b_t = grad_scale m_t entropy_coef / D.
+ *               Rows with c_t = 0 and b_t = 0 are zero-filled.
+ * With kl_coef = 0 and entropy_coef = 0 the loss and the gradient equal those of
+ * grpo_loss_fwd_bwd.  Entropies below about 1e-7 nats are at the resolution of the
+ * fp32 normaliser and are reported with that absolute accuracy.
+ */
+grpo_status grpo_loss_aux_fwd_bwd(const void *logits, grpo_dtype dtype, int64_t n_tokens,
+                                  int64_t vocab, int64_t row_stride, const int64_t *tokens,
+                                  const float *old_logprobs, const float *ref_logprobs,
+                                  const float *advantages, const uint8_t *mask, float eps_low,
+                                  float eps_high, float delta, float temperature, float kl_coef,
+                                  float entropy_coef, double denom, float grad_scale,
+                                  float *loss_out, float *logprobs_out, float *entropy_out,
+                                  int64_t *counts_out, void *grad_logits, void *workspace,
+                                  size_t workspace_bytes, void *stream);
 
 /*
  * Reads the sticky error word the last grpo_loss_fwd_bwd left in `workspace`:

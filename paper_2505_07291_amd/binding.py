@@ -47,6 +47,9 @@ def lib():
         L.grpo_loss_fwd_bwd.restype = i32
         L.grpo_loss_fwd_bwd.argtypes = [vp, i32, i64, i64, i64, vp, vp, vp, vp, f32, f32, f32, f32,
                                         f64, f32, vp, vp, vp, vp, vp, sz, vp]
+        L.grpo_loss_aux_fwd_bwd.restype = i32
+        L.grpo_loss_aux_fwd_bwd.argtypes = [vp, i32, i64, i64, i64, vp, vp, vp, vp, vp, f32, f32, f32,
+                                            f32, f32, f32, f64, f32, vp, vp, vp, vp, vp, vp, sz, vp]
         L.grpo_workspace_error.restype = i32
         L.grpo_workspace_error.argtypes = [vp, vp, vp]
         _lib = L
@@ -187,6 +190,53 @@ def grpo_loss_fwd_bwd(logits, tokens, old_logprobs, advantages, mask=None, eps_l
     if rc != GRPO_OK:
         raise GrpoError(rc, "grpo_loss_fwd_bwd")
     return loss_out, logprobs_out, counts_out, grad_logits
+
+
+def grpo_loss_aux_fwd_bwd(logits, tokens, old_logprobs, ref_logprobs, advantages, mask=None,
+                          eps_low=0.2, eps_high=0.2, delta=4.0, temperature=1.0, kl_coef=0.0,
+                          entropy_coef=0.0, denom=0.0, grad_scale=1.0, *, vocab=None,
+                          grad_logits=None, inplace=False, loss_out=None, logprobs_out=None,
+                          entropy_out=None, want_entropy=True, counts_out=None, workspace=None,
+                          stream=None):
+    """Objective with the KL and entropy terms fused in; see grpo_loss_aux_fwd_bwd in grpo.h.
+
+    Returns (loss [4] f32: total, policy, mean kl, mean entropy; logprobs [n]; entropy [n] or
+    None; counts [5] i64; grad_logits)."""
+    dt, n, v, stride = _logits_args(logits, vocab)
+    dev = logits.device
+    _check(tokens, torch.int64, n, "tokens", dev)
+    _check(old_logprobs, torch.float32, n, "old_logprobs", dev)
+    _check(advantages, torch.float32, n, "advantages", dev)
+    if ref_logprobs is not None:
+        _check(ref_logprobs, torch.float32, n, "ref_logprobs", dev)
+    if mask is not None:
+        _check(mask, torch.uint8, n, "mask", dev)
+    if inplace:
+        grad_logits = logits
+    elif grad_logits is None:
+        grad_logits = torch.empty_strided(logits.shape, logits.stride(), dtype=logits.dtype, device=dev)
+    elif grad_logits.dtype != logits.dtype or grad_logits.shape != logits.shape or \
+            grad_logits.stride() != logits.stride():
+        raise ValueError("grad_logits must match logits in dtype, shape and strides")
+    if loss_out is None:
+        loss_out = torch.empty(4, dtype=torch.float32, device=dev)
+    if logprobs_out is None:
+        logprobs_out = torch.empty(n, dtype=torch.float32, device=dev)
+    if entropy_out is None and want_entropy:
+        entropy_out = torch.empty(n, dtype=torch.float32, device=dev)
+    if counts_out is None:
+        counts_out = torch.empty(5, dtype=torch.int64, device=dev)
+    if workspace is None:
+        workspace = torch.empty(grpo_workspace_bytes(n), dtype=torch.uint8, device=dev)
+    rc = lib().grpo_loss_aux_fwd_bwd(
+        _ptr(logits), dt, n, v, stride, _ptr(tokens), _ptr(old_logprobs), _ptr(ref_logprobs),
+        _ptr(advantages), _ptr(mask), float(eps_low), float(eps_high), float(delta),
+        float(temperature), float(kl_coef), float(entropy_coef), float(denom), float(grad_scale),
+        _ptr(loss_out), _ptr(logprobs_out), _ptr(entropy_out), _ptr(counts_out), _ptr(grad_logits),
+        _ptr(workspace), workspace.numel(), _stream(stream))
+    if rc != GRPO_OK:
+        raise GrpoError(rc, "grpo_loss_aux_fwd_bwd")
+    return loss_out, logprobs_out, entropy_out, counts_out, grad_logits
 
 
 def grpo_workspace_error(workspace, stream=None) -> int:

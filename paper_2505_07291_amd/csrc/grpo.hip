@@ -57,6 +57,11 @@ struct RowParams {
     float inv_T;  // 1 / T
     float lo, hi, delta, grad_scale;
     int bwd;  // 0: log-probs only (grpo_logprobs_fwd), 1: objective + gradient
+    // auxiliary terms (kernels instantiated with AUX only)
+    const float *ref_lp;  // reference-policy log-probs, or NULL (no KL term)
+    float *KL_ws, *H_ws;  // per-row KL estimate and entropy
+    float *entropy_out;   // optional copy of the per-row entropy for the caller
+    float kl_coef, ent_coef;
 };
 
 template <grpo_dtype DT>
@@ -279,6 +284,37 @@ __device__ __forceinline__ float block_sum(float v, float *lds)
     return r;
 }
 
+// a * b with 0 * anything = 0, also for an infinite b (v_mul_legacy_f32): an element at
+// -inf has probability 0 and must contribute 0 to sum p log p, not NaN.
+__device__ __forceinline__ float mul_zero_wins(float a, float b)
+{
+    float r;
+    asm("v_mul_legacy_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
+// Two sums behind one barrier.
+template <int BLOCK>
+__device__ __forceinline__ void block_sum2(float &a, float &b, float *lds_a, float *lds_b)
+{
+    constexpr int NW = BLOCK / 64;
+    a = wave_sum(a);
+    b = wave_sum(b);
+    if constexpr (NW == 1) return;
+    if ((threadIdx.x & 63) == 0) {
+        lds_a[threadIdx.x >> 6] = a;
+        lds_b[threadIdx.x >> 6] = b;
+    }
+    lds_barrier();
+    a = lds_a[0];
+    b = lds_b[0];
+#pragma unroll
+    for (int i = 1; i < NW; ++i) {
+        a += lds_a[i];
+        b += lds_b[i];
+    }
+}
+
 // Per-row scalars once the row statistics are known.
 //   mk     = (max_j z_j) * k                      (k = log2 e / T)
 //   s_excl = sum_{j != y} exp2(z_j k - mk)        (the sampled token is left out so that
@@ -289,46 +325,125 @@ __device__ __forceinline__ float block_sum(float v, float *lds)
 struct RowScalars {
     float logp, J, c, shift, s, s_excl;
     int flags;
+    // auxiliary terms: b = weight of -H in the gradient, q2 and bq the two constants of
+    // the fused gradient g_j = p_j (q2 + bq a'_j), gy_ent the entropy part of g_y
+    float b, q2, bq, gy_ent;
 };
 
-__device__ __forceinline__ RowScalars row_scalars(const RowParams &p, long long row, float zy,
-                                                  float mk, float s_excl)
+// Scalar transcendental functions of the once-per-row arithmetic, built on the
+// hardware's base-2 exponential and logarithm (1 ulp each).  The library versions are
+// exact to the last bit but need dozens of registers at the one point of the kernel
+// where the whole row is resident; the per-row quantities need 1e-6, not 1e-8.
+__device__ __forceinline__ float hw_exp(float x) { return __builtin_amdgcn_exp2f(x * kLog2e); }
+__device__ __forceinline__ float hw_log(float x) { return __builtin_amdgcn_logf(x) * kLn2; }
+// ln(1 + x), x >= 0: the series below 1/32 (next term x^7/7 < 5e-12), else the logarithm
+__device__ __forceinline__ float hw_log1p(float x)
 {
-    RowScalars o;
-    const float ay = fmaf(zy, p.k, -mk);
-    const float s = s_excl + __builtin_amdgcn_exp2f(ay);
-    const float log2s = log2f(s);
-    o.s = s;
-    o.s_excl = s_excl;
-    o.shift = mk + log2s;
-    o.logp = (ay - log2s) * kLn2;
-    o.J = 0.f;
-    o.c = 0.f;
-    o.flags = 0;
-    if (!p.bwd) return o;
+    const float series = x * (1.f + x * (-0.5f + x * (1.f / 3 + x * (-0.25f + x * (0.2f - x * (1.f / 6))))));
+    return x < 0.03125f ? series : hw_log(1.f + x);
+}
+// exp(d) - 1: the series below |d| = 0.1 (next term d^8/40320), else the exponential
+__device__ __forceinline__ float hw_expm1(float d)
+{
+    const float series = d * (1.f + d * (0.5f + d * (1.f / 6 + d * (1.f / 24 + d * (1.f / 120 +
+                         d * (1.f / 720 + d * (1.f / 5040)))))));
+    return fabsf(d) < 0.1f ? series : hw_exp(d) - 1.f;
+}
 
-    const float A = p.adv[row];
-    const float r = expf(o.logp - p.old_lp[row]);
+// J, dJ/dl and the indicator bits of the bracketed surrogate term of section 3.4.
+__device__ __forceinline__ void surrogate(const RowParams &p, float r, float A, float &J, float &dJ,
+                                          int &fl)
+{
     // J = min( min(r, delta) A , clip(r, 1 - eps_low, 1 + eps_high) A )
     const float s1 = fminf(r, p.delta) * A;
     const float s2 = fminf(fmaxf(r, p.lo), p.hi) * A;
     const bool first = s1 <= s2;
-    float J = first ? s1 : s2;
+    J = first ? s1 : s2;
     // dJ/dl = r dJ/dr; a ratio exactly on a boundary counts as not clipped
     const bool open = first ? (r <= p.delta) : (r >= p.lo && r <= p.hi);
-    float dJ = open ? A * r : 0.f;
+    dJ = open ? A * r : 0.f;
     if (r != r || A != A) {  // fminf/fmaxf drop NaNs: put them back
         J = NAN;
         dJ = NAN;
     }
-    int fl = 0;
+    fl = 0;
     if (A > 0.f && r > p.hi) fl |= kFlagClipHigh;
     if (A < 0.f && r < p.lo) fl |= kFlagClipLow;
     if (A < 0.f && r > p.delta) fl |= kFlagDelta;
     if (r < p.lo || r > p.hi) fl |= kFlagOutOfBand;
-    o.J = J;
-    o.flags = fl;
+}
+
+__device__ __forceinline__ RowScalars row_scalars(const RowParams &p, long long row, float zy,
+                                                  float mk, float s_excl)
+{
+    RowScalars o = {};
+    const float ay = fmaf(zy, p.k, -mk);
+    const float s = s_excl + __builtin_amdgcn_exp2f(ay);
+    const float log2s = __builtin_amdgcn_logf(s);
+    o.s = s;
+    o.s_excl = s_excl;
+    o.shift = mk + log2s;
+    o.logp = (ay - log2s) * kLn2;
+    if (!p.bwd) return o;
+
+    float dJ;
+    surrogate(p, hw_exp(o.logp - p.old_lp[row]), p.adv[row], o.J, dJ, o.flags);
     o.c = -(p.grad_scale * dJ) * (float)p.hdr->inv_D;
+    return o;
+}
+
+// The same with the auxiliary terms (sampled-token KL estimator against a reference
+// policy, entropy bonus).  w_excl = sum_{j != y} e_j a_j with a_j = z_j k - mk (log2
+// units) and e_j = exp2(a_j).
+//   H = ln s - ln2 * (sum_j e_j a_j) / s            entropy of softmax(z / T)
+//   kl = exp(d) - d - 1, d = l_ref - l              dkl/dl = 1 - exp(d)
+//   total gradient: g_j = (c/T)(1[j=y] - p_j) + (b/T) p_j (ln p_j + H)
+// where ln p_j + H = ln2 (a_j - Abar), Abar = (sum e a)/s: the normaliser cancels, so
+// the entropy part needs no difference of nearly equal numbers even when p_max -> 1.
+__device__ __forceinline__ RowScalars row_scalars_aux(const RowParams &p, long long row, float zy,
+                                                      float mk, float s_excl, float w_excl,
+                                                      float &kl_out, float &H_out)
+{
+    RowScalars o = {};
+    const float ay = fmaf(zy, p.k, -mk);
+    const float e_y = __builtin_amdgcn_exp2f(ay);
+    const float s = s_excl + e_y;
+    float ln_s;
+    if (e_y > s_excl) {  // the sampled token dominates: ln(1 + x) form keeps l accurate
+        const float t = hw_log1p(s_excl / e_y);
+        ln_s = fmaf(ay, kLn2, t);
+        o.logp = -t;
+    } else {
+        ln_s = hw_log(s);
+        o.logp = fmaf(ay, kLn2, -ln_s);
+    }
+    const float log2s = ln_s * kLog2e;
+    o.s = s;
+    o.s_excl = s_excl;
+    o.shift = mk + log2s;
+    const float abar = (w_excl + mul_zero_wins(e_y, ay)) / s;
+    const float H = fmaf(-kLn2, abar, ln_s);
+
+    float dJ;
+    surrogate(p, hw_exp(o.logp - p.old_lp[row]), p.adv[row], o.J, dJ, o.flags);
+    float kl = 0.f, dkl = 0.f;
+    if (p.ref_lp) {
+        const float d = p.ref_lp[row] - o.logp;
+        const float em1 = hw_expm1(d);
+        dkl = -em1;
+        // exp(d) - d - 1: below |d| = 0.1 the difference cancels, the series does not
+        const float series = d * d * (0.5f + d * (1.f / 6 + d * (1.f / 24 + d * (1.f / 120 +
+                             d * (1.f / 720 + d * (1.f / 5040))))));
+        kl = fabsf(d) < 0.1f ? series : em1 - d;
+    }
+    const float inv_D = (float)p.hdr->inv_D;
+    o.c = (p.grad_scale * (-dJ + p.kl_coef * dkl)) * inv_D;
+    o.b = (p.grad_scale * p.ent_coef) * inv_D;
+    o.bq = o.b * p.inv_T * kLn2;
+    o.q2 = fmaf(o.bq, log2s - abar, -o.c * p.inv_T);
+    o.gy_ent = o.bq * mul_zero_wins(e_y / s, ay - abar);
+    kl_out = kl;
+    H_out = H;
     return o;
 }
 
@@ -381,6 +496,94 @@ __device__ __forceinline__ float exp_sum_vec(const u32x4 &z, float k, float mk)
     return part;
 }
 
+// Keeps the instruction scheduler from interleaving the work of different vectors of
+// the unrolled row loops: with 76 registers per lane holding the row, there is room
+// for the temporaries of one vector at a time, not of several.
+#define VECTOR_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// Makes the compiler forget what it knows about a resident vector.  Without this the
+// bf16 -> fp32 widening done in one pass over the row is kept alive for the next pass
+// (common-subexpression elimination), which turns 4 registers per vector into 12 and
+// spills the row to scratch memory.  Emits no instruction.
+__device__ __forceinline__ void forget(u32x4 &v) { asm volatile("" : "+v"(v)); }
+
+// One 32-bit word of a resident vector -> its elements (2 bf16 or 1 f32).
+template <grpo_dtype DT>
+__device__ __forceinline__ void unpack_word(unsigned w, float (&f)[Elem<DT>::EPV / 4])
+{
+    if constexpr (DT == GRPO_BF16) {
+        f[0] = as_f32(w << 16);
+        f[1] = as_f32(w & 0xffff0000u);
+    } else {
+        f[0] = as_f32(w);
+    }
+}
+
+// The same, also accumulating sum_e e_e a_e (a = exponent in log2 units).  The
+// zero-wins multiply returns 0 for 0 * inf, which is what an element at -inf must
+// contribute.  Word by word, with a scheduling fence between words: the auxiliary
+// variants need more temporaries per element and the row leaves room for few.
+template <grpo_dtype DT>
+__device__ __forceinline__ float exp_sum_vec_aux(u32x4 &z, float k, float mk, float &w)
+{
+    constexpr int EPW = Elem<DT>::EPV / 4;
+    float part = 0.f, partw = 0.f;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        float f[EPW];
+        forget(z);  // the widening of word d may not start before this point
+        unpack_word<DT>(z[d], f);
+#pragma unroll
+        for (int e = 0; e < EPW; ++e) {
+            const float a = fmaf(f[e], k, -mk);
+            const float ex = __builtin_amdgcn_exp2f(a);
+            part += ex;
+            partw += mul_zero_wins(ex, a);
+        }
+        // the running sums must exist here: left alone, the additions drift to the end
+        // of the row pass and every product waits for them in a register of its own
+        asm volatile("" : "+v"(part), "+v"(partw));
+        VECTOR_FENCE();
+    }
+    w += partw;
+    asm volatile("" : "+v"(w));
+    return part;
+}
+
+// Gradient of one vector with the entropy term fused in: g_j = p_j (q2 + bq a'_j),
+// a'_j = z_j k - shift = log2 p_j.  Returns the packed vector.
+template <grpo_dtype DT>
+__device__ __forceinline__ u32x4 grad_vec_aux(u32x4 &z, float k, float shift, float q2, float bq,
+                                              bool has_y, int ey, float gy)
+{
+    constexpr int EPW = Elem<DT>::EPV / 4;
+    u32x4 out;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        float f[EPW], g[EPW];
+        forget(z);
+        unpack_word<DT>(z[d], f);
+#pragma unroll
+        for (int e = 0; e < EPW; ++e) {
+            const float a = fmaf(f[e], k, -shift);
+            g[e] = mul_zero_wins(__builtin_amdgcn_exp2f(a), fmaf(bq, a, q2));
+        }
+        if (has_y) {
+#pragma unroll
+            for (int e = 0; e < EPW; ++e)
+                if (d * EPW + e == ey) g[e] = gy;
+        }
+        if constexpr (DT == GRPO_BF16) {
+            f32x2 pr = {g[0], g[1]};
+            out[d] = __builtin_bit_cast(unsigned, __builtin_convertvector(pr, bf16x2));
+        } else {
+            out[d] = as_u32(g[0]);
+        }
+        VECTOR_FENCE();
+    }
+    return out;
+}
+
 // Gradient of one vector: g_j = -(c/T) p_j with p_j = exp2(z_j k - shift), and at
 // the sampled token g_y = (c/T) (1 - p_y) = (c/T) s_excl / s.
 template <grpo_dtype DT>
@@ -408,6 +611,12 @@ __device__ __forceinline__ void write_row_outputs(const RowParams &p, long long 
         p.flags_ws[row] = (unsigned char)flags;
     }
 }
+__device__ __forceinline__ void write_row_aux(const RowParams &p, long long row, float kl, float H)
+{
+    if (p.KL_ws) p.KL_ws[row] = kl;
+    if (p.H_ws) p.H_ws[row] = H;
+    if (p.entropy_out) p.entropy_out[row] = H;
+}
 
 // Decides whether a row takes part; handles the rows that do not (masked, or with a
 // token id outside the vocabulary).  Returns true when the row must be processed.
@@ -429,6 +638,7 @@ __device__ __forceinline__ bool row_is_live(const RowParams &p, long long row, i
     if (threadIdx.x == 0) {
         // log-probs-only mode has no error word: a bad token id shows up as NaN
         write_row_outputs(p, row, (bad && !p.bwd) ? NAN : 0.f, 0.f, 0);
+        write_row_aux(p, row, 0.f, 0.f);
         if (bad && p.bwd) atomicOr(&p.hdr->error, 1);
     }
     if (p.bwd)
@@ -436,11 +646,6 @@ __device__ __forceinline__ bool row_is_live(const RowParams &p, long long row, i
                             threadIdx.x);
     return false;
 }
-
-// Keeps the instruction scheduler from interleaving the work of different vectors of
-// the unrolled row loops: with 76 registers per lane holding the row, there is room
-// for the temporaries of one vector at a time, not of several.
-#define VECTOR_FENCE() __builtin_amdgcn_sched_barrier(0)
 
 // A value every lane holds alike, moved to scalar registers: what is derived from it
 // (row base addresses, loop conditions) then stays scalar too.
@@ -462,17 +667,12 @@ __device__ __forceinline__ void order_after(unsigned &off, X &x)
     asm volatile("" : "+v"(off), "+v"(x));
 }
 
-// Makes the compiler forget what it knows about a resident vector.  Without this the
-// bf16 -> fp32 widening done in one pass over the row is kept alive for the next pass
-// (common-subexpression elimination), which turns 4 registers per vector into 12 and
-// spills the row to scratch memory.  Emits no instruction.
-__device__ __forceinline__ void forget(u32x4 &v) { asm volatile("" : "+v"(v)); }
 
 // ---------------------------------------------------------------------------
 // Register-resident row kernel: requires ceil(vocab / EPV) <= BLOCK * NV.
 // One workgroup per row at a time, rows strided over a persistent grid.
 // ---------------------------------------------------------------------------
-template <grpo_dtype DT, int BLOCK, int NV>
+template <grpo_dtype DT, int BLOCK, int NV, bool AUX, bool TAIL>
 __global__ void __launch_bounds__(BLOCK) grpo_rows_cached(RowParams p)
 {
     constexpr int EPV = Elem<DT>::EPV;
@@ -480,6 +680,7 @@ __global__ void __launch_bounds__(BLOCK) grpo_rows_cached(RowParams p)
     constexpr unsigned SLAB = BLOCK * 16u;  // bytes one pass of the workgroup covers
     __shared__ float lds_max[BLOCK / 64];
     __shared__ float lds_sum[BLOCK / 64];
+    __shared__ float lds_sumw[BLOCK / 64];
     __shared__ long long lds_row[2];
     const int tid = threadIdx.x;
     const unsigned toff = (unsigned)tid * 16u;
@@ -488,7 +689,9 @@ __global__ void __launch_bounds__(BLOCK) grpo_rows_cached(RowParams p)
     // The ragged last vector (vocab not a multiple of EPV) lives in one extra slot
     // that only the first wavefront carries: lane 0 holds the elements, padded with
     // -inf.  Full rows never enter those branches.
-    const bool tail_wave = tail != 0 && tid < 64;
+    // (The widest instantiation has no registers to spare for that slot and is built
+    // without it; ragged rows of that width take the streaming kernel.)
+    const bool tail_wave = TAIL && tail != 0 && tid < 64;
 
     // ---- which row next ----
     // With a workspace (objective + gradient) rows are handed out through a counter in
@@ -581,28 +784,43 @@ __global__ void __launch_bounds__(BLOCK) grpo_rows_cached(RowParams p)
 
         // sum of exponentials over j != y; in log-probs-only mode this is the last use
         // of the row, so the next row is fetched slot by slot behind it
-        float acc = 0.f;
+        float acc = 0.f, accw = 0.f;
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
             forget(buf[i]);
-            acc += exp_sum_vec<DT>(buf[i], p.k, mk);
+            if constexpr (AUX)
+                acc += exp_sum_vec_aux<DT>(buf[i], p.k, mk, accw);
+            else
+                acc += exp_sum_vec<DT>(buf[i], p.k, mk);
             if (!p.bwd && has_next) {
                 order_after(noff, acc);
                 fetch_slot(zrow_next, i);
             }
             VECTOR_FENCE();
         }
-        if (tail_wave) acc += exp_sum_vec<DT>(tbuf, p.k, mk);
+        if (tail_wave) {
+            if constexpr (AUX)
+                acc += exp_sum_vec_aux<DT>(tbuf, p.k, mk, accw);
+            else
+                acc += exp_sum_vec<DT>(tbuf, p.k, mk);
+        }
         const float zy_row = zy;
         if (!p.bwd && has_next) fetch_rest(zrow_next, y_next);
-        const float s_excl = block_sum<BLOCK>(acc, lds_sum);
-
-        const RowScalars sc = row_scalars(p, row, zy_row, mk, s_excl);
+        RowScalars sc;
+        if constexpr (AUX) {
+            block_sum2<BLOCK>(acc, accw, lds_sum, lds_sumw);
+            float kl, H;
+            sc = row_scalars_aux(p, row, zy_row, mk, acc, accw, kl, H);
+            if (tid == 0) write_row_aux(p, row, kl, H);
+        } else {
+            const float s_excl = block_sum<BLOCK>(acc, lds_sum);
+            sc = row_scalars(p, row, zy_row, mk, s_excl);
+        }
         if (tid == 0) write_row_outputs(p, row, sc.logp, sc.J, sc.flags);
 
         if (p.bwd) {
             char *grow = (char *)p.grad + row * p.row_stride * BYTES;
-            if (sc.c == 0.f) {
+            if (sc.c == 0.f && (!AUX || sc.b == 0.f)) {
                 // the gradient of this row is cut: fetch the next row, then zero-fill
                 if (has_next) {
 #pragma unroll
@@ -612,14 +830,19 @@ __global__ void __launch_bounds__(BLOCK) grpo_rows_cached(RowParams p)
                 zero_row<DT, BLOCK>(grow, nvec_full, tail, tid);
             } else {
                 const float q = -sc.c * p.inv_T;
-                const float gy = (sc.c * p.inv_T) * (sc.s_excl / sc.s);
+                const float gy = (sc.c * p.inv_T) * (sc.s_excl / sc.s) + (AUX ? sc.gy_ent : 0.f);
 #pragma unroll
                 for (int i = 0; i < NV; ++i) {
                     const int v = i * BLOCK + tid;
-                    float g[EPV];
                     forget(buf[i]);
-                    grad_vec<DT>(buf[i], p.k, sc.shift, q, v == vy, ey, gy, g);
-                    u32x4 packed = pack<DT>(g);
+                    u32x4 packed;
+                    if constexpr (AUX) {
+                        packed = grad_vec_aux<DT>(buf[i], p.k, sc.shift, sc.q2, sc.bq, v == vy, ey, gy);
+                    } else {
+                        float g[EPV];
+                        grad_vec<DT>(buf[i], p.k, sc.shift, q, v == vy, ey, gy, g);
+                        packed = pack<DT>(g);
+                    }
                     order_after(noff, packed);
                     if (v < nvec_full) st16(grow + (size_t)i * SLAB + toff, packed);
 #if GRPO_BWD_INTERLEAVE
@@ -629,7 +852,12 @@ __global__ void __launch_bounds__(BLOCK) grpo_rows_cached(RowParams p)
                 }
                 if (tail_wave && tid == 0) {
                     float g[EPV];
-                    grad_vec<DT>(tbuf, p.k, sc.shift, q, vy == nvec_full, ey, gy, g);
+                    if constexpr (AUX) {
+                        const u32x4 pk = grad_vec_aux<DT>(tbuf, p.k, sc.shift, sc.q2, sc.bq, vy == nvec_full, ey, gy);
+                        unpack<DT>(pk, g);  // the tail is stored element by element
+                    } else {
+                        grad_vec<DT>(tbuf, p.k, sc.shift, q, vy == nvec_full, ey, gy, g);
+                    }
                     store_vec<DT>(grow, nvec_full, nvec_full, tail, g);
                 }
 #if !GRPO_BWD_INTERLEAVE
@@ -650,13 +878,14 @@ __global__ void __launch_bounds__(BLOCK) grpo_rows_cached(RowParams p)
 // Streaming row kernel for rows too wide for the register file: an online
 // (max, sum) pass and a gradient pass, i.e. 2 reads + 1 write.
 // ---------------------------------------------------------------------------
-template <grpo_dtype DT, int BLOCK>
+template <grpo_dtype DT, int BLOCK, bool AUX>
 __global__ void __launch_bounds__(BLOCK) grpo_rows_streamed(RowParams p)
 {
     constexpr int EPV = Elem<DT>::EPV;
     constexpr int BYTES = Elem<DT>::BYTES;
     __shared__ float lds_max[BLOCK / 64];
     __shared__ float lds_sum[BLOCK / 64];
+    __shared__ float lds_sumw[BLOCK / 64];
     const int tid = threadIdx.x;
     const int nvec_full = (int)(p.vocab / EPV);
     const int tail = (int)(p.vocab % EPV);
@@ -670,8 +899,9 @@ __global__ void __launch_bounds__(BLOCK) grpo_rows_streamed(RowParams p)
         const int vy = (int)(y / EPV);
         const int ey = (int)(y % EPV);
 
-        // online pass: running maximum m (in logit units) and sum relative to it
-        float m = -INFINITY, s = 0.f;
+        // online pass: running maximum m (in logit units), sum s of exponentials relative
+        // to it and, for the entropy, w = sum e a with a the exponent in log2 units
+        float m = -INFINITY, s = 0.f, w = 0.f;
         for (int v = tid; v < nvec; v += BLOCK) {
             const u32x4 z = load_vec<DT>(zrow, v, nvec_full, tail);
             float f[EPV];
@@ -680,26 +910,46 @@ __global__ void __launch_bounds__(BLOCK) grpo_rows_streamed(RowParams p)
 #pragma unroll
             for (int e = 1; e < EPV; ++e) vm = fmaxf(vm, f[e]);
             if (vm > m) {
-                s *= __builtin_amdgcn_exp2f((m - vm) * p.k);  // m = -inf: s is 0 and stays 0
+                // new reference: every exponent so far moves by dlt, every term by 2^dlt
+                const float dlt = (m - vm) * p.k;  // -inf the first time: s and w are 0 and stay 0
+                const float sc_ = __builtin_amdgcn_exp2f(dlt);
+                if constexpr (AUX) w = (s > 0.f) ? sc_ * fmaf(dlt, s, w) : 0.f;
+                s *= sc_;
                 m = vm;
             }
             const float mk_t = m * p.k;
-            float part = 0.f;
+            float part = 0.f, partw = 0.f;
 #pragma unroll
             for (int e = 0; e < EPV; ++e) {
-                float ex = __builtin_amdgcn_exp2f(fmaf(f[e], p.k, -mk_t));
+                const float a = fmaf(f[e], p.k, -mk_t);
+                float ex = __builtin_amdgcn_exp2f(a);
                 if (v == vy && e == ey) ex = 0.f;
                 part += ex;
+                if constexpr (AUX) partw += mul_zero_wins(ex, a);
             }
-            if (m > -INFINITY) s += part;  // all -inf so far: exponents would be NaN
+            if (m > -INFINITY) {  // all -inf so far: exponents would be NaN
+                s += part;
+                w += partw;
+            }
         }
-        const float mx = block_max<BLOCK>(m, lds_max);
+        const float mx = fmaxf(block_max<BLOCK>(m, lds_max), zy);
         const float mk = mx * p.k;
-        const float scaled = (m > -INFINITY) ? s * __builtin_amdgcn_exp2f((m - mx) * p.k) : 0.f;
-        float s_excl = block_sum<BLOCK>(scaled, lds_sum);
-        if (!(mx > -INFINITY)) s_excl = NAN;  // a row of -inf (or NaN) has no softmax
-
-        const RowScalars sc = row_scalars(p, row, zy, mk, s_excl);
+        const float dlt = (m - mx) * p.k;
+        const float sc_ = __builtin_amdgcn_exp2f(dlt);
+        float scaled = (m > -INFINITY) ? s * sc_ : 0.f;
+        float scaledw = (AUX && m > -INFINITY && s > 0.f) ? sc_ * fmaf(dlt, s, w) : 0.f;
+        RowScalars sc;
+        if constexpr (AUX) {
+            block_sum2<BLOCK>(scaled, scaledw, lds_sum, lds_sumw);
+            if (!(mx > -INFINITY)) scaled = NAN;  // a row of -inf (or NaN) has no softmax
+            float kl, H;
+            sc = row_scalars_aux(p, row, zy, mk, scaled, scaledw, kl, H);
+            if (tid == 0) write_row_aux(p, row, kl, H);
+        } else {
+            float s_excl = block_sum<BLOCK>(scaled, lds_sum);
+            if (!(mx > -INFINITY)) s_excl = NAN;
+            sc = row_scalars(p, row, zy, mk, s_excl);
+        }
         if (tid == 0) write_row_outputs(p, row, sc.logp, sc.J, sc.flags);
         // the LDS arrays are reused by the next row: one barrier separates this row's
         // reads of lds_sum from the next row's writes of lds_max/lds_sum
@@ -707,16 +957,21 @@ __global__ void __launch_bounds__(BLOCK) grpo_rows_streamed(RowParams p)
         if (!p.bwd) continue;
 
         char *grow = (char *)p.grad + row * p.row_stride * BYTES;
-        if (sc.c == 0.f) {
+        if (sc.c == 0.f && (!AUX || sc.b == 0.f)) {
             zero_row<DT, BLOCK>(grow, nvec_full, tail, tid);
             continue;
         }
         const float q = -sc.c * p.inv_T;
-        const float gy = (sc.c * p.inv_T) * (sc.s_excl / sc.s);
+        const float gy = (sc.c * p.inv_T) * (sc.s_excl / sc.s) + (AUX ? sc.gy_ent : 0.f);
         for (int v = tid; v < nvec; v += BLOCK) {
-            const u32x4 z = load_vec<DT>(zrow, v, nvec_full, tail);
+            u32x4 z = load_vec<DT>(zrow, v, nvec_full, tail);
             float g[EPV];
-            grad_vec<DT>(z, p.k, sc.shift, q, v == vy, ey, gy, g);
+            if constexpr (AUX) {
+                const u32x4 pk = grad_vec_aux<DT>(z, p.k, sc.shift, sc.q2, sc.bq, v == vy, ey, gy);
+                unpack<DT>(pk, g);  // exact: the values are already rounded
+            } else {
+                grad_vec<DT>(z, p.k, sc.shift, q, v == vy, ey, gy, g);
+            }
             store_vec<DT>(grow, v, nvec_full, tail, g);
         }
     }
@@ -761,40 +1016,61 @@ __global__ void grpo_reset_queue(WsHeader *hdr)
     }
 }
 
-// loss = -(1/D) sum_t J_t in fp64 and a fixed order; indicator counts.
-__global__ void __launch_bounds__(1024) grpo_finalize(const float *J_ws, const unsigned char *flags_ws,
-                                                      long long n, const WsHeader *hdr,
-                                                      float *loss_out, long long *counts_out)
+// loss = -(1/D) sum_t J_t in fp64 and a fixed order; indicator counts.  With the
+// auxiliary arrays (KL_ws, H_ws non-NULL) loss_out has four entries:
+// total = policy + kl_coef * mean kl - ent_coef * mean H, policy, mean kl, mean H.
+__global__ void __launch_bounds__(1024) grpo_finalize(const float *J_ws, const float *KL_ws,
+                                                      const float *H_ws,
+                                                      const unsigned char *flags_ws, long long n,
+                                                      const WsHeader *hdr, float kl_coef,
+                                                      float ent_coef, float *loss_out,
+                                                      long long *counts_out)
 {
-    __shared__ double lds_j[16];
+    __shared__ double lds_j[16][3];
     __shared__ long long lds_c[16][4];
-    double sj = 0.0;
+    const bool aux = KL_ws != nullptr;
+    double sj[3] = {0.0, 0.0, 0.0};
     long long c[4] = {0, 0, 0, 0};
     for (long long i = threadIdx.x; i < n; i += 1024) {
-        sj += (double)J_ws[i];
+        sj[0] += (double)J_ws[i];
+        if (aux) {
+            sj[1] += (double)KL_ws[i];
+            sj[2] += (double)H_ws[i];
+        }
         const int fl = flags_ws[i];
         c[0] += (fl & kFlagClipHigh) ? 1 : 0;
         c[1] += (fl & kFlagClipLow) ? 1 : 0;
         c[2] += (fl & kFlagDelta) ? 1 : 0;
         c[3] += (fl & kFlagOutOfBand) ? 1 : 0;
     }
-    sj = wave_sum(sj);
+#pragma unroll
+    for (int q = 0; q < 3; ++q) sj[q] = wave_sum(sj[q]);
 #pragma unroll
     for (int q = 0; q < 4; ++q) c[q] = wave_sum(c[q]);
     if ((threadIdx.x & 63) == 0) {
-        lds_j[threadIdx.x >> 6] = sj;
+#pragma unroll
+        for (int q = 0; q < 3; ++q) lds_j[threadIdx.x >> 6][q] = sj[q];
 #pragma unroll
         for (int q = 0; q < 4; ++q) lds_c[threadIdx.x >> 6][q] = c[q];
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-        double tot = 0.0;
+        double tot[3] = {0.0, 0.0, 0.0};
         long long t[4] = {0, 0, 0, 0};
         for (int w = 0; w < 16; ++w) {
-            tot += lds_j[w];
+            for (int q = 0; q < 3; ++q) tot[q] += lds_j[w][q];
             for (int q = 0; q < 4; ++q) t[q] += lds_c[w][q];
         }
-        *loss_out = (float)(0.0 - tot * hdr->inv_D);
+        const double policy = 0.0 - tot[0] * hdr->inv_D;
+        if (aux) {
+            const double klm = tot[1] * hdr->inv_D, hm = tot[2] * hdr->inv_D;
+            loss_out[0] = (float)(policy + (double)kl_coef * klm - (double)ent_coef * hm);
+            loss_out[1] = (float)policy;
+            loss_out[2] = (float)klm;
+            loss_out[3] = (float)hm;
+        } else {
+            loss_out[0] = (float)policy;
+        }
         if (counts_out) {
             counts_out[GRPO_COUNT_TOKENS] = hdr->M;
             counts_out[GRPO_COUNT_CLIP_HIGH] = t[0];
@@ -864,32 +1140,34 @@ int cu_count()
     return cached[dev];
 }
 
-template <grpo_dtype DT, int BLOCK, int NV>
+template <grpo_dtype DT, int BLOCK, int NV, bool AUX, bool TAIL>
 void launch_cached(const RowParams &p, int blocks_per_cu, hipStream_t st)
 {
     long long grid = (long long)cu_count() * blocks_per_cu;
     if (grid > p.n_tokens) grid = p.n_tokens;
-    hipLaunchKernelGGL((grpo_rows_cached<DT, BLOCK, NV>), dim3((unsigned)grid), dim3(BLOCK), 0, st, p);
+    hipLaunchKernelGGL((grpo_rows_cached<DT, BLOCK, NV, AUX, TAIL>), dim3((unsigned)grid), dim3(BLOCK), 0,
+                       st, p);
 }
 
-template <grpo_dtype DT>
+template <grpo_dtype DT, bool AUX>
 void launch_rows(const RowParams &p, hipStream_t st)
 {
     const long long nvec = (p.vocab + Elem<DT>::EPV - 1) / Elem<DT>::EPV;
+    const bool ragged = p.vocab % Elem<DT>::EPV != 0;
     if (nvec <= 256 * 1)
-        launch_cached<DT, 256, 1>(p, 8, st);
+        launch_cached<DT, 256, 1, AUX, true>(p, 8, st);
     else if (nvec <= 256 * 4)
-        launch_cached<DT, 256, 4>(p, 8, st);
+        launch_cached<DT, 256, 4, AUX, true>(p, 8, st);
     else if (nvec <= 1024 * 4)
-        launch_cached<DT, 1024, 4>(p, 2, st);
+        launch_cached<DT, 1024, 4, AUX, true>(p, 2, st);
     else if (nvec <= 1024 * 10)
-        launch_cached<DT, 1024, 10>(p, 1, st);
-    else if (nvec <= 1024 * 19)
-        launch_cached<DT, 1024, 19>(p, 1, st);
+        launch_cached<DT, 1024, 10, AUX, true>(p, 1, st);
+    else if (nvec <= 1024 * 19 && !ragged)
+        launch_cached<DT, 1024, 19, AUX, false>(p, 1, st);
     else {
         long long grid = (long long)cu_count() * 2;
         if (grid > p.n_tokens) grid = p.n_tokens;
-        hipLaunchKernelGGL((grpo_rows_streamed<DT, 1024>), dim3((unsigned)grid), dim3(1024), 0, st, p);
+        hipLaunchKernelGGL((grpo_rows_streamed<DT, 1024, AUX>), dim3((unsigned)grid), dim3(1024), 0, st, p);
     }
 }
 
@@ -907,6 +1185,84 @@ grpo_status check_logits_args(const void *logits, grpo_dtype dtype, int64_t n_to
 }
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+grpo_status loss_impl(bool aux, const void *logits, grpo_dtype dtype, int64_t n_tokens, int64_t vocab,
+                      int64_t row_stride, const int64_t *tokens, const float *old_logprobs,
+                      const float *ref_logprobs, const float *advantages, const uint8_t *mask,
+                      float eps_low, float eps_high, float delta, float temperature, float kl_coef,
+                      float entropy_coef, double denom, float grad_scale, float *loss_out,
+                      float *logprobs_out, float *entropy_out, int64_t *counts_out,
+                      void *grad_logits, void *workspace, size_t workspace_bytes, void *stream)
+{
+    grpo_status rc = check_logits_args(logits, dtype, n_tokens, vocab, row_stride, tokens, temperature);
+    if (rc != GRPO_OK) return rc;
+    if (!(eps_low >= 0.f && eps_low <= 1.f) || !(eps_high >= 0.f) || !std::isfinite(eps_high) ||
+        !(delta > 1.f + eps_high) || std::isnan(denom) || std::isnan(grad_scale) ||
+        !std::isfinite(kl_coef) || !std::isfinite(entropy_coef))
+        return GRPO_ERR_PARAM;
+    if (!loss_out) return GRPO_ERR_NULL;
+    if (n_tokens > 0 && (!old_logprobs || !advantages || !grad_logits)) return GRPO_ERR_NULL;
+    if (n_tokens > 0 && kl_coef != 0.f && !ref_logprobs) return GRPO_ERR_NULL;
+    if (n_tokens > 0 && ((uintptr_t)grad_logits & 15u) != 0) return GRPO_ERR_ALIGN;
+    if (!workspace || ((uintptr_t)workspace & 255u) != 0 ||
+        workspace_bytes < grpo_workspace_bytes(n_tokens))
+        return GRPO_ERR_WORKSPACE;
+
+    char *ws = (char *)workspace;
+    const size_t col = align_up((size_t)n_tokens * 4, 256);
+    WsHeader *hdr = (WsHeader *)ws;
+    float *J_ws = (float *)(ws + kHeaderBytes);
+    float *KL_ws = (float *)(ws + kHeaderBytes + col);
+    float *H_ws = (float *)(ws + kHeaderBytes + 2 * col);
+    unsigned char *flags_ws = (unsigned char *)(ws + kHeaderBytes + 3 * col);
+    hipStream_t st = (hipStream_t)stream;
+
+    hipLaunchKernelGGL(grpo_prepare, dim3(1), dim3(1024), 0, st, mask, (long long)n_tokens, denom, hdr);
+    if (n_tokens > 0) {
+        RowParams p = {};
+        p.logits = logits;
+        p.grad = grad_logits;
+        p.tokens = (const long long *)tokens;
+        p.old_lp = old_logprobs;
+        p.adv = advantages;
+        p.mask = mask;
+        p.logprobs_out = logprobs_out;
+        p.J_ws = J_ws;
+        p.flags_ws = flags_ws;
+        p.hdr = hdr;
+        p.n_tokens = n_tokens;
+        p.vocab = vocab;
+        p.row_stride = row_stride;
+        p.inv_T = 1.0f / temperature;
+        p.k = (float)((double)kLog2e / (double)temperature);
+        p.lo = 1.0f - eps_low;
+        p.hi = 1.0f + eps_high;
+        p.delta = delta;
+        p.grad_scale = grad_scale;
+        p.bwd = 1;
+        if (aux) {
+            p.ref_lp = kl_coef != 0.f ? ref_logprobs : nullptr;
+            p.KL_ws = KL_ws;
+            p.H_ws = H_ws;
+            p.entropy_out = entropy_out;
+            p.kl_coef = kl_coef;
+            p.ent_coef = entropy_coef;
+            if (dtype == GRPO_BF16)
+                launch_rows<GRPO_BF16, true>(p, st);
+            else
+                launch_rows<GRPO_F32, true>(p, st);
+        } else {
+            if (dtype == GRPO_BF16)
+                launch_rows<GRPO_BF16, false>(p, st);
+            else
+                launch_rows<GRPO_F32, false>(p, st);
+        }
+    }
+    hipLaunchKernelGGL(grpo_finalize, dim3(1), dim3(1024), 0, st, J_ws,
+                       aux ? KL_ws : (const float *)nullptr, H_ws, flags_ws, (long long)n_tokens, hdr,
+                       kl_coef, entropy_coef, loss_out, (long long *)counts_out);
+    return hipGetLastError() == hipSuccess ? GRPO_OK : GRPO_ERR_HIP;
+}
 
 }  // namespace
 
@@ -932,8 +1288,8 @@ const char *grpo_status_string(grpo_status status)
 size_t grpo_workspace_bytes(int64_t n_tokens)
 {
     if (n_tokens < 0) return 0;
-    // header | J per row (f32) | indicator bits per row (u8)
-    return kHeaderBytes + align_up((size_t)n_tokens * 4, 256) + align_up((size_t)n_tokens, 256);
+    // header | J, KL estimate, entropy per row (f32 each) | indicator bits per row (u8)
+    return kHeaderBytes + 3 * align_up((size_t)n_tokens * 4, 256) + align_up((size_t)n_tokens, 256);
 }
 
 grpo_status grpo_group_advantages(const float *rewards, int64_t n_rollouts,
@@ -992,9 +1348,9 @@ grpo_status grpo_logprobs_fwd(const void *logits, grpo_dtype dtype, int64_t n_to
     hipStream_t st = (hipStream_t)stream;
     if (workspace) hipLaunchKernelGGL(grpo_reset_queue, dim3(1), dim3(64), 0, st, p.hdr);
     if (dtype == GRPO_BF16)
-        launch_rows<GRPO_BF16>(p, st);
+        launch_rows<GRPO_BF16, false>(p, st);
     else
-        launch_rows<GRPO_F32>(p, st);
+        launch_rows<GRPO_F32, false>(p, st);
     return hipGetLastError() == hipSuccess ? GRPO_OK : GRPO_ERR_HIP;
 }
 
@@ -1006,56 +1362,26 @@ grpo_status grpo_loss_fwd_bwd(const void *logits, grpo_dtype dtype, int64_t n_to
                               int64_t *counts_out, void *grad_logits, void *workspace,
                               size_t workspace_bytes, void *stream)
 {
-    grpo_status rc = check_logits_args(logits, dtype, n_tokens, vocab, row_stride, tokens, temperature);
-    if (rc != GRPO_OK) return rc;
-    if (!(eps_low >= 0.f && eps_low <= 1.f) || !(eps_high >= 0.f) || !std::isfinite(eps_high) ||
-        !(delta > 1.f + eps_high) || std::isnan(denom) || std::isnan(grad_scale))
-        return GRPO_ERR_PARAM;
-    if (!loss_out) return GRPO_ERR_NULL;
-    if (n_tokens > 0 && (!old_logprobs || !advantages || !grad_logits)) return GRPO_ERR_NULL;
-    if (n_tokens > 0 && ((uintptr_t)grad_logits & 15u) != 0) return GRPO_ERR_ALIGN;
-    if (!workspace || ((uintptr_t)workspace & 255u) != 0 ||
-        workspace_bytes < grpo_workspace_bytes(n_tokens))
-        return GRPO_ERR_WORKSPACE;
+    return loss_impl(false, logits, dtype, n_tokens, vocab, row_stride, tokens, old_logprobs, nullptr,
+                     advantages, mask, eps_low, eps_high, delta, temperature, 0.f, 0.f, denom,
+                     grad_scale, loss_out, logprobs_out, nullptr, counts_out, grad_logits, workspace,
+                     workspace_bytes, stream);
+}
 
-    char *ws = (char *)workspace;
-    WsHeader *hdr = (WsHeader *)ws;
-    float *J_ws = (float *)(ws + kHeaderBytes);
-    unsigned char *flags_ws =
-        (unsigned char *)(ws + kHeaderBytes + align_up((size_t)n_tokens * 4, 256));
-    hipStream_t st = (hipStream_t)stream;
-
-    hipLaunchKernelGGL(grpo_prepare, dim3(1), dim3(1024), 0, st, mask, (long long)n_tokens, denom, hdr);
-    if (n_tokens > 0) {
-        RowParams p = {};
-        p.logits = logits;
-        p.grad = grad_logits;
-        p.tokens = (const long long *)tokens;
-        p.old_lp = old_logprobs;
-        p.adv = advantages;
-        p.mask = mask;
-        p.logprobs_out = logprobs_out;
-        p.J_ws = J_ws;
-        p.flags_ws = flags_ws;
-        p.hdr = hdr;
-        p.n_tokens = n_tokens;
-        p.vocab = vocab;
-        p.row_stride = row_stride;
-        p.inv_T = 1.0f / temperature;
-        p.k = (float)((double)kLog2e / (double)temperature);
-        p.lo = 1.0f - eps_low;
-        p.hi = 1.0f + eps_high;
-        p.delta = delta;
-        p.grad_scale = grad_scale;
-        p.bwd = 1;
-        if (dtype == GRPO_BF16)
-            launch_rows<GRPO_BF16>(p, st);
-        else
-            launch_rows<GRPO_F32>(p, st);
-    }
-    hipLaunchKernelGGL(grpo_finalize, dim3(1), dim3(1024), 0, st, J_ws, flags_ws, (long long)n_tokens,
-                       hdr, loss_out, (long long *)counts_out);
-    return hipGetLastError() == hipSuccess ? GRPO_OK : GRPO_ERR_HIP;
+grpo_status grpo_loss_aux_fwd_bwd(const void *logits, grpo_dtype dtype, int64_t n_tokens,
+                                  int64_t vocab, int64_t row_stride, const int64_t *tokens,
+                                  const float *old_logprobs, const float *ref_logprobs,
+                                  const float *advantages, const uint8_t *mask, float eps_low,
+                                  float eps_high, float delta, float temperature, float kl_coef,
+                                  float entropy_coef, double denom, float grad_scale,
+                                  float *loss_out, float *logprobs_out, float *entropy_out,
+                                  int64_t *counts_out, void *grad_logits, void *workspace,
+                                  size_t workspace_bytes, void *stream)
+{
+    return loss_impl(true, logits, dtype, n_tokens, vocab, row_stride, tokens, old_logprobs,
+                     ref_logprobs, advantages, mask, eps_low, eps_high, delta, temperature, kl_coef,
+                     entropy_coef, denom, grad_scale, loss_out, logprobs_out, entropy_out, counts_out,
+                     grad_logits, workspace, workspace_bytes, stream);
 }
 
 grpo_status grpo_workspace_error(const void *workspace, int32_t *flag_out, void *stream)

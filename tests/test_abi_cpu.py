@@ -21,7 +21,7 @@ def declared_functions():
 
 def test_library_exports_every_declared_symbol():
     names = declared_functions()
-    assert {"grpo_group_advantages", "grpo_logprobs_fwd", "grpo_loss_fwd_bwd",
+    assert {"grpo_group_advantages", "grpo_logprobs_fwd", "grpo_loss_fwd_bwd", "grpo_loss_aux_fwd_bwd",
             "grpo_workspace_bytes", "grpo_status_string", "grpo_workspace_error"} <= set(names)
     L = grpo.lib()
     for n in names:
@@ -36,7 +36,7 @@ def test_status_strings_and_workspace_size():
     assert grpo.grpo_workspace_bytes(0) == 256
     for n in (1, 255, 256, 257, 131072):
         b = grpo.grpo_workspace_bytes(n)
-        assert b % 256 == 0 and b >= 256 + 5 * n
+        assert b % 256 == 0 and b >= 256 + 13 * n
 
 
 def loss_args(**over):
@@ -101,3 +101,24 @@ def test_binding_refuses_cpu_tensors():
     z = torch.zeros(4, 64)
     with pytest.raises(ValueError):
         grpo.grpo_logprobs_fwd(z, torch.zeros(4, dtype=torch.int64))
+
+
+def aux_args(**over):
+    a = dict(logits=P, dtype=1, n=16, V=1024, stride=1024, tokens=P, old=P, ref=P, adv=P, mask=P,
+             el=0.2, eh=0.2, delta=4.0, T=1.0, klc=0.001, enc=1e-4, denom=0.0, gs=1.0, loss=P, lp=P,
+             ent=P, counts=P, grad=P, ws=P, ws_bytes=1 << 20, stream=None)
+    a.update(over)
+    return [a[k] for k in ("logits", "dtype", "n", "V", "stride", "tokens", "old", "ref", "adv", "mask",
+                           "el", "eh", "delta", "T", "klc", "enc", "denom", "gs", "loss", "lp", "ent",
+                           "counts", "grad", "ws", "ws_bytes", "stream")]
+
+
+@pytest.mark.parametrize("over,expect", [
+    (dict(ref=None), NULL),                       # a KL term needs reference log-probs
+    (dict(old=None), NULL), (dict(loss=None), NULL), (dict(grad=None), NULL),
+    (dict(klc=float("nan")), PARAM), (dict(enc=float("inf")), PARAM), (dict(delta=1.1), PARAM),
+    (dict(T=0.0), PARAM), (dict(V=0), SHAPE), (dict(dtype=7), DTYPE), (dict(logits=P + 2), ALIGN),
+    (dict(ws_bytes=256 + 5 * 16), WORKSPACE), (dict(ws=None), WORKSPACE),
+])
+def test_loss_aux_rejects_bad_arguments_before_any_launch(over, expect):
+    assert grpo.lib().grpo_loss_aux_fwd_bwd(*aux_args(**over)) == expect

@@ -1,0 +1,140 @@
+"""GPU parity of the objective with the auxiliary KL and entropy terms fused in
+(grpo_loss_aux_fwd_bwd) against the fp64 oracle.
+
+Same bars as the plain objective: log-probs 2e-4 abs, total / policy loss 1e-4 rel,
+gradient 4e-3 x row max, counters exact.  The two new scalars: mean KL estimate
+1e-4 rel (+1e-9 abs), mean entropy 1e-4 rel (+2e-7 abs: ln(1 + x) of the fp32
+normaliser cannot resolve x below 6e-8, so entropies of that size carry that absolute
+error); per-token entropy 2e-4 abs like the log-probs.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2505_07291_amd as grpo
+from paper_2505_07291_amd import workloads as wl
+from oracle import grpo_oracle as orc
+from helpers import grads_to_f64, logits_to_numpy, oracle_logprobs_blocked
+from test_gpu_parity import DEV, REDUCED, TOL_GRAD, TOL_LOGP, TOL_LOSS_REL, f32, say
+
+pytestmark = pytest.mark.gpu
+
+
+def run_aux_case(batch, old, ref, adv_f32, kl_coef, ent_coef, *, denom=0.0, grad_scale=1.0, label=""):
+    T = f32(batch["temperature"])
+    kw = dict(eps_low=f32(batch["eps_low"]), eps_high=f32(batch["eps_high"]), delta=f32(batch["delta"]))
+    N, V = batch["n_tokens"], batch["vocab"]
+    z = logits_to_numpy(batch["logits"])
+    tokens_np = batch["tokens"].cpu().numpy()
+    mask_np = None if batch["mask"] is None else batch["mask"].cpu().numpy()
+    ref_np = None if ref is None else ref.numpy()
+    want = orc.aux_loss_fwd_bwd(z, tokens_np, old.numpy(), ref_np, adv_f32, mask_np, temperature=T,
+                                kl_coef=f32(kl_coef), ent_coef=f32(ent_coef), denom=denom,
+                                grad_scale=f32(grad_scale), grad_rows="all", vocab=V, **kw)
+    say("[gpu] %s grpo_loss_aux_fwd_bwd N=%d V=%d kl_coef=%g ent_coef=%g" % (label, N, V, kl_coef, ent_coef))
+    loss, lp, ent, counts, grad = grpo.grpo_loss_aux_fwd_bwd(
+        batch["logits"], batch["tokens"], old.to(DEV), None if ref is None else ref.to(DEV),
+        torch.as_tensor(adv_f32, device=DEV), batch["mask"], temperature=T, kl_coef=kl_coef,
+        entropy_coef=ent_coef, denom=denom, grad_scale=grad_scale, **kw)
+    torch.cuda.synchronize()
+    got = loss.cpu().numpy().astype(np.float64)
+    e_lp = np.max(np.abs(lp.cpu().numpy() - want["logprobs"]))
+    e_h = np.max(np.abs(ent.cpu().numpy() - want["entropies"]))
+    assert e_lp <= TOL_LOGP and e_h <= 2e-4, (e_lp, e_h)
+    assert counts.cpu().numpy().tolist() == want["counts"].tolist()
+    assert abs(got[0] - want["total"]) <= TOL_LOSS_REL * abs(want["total"]) + 1e-12, (got[0], want["total"])
+    assert abs(got[1] - want["policy"]) <= TOL_LOSS_REL * abs(want["policy"]) + 1e-12
+    assert abs(got[2] - want["kl"]) <= 1e-4 * want["kl"] + 1e-9, (got[2], want["kl"])
+    assert abs(got[3] - want["entropy"]) <= 1e-4 * want["entropy"] + 2e-7, (got[3], want["entropy"])
+    g = grads_to_f64(grad)
+    rowmax = np.max(np.abs(want["grad"]), axis=1)
+    err = np.max(np.abs(g - want["grad"]), axis=1)
+    zero = rowmax == 0
+    assert not g[zero].any(), "a zero-gradient row is not exactly zero"
+    worst = float(np.max(err[~zero] / rowmax[~zero])) if (~zero).any() else 0.0
+    assert worst <= TOL_GRAD, "grad error %g x row max" % worst
+    say("      ok: |dl|=%.1e |dH|=%.1e total=%.6g kl=%.4g H=%.6g grad=%.2e x rowmax" %
+        (e_lp, e_h, got[0], got[2], got[3], worst))
+    return dict(loss=loss, logprobs=lp, grad=grad, counts=counts, want=want)
+
+
+@pytest.mark.parametrize("name", list(REDUCED))
+@pytest.mark.parametrize("coefs", [(0.001, 1e-4), (0.05, 0.02)], ids=["paper_coefs", "large_coefs"])
+def test_aux_reduced_configs_every_element(name, coefs):
+    """Section 4.1 coefficients (KL 0.001, entropy 1e-4) and larger ones that make the two
+    terms a visible part of the gradient, on every config's recipe."""
+    cfg = REDUCED[name]
+    say("\n[case] aux reduced %s: N=%d V=%d" % (name, cfg.n_tokens, cfg.vocab))
+    batch = wl.make_batch(cfg, DEV)
+    rewards = batch["rewards"].cpu().numpy()
+    adv = orc.group_advantages(rewards, group_size=cfg.group_size, eps_std=f32(1e-6))
+    adv_tok = orc.broadcast_advantages(adv, batch["rollout_of_token"].cpu().numpy()).astype(np.float32)
+    lp_orc = oracle_logprobs_blocked(batch)
+    old = wl.make_old_logprobs(cfg, lp_orc)
+    g = torch.Generator().manual_seed(900 + cfg.index)
+    ref = (torch.as_tensor(lp_orc) + torch.randn(cfg.n_tokens, generator=g, dtype=torch.float64) * 0.1).float()
+    run_aux_case(batch, old, ref, adv_tok, coefs[0], coefs[1], label=name)
+
+
+def test_aux_with_zero_coefficients_equals_the_plain_objective():
+    cfg = REDUCED["qwen_short"]
+    batch = wl.make_batch(cfg, DEV)
+    lp_orc = oracle_logprobs_blocked(batch)
+    old = wl.make_old_logprobs(cfg, lp_orc).to(DEV)
+    adv = torch.randn(cfg.n_tokens, generator=torch.Generator().manual_seed(5)).to(DEV)
+    a = grpo.grpo_loss_fwd_bwd(batch["logits"], batch["tokens"], old, adv, batch["mask"])
+    b = grpo.grpo_loss_aux_fwd_bwd(batch["logits"], batch["tokens"], old, None, adv, batch["mask"])
+    torch.cuda.synchronize()
+    # the auxiliary kernel takes the accurate ln(1 + x) route for dominant tokens, so the
+    # log-probs may differ in the last bits; the bars of the plain objective still hold
+    assert torch.equal(a[2], b[3])
+    assert abs(float(a[0]) - float(b[0][0])) <= 1e-6 * abs(float(a[0]))
+    assert float(b[0][0]) == float(b[0][1]) and float(b[0][2]) == 0.0
+    ga, gb = a[3].float(), b[4].float()
+    rowmax = ga.abs().amax(dim=1)
+    assert bool(((ga - gb).abs().amax(dim=1) <= 4e-3 * rowmax).all())
+    assert bool((gb[rowmax == 0] == 0).all())
+
+
+@pytest.mark.parametrize("dtype,vocab,stride", [("bf16", 5, 8), ("bf16", 2047, 2048), ("bf16", 50257, 50264),
+                                                ("bf16", 152069, 152072), ("bf16", 200003, 200008),
+                                                ("f32", 1000, 1004), ("f32", 100003, 100004)])
+def test_aux_ragged_shapes(dtype, vocab, stride):
+    N = 29
+    say("\n[case] aux ragged dtype=%s V=%d stride=%d" % (dtype, vocab, stride))
+    g = torch.Generator().manual_seed(vocab * 3 + 1)
+    dt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    store = torch.full((N, stride), 7.0, dtype=dt)
+    store[:, :vocab] = (torch.randn((N, vocab), generator=g) * 3).to(dt)
+    if vocab > 100:
+        store[3, 10:60] = float("-inf")                       # masked vocabulary entries
+    store = store.to(DEV)
+    tokens = torch.randint(0, vocab, (N,), generator=g)
+    tokens[3] = 0
+    mask = (torch.rand(N, generator=g) > 0.2).to(torch.uint8)
+    mask[:4] = 1
+    batch = dict(logits=store[:, :vocab], tokens=tokens.to(DEV), mask=mask.to(DEV), n_tokens=N,
+                 vocab=vocab, temperature=0.8, eps_low=0.2, eps_high=0.28, delta=3.0)
+    lp_orc = oracle_logprobs_blocked(batch)
+    noise = torch.rand(N, generator=g, dtype=torch.float64) * 3 - 1.5
+    kinks = np.log([0.8, 1.28, 3.0])
+    for t in range(N):
+        while np.min(np.abs(-float(noise[t]) - kinks)) < 1e-3:
+            noise[t] = torch.rand(1, generator=g, dtype=torch.float64)[0] * 3 - 1.5
+    old = (torch.as_tensor(lp_orc) + noise).float()
+    ref = (torch.as_tensor(lp_orc) + torch.randn(N, generator=g, dtype=torch.float64) * 0.3).float()
+    adv = torch.randn(N, generator=g).numpy().astype(np.float32)
+    adv[2] = 0.0
+    run_aux_case(batch, old, ref, adv, 0.04, 0.03, denom=40.0, grad_scale=1.5, label="ragged")
+    assert bool((store[:, vocab:] == 7.0).all())
+
+
+def test_aux_only_entropy_no_reference():
+    """kl_coef = 0 with ref_logprobs = NULL is legal; clipped rows still get the entropy gradient."""
+    cfg = REDUCED["numerics_stress"]
+    batch = wl.make_batch(cfg, DEV)
+    lp_orc = oracle_logprobs_blocked(batch)
+    old = wl.make_old_logprobs(cfg, lp_orc)
+    adv = np.where(np.arange(cfg.n_tokens) % 3 == 0, 0.0, 1.0).astype(np.float32)
+    out = run_aux_case(batch, old, None, adv, 0.0, 0.05, label="entropy only")
+    assert out["want"]["kl"] == 0.0
