@@ -178,6 +178,27 @@ def main():
     torch.cuda.synchronize()
     fwd_ms = sum(a.elapsed_time(b) for a, b in fwd_evs[3:]) / len(fwd_evs[3:])
 
+    # the objective with the KL and entropy terms fused in (section 4.1 coefficients),
+    # on the benchmark's own batch
+    ref = wl.make_old_logprobs(cfg, new_lp, seed=cfg.index + 77).to(dev)
+    loss4 = torch.empty(4, dtype=torch.float32, device=dev)
+    ent = torch.empty(N, dtype=torch.float32, device=dev)
+    aux_evs = []
+    for i in range(3 + max(5, args.steps // 3)):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        grpo.grpo_loss_aux_fwd_bwd(batch["logits"], batch["tokens"], old, ref, adv_tok, batch["mask"],
+                                   cfg.eps_low, cfg.eps_high, cfg.delta, cfg.temperature, 0.001, 1e-4,
+                                   0.0, 1.0, grad_logits=grad, loss_out=loss4, logprobs_out=lp,
+                                   entropy_out=ent, counts_out=counts, workspace=ws, stream=stream)
+        b.record(stream)
+        aux_evs.append((a, b))
+    torch.cuda.synchronize()
+    aux_ms = sum(a.elapsed_time(b) for a, b in aux_evs[3:]) / len(aux_evs[3:])
+    aux_vals = loss4.cpu().tolist()
+    # with an entropy term every unmasked row gets a gradient: 2 reads + 1 write each
+    aux_alg = row_bytes * (3 * M + 1 * n_masked) + 37 * N
+
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
@@ -209,6 +230,12 @@ def main():
                       "frac_2r1w": conv_bytes / kern_full / 1e9 / HBM_PEAK_GBPS,
                       "gbps_design_traffic_1r1w": 2 * N * row_bytes / kern_full / 1e9,
                       "rows_live": full_counts[0]},
+        "aux_loss": {"note": "grpo_loss_aux_fwd_bwd on the same batch, KL 0.001 and entropy 1e-4 fused in",
+                     "tokens_per_s": N / (aux_ms * 1e-3), "kernel_ms": aux_ms,
+                     "achieved_gbps": aux_alg / (aux_ms * 1e-3) / 1e9,
+                     "frac": aux_alg / (aux_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                     "total": aux_vals[0], "policy": aux_vals[1], "mean_kl": aux_vals[2],
+                     "mean_entropy": aux_vals[3]},
         "logprobs_fwd": {"note": "grpo_logprobs_fwd, every row unmasked: one read of the logits",
                          "tokens_per_s": N / (fwd_ms * 1e-3), "kernel_ms": fwd_ms,
                          "gbps": N * row_bytes / (fwd_ms * 1e-3) / 1e9,

@@ -284,14 +284,10 @@ __device__ __forceinline__ float block_sum(float v, float *lds)
     return r;
 }
 
-// a * b with 0 * anything = 0, also for an infinite b (v_mul_legacy_f32): an element at
-// -inf has probability 0 and must contribute 0 to sum p log p, not NaN.
-__device__ __forceinline__ float mul_zero_wins(float a, float b)
-{
-    float r;
-    asm("v_mul_legacy_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
-    return r;
-}
+// Exponents (log2 units) are kept above this floor before they are multiplied by their
+// probability: an element at -inf has probability 0 and must contribute 0 to
+// sum p log p, not 0 * inf = NaN.  2^-1e30 is 0 all the same.
+constexpr float kExpFloor = -1.0e30f;
 
 // Two sums behind one barrier.
 template <int BLOCK>
@@ -327,7 +323,7 @@ struct RowScalars {
     int flags;
     // auxiliary terms: b = weight of -H in the gradient, q2 and bq the two constants of
     // the fused gradient g_j = p_j (q2 + bq a'_j), gy_ent the entropy part of g_y
-    float b, q2, bq, gy_ent;
+    float b, q2, bq, gy_ent, mx, log2s;
 };
 
 // Scalar transcendental functions of the once-per-row arithmetic, built on the
@@ -394,18 +390,18 @@ __device__ __forceinline__ RowScalars row_scalars(const RowParams &p, long long 
 
 // The same with the auxiliary terms (sampled-token KL estimator against a reference
 // policy, entropy bonus).  w_excl = sum_{j != y} e_j a_j with a_j = z_j k - mk (log2
-// units) and e_j = exp2(a_j).
+// units), a_j = (z_j - max) k here, and e_j = exp2(a_j).
 //   H = ln s - ln2 * (sum_j e_j a_j) / s            entropy of softmax(z / T)
 //   kl = exp(d) - d - 1, d = l_ref - l              dkl/dl = 1 - exp(d)
 //   total gradient: g_j = (c/T)(1[j=y] - p_j) + (b/T) p_j (ln p_j + H)
 // where ln p_j + H = ln2 (a_j - Abar), Abar = (sum e a)/s: the normaliser cancels, so
 // the entropy part needs no difference of nearly equal numbers even when p_max -> 1.
 __device__ __forceinline__ RowScalars row_scalars_aux(const RowParams &p, long long row, float zy,
-                                                      float mk, float s_excl, float w_excl,
+                                                      float mx, float s_excl, float w_excl,
                                                       float &kl_out, float &H_out)
 {
     RowScalars o = {};
-    const float ay = fmaf(zy, p.k, -mk);
+    const float ay = (zy - mx) * p.k;
     const float e_y = __builtin_amdgcn_exp2f(ay);
     const float s = s_excl + e_y;
     float ln_s;
@@ -420,8 +416,10 @@ __device__ __forceinline__ RowScalars row_scalars_aux(const RowParams &p, long l
     const float log2s = ln_s * kLog2e;
     o.s = s;
     o.s_excl = s_excl;
-    o.shift = mk + log2s;
-    const float abar = (w_excl + mul_zero_wins(e_y, ay)) / s;
+    o.mx = mx;
+    o.log2s = log2s;
+    const float ay_f = fmaxf(ay, kExpFloor);
+    const float abar = fmaf(e_y, ay_f, w_excl) / s;
     const float H = fmaf(-kLn2, abar, ln_s);
 
     float dJ;
@@ -441,7 +439,7 @@ __device__ __forceinline__ RowScalars row_scalars_aux(const RowParams &p, long l
     o.b = (p.grad_scale * p.ent_coef) * inv_D;
     o.bq = o.b * p.inv_T * kLn2;
     o.q2 = fmaf(o.bq, log2s - abar, -o.c * p.inv_T);
-    o.gy_ent = o.bq * mul_zero_wins(e_y / s, ay - abar);
+    o.gy_ent = o.bq * ((e_y / s) * (ay_f - abar));
     kl_out = kl;
     H_out = H;
     return o;
@@ -469,14 +467,18 @@ __device__ __forceinline__ void set_neg_inf(u32x4 &v, int e)
 // element's bits as extra mantissa: that moves it by less than one bf16 ulp, which is
 // immaterial for a shift (any value near the maximum does) and saves the masking.
 // A raw word whose upper half is +-inf reads as NaN and is skipped by fmaxf.
-template <grpo_dtype DT>
+// With EXACT the upper elements are masked and the result is the true maximum: the
+// entropy gradient of a near-one-hot row is a difference a_max - Abar of order 1e-8,
+// which survives in fp32 only if a_max itself is (nearly) zero.
+template <grpo_dtype DT, bool EXACT>
 __device__ __forceinline__ float vec_max_ref(const u32x4 &z)
 {
     float m;
     if constexpr (DT == GRPO_BF16) {
-        m = fmaxf(as_f32(z[0]), as_f32(z[0] << 16));
+        constexpr unsigned hi_mask = EXACT ? 0xffff0000u : 0xffffffffu;
+        m = fmaxf(as_f32(z[0] & hi_mask), as_f32(z[0] << 16));
 #pragma unroll
-        for (int d = 1; d < 4; ++d) m = fmaxf(m, fmaxf(as_f32(z[d]), as_f32(z[d] << 16)));
+        for (int d = 1; d < 4; ++d) m = fmaxf(m, fmaxf(as_f32(z[d] & hi_mask), as_f32(z[d] << 16)));
     } else {
         m = fmaxf(fmaxf(as_f32(z[0]), as_f32(z[1])), fmaxf(as_f32(z[2]), as_f32(z[3])));
     }
@@ -519,12 +521,11 @@ __device__ __forceinline__ void unpack_word(unsigned w, float (&f)[Elem<DT>::EPV
     }
 }
 
-// The same, also accumulating sum_e e_e a_e (a = exponent in log2 units).  The
-// zero-wins multiply returns 0 for 0 * inf, which is what an element at -inf must
-// contribute.  Word by word, with a scheduling fence between words: the auxiliary
+// The same, also accumulating sum_e e_e a_e (a = exponent in log2 units, floored so
+// that an element at -inf contributes 0).  Word by word, with a scheduling fence between words: the auxiliary
 // variants need more temporaries per element and the row leaves room for few.
 template <grpo_dtype DT>
-__device__ __forceinline__ float exp_sum_vec_aux(u32x4 &z, float k, float mk, float &w)
+__device__ __forceinline__ float exp_sum_vec_aux(u32x4 &z, float k, float mx, float &w)
 {
     constexpr int EPW = Elem<DT>::EPV / 4;
     float part = 0.f, partw = 0.f;
@@ -535,10 +536,12 @@ __device__ __forceinline__ float exp_sum_vec_aux(u32x4 &z, float k, float mk, fl
         unpack_word<DT>(z[d], f);
 #pragma unroll
         for (int e = 0; e < EPW; ++e) {
-            const float a = fmaf(f[e], k, -mk);
+            // (z - max) k rather than fma(z, k, -max k): exactly 0 at the maximum, which the
+            // entropy of a near-one-hot row needs (its sum e a is all cancellation otherwise)
+            const float a = fmaxf((f[e] - mx) * k, kExpFloor);
             const float ex = __builtin_amdgcn_exp2f(a);
             part += ex;
-            partw += mul_zero_wins(ex, a);
+            partw = fmaf(ex, a, partw);
         }
         // the running sums must exist here: left alone, the additions drift to the end
         // of the row pass and every product waits for them in a register of its own
@@ -551,10 +554,10 @@ __device__ __forceinline__ float exp_sum_vec_aux(u32x4 &z, float k, float mk, fl
 }
 
 // Gradient of one vector with the entropy term fused in: g_j = p_j (q2 + bq a'_j),
-// a'_j = z_j k - shift = log2 p_j.  Returns the packed vector.
+// a'_j = (z_j - max) k - log2 s = log2 p_j.  Returns the packed vector.
 template <grpo_dtype DT>
-__device__ __forceinline__ u32x4 grad_vec_aux(u32x4 &z, float k, float shift, float q2, float bq,
-                                              bool has_y, int ey, float gy)
+__device__ __forceinline__ u32x4 grad_vec_aux(u32x4 &z, float k, float mx, float log2s, float q2,
+                                              float bq, bool has_y, int ey, float gy)
 {
     constexpr int EPW = Elem<DT>::EPV / 4;
     u32x4 out;
@@ -565,8 +568,8 @@ __device__ __forceinline__ u32x4 grad_vec_aux(u32x4 &z, float k, float shift, fl
         unpack_word<DT>(z[d], f);
 #pragma unroll
         for (int e = 0; e < EPW; ++e) {
-            const float a = fmaf(f[e], k, -shift);
-            g[e] = mul_zero_wins(__builtin_amdgcn_exp2f(a), fmaf(bq, a, q2));
+            const float a = fmaxf(fmaf(f[e] - mx, k, -log2s), kExpFloor);
+            g[e] = __builtin_amdgcn_exp2f(a) * fmaf(bq, a, q2);
         }
         if (has_y) {
 #pragma unroll
@@ -775,10 +778,10 @@ __global__ void __launch_bounds__(BLOCK) grpo_rows_cached(RowParams p)
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
             forget(buf[i]);
-            mx = fmaxf(mx, vec_max_ref<DT>(buf[i]));
+            mx = fmaxf(mx, vec_max_ref<DT, AUX>(buf[i]));
             VECTOR_FENCE();
         }
-        if (tail_wave) mx = fmaxf(mx, vec_max_ref<DT>(tbuf));
+        if (tail_wave) mx = fmaxf(mx, vec_max_ref<DT, AUX>(tbuf));
         mx = fmaxf(block_max<BLOCK>(mx, lds_max), zy);
         const float mk = mx * p.k;
 
@@ -789,7 +792,7 @@ __global__ void __launch_bounds__(BLOCK) grpo_rows_cached(RowParams p)
         for (int i = 0; i < NV; ++i) {
             forget(buf[i]);
             if constexpr (AUX)
-                acc += exp_sum_vec_aux<DT>(buf[i], p.k, mk, accw);
+                acc += exp_sum_vec_aux<DT>(buf[i], p.k, mx, accw);
             else
                 acc += exp_sum_vec<DT>(buf[i], p.k, mk);
             if (!p.bwd && has_next) {
@@ -800,7 +803,7 @@ __global__ void __launch_bounds__(BLOCK) grpo_rows_cached(RowParams p)
         }
         if (tail_wave) {
             if constexpr (AUX)
-                acc += exp_sum_vec_aux<DT>(tbuf, p.k, mk, accw);
+                acc += exp_sum_vec_aux<DT>(tbuf, p.k, mx, accw);
             else
                 acc += exp_sum_vec<DT>(tbuf, p.k, mk);
         }
@@ -810,7 +813,7 @@ __global__ void __launch_bounds__(BLOCK) grpo_rows_cached(RowParams p)
         if constexpr (AUX) {
             block_sum2<BLOCK>(acc, accw, lds_sum, lds_sumw);
             float kl, H;
-            sc = row_scalars_aux(p, row, zy_row, mk, acc, accw, kl, H);
+            sc = row_scalars_aux(p, row, zy_row, mx, acc, accw, kl, H);
             if (tid == 0) write_row_aux(p, row, kl, H);
         } else {
             const float s_excl = block_sum<BLOCK>(acc, lds_sum);
@@ -837,7 +840,7 @@ __global__ void __launch_bounds__(BLOCK) grpo_rows_cached(RowParams p)
                     forget(buf[i]);
                     u32x4 packed;
                     if constexpr (AUX) {
-                        packed = grad_vec_aux<DT>(buf[i], p.k, sc.shift, sc.q2, sc.bq, v == vy, ey, gy);
+                        packed = grad_vec_aux<DT>(buf[i], p.k, sc.mx, sc.log2s, sc.q2, sc.bq, v == vy, ey, gy);
                     } else {
                         float g[EPV];
                         grad_vec<DT>(buf[i], p.k, sc.shift, q, v == vy, ey, gy, g);
@@ -853,7 +856,7 @@ __global__ void __launch_bounds__(BLOCK) grpo_rows_cached(RowParams p)
                 if (tail_wave && tid == 0) {
                     float g[EPV];
                     if constexpr (AUX) {
-                        const u32x4 pk = grad_vec_aux<DT>(tbuf, p.k, sc.shift, sc.q2, sc.bq, vy == nvec_full, ey, gy);
+                        const u32x4 pk = grad_vec_aux<DT>(tbuf, p.k, sc.mx, sc.log2s, sc.q2, sc.bq, vy == nvec_full, ey, gy);
                         unpack<DT>(pk, g);  // the tail is stored element by element
                     } else {
                         grad_vec<DT>(tbuf, p.k, sc.shift, q, vy == nvec_full, ey, gy, g);
@@ -921,11 +924,11 @@ __global__ void __launch_bounds__(BLOCK) grpo_rows_streamed(RowParams p)
             float part = 0.f, partw = 0.f;
 #pragma unroll
             for (int e = 0; e < EPV; ++e) {
-                const float a = fmaf(f[e], p.k, -mk_t);
+                const float a = AUX ? fmaxf((f[e] - m) * p.k, kExpFloor) : fmaf(f[e], p.k, -mk_t);
                 float ex = __builtin_amdgcn_exp2f(a);
                 if (v == vy && e == ey) ex = 0.f;
                 part += ex;
-                if constexpr (AUX) partw += mul_zero_wins(ex, a);
+                if constexpr (AUX) partw = fmaf(ex, a, partw);
             }
             if (m > -INFINITY) {  // all -inf so far: exponents would be NaN
                 s += part;
@@ -943,7 +946,7 @@ __global__ void __launch_bounds__(BLOCK) grpo_rows_streamed(RowParams p)
             block_sum2<BLOCK>(scaled, scaledw, lds_sum, lds_sumw);
             if (!(mx > -INFINITY)) scaled = NAN;  // a row of -inf (or NaN) has no softmax
             float kl, H;
-            sc = row_scalars_aux(p, row, zy, mk, scaled, scaledw, kl, H);
+            sc = row_scalars_aux(p, row, zy, mx, scaled, scaledw, kl, H);
             if (tid == 0) write_row_aux(p, row, kl, H);
         } else {
             float s_excl = block_sum<BLOCK>(scaled, lds_sum);
@@ -967,7 +970,7 @@ __global__ void __launch_bounds__(BLOCK) grpo_rows_streamed(RowParams p)
             u32x4 z = load_vec<DT>(zrow, v, nvec_full, tail);
             float g[EPV];
             if constexpr (AUX) {
-                const u32x4 pk = grad_vec_aux<DT>(z, p.k, sc.shift, sc.q2, sc.bq, v == vy, ey, gy);
+                const u32x4 pk = grad_vec_aux<DT>(z, p.k, sc.mx, sc.log2s, sc.q2, sc.bq, v == vy, ey, gy);
                 unpack<DT>(pk, g);  // exact: the values are already rounded
             } else {
                 grad_vec<DT>(z, p.k, sc.shift, q, v == vy, ey, gy, g);
