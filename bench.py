@@ -99,7 +99,7 @@ def main():
     batch = wl.make_batch(cfg, dev)
     esz = batch["logits"].element_size()
     # old-policy log-probs: the library's own forward pass plus the recipe's staleness noise
-    new_lp = grpo.grpo_logprobs_fwd(batch["logits"], batch["tokens"], batch["mask"], cfg.temperature)
+    new_lp = grpo.grpo_logprobs_fwd(batch["logits"], batch["tokens"], None, cfg.temperature)
     torch.cuda.synchronize()
     old = wl.make_old_logprobs(cfg, new_lp).to(dev)
 
@@ -147,6 +147,7 @@ def main():
     wall, kern = timed(args.steps, args.warmup)
     assert grpo.grpo_workspace_error(ws) == 0
     c = counts.cpu().tolist()
+    loss_value = float(loss.cpu())
     M = c[0]
     zero_adv = int(((adv_tok == 0) & (batch["mask"] != 0)).sum())
     n_zero_coeff = c[1] + c[2] + c[3] + zero_adv
@@ -216,7 +217,7 @@ def main():
                    "rows_live": n_full, "rows_zero_coeff": n_zero_coeff, "rows_masked": n_masked,
                    "eps_low": cfg.eps_low, "eps_high": cfg.eps_high, "delta": cfg.delta,
                    "temperature": cfg.temperature},
-        "counts": dict(zip(grpo.COUNT_NAMES, c)), "loss": float(loss.cpu()),
+        "counts": dict(zip(grpo.COUNT_NAMES, c)), "loss": loss_value,
         "roofline": {"bound": "hbm", "achieved": alg_bytes / kern / 1e9, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": alg_bytes / kern / 1e9 / HBM_PEAK_GBPS,
                      "traffic": traffic_from_profiles(cfg.name),
