@@ -442,44 +442,65 @@ int oracle_entropies(const void *logits, int dtype, int64_t n_tokens, int64_t V,
     return 0;
 }
 
-/* Objective with the auxiliary terms, from per-token log-probs and entropies.
- * aux_out[0] = policy loss -(1/D) sum m J, aux_out[1] = (1/D) sum m kl,
- * aux_out[2] = (1/D) sum m H;  *total_out = aux0 + kl_coef aux1 - ent_coef aux2.
+/* Objective with the auxiliary terms, from per-token log-probs and entropies, with
+ * optional per-token weights omega_t (NULL = all ones):
+ *   policy = -(1/D) sum_t m_t omega_t J_t, and the same weighting for kl_t and H_t.
+ * omega_t = 1, D = M is the token-level loss of section 4.1; omega_t = 1/|o_i| for
+ * the tokens of rollout i with D = number of rollouts is the sample-level
+ * normalisation printed in the objective of section 3.4 (1/G sum_i 1/|o_i| sum_t).
+ * A row with omega_t = 0 counts as masked (also in M).
+ * aux_out[0] = policy, aux_out[1] = weighted mean kl, aux_out[2] = weighted mean H;
+ * *total_out = aux0 + kl_coef aux1 - ent_coef aux2.
  * coeff_out[t] = grad_scale * dtotal/dl_t through the ratio and the KL term;
- * ent_coeff_out[t] = grad_scale * ent_coef * m_t / D, the weight of -H_t.
+ * ent_coeff_out[t] = grad_scale * ent_coef * m_t omega_t / D, the weight of -H_t.
  * ref_logprobs may be NULL when kl_coef == 0. */
 void oracle_aux_objective_from_logprobs(int64_t n_tokens, const double *logprobs,
                                         const double *entropies, const float *old_logprobs,
                                         const float *ref_logprobs, const float *advantages,
-                                        const uint8_t *mask, double eps_low, double eps_high,
-                                        double delta, double kl_coef, double ent_coef,
-                                        double denom, double grad_scale, double *total_out,
-                                        double *aux_out, int64_t *counts_out,
-                                        double *coeff_out, double *ent_coeff_out)
+                                        const uint8_t *mask, const float *token_weights,
+                                        double eps_low, double eps_high, double delta,
+                                        double kl_coef, double ent_coef, double denom,
+                                        double grad_scale, double *total_out, double *aux_out,
+                                        int64_t *counts_out, double *coeff_out,
+                                        double *ent_coeff_out)
 {
-    double policy = 0.0;
-    oracle_objective_from_logprobs(n_tokens, logprobs, old_logprobs, advantages, mask, eps_low,
-                                   eps_high, delta, denom, grad_scale, &policy, counts_out,
-                                   NULL, coeff_out, NULL);
-    int64_t M = 0;
-    for (int64_t t = 0; t < n_tokens; ++t)
-        M += (!mask || mask[t]) ? 1 : 0;
-    double D = (denom > 0.0) ? denom : (double)M;
-    csum skl = {0.0, 0.0}, sh = {0.0, 0.0};
+    int64_t M = 0, n_hi = 0, n_lo = 0, n_de = 0, n_oob = 0;
     for (int64_t t = 0; t < n_tokens; ++t) {
-        int live = (!mask || mask[t]) && D > 0.0;
-        double kl = 0.0, dkl = 0.0;
-        if (live && ref_logprobs && kl_coef != 0.0)
-            oracle_kl_estimator(logprobs[t], (double)ref_logprobs[t], &kl, &dkl);
+        int live = (!mask || mask[t]) && (!token_weights || token_weights[t] != 0.0f);
+        M += live ? 1 : 0;
+    }
+    double D = (denom > 0.0) ? denom : (double)M;
+    csum sJ = {0.0, 0.0}, skl = {0.0, 0.0}, sh = {0.0, 0.0};
+    for (int64_t t = 0; t < n_tokens; ++t) {
+        int live = (!mask || mask[t]) && (!token_weights || token_weights[t] != 0.0f);
+        double c = 0.0, b = 0.0;
         if (live) {
-            csum_add(&skl, kl);
-            csum_add(&sh, entropies[t]);
+            double w = token_weights ? (double)token_weights[t] : 1.0;
+            double J, dJ, kl = 0.0, dkl = 0.0;
+            int fl;
+            double r = exp(logprobs[t] - (double)old_logprobs[t]);
+            oracle_surrogate_from_ratio(r, (double)advantages[t], eps_low, eps_high, delta, &J,
+                                        &dJ, &fl);
+            if (ref_logprobs && kl_coef != 0.0)
+                oracle_kl_estimator(logprobs[t], (double)ref_logprobs[t], &kl, &dkl);
+            csum_add(&sJ, w * J);
+            csum_add(&skl, w * kl);
+            csum_add(&sh, w * entropies[t]);
+            n_hi += (fl & FLAG_CLIP_HIGH) ? 1 : 0;
+            n_lo += (fl & FLAG_CLIP_LOW) ? 1 : 0;
+            n_de += (fl & FLAG_DELTA) ? 1 : 0;
+            n_oob += (fl & FLAG_OUT_OF_BAND) ? 1 : 0;
+            if (D > 0.0) {
+                c = grad_scale * w * (-dJ + kl_coef * dkl) / D;
+                b = grad_scale * w * ent_coef / D;
+            }
         }
         if (coeff_out)
-            coeff_out[t] += live ? grad_scale * kl_coef * dkl / D : 0.0;
+            coeff_out[t] = c;
         if (ent_coeff_out)
-            ent_coeff_out[t] = live ? grad_scale * ent_coef / D : 0.0;
+            ent_coeff_out[t] = b;
     }
+    double policy = (D > 0.0) ? -csum_value(&sJ) / D : 0.0;
     double klm = (D > 0.0) ? csum_value(&skl) / D : 0.0;
     double hm = (D > 0.0) ? csum_value(&sh) / D : 0.0;
     if (aux_out) {
@@ -489,6 +510,42 @@ void oracle_aux_objective_from_logprobs(int64_t n_tokens, const double *logprobs
     }
     if (total_out)
         *total_out = policy + kl_coef * klm - ent_coef * hm;
+    if (counts_out) {
+        counts_out[0] = M;
+        counts_out[1] = n_hi;
+        counts_out[2] = n_lo;
+        counts_out[3] = n_de;
+        counts_out[4] = n_oob;
+    }
+}
+
+/* Packed (variable-length) layout, section 4.1 "sequence packing": the response
+ * tokens of rollout i are the rows [cu_seqlens[i], cu_seqlens[i+1]) of the batch.
+ * Writes, per row, the rollout it belongs to (-1 outside every range) and its weight
+ * omega_t: 1 for every covered row (token-level), or 1/|o_i| (sample-level, the
+ * 1/|o_i| of the printed objective); 0 outside every range.
+ * Returns 1 if the offsets are not non-decreasing within [0, n_tokens]. */
+int oracle_packed_layout(const int64_t *cu_seqlens, int64_t n_rollouts, int64_t n_tokens,
+                         int sample_level, float *weights_out, int32_t *rollout_of_token_out)
+{
+    for (int64_t t = 0; t < n_tokens; ++t) {
+        if (weights_out)
+            weights_out[t] = 0.0f;
+        if (rollout_of_token_out)
+            rollout_of_token_out[t] = -1;
+    }
+    for (int64_t i = 0; i < n_rollouts; ++i) {
+        int64_t b = cu_seqlens[i], e = cu_seqlens[i + 1];
+        if (b < 0 || e < b || e > n_tokens)
+            return 1;
+        for (int64_t t = b; t < e; ++t) {
+            if (weights_out)
+                weights_out[t] = sample_level ? (float)(1.0 / (double)(e - b)) : 1.0f;
+            if (rollout_of_token_out)
+                rollout_of_token_out[t] = (int32_t)i;
+        }
+    }
+    return 0;
 }
 
 /* Gradient of one row of the total with respect to its logits:

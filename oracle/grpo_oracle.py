@@ -73,8 +73,10 @@ def lib():
         L.oracle_entropies.restype = i32
         L.oracle_entropies.argtypes = [vp, i32, i64, i64, i64, vp, dbl, vp]
         L.oracle_aux_objective_from_logprobs.restype = None
-        L.oracle_aux_objective_from_logprobs.argtypes = [i64, vp, vp, vp, vp, vp, vp, dbl, dbl, dbl,
+        L.oracle_aux_objective_from_logprobs.argtypes = [i64, vp, vp, vp, vp, vp, vp, vp, dbl, dbl, dbl,
                                                          dbl, dbl, dbl, dbl, vp, vp, vp, vp, vp]
+        L.oracle_packed_layout.restype = i32
+        L.oracle_packed_layout.argtypes = [vp, i64, i64, i32, vp, vp]
         L.oracle_aux_grad_rows.restype = None
         L.oracle_aux_grad_rows.argtypes = [vp, i32, i64, i64, vp, vp, vp, dbl, vp, i64, vp]
         L.oracle_num_threads.restype = i32
@@ -263,9 +265,21 @@ def entropies(logits, mask=None, temperature=1.0, vocab=None):
     return out
 
 
+def packed_layout(cu_seqlens, n_tokens, sample_level):
+    """(weights f32 [n_tokens], rollout_of_token i32 [n_tokens]) of a packed batch."""
+    cu = np.ascontiguousarray(cu_seqlens, dtype=np.int64)
+    w = np.zeros(n_tokens, dtype=np.float32)
+    rot = np.zeros(n_tokens, dtype=np.int32)
+    rc = lib().oracle_packed_layout(_ptr(cu), cu.shape[0] - 1, int(n_tokens), int(bool(sample_level)),
+                                    _ptr(w), _ptr(rot))
+    if rc:
+        raise ValueError("oracle_packed_layout: bad cu_seqlens")
+    return w, rot
+
+
 def aux_objective_from_logprobs(logprobs, entropies_, old_logprobs, ref_logprobs, advantages,
-                                mask=None, *, eps_low=0.2, eps_high=0.2, delta=4.0, kl_coef=0.0,
-                                ent_coef=0.0, denom=0.0, grad_scale=1.0):
+                                mask=None, *, token_weights=None, eps_low=0.2, eps_high=0.2,
+                                delta=4.0, kl_coef=0.0, ent_coef=0.0, denom=0.0, grad_scale=1.0):
     lp = np.ascontiguousarray(logprobs, dtype=np.float64)
     N = lp.shape[0]
     H = np.ascontiguousarray(entropies_, dtype=np.float64)
@@ -273,13 +287,14 @@ def aux_objective_from_logprobs(logprobs, entropies_, old_logprobs, ref_logprobs
     ref = None if ref_logprobs is None else np.ascontiguousarray(ref_logprobs, dtype=np.float32)
     adv = np.ascontiguousarray(advantages, dtype=np.float32)
     m = None if mask is None else np.ascontiguousarray(mask, dtype=np.uint8)
+    tw = None if token_weights is None else np.ascontiguousarray(token_weights, dtype=np.float32)
     total = np.zeros(1, dtype=np.float64)
     aux = np.zeros(3, dtype=np.float64)
     counts = np.zeros(5, dtype=np.int64)
     coeff = np.zeros(N, dtype=np.float64)
     ent_coeff = np.zeros(N, dtype=np.float64)
     lib().oracle_aux_objective_from_logprobs(
-        N, _ptr(lp), _ptr(H), _ptr(old), _ptr(ref), _ptr(adv), _ptr(m), float(eps_low),
+        N, _ptr(lp), _ptr(H), _ptr(old), _ptr(ref), _ptr(adv), _ptr(m), _ptr(tw), float(eps_low),
         float(eps_high), float(delta), float(kl_coef), float(ent_coef), float(denom),
         float(grad_scale), _ptr(total), _ptr(aux), _ptr(counts), _ptr(coeff), _ptr(ent_coeff))
     return dict(total=float(total[0]), policy=float(aux[0]), kl=float(aux[1]),
@@ -301,16 +316,20 @@ def aux_grad_rows(logits_rows, tokens_rows, coeff_rows, ent_coeff_rows, temperat
 
 
 def aux_loss_fwd_bwd(logits, tokens, old_logprobs, ref_logprobs, advantages, mask=None, *,
-                     eps_low=0.2, eps_high=0.2, delta=4.0, temperature=1.0, kl_coef=0.0,
-                     ent_coef=0.0, denom=0.0, grad_scale=1.0, grad_rows=None, vocab=None):
+                     token_weights=None, eps_low=0.2, eps_high=0.2, delta=4.0, temperature=1.0,
+                     kl_coef=0.0, ent_coef=0.0, denom=0.0, grad_scale=1.0, grad_rows=None, vocab=None):
     """Total objective with the auxiliary terms in one call (composition of the stages)."""
     a, dt, stride = _logits_view(logits)
     N = a.shape[0]
     V = a.shape[1] if vocab is None else vocab
-    lp = logprobs(a, tokens, mask, temperature, vocab=V)
-    H = entropies(a, mask, temperature, vocab=V)
+    live = None if mask is None else np.ascontiguousarray(mask, dtype=np.uint8).copy()
+    if token_weights is not None:   # a row with zero weight counts as masked: it is never read
+        nz = (np.asarray(token_weights, dtype=np.float32) != 0).astype(np.uint8)
+        live = nz if live is None else (live & nz)
+    lp = logprobs(a, tokens, live, temperature, vocab=V)
+    H = entropies(a, live, temperature, vocab=V)
     obj = aux_objective_from_logprobs(lp, H, old_logprobs, ref_logprobs, advantages, mask,
-                                      eps_low=eps_low, eps_high=eps_high, delta=delta,
+                                      token_weights=token_weights, eps_low=eps_low, eps_high=eps_high, delta=delta,
                                       kl_coef=kl_coef, ent_coef=ent_coef, denom=denom,
                                       grad_scale=grad_scale)
     obj["logprobs"], obj["entropies"] = lp, H

@@ -178,3 +178,82 @@ def test_entropy_gradient_alone_is_the_textbook_form():
     H = -(p * lp).sum()
     assert abs(out["total"] + 0.5 * H) < 1e-14
     assert np.max(np.abs(out["grad"][0] - 0.5 / 2.0 * p * (lp + H))) < 1e-15
+
+
+# ----------------------------------------------------------------------------
+# packed layout and sample-level normalisation (the objective as printed in section 3.4)
+# ----------------------------------------------------------------------------
+
+def test_packed_layout():
+    cu = np.array([0, 3, 3, 10, 14])                        # one empty rollout
+    w, rot = orc.packed_layout(cu, 16, sample_level=True)
+    assert rot.tolist() == [0] * 3 + [2] * 7 + [3] * 4 + [-1, -1]
+    assert np.allclose(w, [1 / 3] * 3 + [1 / 7] * 7 + [1 / 4] * 4 + [0, 0], rtol=1e-7)
+    w1, _ = orc.packed_layout(cu, 16, sample_level=False)
+    assert w1.tolist() == [1.0] * 14 + [0.0, 0.0]
+    for bad in ([0, 5, 4], [0, 20], [-1, 4]):
+        with pytest.raises(ValueError):
+            orc.packed_layout(np.array(bad), 16, True)
+
+
+def test_sample_level_loss_is_the_printed_objective():
+    """1/G sum_i 1/|o_i| sum_t min(...) written out with loops over rollouts, against the
+    weighted form (omega = 1/|o_i|, D = number of rollouts)."""
+    rng = np.random.default_rng(91)
+    lens = [5, 1, 9, 4, 7, 2]
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    N, V, R = int(cu[-1]), 13, len(lens)
+    z = (rng.standard_normal((N, V)) * 2).astype(np.float32)
+    tokens = rng.integers(0, V, N)
+    lp = orc.logprobs(z, tokens)
+    old = (lp + rng.uniform(-2, 2, N)).astype(np.float32)
+    adv_r = rng.standard_normal(R).astype(np.float32)
+    w, rot = orc.packed_layout(cu, N, sample_level=True)
+    adv = adv_r[rot]
+    out = orc.aux_loss_fwd_bwd(z, tokens, old, None, adv, None, token_weights=w, denom=float(R),
+                               eps_low=0.2, eps_high=0.2, delta=4.0)
+    J = 0.0
+    for i in range(R):
+        inner = 0.0
+        for t in range(cu[i], cu[i + 1]):
+            r = math.exp(lp[t] - float(old[t]))
+            A = float(adv_r[i])
+            inner += min(min(r, 4.0) * A, min(max(r, 0.8), 1.2) * A)
+        J += inner / lens[i]
+    assert abs(out["total"] + J / R) < 1e-7                  # omega is stored in fp32
+    # equal lengths: sample-level and token-level coincide
+    cu2 = np.arange(0, 25, 6)
+    w2, _ = orc.packed_layout(cu2, 24, sample_level=True)
+    a = orc.aux_loss_fwd_bwd(z[:24], tokens[:24], old[:24], None, adv[:24], None, token_weights=w2, denom=4.0)
+    b = orc.aux_loss_fwd_bwd(z[:24], tokens[:24], old[:24], None, adv[:24], None)
+    assert abs(a["total"] - b["total"]) < 1e-7
+
+
+def test_weighted_total_gradient_against_autograd_and_zero_weight_rows():
+    rng = np.random.default_rng(93)
+    N, V = 14, 11
+    z, tokens, adv, mask = _batch(rng, N, V)
+    w = rng.uniform(0.1, 2.0, N).astype(np.float32)
+    w[[3, 8]] = 0.0                                            # e.g. prompt tokens of a packed sequence
+    T, gs = 0.9, 1.2
+    live = (mask == 1) & (w != 0)
+    lp = orc.logprobs(z, tokens, live.astype(np.uint8), temperature=T)
+    old = (lp + rng.uniform(-1.5, 1.5, N)).astype(np.float32)
+    ref = (lp + rng.standard_normal(N) * 0.4).astype(np.float32)
+    out = orc.aux_loss_fwd_bwd(z, tokens, old, ref, adv, mask, token_weights=w, temperature=T,
+                               kl_coef=0.05, ent_coef=0.02, denom=0.0, grad_scale=gs, grad_rows="all")
+    assert out["counts"][0] == int(live.sum())                 # zero-weight rows count as masked
+    zt = torch.tensor(z, dtype=torch.float64, requires_grad=True)
+    logp = torch.log_softmax(zt / T, dim=-1)
+    l = logp.gather(1, torch.as_tensor(tokens)[:, None])[:, 0]
+    r = torch.exp(l - torch.as_tensor(old, dtype=torch.float64))
+    A = torch.as_tensor(adv, dtype=torch.float64)
+    J = torch.minimum(torch.clamp(r, max=4.0) * A, torch.clamp(r, 0.8, 1.2) * A)
+    d = torch.as_tensor(ref, dtype=torch.float64) - l
+    H = torch.distributions.Categorical(logits=zt / T).entropy()
+    wm = torch.as_tensor(w.astype(np.float64) * live)
+    total = ((-J + 0.05 * (torch.exp(d) - d - 1) - 0.02 * H) * wm).sum() / float(live.sum())
+    (total * gs).backward()
+    assert abs(out["total"] - float(total.detach())) < 1e-13
+    assert np.max(np.abs(out["grad"] - zt.grad.numpy())) < 1e-13
+    assert not out["grad"][~live].any() and not out["logprobs"][~live].any()
