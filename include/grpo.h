@@ -106,6 +106,25 @@ grpo_status grpo_group_advantages(const float *rewards, int64_t n_rollouts,
                                   int64_t n_tokens, float *adv_tok_out, void *stream);
 
 /*
+ * Packed (variable-length) batches (section 4.1, sequence packing: samples are collated
+ * along the sequence dimension instead of being padded).  The response tokens of rollout
+ * i are the rows [cu_seqlens[i], cu_seqlens[i+1]) of the batch.  Writes per row
+ *   rollout_of_token_out[t] = i            (-1 for rows no rollout owns), as
+ *                             grpo_group_advantages wants it, and
+ *   weights_out[t] = 1 (sample_level = 0) or 1/|o_i| (sample_level != 0), the 1/|o_i| of
+ *                    the objective as printed in section 3.4; 0 for rows no rollout owns,
+ * ready to be passed as token_weights to grpo_loss_aux_fwd_bwd.
+ *  cu_seqlens [n_rollouts+1] i64, device, read; expected non-decreasing within
+ *             [0, n_tokens]; other values are clamped on the device (no out-of-bounds
+ *             access, affected rows unspecified).
+ *  weights_out [n_tokens] f32 and rollout_of_token_out [n_tokens] i32, device, written;
+ *             either may be NULL, not both.
+ */
+grpo_status grpo_packed_layout(const int64_t *cu_seqlens, int64_t n_rollouts, int64_t n_tokens,
+                               int sample_level, float *weights_out, int32_t *rollout_of_token_out,
+                               void *stream);
+
+/*
  * Per-token log-probabilities of the sampled tokens,
  *     logprobs_out[t] = log softmax(logits[t, :] / temperature)[tokens[t]],
  * i.e. log pi_theta(o_{i,t} | q, o_{i,<t}) of section 3.4.  This is how the trainer
@@ -193,14 +212,21 @@ grpo_status grpo_loss_fwd_bwd(const void *logits, grpo_dtype dtype, int64_t n_to
  * Arguments as grpo_loss_fwd_bwd, plus
  *  ref_logprobs [n_tokens] f32, device, read: log pi_ref(y_t); may be NULL iff
  *               kl_coef == 0.
+ *  token_weights [n_tokens] f32, device, read, or NULL (= all ones): omega_t multiplies
+ *               row t in all three sums, -(1/D) sum m omega J etc.  omega = 1 with
+ *               D = M is the token-level loss of section 4.1; omega_t = 1/|o_i| with
+ *               denom = number of rollouts is the sample-level normalisation the
+ *               objective is printed with in section 3.4 (grpo_packed_layout writes
+ *               those weights).  A row with omega_t = 0 is treated exactly like a
+ *               masked row (never read, zero gradient, not counted in M).
  *  kl_coef, entropy_coef: finite.
- *  loss_out     [4] f32, device, written: total, policy part -(1/D) sum m J,
- *               mean kl, mean H (all with the same denominator D).
+ *  loss_out     [4] f32, device, written: total, policy part -(1/D) sum m omega J,
+ *               (1/D) sum m omega kl, (1/D) sum m omega H.
  *  entropy_out  [n_tokens] f32, device, written, or NULL: H_t (0 at masked rows).
  *  grad_logits  grad_scale * dtotal/dlogits
  *                 = c_t/T (1[j = y_t] - p_j) + b_t/T p_j (log p_j + H_t),
- *               c_t = grad_scale m_t (-dJ_t/dl_t + kl_coef (1 - exp(d_t))) / D,
- *               b_t = grad_scale m_t entropy_coef / D.
+ *               c_t = grad_scale m_t omega_t (-dJ_t/dl_t + kl_coef (1 - exp(d_t))) / D,
+ *               b_t = grad_scale m_t omega_t entropy_coef / D.
  *               Rows with c_t = 0 and b_t = 0 are zero-filled.
  * With kl_coef = 0 and entropy_coef = 0 the loss and the gradient equal those of
  * grpo_loss_fwd_bwd.  Entropies below about 1e-7 nats are at the resolution of the
@@ -209,8 +235,9 @@ grpo_status grpo_loss_fwd_bwd(const void *logits, grpo_dtype dtype, int64_t n_to
 grpo_status grpo_loss_aux_fwd_bwd(const void *logits, grpo_dtype dtype, int64_t n_tokens,
                                   int64_t vocab, int64_t row_stride, const int64_t *tokens,
                                   const float *old_logprobs, const float *ref_logprobs,
-                                  const float *advantages, const uint8_t *mask, float eps_low,
-                                  float eps_high, float delta, float temperature, float kl_coef,
+                                  const float *advantages, const uint8_t *mask,
+                                  const float *token_weights, float eps_low, float eps_high,
+                                  float delta, float temperature, float kl_coef,
                                   float entropy_coef, double denom, float grad_scale,
                                   float *loss_out, float *logprobs_out, float *entropy_out,
                                   int64_t *counts_out, void *grad_logits, void *workspace,

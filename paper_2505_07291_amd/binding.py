@@ -48,8 +48,10 @@ def lib():
         L.grpo_loss_fwd_bwd.argtypes = [vp, i32, i64, i64, i64, vp, vp, vp, vp, f32, f32, f32, f32,
                                         f64, f32, vp, vp, vp, vp, vp, sz, vp]
         L.grpo_loss_aux_fwd_bwd.restype = i32
-        L.grpo_loss_aux_fwd_bwd.argtypes = [vp, i32, i64, i64, i64, vp, vp, vp, vp, vp, f32, f32, f32,
+        L.grpo_loss_aux_fwd_bwd.argtypes = [vp, i32, i64, i64, i64, vp, vp, vp, vp, vp, vp, f32, f32, f32,
                                             f32, f32, f32, f64, f32, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.grpo_packed_layout.restype = i32
+        L.grpo_packed_layout.argtypes = [vp, i64, i64, i32, vp, vp, vp]
         L.grpo_workspace_error.restype = i32
         L.grpo_workspace_error.argtypes = [vp, vp, vp]
         _lib = L
@@ -194,8 +196,8 @@ def grpo_loss_fwd_bwd(logits, tokens, old_logprobs, advantages, mask=None, eps_l
 
 def grpo_loss_aux_fwd_bwd(logits, tokens, old_logprobs, ref_logprobs, advantages, mask=None,
                           eps_low=0.2, eps_high=0.2, delta=4.0, temperature=1.0, kl_coef=0.0,
-                          entropy_coef=0.0, denom=0.0, grad_scale=1.0, *, vocab=None,
-                          grad_logits=None, inplace=False, loss_out=None, logprobs_out=None,
+                          entropy_coef=0.0, denom=0.0, grad_scale=1.0, *, token_weights=None,
+                          vocab=None, grad_logits=None, inplace=False, loss_out=None, logprobs_out=None,
                           entropy_out=None, want_entropy=True, counts_out=None, workspace=None,
                           stream=None):
     """Objective with the KL and entropy terms fused in; see grpo_loss_aux_fwd_bwd in grpo.h.
@@ -209,6 +211,8 @@ def grpo_loss_aux_fwd_bwd(logits, tokens, old_logprobs, ref_logprobs, advantages
     _check(advantages, torch.float32, n, "advantages", dev)
     if ref_logprobs is not None:
         _check(ref_logprobs, torch.float32, n, "ref_logprobs", dev)
+    if token_weights is not None:
+        _check(token_weights, torch.float32, n, "token_weights", dev)
     if mask is not None:
         _check(mask, torch.uint8, n, "mask", dev)
     if inplace:
@@ -230,13 +234,32 @@ def grpo_loss_aux_fwd_bwd(logits, tokens, old_logprobs, ref_logprobs, advantages
         workspace = torch.empty(grpo_workspace_bytes(n), dtype=torch.uint8, device=dev)
     rc = lib().grpo_loss_aux_fwd_bwd(
         _ptr(logits), dt, n, v, stride, _ptr(tokens), _ptr(old_logprobs), _ptr(ref_logprobs),
-        _ptr(advantages), _ptr(mask), float(eps_low), float(eps_high), float(delta),
-        float(temperature), float(kl_coef), float(entropy_coef), float(denom), float(grad_scale),
+        _ptr(advantages), _ptr(mask), _ptr(token_weights), float(eps_low), float(eps_high),
+        float(delta), float(temperature), float(kl_coef), float(entropy_coef), float(denom),
+        float(grad_scale),
         _ptr(loss_out), _ptr(logprobs_out), _ptr(entropy_out), _ptr(counts_out), _ptr(grad_logits),
         _ptr(workspace), workspace.numel(), _stream(stream))
     if rc != GRPO_OK:
         raise GrpoError(rc, "grpo_loss_aux_fwd_bwd")
     return loss_out, logprobs_out, entropy_out, counts_out, grad_logits
+
+
+def grpo_packed_layout(cu_seqlens, n_tokens, sample_level, weights_out=None, rollout_of_token_out=None,
+                       stream=None):
+    """(weights f32 [n_tokens], rollout_of_token i32 [n_tokens]) of a packed batch whose rollout i
+    owns rows [cu_seqlens[i], cu_seqlens[i+1]); see grpo_packed_layout in grpo.h."""
+    dev = cu_seqlens.device
+    _check(cu_seqlens, torch.int64, cu_seqlens.shape[0], "cu_seqlens", dev)
+    if weights_out is None:
+        weights_out = torch.empty(n_tokens, dtype=torch.float32, device=dev)
+    if rollout_of_token_out is None:
+        rollout_of_token_out = torch.empty(n_tokens, dtype=torch.int32, device=dev)
+    rc = lib().grpo_packed_layout(_ptr(cu_seqlens), cu_seqlens.shape[0] - 1, int(n_tokens),
+                                  1 if sample_level else 0, _ptr(weights_out),
+                                  _ptr(rollout_of_token_out), _stream(stream))
+    if rc != GRPO_OK:
+        raise GrpoError(rc, "grpo_packed_layout")
+    return weights_out, rollout_of_token_out
 
 
 def grpo_workspace_error(workspace, stream=None) -> int:

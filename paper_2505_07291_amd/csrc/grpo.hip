@@ -59,6 +59,7 @@ struct RowParams {
     int bwd;  // 0: log-probs only (grpo_logprobs_fwd), 1: objective + gradient
     // auxiliary terms (kernels instantiated with AUX only)
     const float *ref_lp;  // reference-policy log-probs, or NULL (no KL term)
+    const float *token_w; // per-token weights omega_t, or NULL (all ones); 0 = masked row
     float *KL_ws, *H_ws;  // per-row KL estimate and entropy
     float *entropy_out;   // optional copy of the per-row entropy for the caller
     float kl_coef, ent_coef;
@@ -434,12 +435,18 @@ __device__ __forceinline__ RowScalars row_scalars_aux(const RowParams &p, long l
                              d * (1.f / 720 + d * (1.f / 5040))))));
         kl = fabsf(d) < 0.1f ? series : em1 - d;
     }
-    const float inv_D = (float)p.hdr->inv_D;
-    o.c = (p.grad_scale * (-dJ + p.kl_coef * dkl)) * inv_D;
-    o.b = (p.grad_scale * p.ent_coef) * inv_D;
+    // omega_t / D: the weight of this row in all three sums
+    const float wD = (p.token_w ? p.token_w[row] : 1.f) * (float)p.hdr->inv_D;
+    o.c = (p.grad_scale * (-dJ + p.kl_coef * dkl)) * wD;
+    o.b = (p.grad_scale * p.ent_coef) * wD;
     o.bq = o.b * p.inv_T * kLn2;
     o.q2 = fmaf(o.bq, log2s - abar, -o.c * p.inv_T);
     o.gy_ent = o.bq * ((e_y / s) * (ay_f - abar));
+    if (p.token_w) {  // the reductions sum omega_t J_t, omega_t kl_t, omega_t H_t
+        const float w = p.token_w[row];
+        o.J *= w;
+        kl *= w;
+    }
     kl_out = kl;
     H_out = H;
     return o;
@@ -617,7 +624,7 @@ __device__ __forceinline__ void write_row_outputs(const RowParams &p, long long 
 __device__ __forceinline__ void write_row_aux(const RowParams &p, long long row, float kl, float H)
 {
     if (p.KL_ws) p.KL_ws[row] = kl;
-    if (p.H_ws) p.H_ws[row] = H;
+    if (p.H_ws) p.H_ws[row] = p.token_w ? H * p.token_w[row] : H;
     if (p.entropy_out) p.entropy_out[row] = H;
 }
 
@@ -628,6 +635,7 @@ __device__ __forceinline__ bool row_is_live(const RowParams &p, long long row, i
                                             int tail, long long &y)
 {
     bool live = p.mask ? (p.mask[row] != 0) : true;
+    if (live && p.token_w) live = p.token_w[row] != 0.f;
     bool bad = false;
     y = 0;
     if (live) {
@@ -985,13 +993,15 @@ __global__ void __launch_bounds__(BLOCK) grpo_rows_streamed(RowParams p)
 // ---------------------------------------------------------------------------
 
 // Counts the unmasked rows and fixes the denominator before any row is processed.
-__global__ void __launch_bounds__(1024) grpo_prepare(const unsigned char *mask, long long n,
+__global__ void __launch_bounds__(1024) grpo_prepare(const unsigned char *mask,
+                                                     const float *token_w, long long n,
                                                      double denom, WsHeader *hdr)
 {
     __shared__ long long lds[16];
     long long cnt = 0;
-    if (mask) {
-        for (long long i = threadIdx.x; i < n; i += 1024) cnt += mask[i] ? 1 : 0;
+    if (mask || token_w) {
+        for (long long i = threadIdx.x; i < n; i += 1024)
+            cnt += ((!mask || mask[i]) && (!token_w || token_w[i] != 0.f)) ? 1 : 0;
     }
     cnt = wave_sum(cnt);
     if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = cnt;
@@ -999,7 +1009,7 @@ __global__ void __launch_bounds__(1024) grpo_prepare(const unsigned char *mask, 
     if (threadIdx.x == 0) {
         long long M = 0;
         for (int i = 0; i < 16; ++i) M += lds[i];
-        if (!mask) M = n;
+        if (!mask && !token_w) M = n;
         const double D = denom > 0.0 ? denom : (double)M;
         hdr->D = D;
         hdr->inv_D = D > 0.0 ? 1.0 / D : 0.0;
@@ -1125,6 +1135,33 @@ __global__ void __launch_bounds__(256) grpo_adv_to_tokens(const float *adv, long
     }
 }
 
+// Packed (variable-length) batches: rollout i owns rows [cu[i], cu[i+1]).  First every
+// row gets "no rollout, weight 0", then each rollout stamps its range.
+__global__ void __launch_bounds__(256) grpo_packed_clear(long long n_tokens, float *weights,
+                                                         int *rollout_of_token)
+{
+    for (long long t = (long long)blockIdx.x * 256 + threadIdx.x; t < n_tokens;
+         t += (long long)gridDim.x * 256) {
+        if (weights) weights[t] = 0.f;
+        if (rollout_of_token) rollout_of_token[t] = -1;
+    }
+}
+__global__ void __launch_bounds__(256) grpo_packed_stamp(const long long *cu, long long n_rollouts,
+                                                         long long n_tokens, int sample_level,
+                                                         float *weights, int *rollout_of_token)
+{
+    for (long long i = blockIdx.x; i < n_rollouts; i += gridDim.x) {
+        long long b = cu[i], e = cu[i + 1];
+        b = b < 0 ? 0 : (b > n_tokens ? n_tokens : b);
+        e = e < b ? b : (e > n_tokens ? n_tokens : e);
+        const float w = sample_level ? (float)(1.0 / (double)(e - b)) : 1.f;
+        for (long long t = b + threadIdx.x; t < e; t += 256) {
+            if (weights) weights[t] = w;
+            if (rollout_of_token) rollout_of_token[t] = (int)i;
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Host side
 // ---------------------------------------------------------------------------
@@ -1192,7 +1229,8 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 grpo_status loss_impl(bool aux, const void *logits, grpo_dtype dtype, int64_t n_tokens, int64_t vocab,
                       int64_t row_stride, const int64_t *tokens, const float *old_logprobs,
                       const float *ref_logprobs, const float *advantages, const uint8_t *mask,
-                      float eps_low, float eps_high, float delta, float temperature, float kl_coef,
+                      const float *token_weights, float eps_low, float eps_high, float delta,
+                      float temperature, float kl_coef,
                       float entropy_coef, double denom, float grad_scale, float *loss_out,
                       float *logprobs_out, float *entropy_out, int64_t *counts_out,
                       void *grad_logits, void *workspace, size_t workspace_bytes, void *stream)
@@ -1220,7 +1258,8 @@ grpo_status loss_impl(bool aux, const void *logits, grpo_dtype dtype, int64_t n_
     unsigned char *flags_ws = (unsigned char *)(ws + kHeaderBytes + 3 * col);
     hipStream_t st = (hipStream_t)stream;
 
-    hipLaunchKernelGGL(grpo_prepare, dim3(1), dim3(1024), 0, st, mask, (long long)n_tokens, denom, hdr);
+    hipLaunchKernelGGL(grpo_prepare, dim3(1), dim3(1024), 0, st, mask, aux ? token_weights : nullptr,
+                       (long long)n_tokens, denom, hdr);
     if (n_tokens > 0) {
         RowParams p = {};
         p.logits = logits;
@@ -1245,6 +1284,7 @@ grpo_status loss_impl(bool aux, const void *logits, grpo_dtype dtype, int64_t n_
         p.bwd = 1;
         if (aux) {
             p.ref_lp = kl_coef != 0.f ? ref_logprobs : nullptr;
+            p.token_w = token_weights;
             p.KL_ws = KL_ws;
             p.H_ws = H_ws;
             p.entropy_out = entropy_out;
@@ -1325,6 +1365,28 @@ grpo_status grpo_group_advantages(const float *rewards, int64_t n_rollouts,
     return hipGetLastError() == hipSuccess ? GRPO_OK : GRPO_ERR_HIP;
 }
 
+grpo_status grpo_packed_layout(const int64_t *cu_seqlens, int64_t n_rollouts, int64_t n_tokens,
+                               int sample_level, float *weights_out, int32_t *rollout_of_token_out,
+                               void *stream)
+{
+    if (n_rollouts < 0 || n_tokens < 0 || n_rollouts > 0x7fffffffll) return GRPO_ERR_SHAPE;
+    if (n_rollouts > 0 && !cu_seqlens) return GRPO_ERR_NULL;
+    if (!weights_out && !rollout_of_token_out) return GRPO_ERR_NULL;
+    if (n_tokens == 0) return GRPO_OK;
+    hipStream_t st = (hipStream_t)stream;
+    long long blocks = (n_tokens + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(grpo_packed_clear, dim3((unsigned)blocks), dim3(256), 0, st, (long long)n_tokens,
+                       weights_out, rollout_of_token_out);
+    if (n_rollouts > 0) {
+        const unsigned grid = (unsigned)(n_rollouts < 4096 ? n_rollouts : 4096);
+        hipLaunchKernelGGL(grpo_packed_stamp, dim3(grid), dim3(256), 0, st, (const long long *)cu_seqlens,
+                           (long long)n_rollouts, (long long)n_tokens, sample_level ? 1 : 0, weights_out,
+                           rollout_of_token_out);
+    }
+    return hipGetLastError() == hipSuccess ? GRPO_OK : GRPO_ERR_HIP;
+}
+
 grpo_status grpo_logprobs_fwd(const void *logits, grpo_dtype dtype, int64_t n_tokens, int64_t vocab,
                               int64_t row_stride, const int64_t *tokens, const uint8_t *mask,
                               float temperature, float *logprobs_out, void *workspace,
@@ -1366,7 +1428,7 @@ grpo_status grpo_loss_fwd_bwd(const void *logits, grpo_dtype dtype, int64_t n_to
                               size_t workspace_bytes, void *stream)
 {
     return loss_impl(false, logits, dtype, n_tokens, vocab, row_stride, tokens, old_logprobs, nullptr,
-                     advantages, mask, eps_low, eps_high, delta, temperature, 0.f, 0.f, denom,
+                     advantages, mask, nullptr, eps_low, eps_high, delta, temperature, 0.f, 0.f, denom,
                      grad_scale, loss_out, logprobs_out, nullptr, counts_out, grad_logits, workspace,
                      workspace_bytes, stream);
 }
@@ -1374,15 +1436,17 @@ grpo_status grpo_loss_fwd_bwd(const void *logits, grpo_dtype dtype, int64_t n_to
 grpo_status grpo_loss_aux_fwd_bwd(const void *logits, grpo_dtype dtype, int64_t n_tokens,
                                   int64_t vocab, int64_t row_stride, const int64_t *tokens,
                                   const float *old_logprobs, const float *ref_logprobs,
-                                  const float *advantages, const uint8_t *mask, float eps_low,
-                                  float eps_high, float delta, float temperature, float kl_coef,
+                                  const float *advantages, const uint8_t *mask,
+                                  const float *token_weights, float eps_low, float eps_high,
+                                  float delta, float temperature, float kl_coef,
                                   float entropy_coef, double denom, float grad_scale,
                                   float *loss_out, float *logprobs_out, float *entropy_out,
                                   int64_t *counts_out, void *grad_logits, void *workspace,
                                   size_t workspace_bytes, void *stream)
 {
     return loss_impl(true, logits, dtype, n_tokens, vocab, row_stride, tokens, old_logprobs,
-                     ref_logprobs, advantages, mask, eps_low, eps_high, delta, temperature, kl_coef,
+                     ref_logprobs, advantages, mask, token_weights, eps_low, eps_high, delta,
+                     temperature, kl_coef,
                      entropy_coef, denom, grad_scale, loss_out, logprobs_out, entropy_out, counts_out,
                      grad_logits, workspace, workspace_bytes, stream);
 }

@@ -22,6 +22,7 @@ def declared_functions():
 def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert {"grpo_group_advantages", "grpo_logprobs_fwd", "grpo_loss_fwd_bwd", "grpo_loss_aux_fwd_bwd",
+            "grpo_packed_layout",
             "grpo_workspace_bytes", "grpo_status_string", "grpo_workspace_error"} <= set(names)
     L = grpo.lib()
     for n in names:
@@ -104,12 +105,12 @@ def test_binding_refuses_cpu_tensors():
 
 
 def aux_args(**over):
-    a = dict(logits=P, dtype=1, n=16, V=1024, stride=1024, tokens=P, old=P, ref=P, adv=P, mask=P,
+    a = dict(logits=P, dtype=1, n=16, V=1024, stride=1024, tokens=P, old=P, ref=P, adv=P, mask=P, tw=None,
              el=0.2, eh=0.2, delta=4.0, T=1.0, klc=0.001, enc=1e-4, denom=0.0, gs=1.0, loss=P, lp=P,
              ent=P, counts=P, grad=P, ws=P, ws_bytes=1 << 20, stream=None)
     a.update(over)
     return [a[k] for k in ("logits", "dtype", "n", "V", "stride", "tokens", "old", "ref", "adv", "mask",
-                           "el", "eh", "delta", "T", "klc", "enc", "denom", "gs", "loss", "lp", "ent",
+                           "tw", "el", "eh", "delta", "T", "klc", "enc", "denom", "gs", "loss", "lp", "ent",
                            "counts", "grad", "ws", "ws_bytes", "stream")]
 
 
@@ -122,3 +123,12 @@ def aux_args(**over):
 ])
 def test_loss_aux_rejects_bad_arguments_before_any_launch(over, expect):
     assert grpo.lib().grpo_loss_aux_fwd_bwd(*aux_args(**over)) == expect
+
+
+def test_packed_layout_rejects_bad_arguments():
+    f = grpo.lib().grpo_packed_layout
+    assert f(None, 4, 100, 1, P, P, None) == NULL
+    assert f(P, 4, 100, 1, None, None, None) == NULL
+    assert f(P, -1, 100, 1, P, P, None) == SHAPE
+    assert f(P, 4, -5, 0, P, P, None) == SHAPE
+    assert f(P, 4, 0, 0, P, None, None) == OK                  # nothing to do

@@ -31,7 +31,8 @@ from test_gpu_parity import DEV, REDUCED, TOL_GRAD, TOL_LOGP, TOL_LOSS_REL, f32,
 pytestmark = pytest.mark.gpu
 
 
-def run_aux_case(batch, old, ref, adv_f32, kl_coef, ent_coef, *, denom=0.0, grad_scale=1.0, label=""):
+def run_aux_case(batch, old, ref, adv_f32, kl_coef, ent_coef, *, denom=0.0, grad_scale=1.0, label="",
+                 token_weights=None):
     T = f32(batch["temperature"])
     kw = dict(eps_low=f32(batch["eps_low"]), eps_high=f32(batch["eps_high"]), delta=f32(batch["delta"]))
     N, V = batch["n_tokens"], batch["vocab"]
@@ -39,14 +40,15 @@ def run_aux_case(batch, old, ref, adv_f32, kl_coef, ent_coef, *, denom=0.0, grad
     tokens_np = batch["tokens"].cpu().numpy()
     mask_np = None if batch["mask"] is None else batch["mask"].cpu().numpy()
     ref_np = None if ref is None else ref.numpy()
+    tw_np = None if token_weights is None else token_weights.cpu().numpy()
     want = orc.aux_loss_fwd_bwd(z, tokens_np, old.numpy(), ref_np, adv_f32, mask_np, temperature=T,
-                                kl_coef=f32(kl_coef), ent_coef=f32(ent_coef), denom=denom,
+                                token_weights=tw_np, kl_coef=f32(kl_coef), ent_coef=f32(ent_coef), denom=denom,
                                 grad_scale=f32(grad_scale), grad_rows="all", vocab=V, **kw)
     say("[gpu] %s grpo_loss_aux_fwd_bwd N=%d V=%d kl_coef=%g ent_coef=%g" % (label, N, V, kl_coef, ent_coef))
     loss, lp, ent, counts, grad = grpo.grpo_loss_aux_fwd_bwd(
         batch["logits"], batch["tokens"], old.to(DEV), None if ref is None else ref.to(DEV),
         torch.as_tensor(adv_f32, device=DEV), batch["mask"], temperature=T, kl_coef=kl_coef,
-        entropy_coef=ent_coef, denom=denom, grad_scale=grad_scale, **kw)
+        entropy_coef=ent_coef, denom=denom, grad_scale=grad_scale, token_weights=token_weights, **kw)
     torch.cuda.synchronize()
     got = loss.cpu().numpy().astype(np.float64)
     e_lp = np.max(np.abs(lp.cpu().numpy() - want["logprobs"]))
@@ -59,14 +61,15 @@ def run_aux_case(batch, old, ref, adv_f32, kl_coef, ent_coef, *, denom=0.0, grad
     assert abs(got[3] - want["entropy"]) <= 1e-4 * want["entropy"] + 2e-7, (got[3], want["entropy"])
     g = grads_to_f64(grad)
     rowmax = np.max(np.abs(want["grad"]), axis=1)
-    M = N if mask_np is None else int(mask_np.sum())
+    M = int(want["counts"][0])
     D = denom if denom > 0 else float(M)
-    kl_floor = (abs(f32(kl_coef) * f32(grad_scale)) / (D * T) * 2.0 ** -22 *
+    wmax = 1.0 if tw_np is None else float(np.max(np.abs(tw_np)))
+    kl_floor = (wmax * abs(f32(kl_coef) * f32(grad_scale)) / (D * T) * 2.0 ** -22 *
                 np.maximum(np.abs(want["logprobs"]), 1.0)) if ref is not None and D > 0 else np.zeros(N)
     zf = batch["logits"].float().cpu().numpy().astype(np.float64)
     rows = np.arange(N)
     pmax = np.exp(zf.max(axis=1) / T - zf[rows, tokens_np] / T + want["logprobs"])
-    ent_floor = (abs(f32(ent_coef) * f32(grad_scale)) / (D * T) * pmax *
+    ent_floor = (wmax * abs(f32(ent_coef) * f32(grad_scale)) / (D * T) * pmax *
                  np.maximum(want["entropies"], 1.0) * 2.0 ** -20) if D > 0 else np.zeros(N)
     err = np.max(np.abs(g - want["grad"]), axis=1) - kl_floor - ent_floor
     zero = want["coeff"] == 0
@@ -222,3 +225,46 @@ def test_aux_full_size(name):
     assert worst <= TOL_GRAD, worst
     say("  ok: total=%.6g policy=%.6g kl=%.4g H=%.5g grad=%.2e x rowmax on %d rows" %
         (got[0], got[1], got[2], got[3], worst, len(rows)))
+
+
+@pytest.mark.parametrize("sample_level", [True, False])
+def test_packed_batch_with_sample_level_weights(sample_level):
+    """Variable-length rollouts packed back to back (no padding rows), advantages broadcast
+    through the rollout index the library derives from cu_seqlens, and the objective
+    normalised per sample as printed in section 3.4 (or per token), with both auxiliary
+    terms.  A few rows before and after the rollouts belong to nobody (weight 0)."""
+    g = torch.Generator().manual_seed(17 + sample_level)
+    G, n_prompts, V = 4, 3, 50257
+    lens = torch.randint(1, 9, (G * n_prompts,), generator=g)
+    lens[5] = 0                                               # an empty response
+    cu = torch.cat([torch.tensor([2]), 2 + torch.cumsum(lens, 0)])
+    N = int(cu[-1]) + 3
+    say("\n[case] packed: %d rollouts, N=%d V=%d sample_level=%s" % (len(lens), N, V, sample_level))
+    w, rot = grpo.grpo_packed_layout(cu.to(DEV), N, sample_level)
+    torch.cuda.synchronize()
+    w_ref, rot_ref = orc.packed_layout(cu.numpy(), N, sample_level)
+    assert np.array_equal(rot.cpu().numpy(), rot_ref)
+    assert np.array_equal(w.cpu().numpy(), w_ref)             # 1/len is correctly rounded on both sides
+    rewards = (torch.rand(G * n_prompts, generator=g) < 0.4).float()
+    adv = orc.group_advantages(rewards.numpy(), group_size=G, eps_std=f32(1e-6))
+    adv_gpu, _ = grpo.grpo_group_advantages(rewards.to(DEV), group_size=G)
+    adv_tok = np.where(rot_ref >= 0, adv[np.maximum(rot_ref, 0)], 0.0).astype(np.float32)
+    store = torch.full((N, V + 7), 7.0, dtype=torch.bfloat16)
+    store[:, :V] = (torch.randn((N, V), generator=g) * 3).to(torch.bfloat16)
+    store[:2] = float("nan")                                  # rows nobody owns are never read
+    store = store.to(DEV)
+    tokens = torch.randint(0, V, (N,), generator=g)
+    batch = dict(logits=store[:, :V], tokens=tokens.to(DEV), mask=None, n_tokens=N, vocab=V,
+                 temperature=1.0, eps_low=0.2, eps_high=0.2, delta=4.0)
+    live = (w_ref != 0).astype(np.uint8)
+    lp_orc = orc.logprobs(logits_to_numpy(batch["logits"]), tokens.numpy(), live)
+    noise = torch.randn(N, generator=g, dtype=torch.float64) * 0.15
+    kinks = np.log([0.8, 1.2, 4.0])
+    for t in range(N):                                        # keep the ratios clear of the kinks
+        while np.min(np.abs(-float(noise[t]) - kinks)) < 1e-3:
+            noise[t] = torch.randn(1, generator=g, dtype=torch.float64)[0] * 0.15
+    old = (torch.as_tensor(lp_orc) + noise).float()
+    ref = (torch.as_tensor(lp_orc) + torch.randn(N, generator=g, dtype=torch.float64) * 0.1).float()
+    denom = float(len(lens)) if sample_level else 0.0
+    out = run_aux_case(batch, old, ref, adv_tok, 0.02, 0.01, denom=denom, token_weights=w, label="packed")
+    assert int(out["counts"][0]) == int(lens.sum())
