@@ -588,6 +588,60 @@ void oracle_aux_grad_rows(const void *logits, int dtype, int64_t V, int64_t row_
     }
 }
 
+/* ================================================================== *
+ * Reward shaping and online filtering (sections 3.1 and 3.3).
+ * ================================================================== */
+
+/* Total reward of section 3.1 ("Length Rewards"):
+ *   r_total = r_task - alpha * | l_target - l_y |
+ * with l_y the response length in tokens and l_target the length asked for in the
+ * prompt (alpha = 3e-4 in section 4.1). */
+void oracle_total_rewards(const float *task_rewards, const int32_t *lengths,
+                          const int32_t *target_lengths, int64_t n_rollouts, double alpha,
+                          double *rewards_out)
+{
+    for (int64_t i = 0; i < n_rollouts; ++i) {
+        double diff = (double)target_lengths[i] - (double)lengths[i];
+        rewards_out[i] = (double)task_rewards[i] - alpha * fabs(diff);
+    }
+}
+
+/* Online data filtering of section 3.3: a group whose completions all received the
+ * same reward has zero advantages and gives no training signal; only the other
+ * groups are kept.  keep_out[g] = 1 iff the rewards of group g are not all equal;
+ * kept_groups_out lists the kept group indices in increasing order (entries past
+ * *n_kept_out are -1); rollout_keep_out[i] (optional) repeats the flag per rollout.
+ * Groups are given by offsets or by a common size, as for the advantages. */
+int oracle_filter_groups(const float *rewards, int64_t n_rollouts, const int32_t *group_offsets,
+                         int64_t n_groups, int64_t group_size, uint8_t *keep_out,
+                         int32_t *kept_groups_out, int32_t *n_kept_out, uint8_t *rollout_keep_out)
+{
+    int32_t n_kept = 0;
+    if (rollout_keep_out)
+        for (int64_t i = 0; i < n_rollouts; ++i)
+            rollout_keep_out[i] = 0;
+    for (int64_t g = 0; g < n_groups; ++g) {
+        int64_t b = group_offsets ? group_offsets[g] : g * group_size;
+        int64_t e = group_offsets ? group_offsets[g + 1] : (g + 1) * group_size;
+        if (b < 0 || e < b || e > n_rollouts)
+            return 1;
+        int differs = 0;
+        for (int64_t i = b + 1; i < e; ++i)
+            if (rewards[i] != rewards[b])
+                differs = 1;
+        keep_out[g] = (uint8_t)differs;
+        if (differs)
+            kept_groups_out[n_kept++] = (int32_t)g;
+        if (rollout_keep_out)
+            for (int64_t i = b; i < e; ++i)
+                rollout_keep_out[i] = (uint8_t)differs;
+    }
+    for (int64_t k = n_kept; k < n_groups; ++k)
+        kept_groups_out[k] = -1;
+    *n_kept_out = n_kept;
+    return 0;
+}
+
 /* Number of OpenMP threads a parallel region would use (for the benchmark's
  * cpu_baseline report). */
 #ifdef _OPENMP

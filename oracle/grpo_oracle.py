@@ -79,6 +79,10 @@ def lib():
         L.oracle_packed_layout.argtypes = [vp, i64, i64, i32, vp, vp]
         L.oracle_aux_grad_rows.restype = None
         L.oracle_aux_grad_rows.argtypes = [vp, i32, i64, i64, vp, vp, vp, dbl, vp, i64, vp]
+        L.oracle_total_rewards.restype = None
+        L.oracle_total_rewards.argtypes = [vp, vp, vp, i64, dbl, vp]
+        L.oracle_filter_groups.restype = i32
+        L.oracle_filter_groups.argtypes = [vp, i64, vp, i64, i64, vp, vp, vp, vp]
         L.oracle_num_threads.restype = i32
         L.oracle_num_threads.argtypes = []
         _lib = L
@@ -341,3 +345,37 @@ def aux_loss_fwd_bwd(logits, tokens, old_logprobs, ref_logprobs, advantages, mas
         obj["grad"] = aux_grad_rows(a[gr], tok[gr], obj["coeff"][gr], obj["ent_coeff"][gr],
                                     temperature, vocab=V)
     return obj
+
+
+# ---------------------------------------------------------------------------
+# reward shaping and online filtering
+# ---------------------------------------------------------------------------
+
+def total_rewards(task_rewards, lengths, target_lengths, alpha):
+    tr = np.ascontiguousarray(task_rewards, dtype=np.float32)
+    ln = np.ascontiguousarray(lengths, dtype=np.int32)
+    tg = np.ascontiguousarray(target_lengths, dtype=np.int32)
+    out = np.zeros(tr.shape[0], dtype=np.float64)
+    lib().oracle_total_rewards(_ptr(tr), _ptr(ln), _ptr(tg), tr.shape[0], float(alpha), _ptr(out))
+    return out
+
+
+def filter_groups(rewards, group_size=None, group_offsets=None):
+    """Returns (keep u8 [n_groups], kept_groups i32 [n_groups], n_kept, rollout_keep u8 [R])."""
+    rw = np.ascontiguousarray(rewards, dtype=np.float32)
+    R = rw.shape[0]
+    if group_offsets is not None:
+        off = np.ascontiguousarray(group_offsets, dtype=np.int32)
+        n_groups, gs = off.shape[0] - 1, 0
+    else:
+        off, gs = None, int(group_size)
+        n_groups = R // gs
+    keep = np.zeros(n_groups, dtype=np.uint8)
+    kept = np.zeros(n_groups, dtype=np.int32)
+    n_kept = np.zeros(1, dtype=np.int32)
+    rk = np.zeros(R, dtype=np.uint8)
+    rc = lib().oracle_filter_groups(_ptr(rw), R, _ptr(off), n_groups, gs, _ptr(keep), _ptr(kept),
+                                    _ptr(n_kept), _ptr(rk))
+    if rc:
+        raise ValueError("oracle_filter_groups: bad group offsets")
+    return keep, kept, int(n_kept[0]), rk
