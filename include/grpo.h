@@ -106,6 +106,39 @@ grpo_status grpo_group_advantages(const float *rewards, int64_t n_rollouts,
                                   int64_t n_tokens, float *adv_tok_out, void *stream);
 
 /*
+ * Total reward with the length penalty of section 3.1,
+ *     rewards_out[i] = task_rewards[i] - alpha * | target_lengths[i] - lengths[i] |,
+ * lengths in tokens (alpha = 3e-4 in section 4.1).  The result feeds
+ * grpo_group_advantages.
+ *  task_rewards [n_rollouts] f32, lengths and target_lengths [n_rollouts] i32, device, read;
+ *  rewards_out [n_rollouts] f32, device, written (may be task_rewards itself).
+ *  alpha finite.  n_rollouts == 0 does nothing.
+ */
+grpo_status grpo_total_rewards(const float *task_rewards, const int32_t *lengths,
+                               const int32_t *target_lengths, int64_t n_rollouts, float alpha,
+                               float *rewards_out, void *stream);
+
+/*
+ * Online data filtering of section 3.3: a group whose completions all received the same
+ * reward has zero advantages and carries no training signal; the trainer keeps sampling
+ * until it has a batch of groups that do.  This call finds them.
+ *  rewards, n_rollouts, group_offsets | NULL, n_groups, group_size: as in
+ *               grpo_group_advantages (invalid offsets are clamped on the device).
+ *  keep_out        [n_groups] u8, device, written: 1 iff the rewards of the group are
+ *                  not all equal (exact fp32 comparison); 0 for an empty group.
+ *  kept_groups_out [n_groups] i32, device, written: indices of the kept groups in
+ *                  increasing order, then -1.
+ *  n_kept_out      [1] i32, device, written: how many groups are kept.
+ *  rollout_keep_out[n_rollouts] u8, device, written, or NULL: the group's flag per rollout
+ *                  (rollouts no group owns are left untouched).
+ * n_groups == 0 writes n_kept_out = 0.
+ */
+grpo_status grpo_filter_groups(const float *rewards, int64_t n_rollouts, const int32_t *group_offsets,
+                               int64_t n_groups, int64_t group_size, uint8_t *keep_out,
+                               int32_t *kept_groups_out, int32_t *n_kept_out,
+                               uint8_t *rollout_keep_out, void *stream);
+
+/*
  * Packed (variable-length) batches (section 4.1, sequence packing: samples are collated
  * along the sequence dimension instead of being padded).  The response tokens of rollout
  * i are the rows [cu_seqlens[i], cu_seqlens[i+1]) of the batch.  Writes per row

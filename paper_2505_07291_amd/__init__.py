@@ -2,7 +2,8 @@
 (forward + fused backward over the full vocabulary) as hand-written gfx950 kernels
 behind a C ABI (include/grpo.h).  This package is the thin binding plus the seeded
 synthetic workloads; it has no CPU implementation of the path."""
-from .binding import (COUNT_NAMES, GRPO_BF16, GRPO_F32, GrpoError, grpo_group_advantages,  # noqa: F401
+from .binding import (COUNT_NAMES, GRPO_BF16, GRPO_F32, GrpoError, grpo_filter_groups,  # noqa: F401
+                      grpo_group_advantages, grpo_total_rewards,
                       grpo_logprobs_fwd, grpo_loss_aux_fwd_bwd, grpo_loss_fwd_bwd, grpo_packed_layout,
                       grpo_workspace_bytes,
                       grpo_workspace_error, lib, status_string)

@@ -50,6 +50,10 @@ def lib():
         L.grpo_loss_aux_fwd_bwd.restype = i32
         L.grpo_loss_aux_fwd_bwd.argtypes = [vp, i32, i64, i64, i64, vp, vp, vp, vp, vp, vp, f32, f32, f32,
                                             f32, f32, f32, f64, f32, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.grpo_total_rewards.restype = i32
+        L.grpo_total_rewards.argtypes = [vp, vp, vp, i64, f32, vp, vp]
+        L.grpo_filter_groups.restype = i32
+        L.grpo_filter_groups.argtypes = [vp, i64, vp, i64, i64, vp, vp, vp, vp, vp]
         L.grpo_packed_layout.restype = i32
         L.grpo_packed_layout.argtypes = [vp, i64, i64, i32, vp, vp, vp]
         L.grpo_workspace_error.restype = i32
@@ -242,6 +246,45 @@ def grpo_loss_aux_fwd_bwd(logits, tokens, old_logprobs, ref_logprobs, advantages
     if rc != GRPO_OK:
         raise GrpoError(rc, "grpo_loss_aux_fwd_bwd")
     return loss_out, logprobs_out, entropy_out, counts_out, grad_logits
+
+
+def grpo_total_rewards(task_rewards, lengths, target_lengths, alpha, rewards_out=None, stream=None):
+    """r_task - alpha |l_target - l_y| per rollout; see grpo_total_rewards in grpo.h."""
+    dev = task_rewards.device
+    R = task_rewards.shape[0]
+    _check(task_rewards, torch.float32, R, "task_rewards", dev)
+    _check(lengths, torch.int32, R, "lengths", dev)
+    _check(target_lengths, torch.int32, R, "target_lengths", dev)
+    if rewards_out is None:
+        rewards_out = torch.empty(R, dtype=torch.float32, device=dev)
+    rc = lib().grpo_total_rewards(_ptr(task_rewards), _ptr(lengths), _ptr(target_lengths), R,
+                                  float(alpha), _ptr(rewards_out), _stream(stream))
+    if rc != GRPO_OK:
+        raise GrpoError(rc, "grpo_total_rewards")
+    return rewards_out
+
+
+def grpo_filter_groups(rewards, group_size=None, group_offsets=None, stream=None):
+    """Returns (keep u8 [n_groups], kept_groups i32 [n_groups], n_kept i32 [1], rollout_keep u8 [R]);
+    see grpo_filter_groups in grpo.h."""
+    dev = rewards.device
+    R = rewards.shape[0]
+    _check(rewards, torch.float32, R, "rewards", dev)
+    if group_offsets is not None:
+        _check(group_offsets, torch.int32, group_offsets.shape[0], "group_offsets", dev)
+        n_groups, gs = group_offsets.shape[0] - 1, 0
+    else:
+        gs = int(group_size)
+        n_groups = R // gs if gs > 0 else 0
+    keep = torch.empty(n_groups, dtype=torch.uint8, device=dev)
+    kept = torch.empty(n_groups, dtype=torch.int32, device=dev)
+    n_kept = torch.empty(1, dtype=torch.int32, device=dev)
+    rk = torch.zeros(R, dtype=torch.uint8, device=dev)
+    rc = lib().grpo_filter_groups(_ptr(rewards), R, _ptr(group_offsets), n_groups, gs, _ptr(keep),
+                                  _ptr(kept), _ptr(n_kept), _ptr(rk), _stream(stream))
+    if rc != GRPO_OK:
+        raise GrpoError(rc, "grpo_filter_groups")
+    return keep, kept, n_kept, rk
 
 
 def grpo_packed_layout(cu_seqlens, n_tokens, sample_level, weights_out=None, rollout_of_token_out=None,

@@ -1135,6 +1135,80 @@ __global__ void __launch_bounds__(256) grpo_adv_to_tokens(const float *adv, long
     }
 }
 
+// r_total = r_task - alpha |l_target - l_y| (section 3.1).  The length difference is formed
+// in integers, so it is exact.
+__global__ void __launch_bounds__(256) grpo_total_rewards_k(const float *task, const int *len,
+                                                            const int *target, long long n,
+                                                            float alpha, float *out)
+{
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256) {
+        const long long d = (long long)target[i] - (long long)len[i];
+        out[i] = task[i] - alpha * (float)(d < 0 ? -d : d);
+    }
+}
+
+// Online filter (section 3.3): flags the groups whose rewards are not all equal.  One
+// wavefront per group.
+__global__ void __launch_bounds__(64) grpo_filter_flag(const float *rewards, long long n_rollouts,
+                                                       const int *offsets, long long n_groups,
+                                                       long long group_size, unsigned char *keep,
+                                                       unsigned char *rollout_keep)
+{
+    const int lane = threadIdx.x;
+    for (long long g = blockIdx.x; g < n_groups; g += gridDim.x) {
+        long long b = offsets ? (long long)offsets[g] : g * group_size;
+        long long e = offsets ? (long long)offsets[g + 1] : (g + 1) * group_size;
+        b = b < 0 ? 0 : (b > n_rollouts ? n_rollouts : b);
+        e = e < b ? b : (e > n_rollouts ? n_rollouts : e);
+        int differs = 0;
+        if (e > b) {
+            const float first = rewards[b];
+            for (long long i = b + lane; i < e; i += 64) differs |= rewards[i] != first ? 1 : 0;
+        }
+        differs = __any(differs) ? 1 : 0;
+        if (lane == 0) keep[g] = (unsigned char)differs;
+        if (rollout_keep)
+            for (long long i = b + lane; i < e; i += 64) rollout_keep[i] = (unsigned char)differs;
+    }
+}
+
+// Ordered compaction of the kept group indices: one workgroup walks the flags in chunks
+// of 1024 with a running offset, so the output order is the input order.
+__global__ void __launch_bounds__(1024) grpo_filter_compact(const unsigned char *keep, long long n_groups,
+                                                            int *kept_groups, int *n_kept)
+{
+    __shared__ int wave_tot[16];
+    __shared__ int base;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    if (tid == 0) base = 0;
+    __syncthreads();
+    for (long long g0 = 0; g0 < n_groups; g0 += 1024) {
+        const long long g = g0 + tid;
+        const int k = (g < n_groups && keep[g]) ? 1 : 0;
+        int incl = k;  // inclusive scan inside the wavefront
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int up = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += up;
+        }
+        if (lane == 63) wave_tot[wv] = incl;
+        __syncthreads();
+        int before = base;
+        for (int w2 = 0; w2 < wv; ++w2) before += wave_tot[w2];
+        if (k) kept_groups[before + incl - 1] = (int)g;
+        __syncthreads();
+        if (tid == 0) {
+            int tot = 0;
+            for (int w2 = 0; w2 < 16; ++w2) tot += wave_tot[w2];
+            base += tot;
+        }
+        __syncthreads();
+    }
+    const int total = base;
+    for (long long g = total + tid; g < n_groups; g += 1024) kept_groups[g] = -1;
+    if (tid == 0) *n_kept = total;
+}
+
 // Packed (variable-length) batches: rollout i owns rows [cu[i], cu[i+1]).  First every
 // row gets "no rollout, weight 0", then each rollout stamps its range.
 __global__ void __launch_bounds__(256) grpo_packed_clear(long long n_tokens, float *weights,
@@ -1362,6 +1436,44 @@ grpo_status grpo_group_advantages(const float *rewards, int64_t n_rollouts,
         hipLaunchKernelGGL(grpo_adv_to_tokens, dim3((unsigned)blocks), dim3(256), 0, st, adv_out,
                            (long long)n_rollouts, rollout_of_token, (long long)n_tokens, adv_tok_out);
     }
+    return hipGetLastError() == hipSuccess ? GRPO_OK : GRPO_ERR_HIP;
+}
+
+grpo_status grpo_total_rewards(const float *task_rewards, const int32_t *lengths,
+                               const int32_t *target_lengths, int64_t n_rollouts, float alpha,
+                               float *rewards_out, void *stream)
+{
+    if (n_rollouts < 0) return GRPO_ERR_SHAPE;
+    if (!std::isfinite(alpha)) return GRPO_ERR_PARAM;
+    if (n_rollouts == 0) return GRPO_OK;
+    if (!task_rewards || !lengths || !target_lengths || !rewards_out) return GRPO_ERR_NULL;
+    long long blocks = (n_rollouts + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(grpo_total_rewards_k, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
+                       task_rewards, lengths, target_lengths, (long long)n_rollouts, alpha, rewards_out);
+    return hipGetLastError() == hipSuccess ? GRPO_OK : GRPO_ERR_HIP;
+}
+
+grpo_status grpo_filter_groups(const float *rewards, int64_t n_rollouts, const int32_t *group_offsets,
+                               int64_t n_groups, int64_t group_size, uint8_t *keep_out,
+                               int32_t *kept_groups_out, int32_t *n_kept_out,
+                               uint8_t *rollout_keep_out, void *stream)
+{
+    if (n_rollouts < 0 || n_groups < 0 || n_groups > 0x7fffffffll) return GRPO_ERR_SHAPE;
+    if (!group_offsets && n_groups > 0 && (group_size <= 0 || n_groups * group_size != n_rollouts))
+        return GRPO_ERR_SHAPE;
+    if (!n_kept_out) return GRPO_ERR_NULL;
+    if (n_groups > 0 && (!keep_out || !kept_groups_out)) return GRPO_ERR_NULL;
+    if (n_groups > 0 && n_rollouts > 0 && !rewards) return GRPO_ERR_NULL;
+    hipStream_t st = (hipStream_t)stream;
+    if (n_groups > 0) {
+        const unsigned grid = (unsigned)(n_groups < 4096 ? n_groups : 4096);
+        hipLaunchKernelGGL(grpo_filter_flag, dim3(grid), dim3(64), 0, st, rewards, (long long)n_rollouts,
+                           group_offsets, (long long)n_groups, (long long)group_size, keep_out,
+                           rollout_keep_out);
+    }
+    hipLaunchKernelGGL(grpo_filter_compact, dim3(1), dim3(1024), 0, st, keep_out, (long long)n_groups,
+                       kept_groups_out, n_kept_out);
     return hipGetLastError() == hipSuccess ? GRPO_OK : GRPO_ERR_HIP;
 }
 

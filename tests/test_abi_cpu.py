@@ -22,7 +22,7 @@ def declared_functions():
 def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert {"grpo_group_advantages", "grpo_logprobs_fwd", "grpo_loss_fwd_bwd", "grpo_loss_aux_fwd_bwd",
-            "grpo_packed_layout",
+            "grpo_packed_layout", "grpo_total_rewards", "grpo_filter_groups",
             "grpo_workspace_bytes", "grpo_status_string", "grpo_workspace_error"} <= set(names)
     L = grpo.lib()
     for n in names:
@@ -132,3 +132,19 @@ def test_packed_layout_rejects_bad_arguments():
     assert f(P, -1, 100, 1, P, P, None) == SHAPE
     assert f(P, 4, -5, 0, P, P, None) == SHAPE
     assert f(P, 4, 0, 0, P, None, None) == OK                  # nothing to do
+
+
+def test_reward_helpers_reject_bad_arguments():
+    L = grpo.lib()
+    f = L.grpo_total_rewards
+    assert f(None, P, P, 8, 3e-4, P, None) == NULL
+    assert f(P, P, P, 8, 3e-4, None, None) == NULL
+    assert f(P, P, P, -1, 3e-4, P, None) == SHAPE
+    assert f(P, P, P, 8, float("nan"), P, None) == PARAM
+    assert f(None, None, None, 0, 3e-4, None, None) == OK
+    h = L.grpo_filter_groups
+    assert h(P, 8, None, 2, 4, P, P, None, None, None) == NULL       # n_kept_out missing
+    assert h(P, 8, None, 2, 4, None, P, P, None, None) == NULL
+    assert h(None, 8, None, 2, 4, P, P, P, None, None) == NULL
+    assert h(P, 8, None, 2, 3, P, P, P, None, None) == SHAPE
+    assert h(P, 8, None, -2, 4, P, P, P, None, None) == SHAPE
