@@ -167,7 +167,7 @@ def main():
     full_counts = counts.cpu().tolist()
 
     # the old-policy log-probs pass (one read of the logits), every row unmasked
-    fwd_ws = torch.empty(256, dtype=torch.uint8, device=dev)
+    fwd_ws = torch.empty(grpo.grpo_workspace_bytes(0), dtype=torch.uint8, device=dev)
     fwd_evs = []
     for i in range(3 + max(5, args.steps // 3)):
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

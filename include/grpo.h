@@ -173,7 +173,8 @@ grpo_status grpo_packed_layout(const int64_t *cu_seqlens, int64_t n_rollouts, in
  *              Rows with mask 0 give logprobs_out = 0 and none of their inputs
  *              (logits, token) is read.
  *  logprobs_out[n_tokens] f32, device, written.
- *  workspace   device, optional (NULL allowed): at least 256 bytes, 256-byte aligned,
+ *  workspace   device, optional (NULL allowed): at least grpo_workspace_bytes(0) bytes,
+ *              256-byte aligned,
  *              contents ignored on entry.  With it rows are handed to workgroups
  *              through a queue, which keeps the GPU evenly loaded when many rows are
  *              masked; without it rows are assigned in a fixed strided pattern.  The

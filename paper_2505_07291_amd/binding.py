@@ -136,7 +136,7 @@ def grpo_group_advantages(rewards, group_size=None, group_offsets=None, eps_std=
 def grpo_logprobs_fwd(logits, tokens, mask=None, temperature=1.0, vocab=None, logprobs_out=None,
                       workspace=None, use_queue=True, stream=None):
     """log softmax(logits / T)[tokens] per row; see grpo_logprobs_fwd in grpo.h.
-    A 256-byte workspace for the row queue is allocated unless one is passed or
+    A small workspace for the row queue is allocated unless one is passed or
     ``use_queue`` is False."""
     dt, n, v, stride = _logits_args(logits, vocab)
     dev = logits.device
@@ -146,7 +146,7 @@ def grpo_logprobs_fwd(logits, tokens, mask=None, temperature=1.0, vocab=None, lo
     if logprobs_out is None:
         logprobs_out = torch.empty(n, dtype=torch.float32, device=dev)
     if workspace is None and use_queue and n > 0:
-        workspace = torch.empty(256, dtype=torch.uint8, device=dev)
+        workspace = torch.empty(grpo_workspace_bytes(0), dtype=torch.uint8, device=dev)
     rc = lib().grpo_logprobs_fwd(_ptr(logits), dt, n, v, stride, _ptr(tokens), _ptr(mask),
                                  float(temperature), _ptr(logprobs_out), _ptr(workspace),
                                  0 if workspace is None else workspace.numel(), _stream(stream))

@@ -36,9 +36,21 @@ struct WsHeader {
     long long M;   // rows with mask != 0
     int error;     // sticky data-error word (bit 0: token id out of range)
     int pad;
-    unsigned long long next_row;  // work queue of the row kernel: next row nobody has taken
 };
-constexpr size_t kHeaderBytes = 256;
+// The row queue: up to kQueueParts counters, each on a 128-byte line of its own, follow
+// the 256-byte header.  With P counters in use, counter q hands out the rows q, q + P,
+// q + 2P, ...  One counter for the whole GPU sustains only some 15-25 million increments
+// a second under contention (measured): enough for 300 KB rows (8 million rows a second),
+// not for 64 KB rows.  Narrow rows therefore use eight interleaved partitions, each
+// started on by an eighth of the workgroups and then stolen from in turn, which keeps
+// single-row granularity; wide rows use one counter, which measured 4-6 % faster there.
+constexpr int kQueueParts = 8;
+constexpr int kQueueStride = 16;  // in unsigned long long: 128 bytes
+constexpr size_t kHeaderBytes = 256 + (size_t)kQueueParts * kQueueStride * 8;
+__device__ __forceinline__ unsigned long long *queue_counters(WsHeader *hdr)
+{
+    return (unsigned long long *)((char *)hdr + 256);
+}
 constexpr long long kMaxVocab = 1ll << 28;  // byte offsets inside a row stay below 2^32
 
 struct RowParams {
@@ -57,6 +69,8 @@ struct RowParams {
     float inv_T;  // 1 / T
     float lo, hi, delta, grad_scale;
     int bwd;  // 0: log-probs only (grpo_logprobs_fwd), 1: objective + gradient
+    int queue_chunk;  // rows taken from the queue per increment
+    int queue_parts;  // counters in use (1 or kQueueParts)
     // auxiliary terms (kernels instantiated with AUX only)
     const float *ref_lp;  // reference-policy log-probs, or NULL (no KL term)
     const float *token_w; // per-token weights omega_t, or NULL (all ones); 0 = masked row
@@ -684,7 +698,7 @@ __device__ __forceinline__ void order_after(unsigned &off, X &x)
 // One workgroup per row at a time, rows strided over a persistent grid.
 // ---------------------------------------------------------------------------
 template <grpo_dtype DT, int BLOCK, int NV, bool AUX, bool TAIL>
-__global__ void __launch_bounds__(BLOCK) grpo_rows_cached(RowParams p)
+__global__ void __launch_bounds__(BLOCK, 4) grpo_rows_cached(RowParams p)  // 4 waves per SIMD: 128 VGPRs
 {
     constexpr int EPV = Elem<DT>::EPV;
     constexpr int BYTES = Elem<DT>::BYTES;
@@ -712,18 +726,42 @@ __global__ void __launch_bounds__(BLOCK) grpo_rows_cached(RowParams p)
     const bool queued = p.hdr != nullptr;
     long long strided_next = blockIdx.x;
     unsigned grabs = 0;
+    // very narrow rows are also handed out several at a time
+    const long long chunk = p.queue_chunk;
+    long long chunk_next = 0, chunk_end = 0;  // positions inside the current partition
+    // consecutive workgroups sit on different XCDs; dividing by 8 first spreads every
+    // partition over all XCDs (tying a partition to one XCD measured 4 % slower)
+    const int nparts = p.queue_parts;
+    int part = (int)((blockIdx.x / 8) % nparts), parts_done = 0;
     auto grab = [&]() -> long long {
         if (!queued) {
             const long long r = strided_next;
             strided_next += gridDim.x;
             return r;
         }
-        // two LDS slots used alternately: the barrier of grab k+1 separates the reads
-        // of grab k from the write of grab k+2 into the same slot
-        const unsigned slot = grabs++ & 1u;
-        if (tid == 0) lds_row[slot] = (long long)atomicAdd(&p.hdr->next_row, 1ull);
-        lds_barrier();
-        return uniform(lds_row[slot]);
+        for (;;) {
+            if (chunk_next < chunk_end) {
+                const long long r = part + (long long)nparts * chunk_next++;
+                if (r < p.n_tokens) return r;
+                chunk_next = chunk_end;  // ran off the end of this partition
+            }
+            if (parts_done == nparts) return p.n_tokens;
+            // two LDS slots used alternately: the barrier of grab k+1 separates the reads
+            // of grab k from the write of grab k+2 into the same slot
+            const unsigned slot = grabs++ & 1u;
+            if (tid == 0)
+                lds_row[slot] = (long long)atomicAdd(queue_counters(p.hdr) + part * kQueueStride,
+                                                     (unsigned long long)chunk);
+            lds_barrier();
+            const long long base = uniform(lds_row[slot]);
+            if (part + (long long)nparts * base >= p.n_tokens) {
+                part = (part + 1) % nparts;  // this partition is exhausted: help with the next
+                ++parts_done;
+                continue;
+            }
+            chunk_next = base;
+            chunk_end = base + chunk;
+        }
     };
     // next row that needs the full treatment; rows that do not (masked, bad token id)
     // are finished on the way
@@ -1005,6 +1043,7 @@ __global__ void __launch_bounds__(1024) grpo_prepare(const unsigned char *mask,
     }
     cnt = wave_sum(cnt);
     if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = cnt;
+    if (threadIdx.x < kQueueParts) queue_counters(hdr)[threadIdx.x * kQueueStride] = 0ull;
     __syncthreads();
     if (threadIdx.x == 0) {
         long long M = 0;
@@ -1016,15 +1055,14 @@ __global__ void __launch_bounds__(1024) grpo_prepare(const unsigned char *mask,
         hdr->M = M;
         hdr->error = 0;
         hdr->pad = 0;
-        hdr->next_row = 0ull;
     }
 }
 
 // Log-probs-only calls that bring a workspace use it for the row queue alone.
 __global__ void grpo_reset_queue(WsHeader *hdr)
 {
+    if (threadIdx.x < kQueueParts) queue_counters(hdr)[threadIdx.x * kQueueStride] = 0ull;
     if (threadIdx.x == 0) {
-        hdr->next_row = 0ull;
         hdr->error = 0;
     }
 }
@@ -1264,16 +1302,29 @@ void launch_cached(const RowParams &p, int blocks_per_cu, hipStream_t st)
 }
 
 template <grpo_dtype DT, bool AUX>
-void launch_rows(const RowParams &p, hipStream_t st)
+void launch_rows(const RowParams &p_in, hipStream_t st)
 {
+    RowParams p = p_in;
+    {   // rows per queue increment: 1 from 32 KB per row upwards, more for narrower rows
+        const long long row_bytes = p.vocab * Elem<DT>::BYTES;
+        long long c = (32768 + row_bytes - 1) / row_bytes;
+        p.queue_chunk = (int)(c < 1 ? 1 : (c > 64 ? 64 : c));
+        p.queue_parts = row_bytes < 200 * 1024 ? kQueueParts : 1;
+    }
     const long long nvec = (p.vocab + Elem<DT>::EPV - 1) / Elem<DT>::EPV;
     const bool ragged = p.vocab % Elem<DT>::EPV != 0;
+    // Narrow rows take small workgroups, several per CU (each around 16 slots per lane): the
+    // phases of different rows then overlap inside a CU and the per-row bookkeeping
+    // (queue, three barriers, scalar arithmetic) is hidden.  Only rows too wide for that
+    // use one 1024-lane workgroup per CU.
     if (nvec <= 256 * 1)
         launch_cached<DT, 256, 1, AUX, true>(p, 8, st);
     else if (nvec <= 256 * 4)
         launch_cached<DT, 256, 4, AUX, true>(p, 8, st);
-    else if (nvec <= 1024 * 4)
-        launch_cached<DT, 1024, 4, AUX, true>(p, 2, st);
+    else if (nvec <= 256 * 16)
+        launch_cached<DT, 256, 16, AUX, true>(p, 4, st);
+    else if (nvec <= 512 * 16)
+        launch_cached<DT, 512, 16, AUX, true>(p, 2, st);
     else if (nvec <= 1024 * 10)
         launch_cached<DT, 1024, 10, AUX, true>(p, 1, st);
     else if (nvec <= 1024 * 19 && !ragged)

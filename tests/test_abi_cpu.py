@@ -34,7 +34,7 @@ def test_status_strings_and_workspace_size():
         assert len(grpo.status_string(code)) > 1
     assert grpo.status_string(99) == "unknown status"
     assert grpo.grpo_workspace_bytes(-1) == 0
-    assert grpo.grpo_workspace_bytes(0) == 256
+    assert grpo.grpo_workspace_bytes(0) >= 256 and grpo.grpo_workspace_bytes(0) % 256 == 0
     for n in (1, 255, 256, 257, 131072):
         b = grpo.grpo_workspace_bytes(n)
         assert b % 256 == 0 and b >= 256 + 13 * n
@@ -78,7 +78,7 @@ def test_logprobs_and_advantages_reject_bad_arguments():
     assert f(P + 4, 1, 4, 64, 64, P, None, 1.0, P, None, 0, None) == ALIGN
     assert f(P, 1, 4, 63, 63, P, None, 1.0, P, None, 0, None) == ALIGN     # 126-byte row pitch
     assert f(P, 1, 4, 64, 64, P, None, 0.0, P, None, 0, None) == PARAM
-    assert f(P, 1, 4, 64, 64, P, None, 1.0, P, P + 8, 256, None) == WORKSPACE   # misaligned
+    assert f(P, 1, 4, 64, 64, P, None, 1.0, P, P + 8, 1 << 16, None) == WORKSPACE   # misaligned
     assert f(P, 1, 4, 64, 64, P, None, 1.0, P, P, 100, None) == WORKSPACE       # too small
     assert f(P, 1, 0, 64, 64, None, None, 1.0, None, None, 0, None) == OK   # nothing to do
     g = L.grpo_group_advantages
