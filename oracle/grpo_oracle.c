@@ -35,7 +35,9 @@
  * finite differences, a hand-derived branch table; for the auxiliary terms:
  * library entropy, binary-entropy closed form, the identity
  * sum_y pi(y) kl(y) = KL(pi || pi_ref), autograd and finite differences of the
- * total).  None is "parity unpinned".
+ * total; for the language-model head: library matrix products, the identity
+ * weight matrix, finite differences through the whole composition, column
+ * sums of dW).  None is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -639,6 +641,87 @@ int oracle_filter_groups(const float *rewards, int64_t n_rollouts, const int32_t
     for (int64_t k = n_kept; k < n_groups; ++k)
         kept_groups_out[k] = -1;
     *n_kept_out = n_kept;
+    return 0;
+}
+
+/* ------------------------------------------------------------------ *
+ * Language-model head in front of the objective.  The policy pi_theta of
+ * section 3.4 is the softmax of the logits z_t = W h_t that the model's last
+ * linear layer produces from the final hidden state h_t of token position t
+ * (W holds one row of d weights per vocabulary entry, no bias).  When the
+ * objective is differentiated with respect to h and W instead of z the chain
+ * rule adds two contractions to the gradient G = dL/dz:
+ *     dL/dh_t = sum_v G[t][v] W[v][:],      dL/dW[v][:] = sum_t G[t][v] h_t.
+ * The three functions below are those definitions, written as plain loops.
+ * Stored bf16 / fp32 values widen exactly; each product of two widened bf16
+ * values is exact in fp64 and a plain running sum of d (or V, or n) of them
+ * carries a relative error near 1e-13, far below every tolerance that uses
+ * these results, so no compensated sum is spent here.
+ * ------------------------------------------------------------------ */
+
+/* logits_out[i][v] = sum_k hidden[row_i][k] * weight[v][k]; row_i = rows[i],
+ * or i when rows is NULL (then n_sel = number of rows of hidden). */
+int oracle_lmhead_logits(const void *hidden, int h_dtype, int64_t d, int64_t h_stride,
+                         const void *weight, int w_dtype, int64_t V, int64_t w_stride,
+                         const int64_t *rows, int64_t n_sel, double *logits_out)
+{
+    if (!hidden || !weight || !logits_out || d <= 0 || V <= 0 || n_sel < 0)
+        return 1;
+#pragma omp parallel
+    {
+        double *h = (double *)malloc((size_t)d * sizeof(double));
+        for (int64_t i = 0; i < n_sel; ++i) {
+            int64_t t = rows ? rows[i] : i;
+            for (int64_t k = 0; k < d; ++k)
+                h[k] = logit_at(hidden, h_dtype, t * h_stride + k);
+#pragma omp for schedule(static)
+            for (int64_t v = 0; v < V; ++v) {
+                double acc = 0.0;
+                for (int64_t k = 0; k < d; ++k)
+                    acc += h[k] * logit_at(weight, w_dtype, v * w_stride + k);
+                logits_out[i * V + v] = acc;
+            }
+        }
+        free(h);
+    }
+    return 0;
+}
+
+/* dH_out[i][k] = sum_v G[i][v] * weight[v][k]  (G has n_sel rows of V). */
+int oracle_lmhead_grad_hidden(const double *G, int64_t n_sel, int64_t V,
+                              const void *weight, int w_dtype, int64_t d, int64_t w_stride,
+                              double *dH_out)
+{
+    if (!G || !weight || !dH_out || d <= 0 || V <= 0 || n_sel < 0)
+        return 1;
+#pragma omp parallel for schedule(static) collapse(2)
+    for (int64_t i = 0; i < n_sel; ++i)
+        for (int64_t k = 0; k < d; ++k) {
+            double acc = 0.0;
+            for (int64_t v = 0; v < V; ++v)
+                acc += G[i * V + v] * logit_at(weight, w_dtype, v * w_stride + k);
+            dH_out[i * d + k] = acc;
+        }
+    return 0;
+}
+
+/* dW_out[j][k] = sum_t G[t][v_j] * hidden[t][k] over all n_rows token rows;
+ * v_j = vocab_rows[j], or j when vocab_rows is NULL (then n_sel = V). */
+int oracle_lmhead_grad_weight(const double *G, int64_t n_rows, int64_t V,
+                              const void *hidden, int h_dtype, int64_t d, int64_t h_stride,
+                              const int64_t *vocab_rows, int64_t n_sel, double *dW_out)
+{
+    if (!G || !hidden || !dW_out || d <= 0 || V <= 0 || n_rows < 0 || n_sel < 0)
+        return 1;
+#pragma omp parallel for schedule(static) collapse(2)
+    for (int64_t j = 0; j < n_sel; ++j)
+        for (int64_t k = 0; k < d; ++k) {
+            int64_t v = vocab_rows ? vocab_rows[j] : j;
+            double acc = 0.0;
+            for (int64_t t = 0; t < n_rows; ++t)
+                acc += G[t * V + v] * logit_at(hidden, h_dtype, t * h_stride + k);
+            dW_out[j * d + k] = acc;
+        }
     return 0;
 }
 

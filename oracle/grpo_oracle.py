@@ -83,6 +83,12 @@ def lib():
         L.oracle_total_rewards.argtypes = [vp, vp, vp, i64, dbl, vp]
         L.oracle_filter_groups.restype = i32
         L.oracle_filter_groups.argtypes = [vp, i64, vp, i64, i64, vp, vp, vp, vp]
+        L.oracle_lmhead_logits.restype = i32
+        L.oracle_lmhead_logits.argtypes = [vp, i32, i64, i64, vp, i32, i64, i64, vp, i64, vp]
+        L.oracle_lmhead_grad_hidden.restype = i32
+        L.oracle_lmhead_grad_hidden.argtypes = [vp, i64, i64, vp, i32, i64, i64, vp]
+        L.oracle_lmhead_grad_weight.restype = i32
+        L.oracle_lmhead_grad_weight.argtypes = [vp, i64, i64, vp, i32, i64, i64, vp, i64, vp]
         L.oracle_num_threads.restype = i32
         L.oracle_num_threads.argtypes = []
         _lib = L
@@ -379,3 +385,65 @@ def filter_groups(rewards, group_size=None, group_offsets=None):
     if rc:
         raise ValueError("oracle_filter_groups: bad group offsets")
     return keep, kept, int(n_kept[0]), rk
+
+
+def lmhead_logits(hidden, weight, rows=None):
+    """z = h W^T in fp64 for the token rows in ``rows`` (all rows when None).
+    hidden [N, d] and weight [V, d] are float32, float64 or uint16 bf16 bit patterns."""
+    h, hdt, hs = _logits_view(hidden)
+    w, wdt, ws = _logits_view(weight)
+    d = h.shape[1]
+    assert w.shape[1] == d
+    V = w.shape[0]
+    r = None if rows is None else np.ascontiguousarray(rows, dtype=np.int64)
+    n = h.shape[0] if r is None else r.shape[0]
+    out = np.zeros((n, V), dtype=np.float64)
+    rc = lib().oracle_lmhead_logits(_ptr(h), hdt, d, hs, _ptr(w), wdt, V, ws, _ptr(r), n, _ptr(out))
+    if rc:
+        raise ValueError("oracle_lmhead_logits failed (rc=%d)" % rc)
+    return out
+
+
+def lmhead_grad_hidden(G, weight):
+    """dL/dh rows: G [n, V] (fp64 gradient with respect to the logits) times W."""
+    G = np.ascontiguousarray(G, dtype=np.float64)
+    w, wdt, ws = _logits_view(weight)
+    V, d = w.shape
+    assert G.ndim == 2 and G.shape[1] == V
+    out = np.zeros((G.shape[0], d), dtype=np.float64)
+    rc = lib().oracle_lmhead_grad_hidden(_ptr(G), G.shape[0], V, _ptr(w), wdt, d, ws, _ptr(out))
+    if rc:
+        raise ValueError("oracle_lmhead_grad_hidden failed (rc=%d)" % rc)
+    return out
+
+
+def lmhead_grad_weight(G, hidden, vocab_rows=None):
+    """dL/dW rows ``vocab_rows`` (all when None): G^T [V, N] times the hidden states [N, d]."""
+    G = np.ascontiguousarray(G, dtype=np.float64)
+    h, hdt, hs = _logits_view(hidden)
+    N, d = h.shape
+    assert G.ndim == 2 and G.shape[0] == N
+    V = G.shape[1]
+    r = None if vocab_rows is None else np.ascontiguousarray(vocab_rows, dtype=np.int64)
+    n = V if r is None else r.shape[0]
+    out = np.zeros((n, d), dtype=np.float64)
+    rc = lib().oracle_lmhead_grad_weight(_ptr(G), N, V, _ptr(h), hdt, d, hs, _ptr(r), n, _ptr(out))
+    if rc:
+        raise ValueError("oracle_lmhead_grad_weight failed (rc=%d)" % rc)
+    return out
+
+
+def lmhead_loss_fwd_bwd(hidden, weight, tokens, old_logprobs, advantages, mask=None, *,
+                        eps_low=0.2, eps_high=0.2, delta=4.0, temperature=1.0, denom=0.0,
+                        grad_scale=1.0, want_grads=True):
+    """The objective of ``loss_fwd_bwd`` on logits z = h W^T that are never rounded,
+    and its gradient with respect to the hidden states and the head's weights."""
+    z = lmhead_logits(hidden, weight)
+    res = loss_fwd_bwd(z, tokens, old_logprobs, advantages, mask, eps_low=eps_low,
+                       eps_high=eps_high, delta=delta, temperature=temperature, denom=denom,
+                       grad_scale=grad_scale, grad_rows="all" if want_grads else None)
+    res["logits"] = z
+    if want_grads:
+        res["grad_hidden"] = lmhead_grad_hidden(res["grad"], weight)
+        res["grad_weight"] = lmhead_grad_weight(res["grad"], hidden)
+    return res

@@ -1,0 +1,145 @@
+"""Pins of the oracle's language-model-head functions (logits z = h W^T in front of the
+objective of section 3.4, and the chain rule back to h and W), CPU only: library matrix
+products, the identity weight matrix, closed forms, autograd, finite differences."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import grpo_oracle as orc
+from test_oracle_pins import to_bf16_bits, bf16_bits_to_f64
+
+
+def _problem(seed, N=6, d=5, V=9, dtype="f64"):
+    rng = np.random.default_rng(seed)
+    h = rng.standard_normal((N, d))
+    w = rng.standard_normal((V, d)) * 0.8
+    if dtype == "bf16":
+        h, w = to_bf16_bits(h.astype(np.float32)), to_bf16_bits(w.astype(np.float32))
+    elif dtype == "f32":
+        h, w = h.astype(np.float32), w.astype(np.float32)
+    tokens = rng.integers(0, V, N)
+    adv = rng.standard_normal(N).astype(np.float32)
+    mask = (rng.random(N) < 0.8).astype(np.uint8)
+    mask[0] = 1
+    return rng, h, w, tokens, adv, mask
+
+
+def _wide(a):
+    return bf16_bits_to_f64(a) if a.dtype == np.uint16 else a.astype(np.float64)
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32", "bf16"])
+def test_contractions_match_library_products(dtype):
+    # non-square everywhere, so a transposed operand or a swapped index cannot pass
+    rng, h, w, *_ = _problem(1, N=7, d=13, V=19, dtype=dtype)
+    H, W = _wide(h), _wide(w)
+    z = orc.lmhead_logits(h, w)
+    assert z.shape == (7, 19)
+    assert np.abs(z - H @ W.T).max() < 1e-13
+    assert np.abs(orc.lmhead_logits(h, w, rows=[5, 0, 5]) - (H @ W.T)[[5, 0, 5]]).max() < 1e-13
+    G = rng.standard_normal((7, 19))
+    assert np.abs(orc.lmhead_grad_hidden(G, w) - G @ W).max() < 1e-13
+    assert np.abs(orc.lmhead_grad_weight(G, h) - G.T @ H).max() < 1e-13
+    assert np.abs(orc.lmhead_grad_weight(G, h, [18, 3]) - (G.T @ H)[[18, 3]]).max() < 1e-13
+
+
+def test_row_strides_are_honoured():
+    rng = np.random.default_rng(2)
+    hb = rng.standard_normal((4, 16)).astype(np.float32)
+    wb = rng.standard_normal((6, 24)).astype(np.float32)
+    h, w = hb[:, :5], wb[:, :5]          # contiguous rows, row stride larger than d
+    z = orc.lmhead_logits(h, w)
+    assert np.abs(z - h.astype(np.float64) @ w.astype(np.float64).T).max() < 1e-13
+    G = rng.standard_normal((4, 6))
+    assert np.abs(orc.lmhead_grad_hidden(G, w) - G @ w.astype(np.float64)).max() < 1e-13
+    assert np.abs(orc.lmhead_grad_weight(G, h) - G.T @ h.astype(np.float64)).max() < 1e-13
+
+
+def test_identity_weight_reduces_to_the_logits_objective():
+    # W = I (V = d): z = h, dL/dh = dL/dz, dL/dW = G^T h
+    rng, h, _, tokens, adv, mask = _problem(3, N=8, d=12, V=12, dtype="bf16")
+    w = to_bf16_bits(np.eye(12, dtype=np.float32))
+    old = (rng.standard_normal(8) * 0.3 - 2.5).astype(np.float32)
+    a = orc.lmhead_loss_fwd_bwd(h, w, tokens, old, adv, mask, temperature=0.7)
+    b = orc.loss_fwd_bwd(h, tokens, old, adv, mask, temperature=0.7, grad_rows="all")
+    assert a["loss"] == b["loss"] and np.array_equal(a["logprobs"], b["logprobs"])
+    assert np.array_equal(a["counts"], b["counts"])
+    assert np.array_equal(a["grad_hidden"], b["grad"])
+    assert np.abs(a["grad_weight"] - b["grad"].T @ bf16_bits_to_f64(h)).max() < 1e-15
+
+
+def test_equal_weight_rows_give_a_uniform_policy():
+    # every vocabulary row of W equal: z is constant along the row, pi is uniform,
+    # log pi(y) = -ln V, and both gradients vanish (G rows sum to zero)
+    rng, h, _, tokens, adv, mask = _problem(4, N=5, d=6, V=10)
+    w = np.tile(rng.standard_normal((1, 6)), (10, 1))
+    old = np.full(5, -math.log(10), np.float32)
+    r = orc.lmhead_loss_fwd_bwd(h, w, tokens, old, adv, mask)
+    m = mask.astype(bool)
+    assert np.abs(r["logprobs"][m] + math.log(10)).max() < 1e-14
+    assert np.abs(r["grad_hidden"]).max() < 1e-15
+    assert np.abs(r["grad_weight"].sum(axis=0)).max() < 1e-15
+
+
+def test_weight_gradient_columns_sum_to_zero_and_masked_rows_vanish():
+    rng, h, w, tokens, adv, mask = _problem(5, N=16, d=7, V=33, dtype="bf16")
+    mask[3] = 0
+    old = (orc.logprobs(orc.lmhead_logits(h, w), tokens) + rng.standard_normal(16) * 0.1)
+    r = orc.lmhead_loss_fwd_bwd(h, w, tokens, old.astype(np.float32), adv, mask)
+    assert np.abs(r["grad_weight"].sum(axis=0)).max() < 1e-15
+    assert np.all(r["grad_hidden"][mask == 0] == 0)
+    assert np.abs(r["grad_hidden"][mask == 1]).max() > 0
+
+
+def _torch_loss(H, W, tokens, old, adv, mask, eps_low, eps_high, delta, T):
+    z = H @ W.T / T
+    lp = torch.log_softmax(z, dim=-1).gather(1, tokens[:, None])[:, 0]
+    r = torch.exp(lp - old)
+    J = torch.minimum(torch.clamp(r, max=delta) * adv, torch.clamp(r, 1 - eps_low, 1 + eps_high) * adv)
+    return -(J * mask).sum() / mask.sum()
+
+
+@pytest.mark.parametrize("seed,T", [(11, 1.0), (12, 0.7)])
+def test_gradients_match_autograd(seed, T):
+    rng, h, w, tokens, adv, mask = _problem(seed, N=24, d=8, V=17)
+    new = orc.logprobs(orc.lmhead_logits(h, w), tokens, temperature=T)
+    old = (new + rng.uniform(-1.8, 1.8, 24)).astype(np.float32)    # both clip sides and the delta cap
+    kw = dict(eps_low=0.2, eps_high=0.3, delta=4.0)
+    res = orc.lmhead_loss_fwd_bwd(h, w, tokens, old, adv, mask, temperature=T, **kw)
+    H = torch.tensor(h, requires_grad=True)
+    W = torch.tensor(w, requires_grad=True)
+    loss = _torch_loss(H, W, torch.tensor(tokens), torch.tensor(old, dtype=torch.float64),
+                       torch.tensor(adv, dtype=torch.float64), torch.tensor(mask, dtype=torch.float64),
+                       T=T, **kw)
+    loss.backward()
+    assert abs(res["loss"] - loss.item()) < 1e-13
+    assert np.abs(res["grad_hidden"] - H.grad.numpy()).max() < 1e-13
+    assert np.abs(res["grad_weight"] - W.grad.numpy()).max() < 1e-13
+    assert res["counts"][1] > 0 and res["counts"][2] > 0 and res["counts"][3] > 0
+
+
+def test_gradients_match_central_differences():
+    rng, h, w, tokens, adv, mask = _problem(21, N=10, d=4, V=7)
+    new = orc.logprobs(orc.lmhead_logits(h, w), tokens)
+    # keep every ratio a safe distance inside a smooth region of the surrogate
+    old = (new + rng.choice([-0.1, 0.05, 0.12], 10)).astype(np.float32)
+    res = orc.lmhead_loss_fwd_bwd(h, w, tokens, old, adv, mask, grad_scale=1.5)
+    step = 1e-6
+
+    def loss_at(hh, ww):
+        return 1.5 * orc.lmhead_loss_fwd_bwd(hh, ww, tokens, old, adv, mask, want_grads=False)["loss"]
+
+    for (t, k) in [(0, 0), (4, 3), (9, 1)]:
+        hp, hm = h.copy(), h.copy()
+        hp[t, k] += step
+        hm[t, k] -= step
+        fd = (loss_at(hp, w) - loss_at(hm, w)) / (2 * step)
+        assert abs(fd - res["grad_hidden"][t, k]) < 1e-8, (t, k)
+    for (v, k) in [(0, 0), (6, 2), (int(tokens[0]), 1)]:
+        wp, wm = w.copy(), w.copy()
+        wp[v, k] += step
+        wm[v, k] -= step
+        fd = (loss_at(h, wp) - loss_at(h, wm)) / (2 * step)
+        assert abs(fd - res["grad_weight"][v, k]) < 1e-8, (v, k)
