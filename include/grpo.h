@@ -284,6 +284,75 @@ grpo_status grpo_loss_aux_fwd_bwd(const void *logits, grpo_dtype dtype, int64_t 
  */
 grpo_status grpo_workspace_error(const void *workspace, int32_t *flag_out, void *stream);
 
+/* ------------------------------------------------------------------------- *
+ * Language-model head fused with the objective.
+ *
+ * The policy pi_theta of section 3.4 is the softmax of the logits z_t = W h_t that
+ * the model's last linear layer (no bias) computes from the final hidden state
+ * h_t of each token position.  These two calls take h and W instead of z: the
+ * logits are formed tile by tile on the matrix cores and reduced from the fp32
+ * accumulators, so log pi(y) is not affected by a bf16 rounding of z.
+ *
+ *  hidden   [n_tokens, d_model] bf16, device, read; row pitch hidden_stride
+ *           elements (>= d_model), base and pitch 16-byte aligned.
+ *  weight   [vocab, d_model] bf16, device, read; row v holds the d_model weights of
+ *           vocabulary entry v; row pitch weight_stride, aligned like hidden.
+ *  d_model  a multiple of 64, at most 2^20.  vocab in [1, 2^28].
+ *  tokens, mask, temperature, old_logprobs, advantages, eps_low, eps_high, delta,
+ *  denom, grad_scale, loss_out, logprobs_out, counts_out: as in
+ *           grpo_logprobs_fwd / grpo_loss_fwd_bwd.
+ *  workspace  device, 256-byte aligned, at least
+ *           grpo_lmhead_workspace_bytes(n_tokens, vocab, d_model, with_backward)
+ *           bytes.  Forward only it is small (8 bytes per token and 256 vocabulary
+ *           entries); with the backward it also holds the logits in fp32, the
+ *           gradient with respect to them in bf16 (twice: row-major and
+ *           transposed) and transposed copies of W and h, about
+ *           8 * n_tokens * vocab + 2 * vocab * d_model bytes.  Contents on entry are
+ *           ignored; the error word is read with grpo_workspace_error.
+ * Errors as for grpo_loss_fwd_bwd; additionally GRPO_ERR_SHAPE when d_model is not
+ * a multiple of 64 or a pitch is smaller than d_model.  All work is enqueued on
+ * `stream`; nothing is allocated.
+ * ------------------------------------------------------------------------- */
+
+/* Pure host function; 0 for invalid sizes. */
+size_t grpo_lmhead_workspace_bytes(int64_t n_tokens, int64_t vocab, int64_t d_model, int with_backward);
+
+/*
+ * logprobs_out[t] = log softmax(W h_t / T)[y_t] for rows with mask 1 (0 at masked
+ * rows, NaN where the token id is outside [0, vocab)): what the trainer recomputes
+ * as the old policy's log-probs before its optimiser steps (section 4.1).  The
+ * logits never reach memory.
+ */
+grpo_status grpo_lmhead_logprobs_fwd(const void *hidden, int64_t hidden_stride, const void *weight,
+                                     int64_t weight_stride, int64_t n_tokens, int64_t vocab,
+                                     int64_t d_model, const int64_t *tokens, const uint8_t *mask,
+                                     float temperature, float *logprobs_out, void *workspace,
+                                     size_t workspace_bytes, void *stream);
+
+/*
+ * The objective of grpo_loss_fwd_bwd on z = h W^T and its gradient with respect to
+ * h and W (chain rule through the head: dL/dh_t = sum_v G[t][v] W[v][:],
+ * dL/dW[v][:] = sum_t G[t][v] h_t, with G = grad_scale * dloss/dz as defined for
+ * grpo_loss_fwd_bwd).
+ *  grad_hidden  [n_tokens, d_model] bf16, device, written (zero rows where the
+ *               objective has no gradient); row pitch grad_hidden_stride elements.
+ *  grad_weight  [vocab, d_model] f32, device; row pitch grad_weight_stride elements.
+ *               accumulate_grad_weight == 0: overwritten; != 0: added to, which is
+ *               how a trainer sums micro-batches (pass the global token count as
+ *               denom in that case).
+ * G is rounded to bf16 before the two products, which accumulate in fp32.
+ */
+grpo_status grpo_lmhead_loss_fwd_bwd(const void *hidden, int64_t hidden_stride, const void *weight,
+                                     int64_t weight_stride, int64_t n_tokens, int64_t vocab,
+                                     int64_t d_model, const int64_t *tokens, const float *old_logprobs,
+                                     const float *advantages, const uint8_t *mask, float eps_low,
+                                     float eps_high, float delta, float temperature, double denom,
+                                     float grad_scale, float *loss_out, float *logprobs_out,
+                                     int64_t *counts_out, void *grad_hidden, int64_t grad_hidden_stride,
+                                     float *grad_weight, int64_t grad_weight_stride,
+                                     int accumulate_grad_weight, void *workspace, size_t workspace_bytes,
+                                     void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -58,6 +58,14 @@ def lib():
         L.grpo_packed_layout.argtypes = [vp, i64, i64, i32, vp, vp, vp]
         L.grpo_workspace_error.restype = i32
         L.grpo_workspace_error.argtypes = [vp, vp, vp]
+        L.grpo_lmhead_workspace_bytes.restype = sz
+        L.grpo_lmhead_workspace_bytes.argtypes = [i64, i64, i64, i32]
+        L.grpo_lmhead_logprobs_fwd.restype = i32
+        L.grpo_lmhead_logprobs_fwd.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, vp, f32, vp, vp, sz, vp]
+        L.grpo_lmhead_loss_fwd_bwd.restype = i32
+        L.grpo_lmhead_loss_fwd_bwd.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, vp, vp, vp, f32, f32,
+                                               f32, f32, f64, f32, vp, vp, vp, vp, i64, vp, i64, i32,
+                                               vp, sz, vp]
         _lib = L
     return _lib
 
@@ -311,3 +319,88 @@ def grpo_workspace_error(workspace, stream=None) -> int:
     if rc != GRPO_OK:
         raise GrpoError(rc, "grpo_workspace_error")
     return int(flag.value)
+
+
+def grpo_lmhead_workspace_bytes(n_tokens: int, vocab: int, d_model: int, with_backward: bool) -> int:
+    return int(lib().grpo_lmhead_workspace_bytes(int(n_tokens), int(vocab), int(d_model),
+                                                 1 if with_backward else 0))
+
+
+def _lmhead_args(hidden, weight):
+    for name, t in (("hidden", hidden), ("weight", weight)):
+        if t.dim() != 2 or t.stride(1) != 1 or t.dtype != torch.bfloat16 or not t.is_cuda:
+            raise ValueError("%s must be a 2-D bfloat16 device tensor with unit stride along d_model" % name)
+    n, d = hidden.shape
+    v = weight.shape[0]
+    if weight.shape[1] != d:
+        raise ValueError("hidden is [n_tokens, d_model] and weight [vocab, d_model]: d_model differs")
+    hs = hidden.stride(0) if n > 1 else max(hidden.stride(0), d)
+    ws = weight.stride(0) if v > 1 else max(weight.stride(0), d)
+    return n, v, d, hs, ws
+
+
+def grpo_lmhead_logprobs_fwd(hidden, weight, tokens, mask=None, temperature=1.0, logprobs_out=None,
+                             workspace=None, stream=None):
+    """log softmax(hidden @ weight.T / T)[tokens] per row without materialising the logits; see
+    grpo_lmhead_logprobs_fwd in grpo.h."""
+    n, v, d, hs, ws = _lmhead_args(hidden, weight)
+    dev = hidden.device
+    _check(tokens, torch.int64, n, "tokens", dev)
+    if mask is not None:
+        _check(mask, torch.uint8, n, "mask", dev)
+    if logprobs_out is None:
+        logprobs_out = torch.empty(n, dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = torch.empty(grpo_lmhead_workspace_bytes(n, v, d, False), dtype=torch.uint8, device=dev)
+    rc = lib().grpo_lmhead_logprobs_fwd(_ptr(hidden), hs, _ptr(weight), ws, n, v, d, _ptr(tokens),
+                                        _ptr(mask), float(temperature), _ptr(logprobs_out),
+                                        _ptr(workspace), workspace.numel(), _stream(stream))
+    if rc != GRPO_OK:
+        raise GrpoError(rc, "grpo_lmhead_logprobs_fwd")
+    return logprobs_out
+
+
+def grpo_lmhead_loss_fwd_bwd(hidden, weight, tokens, old_logprobs, advantages, mask=None, eps_low=0.2,
+                             eps_high=0.2, delta=4.0, temperature=1.0, denom=0.0, grad_scale=1.0, *,
+                             grad_hidden=None, grad_weight=None, accumulate_grad_weight=False,
+                             loss_out=None, logprobs_out=None, counts_out=None, workspace=None,
+                             stream=None):
+    """Objective on hidden @ weight.T with gradients for both operands; see
+    grpo_lmhead_loss_fwd_bwd in grpo.h.  Returns (loss [1], logprobs [n], counts [5],
+    grad_hidden bf16 [n, d], grad_weight f32 [vocab, d])."""
+    n, v, d, hs, ws = _lmhead_args(hidden, weight)
+    dev = hidden.device
+    _check(tokens, torch.int64, n, "tokens", dev)
+    _check(old_logprobs, torch.float32, n, "old_logprobs", dev)
+    _check(advantages, torch.float32, n, "advantages", dev)
+    if mask is not None:
+        _check(mask, torch.uint8, n, "mask", dev)
+    if grad_hidden is None:
+        grad_hidden = torch.empty((n, d), dtype=torch.bfloat16, device=dev)
+    if grad_weight is None:
+        if accumulate_grad_weight:
+            raise ValueError("accumulate_grad_weight needs the grad_weight tensor to add to")
+        grad_weight = torch.empty((v, d), dtype=torch.float32, device=dev)
+    if grad_hidden.dtype != torch.bfloat16 or grad_hidden.shape != (n, d) or grad_hidden.stride(1) != 1:
+        raise ValueError("grad_hidden must be bfloat16 [n_tokens, d_model] with unit inner stride")
+    if grad_weight.dtype != torch.float32 or grad_weight.shape != (v, d) or grad_weight.stride(1) != 1:
+        raise ValueError("grad_weight must be float32 [vocab, d_model] with unit inner stride")
+    if loss_out is None:
+        loss_out = torch.empty(1, dtype=torch.float32, device=dev)
+    if logprobs_out is None:
+        logprobs_out = torch.empty(n, dtype=torch.float32, device=dev)
+    if counts_out is None:
+        counts_out = torch.empty(5, dtype=torch.int64, device=dev)
+    if workspace is None:
+        workspace = torch.empty(grpo_lmhead_workspace_bytes(n, v, d, True), dtype=torch.uint8, device=dev)
+    ghs = grad_hidden.stride(0) if n > 1 else max(grad_hidden.stride(0), d)
+    gws = grad_weight.stride(0) if v > 1 else max(grad_weight.stride(0), d)
+    rc = lib().grpo_lmhead_loss_fwd_bwd(
+        _ptr(hidden), hs, _ptr(weight), ws, n, v, d, _ptr(tokens), _ptr(old_logprobs), _ptr(advantages),
+        _ptr(mask), float(eps_low), float(eps_high), float(delta), float(temperature), float(denom),
+        float(grad_scale), _ptr(loss_out), _ptr(logprobs_out), _ptr(counts_out), _ptr(grad_hidden), ghs,
+        _ptr(grad_weight), gws, 1 if accumulate_grad_weight else 0, _ptr(workspace), workspace.numel(),
+        _stream(stream))
+    if rc != GRPO_OK:
+        raise GrpoError(rc, "grpo_lmhead_loss_fwd_bwd")
+    return loss_out, logprobs_out, counts_out, grad_hidden, grad_weight

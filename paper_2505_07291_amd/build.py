@@ -41,7 +41,7 @@ def is_stale() -> bool:
     if not os.path.exists(LIB_PATH):
         return True
     t = os.path.getmtime(LIB_PATH)
-    deps = SOURCES + [os.path.join(INCLUDE, "grpo.h")]
+    deps = SOURCES + [os.path.join(_PKG, "csrc", "lmhead.hpp"), os.path.join(INCLUDE, "grpo.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 

@@ -1627,3 +1627,5 @@ grpo_status grpo_workspace_error(const void *workspace, int32_t *flag_out, void 
 }
 
 }  // extern "C"
+
+#include "lmhead.hpp"
