@@ -340,7 +340,8 @@ grpo_status grpo_lmhead_logprobs_fwd(const void *hidden, int64_t hidden_stride, 
  *               accumulate_grad_weight == 0: overwritten; != 0: added to, which is
  *               how a trainer sums micro-batches (pass the global token count as
  *               denom in that case).
- * G is rounded to bf16 before the two products, which accumulate in fp32.
+ * G is rounded to bf16 (8 significant bits: relative error at most 2^-8 per element)
+ * before the two products, which accumulate in fp32.
  */
 grpo_status grpo_lmhead_loss_fwd_bwd(const void *hidden, int64_t hidden_stride, const void *weight,
                                      int64_t weight_stride, int64_t n_tokens, int64_t vocab,

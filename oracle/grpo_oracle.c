@@ -687,21 +687,27 @@ int oracle_lmhead_logits(const void *hidden, int h_dtype, int64_t d, int64_t h_s
     return 0;
 }
 
-/* dH_out[i][k] = sum_v G[i][v] * weight[v][k]  (G has n_sel rows of V). */
+/* dH_out[i][k] = sum_v G[i][v] * weight[v][k]  (G has n_sel rows of V).  The sum over
+ * v is the outer loop so that the weights are walked row by row. */
 int oracle_lmhead_grad_hidden(const double *G, int64_t n_sel, int64_t V,
                               const void *weight, int w_dtype, int64_t d, int64_t w_stride,
                               double *dH_out)
 {
     if (!G || !weight || !dH_out || d <= 0 || V <= 0 || n_sel < 0)
         return 1;
-#pragma omp parallel for schedule(static) collapse(2)
-    for (int64_t i = 0; i < n_sel; ++i)
-        for (int64_t k = 0; k < d; ++k) {
-            double acc = 0.0;
-            for (int64_t v = 0; v < V; ++v)
-                acc += G[i * V + v] * logit_at(weight, w_dtype, v * w_stride + k);
-            dH_out[i * d + k] = acc;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t i = 0; i < n_sel; ++i) {
+        double *out = dH_out + i * d;
+        for (int64_t k = 0; k < d; ++k)
+            out[k] = 0.0;
+        for (int64_t v = 0; v < V; ++v) {
+            const double g = G[i * V + v];
+            if (g == 0.0)
+                continue;
+            for (int64_t k = 0; k < d; ++k)
+                out[k] += g * logit_at(weight, w_dtype, v * w_stride + k);
         }
+    }
     return 0;
 }
 

@@ -218,3 +218,62 @@ def make_old_logprobs(cfg: Workload, new_logprobs, seed=None, guard=1e-3):
             break
         noise[bad] = draw(k)
     return (new + noise).to(torch.float32)
+
+
+def make_lmhead_batch(cfg: Workload, d_model: int, device="cpu", seed=None, chunk_rows=4096):
+    """The inputs of the fused language-model-head path for the recipe of ``cfg``: final
+    hidden states [N, d_model] and head weights [vocab, d_model] in bf16 instead of logits.
+
+    hidden ~ N(0, 1) and weight ~ N(0, logit_std^2 / d_model), so the logits h W^T have the
+    configured standard deviation; for "normal_boost" each row's hidden state is moved along
+    its sampled token's weight row so that this one logit rises by 8 (the other logits
+    move by 8 cos(w_v, w_y), a few tenths).  Tokens, mask, rewards and lengths are the
+    ones ``make_batch`` draws for the same seed.  Only the "normal" recipes exist here.
+    """
+    if cfg.logits not in ("normal", "normal_boost"):
+        raise ValueError("make_lmhead_batch supports the normal and normal_boost recipes")
+    device = torch.device(device)
+    seed = BASE_SEED + cfg.index if seed is None else seed
+    N, V, R, L = cfg.n_tokens, cfg.vocab, cfg.n_rollouts, cfg.seq_len
+    small = _gen("cpu", seed)
+    big = _gen(device, seed + 2000)
+    if cfg.len_dist == "uniform":
+        lengths = torch.randint(cfg.len_lo, cfg.len_hi + 1, (R,), generator=small)
+    elif cfg.len_dist == "lognormal":
+        z = torch.randn(R, generator=small, dtype=torch.float64)
+        lengths = torch.exp(math.log(300.0 * L / 1024.0) + 0.8 * z).round().clamp(1, L).to(torch.int64)
+    else:
+        lengths = torch.full((R,), L, dtype=torch.int64)
+    lengths = lengths.clamp(max=L)
+    pos = torch.arange(L).expand(R, L)
+    mask = (pos < lengths[:, None]).to(torch.uint8).reshape(N)
+    rollout_of_token = torch.arange(R, dtype=torch.int32)[:, None].expand(R, L).reshape(N).contiguous()
+    if cfg.reward == "bernoulli":
+        rewards = (torch.rand(R, generator=small) < cfg.reward_p).to(torch.float32)
+    elif cfg.reward == "uniform":
+        rewards = torch.rand(R, generator=small)
+    else:
+        rewards = torch.randint(0, 3, (R,), generator=small).to(torch.float32) * 0.5
+    for g in range(min(cfg.forced_zero_groups, cfg.n_prompts)):
+        rewards[g * cfg.group_size:(g + 1) * cfg.group_size] = 0.0
+    tokens = torch.randint(0, V, (N,), generator=small, dtype=torch.int64).to(device)
+
+    weight = torch.empty((V, d_model), dtype=torch.bfloat16, device=device)
+    for v0 in range(0, V, chunk_rows):
+        v1 = min(V, v0 + chunk_rows)
+        w = torch.randn((v1 - v0, d_model), generator=big, device=device, dtype=torch.float32)
+        weight[v0:v1] = (w * (cfg.logit_std / math.sqrt(d_model))).to(torch.bfloat16)
+    hidden = torch.empty((N, d_model), dtype=torch.bfloat16, device=device)
+    for r0 in range(0, N, chunk_rows):
+        r1 = min(N, r0 + chunk_rows)
+        h = torch.randn((r1 - r0, d_model), generator=big, device=device, dtype=torch.float32)
+        if cfg.logits == "normal_boost":
+            wy = weight[tokens[r0:r1]].to(torch.float32)
+            h += 8.0 * wy / (wy * wy).sum(dim=1, keepdim=True).clamp_min(1e-20)
+        hidden[r0:r1] = h.to(torch.bfloat16)
+    return dict(cfg=cfg, hidden=hidden, weight=weight, d_model=d_model, tokens=tokens,
+                mask=mask.to(device), rewards=rewards.to(device),
+                rollout_of_token=rollout_of_token.to(device), lengths=lengths,
+                n_tokens=N, vocab=V, n_rollouts=R, group_size=cfg.group_size,
+                eps_low=cfg.eps_low, eps_high=cfg.eps_high, delta=cfg.delta,
+                temperature=cfg.temperature, seed=seed)

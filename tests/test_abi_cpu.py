@@ -148,3 +148,56 @@ def test_reward_helpers_reject_bad_arguments():
     assert h(None, 8, None, 2, 4, P, P, P, None, None) == NULL
     assert h(P, 8, None, 2, 3, P, P, P, None, None) == SHAPE
     assert h(P, 8, None, -2, 4, P, P, P, None, None) == SHAPE
+
+
+def lmhead_args(**over):
+    a = dict(hidden=P, hs=128, weight=P, wstride=128, n=16, V=1000, d=128, tokens=P, old=P, adv=P, mask=P,
+             el=0.2, eh=0.2, delta=4.0, T=1.0, denom=0.0, gs=1.0, loss=P, lp=P, counts=P,
+             gh=P, ghs=128, gw=P, gws=128, acc=0, ws=P, ws_bytes=1 << 30, stream=None)
+    a.update(over)
+    return [a[k] for k in ("hidden", "hs", "weight", "wstride", "n", "V", "d", "tokens", "old", "adv",
+                           "mask", "el", "eh", "delta", "T", "denom", "gs", "loss", "lp", "counts",
+                           "gh", "ghs", "gw", "gws", "acc", "ws", "ws_bytes", "stream")]
+
+
+@pytest.mark.parametrize("over,expect", [
+    (dict(hidden=None), NULL), (dict(weight=None), NULL), (dict(tokens=None), NULL), (dict(old=None), NULL),
+    (dict(adv=None), NULL), (dict(loss=None), NULL), (dict(gh=None), NULL), (dict(gw=None), NULL),
+    (dict(n=-1), SHAPE), (dict(V=0), SHAPE), (dict(d=0), SHAPE), (dict(d=96, hs=96, wstride=96), SHAPE),
+    (dict(hs=64), SHAPE), (dict(wstride=120), SHAPE), (dict(ghs=64), SHAPE), (dict(gws=100), SHAPE),
+    (dict(V=(1 << 28) + 1), SHAPE), (dict(d=1 << 21, hs=1 << 21, wstride=1 << 21), SHAPE),
+    (dict(hidden=P + 8), ALIGN), (dict(weight=P + 2), ALIGN), (dict(hs=132), ALIGN), (dict(wstride=129), ALIGN),
+    (dict(T=0.0), PARAM), (dict(T=float("nan")), PARAM), (dict(el=1.5), PARAM), (dict(eh=-0.1), PARAM),
+    (dict(delta=1.2), PARAM), (dict(denom=float("nan")), PARAM),
+    (dict(ws=None), WORKSPACE), (dict(ws=P + 64), WORKSPACE), (dict(ws_bytes=4096), WORKSPACE),
+])
+def test_lmhead_loss_rejects_bad_arguments_before_any_launch(over, expect):
+    assert grpo.lib().grpo_lmhead_loss_fwd_bwd(*lmhead_args(**over)) == expect
+
+
+def test_lmhead_logprobs_rejects_bad_arguments_and_sizes_its_workspace():
+    L = grpo.lib()
+    ok = dict(hidden=P, hs=128, weight=P, wstride=128, n=16, V=1000, d=128, tokens=P, mask=None, T=1.0,
+              lp=P, ws=P, ws_bytes=1 << 30, stream=None)
+
+    def call(**over):
+        a = dict(ok)
+        a.update(over)
+        return L.grpo_lmhead_logprobs_fwd(*[a[k] for k in ("hidden", "hs", "weight", "wstride", "n", "V", "d",
+                                                           "tokens", "mask", "T", "lp", "ws", "ws_bytes",
+                                                           "stream")])
+    assert call(n=0, hidden=None, tokens=None, lp=None) == OK     # nothing to do
+    assert call(lp=None) == NULL and call(hidden=None) == NULL
+    assert call(d=100, hs=100, wstride=100) == SHAPE and call(T=-1.0) == PARAM
+    assert call(ws=None) == WORKSPACE and call(ws_bytes=64) == WORKSPACE
+    assert call(hs=130) == ALIGN
+    # workspace sizes: forward is per-token and per-256-vocabulary-entries small; backward holds
+    # the logits (fp32), their gradient (bf16, twice) and the transposed operands
+    n, V, d = 16384, 152064, 5120
+    fwd = grpo.grpo_lmhead_workspace_bytes(n, V, d, False)
+    bwd = grpo.grpo_lmhead_workspace_bytes(n, V, d, True)
+    assert fwd % 256 == 0 and bwd % 256 == 0
+    assert fwd < 100 << 20 and fwd >= grpo.grpo_workspace_bytes(n) + 8 * n * ((V + 255) // 256)
+    assert bwd >= 8 * n * V + 2 * V * d and bwd < 9 * n * V + 4 * V * d
+    assert grpo.grpo_lmhead_workspace_bytes(-1, V, d, True) == 0
+    assert grpo.grpo_lmhead_workspace_bytes(n, 0, d, True) == 0

@@ -1,0 +1,289 @@
+"""GPU parity of the fused language-model-head path (hidden states and head weights in,
+loss / log-probs / counts / dL/dH / dL/dW out) against the fp64 oracle.
+
+Tolerances:
+  per-token log-prob  |dl| <= 2e-4, loss rel <= 1e-4, indicator counts exact (as for the
+      logits path: the logits come out of fp32 accumulators, no bf16 rounding in between);
+  dL/dH, dL/dW: the kernel rounds G = dL/dz to bf16 before the two products, which
+      accumulate in fp32, and rounds dL/dH to bf16 on output.  bf16 keeps 8 significant
+      bits, so rounding to nearest moves a value by at most u = 2^-8 of its magnitude.
+      Worst case, element by element:
+         |d dH[t,k]| <= u sum_v |G[t,v]| |W[v,k]| + u |dH[t,k]|
+         |d dW[v,k]| <= u sum_t |G[t,v]| |H[t,k]|
+      tested with 5 % of slack for the fp32 parts (accumulation order, softmax) plus, for
+      dL/dH, the absolute resolution 2^-22 |c_t / T| max|W| of 1 - p_y on rows whose sampled
+      token holds nearly all the probability;
+  in addition the error must look like rounding noise, not like a systematic term: over a
+      whole matrix its Frobenius norm stays below 0.6 u times the norm of the bounds above
+      (independent roundings have an r.m.s. of at most u / sqrt(3) = 0.58 u of the value).
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2505_07291_amd as grpo
+from paper_2505_07291_amd import workloads as wl
+from oracle import grpo_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda"
+TOL_LOGP = 2e-4
+TOL_LOSS_REL = 1e-4
+U = 2.0 ** -8
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def f32(x):
+    return float(np.float32(x))
+
+
+def bits(t):
+    return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
+def wide(b):
+    return (b.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def oracle_inputs(batch):
+    """Oracle advantages per token and log-probs; old log-probs from those."""
+    cfg = batch["cfg"]
+    adv = orc.group_advantages(batch["rewards"].cpu().numpy(), group_size=batch["group_size"])
+    adv_tok = orc.broadcast_advantages(adv, batch["rollout_of_token"].cpu().numpy()).astype(np.float32)
+    hb, wb = bits(batch["hidden"]), bits(batch["weight"])
+    z = orc.lmhead_logits(hb, wb)
+    lp = orc.logprobs(z, batch["tokens"].cpu().numpy(), batch["mask"].cpu().numpy(),
+                      temperature=f32(batch["temperature"]))
+    old = wl.make_old_logprobs(cfg, lp)
+    return hb, wb, adv_tok, lp, old
+
+
+def check_grads(dH, dW, res, hb, wb, T, label):
+    G = res["grad"]
+    Hw, Ww = wide(hb), wide(wb)
+    dH_o, dW_o = res["grad_hidden"], res["grad_weight"]
+    bound_H = np.abs(G) @ np.abs(Ww)
+    bound_W = np.abs(G).T @ np.abs(Hw)
+    floor_H = (2.0 ** -22) * np.abs(res["coeff"] / T)[:, None] * np.abs(Ww).max()
+    eH = np.abs(dH.double().cpu().numpy() - dH_o)
+    eW = np.abs(dW.double().cpu().numpy() - dW_o)
+    say("[gpu] %s dH err max %.3e (max|dH| %.3e), dW err max %.3e (max|dW| %.3e)" %
+        (label, eH.max(), np.abs(dH_o).max(), eW.max(), np.abs(dW_o).max()))
+    assert np.all(eH <= 1.05 * U * (bound_H + np.abs(dH_o)) + floor_H), "dL/dH outside its rounding bound"
+    assert np.all(eW <= 1.05 * U * bound_W + 1e-30), "dL/dW outside its rounding bound"
+    assert np.linalg.norm(eH) <= 0.6 * U * np.linalg.norm(bound_H + np.abs(dH_o)) + np.linalg.norm(floor_H)
+    assert np.linalg.norm(eW) <= 0.6 * U * np.linalg.norm(bound_W)
+    # rows without gradient are exact zeros
+    dead = res["coeff"] == 0
+    assert np.all(dH.cpu().float().numpy()[dead] == 0.0)
+
+
+def run_case(cfg, d_model, *, denom=0.0, grad_scale=1.0, label=""):
+    batch = wl.make_lmhead_batch(cfg, d_model, device=DEV)
+    hb, wb, adv_tok, lp_o, old = oracle_inputs(batch)
+    kw = dict(eps_low=f32(cfg.eps_low), eps_high=f32(cfg.eps_high), delta=f32(cfg.delta))
+    T = f32(cfg.temperature)
+    N, V = batch["n_tokens"], batch["vocab"]
+    mask_np = batch["mask"].cpu().numpy()
+    res = orc.lmhead_loss_fwd_bwd(hb, wb, batch["tokens"].cpu().numpy(), old.numpy(), adv_tok, mask_np,
+                                  temperature=T, denom=denom, grad_scale=f32(grad_scale), **kw)
+    say("[gpu] %s grpo_lmhead_loss_fwd_bwd N=%d V=%d d=%d T=%g" % (label, N, V, d_model, T))
+    loss, lp, counts, dH, dW = grpo.grpo_lmhead_loss_fwd_bwd(
+        batch["hidden"], batch["weight"], batch["tokens"], old.to(DEV), torch.as_tensor(adv_tok, device=DEV),
+        batch["mask"], temperature=T, denom=denom, grad_scale=grad_scale, **kw)
+    torch.cuda.synchronize()
+    lp_g = lp.cpu().numpy().astype(np.float64)
+    err = np.abs(lp_g - res["logprobs"]).max()
+    say("[gpu] %s log-prob err %.3e, loss %.8g vs %.8g, counts %s" %
+        (label, err, loss.item(), res["loss"], counts.tolist()))
+    assert err <= TOL_LOGP
+    assert np.all(lp_g[mask_np == 0] == 0.0)
+    assert counts.cpu().numpy().tolist() == res["counts"].tolist()
+    assert abs(loss.item() - res["loss"]) <= TOL_LOSS_REL * abs(res["loss"]) + 1e-7
+    check_grads(dH, dW, res, hb, wb, T, label)
+    # the forward-only entry point gives the same log-probs, bit for bit
+    lp2 = grpo.grpo_lmhead_logprobs_fwd(batch["hidden"], batch["weight"], batch["tokens"], batch["mask"], T)
+    torch.cuda.synchronize()
+    assert torch.equal(lp2, lp)
+    return batch, old, adv_tok, (loss, lp, counts, dH, dW)
+
+
+SHAPES = [
+    # (config, prompts, group, seq_len, vocab, d_model): several 256-tiles and ragged tails in
+    # every dimension that has one
+    ("qwen_short", 2, 4, 64, 1000, 128),      # 512 rows, V ragged (4 column tiles)
+    ("qwen_short", 3, 4, 25, 777, 64),        # 300 rows ragged, one k-step
+    ("qwen_medium", 2, 4, 100, 2600, 192),    # T = 0.7, 800 rows, 11 column tiles
+    ("long_reasoning", 4, 4, 40, 1300, 320),  # mostly masked rows, two all-zero groups
+    ("numerics_stress", 2, 4, 64, 900, 128),  # ratios e^-3..e^3: both clip sides and the delta cap
+]
+
+
+@pytest.mark.parametrize("name,P,G,L,V,D", SHAPES)
+def test_reduced_configs_every_element(name, P, G, L, V, D):
+    cfg = wl.CONFIGS[name].scaled(n_prompts=P, seq_len=L, vocab=V, group_size=G)
+    if cfg.logits not in ("normal", "normal_boost"):
+        cfg = wl.replace(cfg, logits="normal", logit_std=3.0)
+    run_case(cfg, D, label="%s %dx%dx%d" % (name, P * G * L, V, D))
+
+
+def test_denominator_grad_scale_accumulate_and_determinism():
+    cfg = wl.CONFIGS["qwen_short"].scaled(n_prompts=2, seq_len=40, vocab=1500, group_size=4)
+    batch, old, adv_tok, out = run_case(cfg, 128, denom=1000.0, grad_scale=2.5, label="denom/scale")
+    loss, lp, counts, dH, dW = out
+    kw = dict(eps_low=f32(cfg.eps_low), eps_high=f32(cfg.eps_high), delta=f32(cfg.delta),
+              temperature=f32(cfg.temperature), denom=1000.0, grad_scale=2.5)
+    args = (batch["hidden"], batch["weight"], batch["tokens"], old.to(DEV),
+            torch.as_tensor(adv_tok, device=DEV), batch["mask"])
+    # run to run: identical bits
+    loss2, lp2, counts2, dH2, dW2 = grpo.grpo_lmhead_loss_fwd_bwd(*args, **kw)
+    torch.cuda.synchronize()
+    assert torch.equal(loss, loss2) and torch.equal(lp, lp2) and torch.equal(dH, dH2) and torch.equal(dW, dW2)
+    # accumulate: the second call adds the same gradient
+    acc = dW.clone()
+    grpo.grpo_lmhead_loss_fwd_bwd(*args, grad_weight=acc, accumulate_grad_weight=True, **kw)
+    torch.cuda.synchronize()
+    assert torch.equal(acc, dW + dW)
+
+
+def test_strided_operands():
+    cfg = wl.CONFIGS["qwen_short"].scaled(n_prompts=1, seq_len=70, vocab=600, group_size=4)
+    batch = wl.make_lmhead_batch(cfg, 128, device=DEV)
+    n, V, d = batch["n_tokens"], batch["vocab"], 128
+    hs = torch.zeros((n, d + 64), dtype=torch.bfloat16, device=DEV)
+    ws = torch.zeros((V, d + 8), dtype=torch.bfloat16, device=DEV)
+    hs[:, :d] = batch["hidden"]
+    ws[:, :d] = batch["weight"]
+    lp_a = grpo.grpo_lmhead_logprobs_fwd(batch["hidden"], batch["weight"], batch["tokens"], batch["mask"])
+    lp_b = grpo.grpo_lmhead_logprobs_fwd(hs[:, :d], ws[:, :d], batch["tokens"], batch["mask"])
+    torch.cuda.synchronize()
+    assert torch.equal(lp_a, lp_b)
+    old = lp_a + 0.05
+    adv = torch.randn(n, device=DEV, generator=torch.Generator(DEV).manual_seed(5))
+    a = grpo.grpo_lmhead_loss_fwd_bwd(batch["hidden"], batch["weight"], batch["tokens"], old, adv, batch["mask"])
+    gh = torch.full((n, d + 32), 7.0, dtype=torch.bfloat16, device=DEV)
+    gw = torch.full((V, d + 4), 7.0, dtype=torch.float32, device=DEV)
+    b = grpo.grpo_lmhead_loss_fwd_bwd(hs[:, :d], ws[:, :d], batch["tokens"], old, adv, batch["mask"],
+                                      grad_hidden=gh[:, :d], grad_weight=gw[:, :d])
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[3], gh[:, :d]) and torch.equal(a[4], gw[:, :d])
+    assert torch.all(gh[:, d:] == 7.0) and torch.all(gw[:, d:] == 7.0)   # padding untouched
+
+
+def test_edge_cases():
+    V, d = 300, 64
+    w = (torch.randn(V, d, device=DEV) * 0.3).bfloat16()
+    # no tokens: zero loss, zero weight gradient
+    h0 = torch.zeros((0, d), dtype=torch.bfloat16, device=DEV)
+    e = lambda dt: torch.zeros(0, dtype=dt, device=DEV)
+    gw = torch.full((V, d), 3.0, device=DEV)
+    loss, lp, counts, dH, dW = grpo.grpo_lmhead_loss_fwd_bwd(h0, w, e(torch.int64), e(torch.float32),
+                                                             e(torch.float32), e(torch.uint8), grad_weight=gw)
+    torch.cuda.synchronize()
+    assert loss.item() == 0.0 and counts.tolist() == [0, 0, 0, 0, 0] and torch.all(gw == 0.0)
+    # every row masked
+    n = 130
+    h = torch.randn(n, d, device=DEV).bfloat16()
+    tok = torch.randint(0, V, (n,), device=DEV)
+    z = torch.zeros(n, device=DEV)
+    loss, lp, counts, dH, dW = grpo.grpo_lmhead_loss_fwd_bwd(h, w, tok, z, z + 1, torch.zeros(n, dtype=torch.uint8, device=DEV))
+    torch.cuda.synchronize()
+    assert loss.item() == 0.0 and torch.all(lp == 0) and torch.all(dH == 0) and torch.all(dW == 0)
+    # a token id outside the vocabulary: the row is dropped and the error word set
+    tok_bad = tok.clone()
+    tok_bad[7] = V + 5
+    ws = torch.empty(grpo.grpo_lmhead_workspace_bytes(n, V, d, True), dtype=torch.uint8, device=DEV)
+    m1 = torch.ones(n, dtype=torch.uint8, device=DEV)
+    loss, lp, counts, dH, dW = grpo.grpo_lmhead_loss_fwd_bwd(h, w, tok_bad, z - 5, z + 1, m1, workspace=ws)
+    assert grpo.grpo_workspace_error(ws) == 1
+    assert lp[7].item() == 0.0 and torch.all(dH[7] == 0)
+    loss, lp, counts, dH, dW = grpo.grpo_lmhead_loss_fwd_bwd(h, w, tok, z - 5, z + 1, m1, workspace=ws)
+    assert grpo.grpo_workspace_error(ws) == 0
+    # V = 1: the only token has probability 1, log-prob 0, no gradient
+    w1 = w[:1].contiguous()
+    tok0 = torch.zeros(n, dtype=torch.int64, device=DEV)
+    loss, lp, counts, dH, dW = grpo.grpo_lmhead_loss_fwd_bwd(h, w1, tok0, z, z + 1, m1)
+    torch.cuda.synchronize()
+    assert lp.abs().max().item() < 1e-6 and torch.all(dH == 0) and torch.all(dW == 0)
+    assert abs(loss.item() + 1.0) < 1e-6      # r = 1, A = 1: loss = -1
+    # argument errors are reported, not launched
+    with pytest.raises(grpo.GrpoError):
+        grpo.grpo_lmhead_logprobs_fwd(h[:, :48], w[:, :48], tok)        # d_model not a multiple of 64
+    with pytest.raises(grpo.GrpoError):
+        grpo.grpo_lmhead_loss_fwd_bwd(h, w, tok, z, z, m1, delta=1.1)    # delta <= 1 + eps_high
+    with pytest.raises(grpo.GrpoError):
+        grpo.grpo_lmhead_logprobs_fwd(h, w, tok, workspace=torch.empty(256, dtype=torch.uint8, device=DEV))
+
+
+def test_full_size_qwen_short_sampled_rows():
+    """BASELINE configs[1] with a 5120-wide head (the hidden size of the paper's 32B model):
+    log-probs and dL/dH rows against the oracle on sampled rows of every class, dL/dW through
+    properties that hold at any size."""
+    cfg = wl.CONFIGS["qwen_short"]
+    d = 5120
+    batch = wl.make_lmhead_batch(cfg, d, device=DEV)
+    N, V = batch["n_tokens"], batch["vocab"]
+    T = f32(cfg.temperature)
+    kw = dict(eps_low=f32(cfg.eps_low), eps_high=f32(cfg.eps_high), delta=f32(cfg.delta))
+    mask_np = batch["mask"].cpu().numpy()
+    tokens_np = batch["tokens"].cpu().numpy()
+    rng = np.random.default_rng(11)
+    live_rows = np.flatnonzero(mask_np == 1)
+    rows = np.sort(np.concatenate([rng.choice(live_rows, 20, replace=False),
+                                   rng.choice(np.flatnonzero(mask_np == 0), 4, replace=False)]))
+    hb, wb = bits(batch["hidden"]), bits(batch["weight"])
+    say("[gpu] full-size lmhead: oracle logits for %d sampled rows" % len(rows))
+    z_rows = orc.lmhead_logits(hb, wb, rows=rows)
+    lp_rows = orc.logprobs(z_rows, tokens_np[rows], mask_np[rows], temperature=T)
+    # old log-probs for every row come from a cheap stand-in (the sampled rows get the oracle's)
+    adv = orc.group_advantages(batch["rewards"].cpu().numpy(), group_size=batch["group_size"])
+    adv_tok = orc.broadcast_advantages(adv, batch["rollout_of_token"].cpu().numpy()).astype(np.float32)
+    say("[gpu] full-size lmhead: grpo_lmhead_logprobs_fwd N=%d V=%d d=%d" % (N, V, d))
+    lp_g = grpo.grpo_lmhead_logprobs_fwd(batch["hidden"], batch["weight"], batch["tokens"], batch["mask"], T)
+    torch.cuda.synchronize()
+    err = np.abs(lp_g.cpu().numpy().astype(np.float64)[rows] - lp_rows).max()
+    say("[gpu] full-size lmhead: log-prob err on sampled rows %.3e" % err)
+    assert err <= TOL_LOGP
+    # old = fixed offsets from a host generator; sampled rows use the oracle's log-probs, the
+    # others the library's: the objective at the sampled rows then depends on oracle values only
+    gen = torch.Generator().manual_seed(77)
+    noise = (torch.randn(N, generator=gen) * 0.1).clamp(-0.15, 0.15)
+    base = lp_g.cpu().double()
+    base[torch.as_tensor(rows)] = torch.as_tensor(lp_rows)
+    old = (base + noise.double()).float()
+    M = int(mask_np.sum())
+    say("[gpu] full-size lmhead: grpo_lmhead_loss_fwd_bwd")
+    loss, lp, counts, dH, dW = grpo.grpo_lmhead_loss_fwd_bwd(
+        batch["hidden"], batch["weight"], batch["tokens"], old.to(DEV), torch.as_tensor(adv_tok, device=DEV),
+        batch["mask"], temperature=T, **kw)
+    torch.cuda.synchronize()
+    assert torch.equal(lp, lp_g)
+    assert int(counts[0]) == M
+    obj = orc.objective_from_logprobs(lp_rows, old.numpy()[rows], adv_tok[rows], mask_np[rows],
+                                      denom=float(M), **kw)
+    G_rows = orc.grad_rows(z_rows, tokens_np[rows], obj["coeff"], temperature=T)
+    dH_o = orc.lmhead_grad_hidden(G_rows, wb)
+    Ww_max = float(np.abs(wide(wb[:4096])).max())
+    bound = np.abs(G_rows) @ np.abs(wide(wb))
+    eH = np.abs(dH.cpu().double().numpy()[rows] - dH_o)
+    floor = (2.0 ** -22) * np.abs(obj["coeff"] / T)[:, None] * Ww_max
+    say("[gpu] full-size lmhead: dH err max %.3e (max|dH| %.3e)" % (eH.max(), np.abs(dH_o).max()))
+    assert np.all(eH <= 1.05 * U * (bound + np.abs(dH_o)) + floor)
+    assert np.all(dH.cpu().float().numpy()[rows][obj["coeff"] == 0] == 0.0)
+    # dL/dW: (1) <dW, W> = <G, Z> = <dH, H> ties the two products to each other;
+    # (2) its column sums vanish up to the bf16 rounding of G, because every row of G sums to 0
+    inner_W = (dW.double() * batch["weight"].double()).sum().item()
+    inner_H = (dH.double() * batch["hidden"].double()).sum().item()
+    scale = (dW.double().abs() * batch["weight"].double().abs()).sum().item()
+    say("[gpu] full-size lmhead: <dW,W> %.6e <dH,H> %.6e (scale %.3e)" % (inner_W, inner_H, scale))
+    assert abs(inner_W - inner_H) <= U * scale
+    col = dW.double().sum(dim=0).abs().max().item()
+    col_scale = dW.double().abs().sum(dim=0).max().item()
+    assert col <= U * col_scale
