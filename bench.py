@@ -69,6 +69,66 @@ def cpu_baseline(batch, old, adv_tok, budget_s=10.0, block=512):
                        "forward+backward in blocks of %d rows, %.1f s" % (done, live, block, t_used))
 
 
+def lmhead_leg(grpo, wl, cfg, d_model, dev, stream, reps):
+    """The fused language-model-head path on the same recipe: hidden states [N, d_model] and head
+    weights [V, d_model] instead of logits.  A dense contraction, so its roofline is the bf16
+    matrix-core peak; flops are the algorithmic 2 N V d per product (one product forward,
+    three with the backward)."""
+    import torch
+    N, V = cfg.n_tokens, cfg.vocab
+    log("[bench] language-model-head leg: N=%d V=%d d=%d" % (N, V, d_model))
+    b = wl.make_lmhead_batch(cfg, d_model, dev)
+    lp = torch.empty(N, dtype=torch.float32, device=dev)
+    ws_f = torch.empty(grpo.grpo_lmhead_workspace_bytes(N, V, d_model, False), dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(grpo.grpo_lmhead_workspace_bytes(N, V, d_model, True), dtype=torch.uint8, device=dev)
+    dH = torch.empty((N, d_model), dtype=torch.bfloat16, device=dev)
+    dW = torch.empty((V, d_model), dtype=torch.float32, device=dev)
+    loss = torch.empty(1, dtype=torch.float32, device=dev)
+    counts = torch.empty(5, dtype=torch.int64, device=dev)
+    adv, adv_tok = grpo.grpo_group_advantages(b["rewards"], group_size=cfg.group_size,
+                                              rollout_of_token=b["rollout_of_token"], stream=stream)
+
+    def fwd():
+        grpo.grpo_lmhead_logprobs_fwd(b["hidden"], b["weight"], b["tokens"], b["mask"], cfg.temperature,
+                                      logprobs_out=lp, workspace=ws_f, stream=stream)
+    fwd()
+    torch.cuda.synchronize()
+    old = wl.make_old_logprobs(cfg, lp).to(dev)
+
+    def fwd_bwd():
+        grpo.grpo_lmhead_loss_fwd_bwd(b["hidden"], b["weight"], b["tokens"], old, adv_tok, b["mask"],
+                                      cfg.eps_low, cfg.eps_high, cfg.delta, cfg.temperature, 0.0, 1.0,
+                                      grad_hidden=dH, grad_weight=dW, loss_out=loss, logprobs_out=lp,
+                                      counts_out=counts, workspace=ws_b, stream=stream)
+
+    def timed(fn):
+        fn()
+        evs = []
+        for _ in range(reps):
+            a, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            fn()
+            e.record(stream)
+            evs.append((a, e))
+        torch.cuda.synchronize()
+        return sum(a.elapsed_time(e) for a, e in evs) / reps
+    ms_f = timed(fwd)
+    ms_b = timed(fwd_bwd)
+    flops = 2.0 * N * V * d_model
+    return {"note": "grpo_lmhead_logprobs_fwd / grpo_lmhead_loss_fwd_bwd: hidden [N, d] and head "
+                    "weights [V, d] in bf16, logits formed on the matrix cores",
+            "d_model": d_model, "fwd_ms": ms_f, "fwd_tokens_per_s": N / (ms_f * 1e-3),
+            "fwd_bwd_ms": ms_b, "fwd_bwd_tokens_per_s": N / (ms_b * 1e-3), "loss": float(loss.cpu()),
+            "roofline": {"bound": "mfma", "achieved": flops / (ms_f * 1e-3) / 1e12, "peak": 2500.0,
+                         "unit": "TFLOP/s", "frac": flops / (ms_f * 1e-3) / 1e12 / 2500.0,
+                         "kernel": "lm_gemm_nt (forward: logits + softmax partials)",
+                         "algorithmic_flops": flops, "traffic": None},
+            "roofline_fwd_bwd": {"bound": "mfma", "achieved": 3 * flops / (ms_b * 1e-3) / 1e12,
+                                 "peak": 2500.0, "unit": "TFLOP/s",
+                                 "frac": 3 * flops / (ms_b * 1e-3) / 1e12 / 2500.0,
+                                 "algorithmic_flops": 3 * flops}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -76,6 +136,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="qwen_short")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-lmhead", action="store_true",
+                    help="skip the fused language-model-head leg (hidden states and head weights in)")
+    ap.add_argument("--d-model", type=int, default=5120,
+                    help="hidden size of the language-model-head leg (5120: a 32B Qwen-family model)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 1 GiB device copies (reference for HBM counters)")
     args = ap.parse_args()
@@ -242,6 +306,8 @@ def main():
                          "gbps": N * row_bytes / (fwd_ms * 1e-3) / 1e9,
                          "frac": N * row_bytes / (fwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS},
     }
+    if not args.no_lmhead and cfg.logits in ("normal", "normal_boost") and cfg.dtype == "bf16":
+        out["lmhead"] = lmhead_leg(grpo, wl, cfg, args.d_model, dev, stream, max(3, args.steps // 6))
     if not args.no_cpu_baseline:
         log("[bench] timing the fp64 oracle on a sample of the batch (about 12 s)")
         step()

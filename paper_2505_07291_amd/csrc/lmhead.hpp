@@ -13,13 +13,17 @@
 // and H^T are transposed copies, so every operand of every product is K-contiguous and
 // one kernel serves all three.
 //
-// Kernel shape (gfx950): 256 lanes = 4 wavefronts per workgroup, one 256 x 256 tile of C
-// per workgroup, K in steps of 64.  Each wavefront owns a 128 x 128 quarter as 4 x 4
-// blocks of v_mfma_f32_32x32x16_bf16 (256 accumulator registers per lane).  Operand
+// Kernel shape (gfx950): 512 lanes = 8 wavefronts per workgroup (two per SIMD), one
+// 256 x 256 tile of C per workgroup, K in steps of 64.  Each wavefront owns a 128 x 64 part
+// as 4 x 2 blocks of v_mfma_f32_32x32x16_bf16 (128 accumulator registers per lane).  Eight
+// wavefronts rather than four because one wavefront sustains only about one 16-byte-per-lane
+// load every 170 cycles and one ds_read_b128 every 58 (measured, whatever is in flight):
+// at four wavefronts the tile's operand loads take longer than its products.  Operand
 // tiles go from global memory straight into LDS (global_load_lds_dwordx4, no register
-// staging), double buffered: 2 x (32 KB + 32 KB).  Inside a tile row the eight 16-byte
-// chunks are stored at chunk ^ (row & 7), applied on the global-address side, so that
-// the ds_read_b128 fragment reads (32 rows x one chunk) touch every bank once.
+// staging) through a ring of five 32 KB slots, all 160 KB of a CU.  Inside a tile row
+// the eight 16-byte chunks are stored at chunk ^ ((row >> 1) & 7), applied on the
+// global-address side, so that 16 consecutive rows of one logical chunk (a quarter of a
+// ds_read_b128 fragment read) fall on 16 different groups of four banks.
 
 namespace {
 
@@ -29,14 +33,14 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int LM_BM = 256, LM_BN = 256, LM_BK = 64;
-constexpr int LM_THREADS = 256;
-constexpr int LM_CPR = LM_BK / 8;                    // 16-byte chunks per tile row
+constexpr int LM_THREADS = 512;                      // 8 wavefronts, two per SIMD
+constexpr int LM_WM = 2, LM_WN = 4;                  // wavefront grid over the tile
+constexpr int LM_FA = 4, LM_FB = 2;                  // 32 x 32 blocks per wavefront: 128 x 64
+constexpr int LM_CPR = LM_BK / 8;                    // 16-byte chunks per tile row: 8
 constexpr int LM_TILE_BYTES = LM_BM * LM_BK * 2;     // one operand tile: 32 KB
-constexpr int LM_STAGE_BYTES = 2 * LM_TILE_BYTES;    // A tile + B tile
-constexpr int LM_STAGES = 2;
-constexpr int LM_LPT = LM_BM * LM_CPR / LM_THREADS;  // 16-byte loads per lane and operand tile: 8
-constexpr int LM_EXTRA_BYTES = 1024;                 // sampled-token columns of the tile's rows
-constexpr int LM_LDS_BYTES = LM_STAGES * LM_STAGE_BYTES + LM_EXTRA_BYTES;
+constexpr int LM_SLOTS = 5;                          // operand tiles resident in LDS: all 160 KB
+constexpr int LM_LPT = LM_BM * LM_CPR / LM_THREADS;  // 16-byte loads per lane and operand tile: 4
+constexpr int LM_LDS_BYTES = LM_SLOTS * LM_TILE_BYTES;
 constexpr int LM_GROUP_M = 8;                        // tile rows that share a sweep along N
 
 enum { LM_EPI_LSE = 0, LM_EPI_BF16 = 1, LM_EPI_F32 = 2 };
@@ -114,33 +118,20 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
     if (!lm_map_tile(p, tm, tn)) return;  // whole workgroup alike, before any barrier
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / LM_WN, wn = wave % LM_WN;  // this wavefront's 128 x 64 part of the tile
     const int row0 = tm * LM_BM, col0 = tn * LM_BN;
-    int *ycol_s = (int *)(lm_smem + LM_STAGES * LM_STAGE_BYTES);
 
-    if (EPI == LM_EPI_LSE) {
-        // column of the sampled token inside this tile, -1 when it is elsewhere or the row
-        // takes no part
-        const int r = row0 + tid;
-        int yc = -1;
-        if (r < p.M && (!p.mask || p.mask[r])) {
-            const long long y = p.tokens[r];
-            if (y >= col0 && y < (long long)col0 + LM_BN && y < p.N) yc = (int)(y - col0);
-        }
-        ycol_s[tid] = yc;
-    }
-
-    // Byte offsets of this lane's eight 16-byte loads per operand tile, relative to the
-    // tile's first row at k = 0.  Load i of a wavefront fills LDS chunks [i*256 + wave*64,
+    // Byte offsets of this lane's four 16-byte loads per operand tile, relative to the
+    // tile's first row at k = 0.  Load i of a wavefront fills LDS chunks [i*512 + wave*64,
     // +64) of the tile; chunk c sits in tile row c / 8 at physical position c % 8 and holds
-    // logical chunk (c % 8) ^ (row & 7).  Rows past the end of the matrix re-read the last
-    // row (their results are never stored).
+    // logical chunk (c % 8) ^ ((row >> 1) & 7).  Rows past the end of the matrix re-read the
+    // last row (their results are never stored).
     unsigned a_off[LM_LPT], b_off[LM_LPT];
 #pragma unroll
     for (int i = 0; i < LM_LPT; ++i) {
         const int c = i * LM_THREADS + tid;
         const int r = c / LM_CPR, pc = c % LM_CPR;
-        const int lc = pc ^ (r & (LM_CPR - 1));
+        const int lc = pc ^ ((r >> 1) & (LM_CPR - 1));
         const int ra = min(row0 + r, p.M - 1) - row0;
         const int rb = min(col0 + r, p.N - 1) - col0;
         a_off[i] = (unsigned)(((long long)ra * p.lda + lc * 8) * 2);
@@ -148,20 +139,24 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
     }
     const char *a_tile = (const char *)p.A + (long long)row0 * p.lda * 2;
     const char *b_tile = (const char *)p.B + (long long)col0 * p.ldb * 2;
+    const int KT = p.K / LM_BK;
 
-    auto issue = [&](int kt, int stage) {
-        const char *ab = a_tile + (long long)kt * (LM_BK * 2);
-        const char *bb = b_tile + (long long)kt * (LM_BK * 2);
-        char *sa = lm_smem + stage * LM_STAGE_BYTES + wave * 1024;
-        char *sb = sa + LM_TILE_BYTES;
+    // LDS is a ring of five 32 KB slots that operand tiles pass through in the order
+    // A(0), B(0), A(1), B(1), ...: entry q = 2 kt + (0 for A, 1 for B) lives in slot q % 5.
+    // Two slots hold the tile being multiplied, the other three the next loads, which are
+    // issued two at a time between the products.  Past the last tile the last one is loaded
+    // again, into a slot nobody reads any more: every iteration then issues the same number
+    // of loads and "landed" is a fixed vmcnt value.
+    auto slot_of = [&](int q) { return lm_smem + (q % LM_SLOTS) * LM_TILE_BYTES; };
+    auto issue_half = [&](int q, bool b_operand, int half) {
+        const long long k0 = (long long)min(q >> 1, KT - 1) * (LM_BK * 2);
+        char *sd = slot_of(q) + wave * 1024;
+        const char *src = (b_operand ? b_tile : a_tile) + k0;
 #pragma unroll
-        for (int i = 0; i < LM_LPT; ++i)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(ab + a_off[i]),
-                                             (__attribute__((address_space(3))) void *)(sa + i * 4096), 16, 0, 0);
-#pragma unroll
-        for (int i = 0; i < LM_LPT; ++i)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(bb + b_off[i]),
-                                             (__attribute__((address_space(3))) void *)(sb + i * 4096), 16, 0, 0);
+        for (int i = half * (LM_LPT / 2); i < (half + 1) * (LM_LPT / 2); ++i)
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void *)(src + (b_operand ? b_off[i] : a_off[i])),
+                (__attribute__((address_space(3))) void *)(sd + i * (LM_THREADS * 16)), 16, 0, 0);
     };
 
     // Fragment addresses: lane (r = lane % 32, half = lane / 32) reads, for k-step ks, the
@@ -170,83 +165,105 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
     unsigned frag_off[LM_BK / 16];
 #pragma unroll
     for (int ks = 0; ks < LM_BK / 16; ++ks)
-        frag_off[ks] = (unsigned)((fr * LM_CPR + ((2 * ks + fh) ^ (fr & 7))) * 16);
-    const unsigned a_wave = (unsigned)(wm * 128 * LM_BK * 2);
-    const unsigned b_wave = (unsigned)(LM_TILE_BYTES + wn * 128 * LM_BK * 2);
+        frag_off[ks] = (unsigned)((fr * LM_CPR + ((2 * ks + fh) ^ ((fr >> 1) & (LM_CPR - 1)))) * 16);
+    const unsigned a_wave = (unsigned)(wm * (LM_FA * 32) * LM_BK * 2);
+    const unsigned b_wave = (unsigned)(wn * (LM_FB * 32) * LM_BK * 2);
 
-    f32x16 acc[4][4];
+    f32x16 acc[LM_FA][LM_FB];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < LM_FA; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < LM_FB; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // Pipeline.  Fragments are double buffered in registers (F[0], F[1]) and read one
-    // k-step ahead of the products that use them.  The barrier sits before the last
-    // k-step of a tile: by then every wavefront holds that k-step's fragments in
-    // registers, so nobody reads the tile's buffer any more, and everybody's loads of the
-    // next tile (issued one iteration earlier) have landed.  Right after the barrier the
-    // loads of the tile after next go into the freed buffer and the first fragments of
-    // the next tile are read; the 16 products of the last k-step cover both latencies.
-    const int KT = p.K / LM_BK;
-    bf16x8 F[2][8];
-    auto read_frags = [&](bf16x8 (&f)[8], const char *st, int ks) {
+    // Fragments are double buffered in registers (F[0], F[1]) and read one k-step ahead of
+    // the products that use them.  One barrier per tile, before its last k-step: by then
+    // every wavefront holds that k-step's fragments in registers, so the tile's two slots
+    // are free, and everybody's loads of the next tile have landed.
+    bf16x8 F[2][LM_FA + LM_FB];
+    auto read_frags = [&](bf16x8 (&f)[LM_FA + LM_FB], int kt, int ks) {
+        const char *sa = slot_of(2 * kt), *sb = slot_of(2 * kt + 1);
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            f[i] = *(const bf16x8 *)(st + a_wave + i * (32 * LM_BK * 2) + frag_off[ks]);
+        for (int i = 0; i < LM_FA; ++i)
+            f[i] = *(const bf16x8 *)(sa + a_wave + i * (32 * LM_BK * 2) + frag_off[ks]);
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            f[4 + j] = *(const bf16x8 *)(st + b_wave + j * (32 * LM_BK * 2) + frag_off[ks]);
+        for (int j = 0; j < LM_FB; ++j)
+            f[LM_FA + j] = *(const bf16x8 *)(sb + b_wave + j * (32 * LM_BK * 2) + frag_off[ks]);
     };
-    auto products = [&](const bf16x8 (&f)[8]) {
+    auto products = [&](const bf16x8 (&f)[LM_FA + LM_FB]) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < LM_FA; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i], f[4 + j], acc[i][j], 0, 0, 0);
+            for (int j = 0; j < LM_FB; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i], f[LM_FA + j], acc[i][j], 0, 0, 0);
     };
-    static_assert(LM_BK / 16 == 4, "the pipeline below is written for four k-steps per tile");
+    // one k-step: 6 LDS reads, 8 products, 2 global -> LDS loads: a read with each of the
+    // first six products, then the two loads after a product each
+    auto interleave = [&]() {
+#pragma unroll
+        for (int i = 0; i < LM_FA + LM_FB; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < LM_LPT / 2; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    static_assert(LM_BK / 16 == 4 && LM_SLOTS == 5 && LM_LPT == 4 && LM_FA * LM_FB >= LM_FA + LM_FB + LM_LPT / 2,
+                  "the pipeline and its wait counts are written for 4 k-steps, 5 slots, 4 loads per operand tile");
 
-    issue(0, 0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (KT > 1) issue(1, 1);
-    read_frags(F[0], lm_smem, 0);
+    // Memory loads return in order, so "at most n outstanding" means that everything older
+    // than the n youngest loads is in LDS.  The wait, the wait for the own LDS reads and the
+    // workgroup barrier are one asm statement so that nothing is scheduled in between.
+    issue_half(0, false, 0);
+    issue_half(0, false, 1);
+    issue_half(1, true, 0);
+    issue_half(1, true, 1);
+    issue_half(2, false, 0);
+    issue_half(2, false, 1);
+    issue_half(3, true, 0);
+    asm volatile("s_waitcnt vmcnt(6) lgkmcnt(0)\n\ts_barrier" ::: "memory");  // A(0), B(0) are there
+    read_frags(F[0], 0, 0);
     for (int kt = 0; kt < KT; ++kt) {
-        const char *cur = lm_smem + (kt & 1) * LM_STAGE_BYTES;
-        const char *nxt = lm_smem + ((kt + 1) & 1) * LM_STAGE_BYTES;
-        read_frags(F[1], cur, 1);
+        read_frags(F[1], kt, 1);
         products(F[0]);
-        __builtin_amdgcn_sched_barrier(0);
-        read_frags(F[0], cur, 2);
+        issue_half(2 * kt + 3, true, 1);   // rest of B(kt + 1)
+        interleave();
+        read_frags(F[0], kt, 2);
         products(F[1]);
-        __builtin_amdgcn_sched_barrier(0);
-        read_frags(F[1], cur, 3);
+        issue_half(2 * kt + 4, false, 0);  // A(kt + 2)
+        interleave();
+        read_frags(F[1], kt, 3);
         products(F[0]);
-        __builtin_amdgcn_sched_barrier(0);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        if (kt + 2 < KT) issue(kt + 2, kt & 1);
-        if (kt + 1 < KT) read_frags(F[0], nxt, 0);
-        __builtin_amdgcn_sched_barrier(0);
+        issue_half(2 * kt + 4, false, 1);
+        interleave();
+        // outstanding, oldest first: ..., B(kt + 1), A(kt + 2): 4 left = tile kt + 1 landed
+        asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        read_frags(F[0], kt + 1, 0);
         products(F[1]);
-        __builtin_amdgcn_sched_barrier(0);
+        issue_half(2 * kt + 5, true, 0);   // B(kt + 2) into the slot A(kt) just left
+        interleave();
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     // Accumulator layout of a 32 x 32 block: lane l holds column l % 32; register v holds
     // row 8 (v / 4) + 4 (l / 32) + v % 4.
     const int cl = lane & 31, g = lane >> 5;
+    const int wrow = wm * (LM_FA * 32), wcol = wn * (LM_FB * 32);
     if (EPI == LM_EPI_BF16 || EPI == LM_EPI_F32) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < LM_FA; ++i)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int row = row0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+                const int row = row0 + wrow + i * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
                 if (row >= p.M) continue;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int col = col0 + wn * 128 + j * 32 + cl;
+                for (int j = 0; j < LM_FB; ++j) {
+                    const int col = col0 + wcol + j * 32 + cl;
                     if (col >= p.N) continue;
                     if (EPI == LM_EPI_BF16) {
                         ((__bf16 *)p.C)[(long long)row * p.ldc + col] = (__bf16)acc[i][j][v];
@@ -262,23 +279,36 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
     // Softmax partials of this tile: for every row the maximum of z k over the tile's
     // columns and the sum of exp2(z k - max), the sampled token's column left out of both
     // (its accumulator goes to zy instead) so that 1 - p_y keeps its precision later.
-    __syncthreads();  // the stage buffers are free now: reuse their start as scratch
-    float *red_m = (float *)lm_smem;  // [2][256]
-    float *red_s = red_m + 2 * LM_BM;
+    __syncthreads();  // the operand slots are free now: reuse their start as scratch
+    float *red_m = (float *)lm_smem;  // [LM_WN][256]
+    float *red_s = red_m + LM_WN * LM_BM;
+    int *ycol_s = (int *)(red_s + LM_WN * LM_BM);
+    if (tid < LM_BM) {
+        // column of the sampled token inside this tile, -1 when it is elsewhere or the row
+        // takes no part
+        const int r = row0 + tid;
+        int yc = -1;
+        if (r < p.M && (!p.mask || p.mask[r])) {
+            const long long y = p.tokens[r];
+            if (y >= col0 && y < (long long)col0 + LM_BN && y < p.N) yc = (int)(y - col0);
+        }
+        ycol_s[tid] = yc;
+    }
+    __syncthreads();
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < LM_FA; ++i)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const int rl0 = wm * 128 + i * 32 + q * 8 + g * 4;
+            const int rl0 = wrow + i * 32 + q * 8 + g * 4;
             const i32x4 yv = *(const i32x4 *)(ycol_s + rl0);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int rl = rl0 + e;
                 const int row = row0 + rl;
-                float a[4];
+                float a[LM_FB];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int cloc = wn * 128 + j * 32 + cl;
+                for (int j = 0; j < LM_FB; ++j) {
+                    const int cloc = wcol + j * 32 + cl;
                     const float z = acc[i][j][q * 4 + e];
                     const bool in = col0 + cloc < p.N;
                     if (STORE_Z && in && row < p.M) p.Z[(long long)row * p.ldz + col0 + cloc] = z;
@@ -286,12 +316,14 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
                     if (is_y) p.zy[row] = z;
                     a[j] = (is_y || !in) ? -INFINITY : z * p.k;
                 }
-                float m = fmaxf(fmaxf(a[0], a[1]), fmaxf(a[2], a[3]));
+                float m = a[0];
+#pragma unroll
+                for (int j = 1; j < LM_FB; ++j) m = fmaxf(m, a[j]);
                 m = lm_row32_max(m);
                 const float ref = m == -INFINITY ? 0.f : m;  // a row of the tile with nothing to sum
                 float s = 0.f;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) s += __builtin_amdgcn_exp2f(a[j] - ref);
+                for (int j = 0; j < LM_FB; ++j) s += __builtin_amdgcn_exp2f(a[j] - ref);
                 s = lm_row32_sum(s);
                 if (cl == 0) {
                     red_m[wn * LM_BM + rl] = m;
@@ -300,16 +332,17 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
             }
         }
     __syncthreads();
-    {
+    if (tid < LM_BM) {
         const int row = row0 + tid;
         if (row < p.M) {
-            const float m0 = red_m[tid], m1 = red_m[LM_BM + tid];
-            const float s0 = red_s[tid], s1 = red_s[LM_BM + tid];
-            const float m = fmaxf(m0, m1);
+            float m = -INFINITY;
+#pragma unroll
+            for (int w = 0; w < LM_WN; ++w) m = fmaxf(m, red_m[w * LM_BM + tid]);
             float s = 0.f;
-            if (m != -INFINITY) {
-                if (m0 != -INFINITY) s += s0 * __builtin_amdgcn_exp2f(m0 - m);
-                if (m1 != -INFINITY) s += s1 * __builtin_amdgcn_exp2f(m1 - m);
+#pragma unroll
+            for (int w = 0; w < LM_WN; ++w) {
+                const float mw = red_m[w * LM_BM + tid];
+                if (mw != -INFINITY) s += red_s[w * LM_BM + tid] * __builtin_amdgcn_exp2f(mw - m);
             }
             p.part_m[(long long)tn * p.M + row] = m;
             p.part_s[(long long)tn * p.M + row] = s;
@@ -472,8 +505,8 @@ LmLayout lm_layout(int64_t n, int64_t V, int64_t d, bool bwd)
 {
     LmLayout L = {};
     L.tiles_n = (int)((V + LM_BN - 1) / LM_BN);
-    L.ldz = L.ldg = (long long)align_up((size_t)V, LM_BK);
-    L.ldgt = (long long)align_up((size_t)n, LM_BK);
+    L.ldz = L.ldg = (long long)align_up((size_t)V, 64);  // whole K steps, 128-byte rows
+    L.ldgt = (long long)align_up((size_t)n, 64);
     size_t off = align_up(grpo_workspace_bytes(n), 256);
     L.rows_bytes = off;
     auto take = [&](size_t bytes) {
@@ -616,9 +649,9 @@ grpo_status lm_impl(bool bwd, const void *hidden, int64_t hidden_stride, const v
                                0, st, (const float *)(ws + L.Z), L.ldz, M, V, (const long long *)tokens, w, k,
                                G, L.ldg, Gt, L.ldgt);
             // W^T [d][ldg] and H^T [d][ldgt]
-            hipLaunchKernelGGL(lm_transpose, dim3((unsigned)(D / 64), (unsigned)(L.ldg / 64)), dim3(256), 0, st,
+            hipLaunchKernelGGL(lm_transpose, dim3((unsigned)((D + 63) / 64), (unsigned)(L.ldg / 64)), dim3(256), 0, st,
                                (const __bf16 *)weight, (long long)weight_stride, V, D, Wt, L.ldg);
-            hipLaunchKernelGGL(lm_transpose, dim3((unsigned)(D / 64), (unsigned)(L.ldgt / 64)), dim3(256), 0, st,
+            hipLaunchKernelGGL(lm_transpose, dim3((unsigned)((D + 63) / 64), (unsigned)(L.ldgt / 64)), dim3(256), 0, st,
                                (const __bf16 *)hidden, (long long)hidden_stride, M, D, Ht, L.ldgt);
 
             GemmParams gh = {};  // dL/dH [M][d] = G [M][V] . W [V][d]

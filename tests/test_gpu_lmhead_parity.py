@@ -215,7 +215,7 @@ def test_edge_cases():
     assert abs(loss.item() + 1.0) < 1e-6      # r = 1, A = 1: loss = -1
     # argument errors are reported, not launched
     with pytest.raises(grpo.GrpoError):
-        grpo.grpo_lmhead_logprobs_fwd(h[:, :48], w[:, :48], tok)        # d_model not a multiple of 64
+        grpo.grpo_lmhead_logprobs_fwd(h[:, :48], w[:, :48], tok)        # d_model not a multiple of 32
     with pytest.raises(grpo.GrpoError):
         grpo.grpo_lmhead_loss_fwd_bwd(h, w, tok, z, z, m1, delta=1.1)    # delta <= 1 + eps_high
     with pytest.raises(grpo.GrpoError):
