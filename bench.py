@@ -114,19 +114,28 @@ def lmhead_leg(grpo, wl, cfg, d_model, dev, stream, reps):
         return sum(a.elapsed_time(e) for a, e in evs) / reps
     ms_f = timed(fwd)
     ms_b = timed(fwd_bwd)
-    flops = 2.0 * N * V * d_model
+    c = counts.cpu().tolist()
+    n_unmasked = c[0]
+    zero_adv = int(((adv_tok == 0) & (b["mask"] != 0)).sum())
+    n_grad = n_unmasked - (c[1] + c[2] + c[3] + zero_adv)   # rows whose objective has a gradient
+    # algorithmic flops: rows that take no part need none (2 V d per unmasked row for the logits,
+    # twice that again per row with a gradient for dL/dH and dL/dW)
+    flops_f = 2.0 * n_unmasked * V * d_model
+    flops_b = flops_f + 4.0 * n_grad * V * d_model
     return {"note": "grpo_lmhead_logprobs_fwd / grpo_lmhead_loss_fwd_bwd: hidden [N, d] and head "
-                    "weights [V, d] in bf16, logits formed on the matrix cores",
-            "d_model": d_model, "fwd_ms": ms_f, "fwd_tokens_per_s": N / (ms_f * 1e-3),
+                    "weights [V, d] in bf16, logits formed on the matrix cores; tokens/s count all N rows, "
+                    "flops only the rows that take part",
+            "d_model": d_model, "rows": N, "rows_unmasked": n_unmasked, "rows_with_gradient": n_grad,
+            "fwd_ms": ms_f, "fwd_tokens_per_s": N / (ms_f * 1e-3),
             "fwd_bwd_ms": ms_b, "fwd_bwd_tokens_per_s": N / (ms_b * 1e-3), "loss": float(loss.cpu()),
-            "roofline": {"bound": "mfma", "achieved": flops / (ms_f * 1e-3) / 1e12, "peak": 2500.0,
-                         "unit": "TFLOP/s", "frac": flops / (ms_f * 1e-3) / 1e12 / 2500.0,
+            "roofline": {"bound": "mfma", "achieved": flops_f / (ms_f * 1e-3) / 1e12, "peak": 2500.0,
+                         "unit": "TFLOP/s", "frac": flops_f / (ms_f * 1e-3) / 1e12 / 2500.0,
                          "kernel": "lm_gemm_nt (forward: logits + softmax partials)",
-                         "algorithmic_flops": flops, "traffic": None},
-            "roofline_fwd_bwd": {"bound": "mfma", "achieved": 3 * flops / (ms_b * 1e-3) / 1e12,
+                         "algorithmic_flops": flops_f, "traffic": None},
+            "roofline_fwd_bwd": {"bound": "mfma", "achieved": flops_b / (ms_b * 1e-3) / 1e12,
                                  "peak": 2500.0, "unit": "TFLOP/s",
-                                 "frac": 3 * flops / (ms_b * 1e-3) / 1e12 / 2500.0,
-                                 "algorithmic_flops": 3 * flops}}
+                                 "frac": flops_b / (ms_b * 1e-3) / 1e12 / 2500.0,
+                                 "algorithmic_flops": flops_b}}
 
 
 def main():

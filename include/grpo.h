@@ -303,12 +303,16 @@ grpo_status grpo_workspace_error(const void *workspace, int32_t *flag_out, void 
  *           grpo_logprobs_fwd / grpo_loss_fwd_bwd.
  *  workspace  device, 256-byte aligned, at least
  *           grpo_lmhead_workspace_bytes(n_tokens, vocab, d_model, with_backward)
- *           bytes.  Forward only it is small (8 bytes per token and 256 vocabulary
- *           entries); with the backward it also holds the logits in fp32, the
+ *           bytes.  Forward only it holds a compacted copy of the hidden states
+ *           of the rows that take part and 8 bytes per token and 256 vocabulary
+ *           entries; with the backward it also holds the logits in fp32, the
  *           gradient with respect to them in bf16 (twice: row-major and
  *           transposed) and transposed copies of W and h, about
  *           8 * n_tokens * vocab + 2 * vocab * d_model bytes.  Contents on entry are
  *           ignored; the error word is read with grpo_workspace_error.
+ * Rows with mask 0 cost no matrix work, and neither do, in the backward, rows whose
+ * objective has no gradient (clipped, delta-capped, zero advantage): the rows that
+ * take part are compacted on the device first.
  * Errors as for grpo_loss_fwd_bwd; additionally GRPO_ERR_SHAPE when d_model is not
  * a multiple of 32 or a pitch is smaller than d_model.  All work is enqueued on
  * `stream`; nothing is allocated.

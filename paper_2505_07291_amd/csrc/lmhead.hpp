@@ -49,17 +49,21 @@ struct GemmParams {
     const __bf16 *A;
     const __bf16 *B;
     long long lda, ldb;  // elements; rows 16-byte aligned
-    int M, N, K;         // K % LM_BK == 0, K > 0
-    int tiles_m, tiles_n;
+    int M, N, K;         // host-side sizes: M and K are upper bounds when the device values below are given
+    const int *M_dev;    // optional: number of rows of A actually present (<= M)
+    const int *K_dev;    // optional: length of the contraction actually present, rounded up to LM_BK
+                         // in the kernel (the padding must hold zeros); 0 gives a zero result
+    int tiles_n;
     // LM_EPI_BF16 / LM_EPI_F32
     void *C;
     long long ldc;
+    const int *c_rows;   // LM_EPI_BF16, optional: row i of the result goes to row c_rows[i] of C
     int accumulate;      // LM_EPI_F32: C += result
     // LM_EPI_LSE
-    const long long *tokens;
-    const unsigned char *mask;
+    const int *tokens32; // [M]: sampled token of each row of A
     float k;             // log2(e) / T
-    float *part_m, *part_s;  // [tiles_n][M]: max and sum of exp2(z k - max) over the tile's columns, y left out
+    float *part_m, *part_s;  // [tiles_n][part_stride]: max and sum of exp2(z k - max) over the tile's columns, y left out
+    long long part_stride;
     float *zy;               // [M]: the accumulator at the sampled token's column
     float *Z;                // optional fp32 copy of the logits, [M][ldz]
     long long ldz;
@@ -69,17 +73,19 @@ struct GemmParams {
 // each XCD has its own L2.  Workgroups of one XCD are given a contiguous run of the
 // tile order below, and that order walks LM_GROUP_M tile rows down before it moves one
 // tile column on, so the tiles in flight on an XCD at any moment share a few A and B
-// panels and most operand traffic is served by that XCD's L2.
-__device__ __forceinline__ bool lm_map_tile(const GemmParams &p, int &tm, int &tn)
+// panels and most operand traffic is served by that XCD's L2.  The number of tile rows
+// comes from the device-side row count, so that the live tiles are spread over all XCDs
+// whatever part of the launched grid they are.
+__device__ __forceinline__ bool lm_map_tile(int tiles_m, int tiles_n, int &tm, int &tn)
 {
-    const int total = p.tiles_m * p.tiles_n;
+    const int total = tiles_m * tiles_n;
     const int per_xcd = (total + 7) / 8;
     const int L = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
     if ((int)(blockIdx.x >> 3) >= per_xcd || L >= total) return false;
-    const int group_tiles = LM_GROUP_M * p.tiles_n;
+    const int group_tiles = LM_GROUP_M * tiles_n;
     const int grp = L / group_tiles;
     const int in_grp = L - grp * group_tiles;
-    const int rows_here = min(LM_GROUP_M, p.tiles_m - grp * LM_GROUP_M);
+    const int rows_here = min(LM_GROUP_M, tiles_m - grp * LM_GROUP_M);
     tm = grp * LM_GROUP_M + in_grp % rows_here;
     tn = in_grp / rows_here;
     return true;
@@ -114,8 +120,10 @@ template <int EPI, bool STORE_Z>
 __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
 {
     extern __shared__ __attribute__((aligned(1024))) char lm_smem[];
+    const int M = p.M_dev ? min(*p.M_dev, p.M) : p.M;
+    const int K = p.K_dev ? min((*p.K_dev + LM_BK - 1) / LM_BK * LM_BK, p.K) : p.K;
     int tm, tn;
-    if (!lm_map_tile(p, tm, tn)) return;  // whole workgroup alike, before any barrier
+    if (!lm_map_tile((M + LM_BM - 1) / LM_BM, p.tiles_n, tm, tn)) return;  // whole workgroup alike, before any barrier
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / LM_WN, wn = wave % LM_WN;  // this wavefront's 128 x 64 part of the tile
@@ -132,14 +140,14 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
         const int c = i * LM_THREADS + tid;
         const int r = c / LM_CPR, pc = c % LM_CPR;
         const int lc = pc ^ ((r >> 1) & (LM_CPR - 1));
-        const int ra = min(row0 + r, p.M - 1) - row0;
+        const int ra = min(row0 + r, M - 1) - row0;
         const int rb = min(col0 + r, p.N - 1) - col0;
         a_off[i] = (unsigned)(((long long)ra * p.lda + lc * 8) * 2);
         b_off[i] = (unsigned)(((long long)rb * p.ldb + lc * 8) * 2);
     }
     const char *a_tile = (const char *)p.A + (long long)row0 * p.lda * 2;
     const char *b_tile = (const char *)p.B + (long long)col0 * p.ldb * 2;
-    const int KT = p.K / LM_BK;
+    const int KT = K / LM_BK;
 
     // LDS is a ring of five 32 KB slots that operand tiles pass through in the order
     // A(0), B(0), A(1), B(1), ...: entry q = 2 kt + (0 for A, 1 for B) lives in slot q % 5.
@@ -219,6 +227,7 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
     // Memory loads return in order, so "at most n outstanding" means that everything older
     // than the n youngest loads is in LDS.  The wait, the wait for the own LDS reads and the
     // workgroup barrier are one asm statement so that nothing is scheduled in between.
+    if (KT > 0) {
     issue_half(0, false, 0);
     issue_half(0, false, 1);
     issue_half(1, true, 0);
@@ -249,6 +258,7 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
         interleave();
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }  // KT > 0
 
     // Accumulator layout of a 32 x 32 block: lane l holds column l % 32; register v holds
     // row 8 (v / 4) + 4 (l / 32) + v % 4.
@@ -260,15 +270,16 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int row = row0 + wrow + i * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-                if (row >= p.M) continue;
+                if (row >= M) continue;
+                const long long orow = (EPI == LM_EPI_BF16 && p.c_rows) ? p.c_rows[row] : row;
 #pragma unroll
                 for (int j = 0; j < LM_FB; ++j) {
                     const int col = col0 + wcol + j * 32 + cl;
                     if (col >= p.N) continue;
                     if (EPI == LM_EPI_BF16) {
-                        ((__bf16 *)p.C)[(long long)row * p.ldc + col] = (__bf16)acc[i][j][v];
+                        ((__bf16 *)p.C)[orow * p.ldc + col] = (__bf16)acc[i][j][v];
                     } else {
-                        float *c = (float *)p.C + (long long)row * p.ldc + col;
+                        float *c = (float *)p.C + orow * p.ldc + col;
                         *c = p.accumulate ? *c + acc[i][j][v] : acc[i][j][v];
                     }
                 }
@@ -284,13 +295,12 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
     float *red_s = red_m + LM_WN * LM_BM;
     int *ycol_s = (int *)(red_s + LM_WN * LM_BM);
     if (tid < LM_BM) {
-        // column of the sampled token inside this tile, -1 when it is elsewhere or the row
-        // takes no part
+        // column of the sampled token inside this tile, -1 when it is elsewhere
         const int r = row0 + tid;
         int yc = -1;
-        if (r < p.M && (!p.mask || p.mask[r])) {
-            const long long y = p.tokens[r];
-            if (y >= col0 && y < (long long)col0 + LM_BN && y < p.N) yc = (int)(y - col0);
+        if (r < M) {
+            const int y = p.tokens32[r];
+            if (y >= col0 && y < col0 + LM_BN && y < p.N) yc = y - col0;
         }
         ycol_s[tid] = yc;
     }
@@ -311,7 +321,7 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
                     const int cloc = wcol + j * 32 + cl;
                     const float z = acc[i][j][q * 4 + e];
                     const bool in = col0 + cloc < p.N;
-                    if (STORE_Z && in && row < p.M) p.Z[(long long)row * p.ldz + col0 + cloc] = z;
+                    if (STORE_Z && in && row < M) p.Z[(long long)row * p.ldz + col0 + cloc] = z;
                     const bool is_y = cloc == yv[e];
                     if (is_y) p.zy[row] = z;
                     a[j] = (is_y || !in) ? -INFINITY : z * p.k;
@@ -334,7 +344,7 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
     __syncthreads();
     if (tid < LM_BM) {
         const int row = row0 + tid;
-        if (row < p.M) {
+        if (row < M) {
             float m = -INFINITY;
 #pragma unroll
             for (int w = 0; w < LM_WN; ++w) m = fmaxf(m, red_m[w * LM_BM + tid]);
@@ -344,105 +354,214 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
                 const float mw = red_m[w * LM_BM + tid];
                 if (mw != -INFINITY) s += red_s[w * LM_BM + tid] * __builtin_amdgcn_exp2f(mw - m);
             }
-            p.part_m[(long long)tn * p.M + row] = m;
-            p.part_s[(long long)tn * p.M + row] = s;
+            p.part_m[(long long)tn * p.part_stride + row] = m;
+            p.part_s[(long long)tn * p.part_stride + row] = s;
         }
     }
 }
 
-// Per-row arrays the fused path keeps between its kernels.
+// Per-row arrays the fused path keeps between its kernels.  Rows that take part (mask 1,
+// token id inside the vocabulary) are compacted: "compact row i" is original row rows[i],
+// i < *n_live.  Of those, the ones with a gradient (c != 0) are compacted once more for
+// the backward: "gradient row j" is compact row rows2[j], original row orig2[j], j < *n_grad.
+// The masked tail of every rollout and the clipped tokens then cost no matrix work at all.
 struct LmRows {
-    float *zy;     // logit of the sampled token (fp32 accumulator)
+    int *rows, *tokens32, *n_live;   // [n], [n] (by compact row), [1]
+    int *rows2, *orig2, *n_grad;     // [n], [n], [1]
+    float *zy;     // by compact row: logit of the sampled token (fp32 accumulator)
     float *shift;  // max k + log2(sum): p_j = exp2(z_j k - shift)
-    float *q;      // c / T, 0 for rows without gradient
+    float *q;      // c / T
     float *gy;     // gradient at the sampled token: q (1 - p_y), from the sum without y
     float *part_m, *part_s;
+    long long part_stride;
     int tiles_n;
 };
 
-// Merges the tile partials of each row, then the objective's once-per-row arithmetic.
+// Ordered compaction by one workgroup: keeps the indices i < n with keep(i), in order.
+// `emit(pos, i)` stores entry number pos; returns the count (in every lane).
+template <typename Keep, typename Emit>
+__device__ __forceinline__ int lm_ordered_select(long long n, Keep keep, Emit emit)
+{
+    __shared__ int wave_tot[16];
+    __shared__ int base;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    if (tid == 0) base = 0;
+    __syncthreads();
+    for (long long i0 = 0; i0 < n; i0 += 1024) {
+        const long long i = i0 + tid;
+        const int kp = (i < n && keep(i)) ? 1 : 0;
+        int incl = kp;  // inclusive scan inside the wavefront
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int up = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += up;
+        }
+        if (lane == 63) wave_tot[wv] = incl;
+        __syncthreads();
+        int before = base;
+        for (int w2 = 0; w2 < wv; ++w2) before += wave_tot[w2];
+        if (kp) emit(before + incl - 1, i);
+        __syncthreads();
+        if (tid == 0) {
+            int tot = 0;
+            for (int w2 = 0; w2 < 16; ++w2) tot += wave_tot[w2];
+            base += tot;
+        }
+        __syncthreads();
+    }
+    return base;
+}
+
+// Rows that take part -> rows[], tokens32[], *n_live; rows that do not get their defined
+// outputs here (log-prob 0, or NaN for a bad token id in the log-probs-only call).
+__global__ void __launch_bounds__(1024) lm_select_rows(RowParams p, LmRows w)
+{
+    const int total = lm_ordered_select(
+        p.n_tokens,
+        [&](long long r) {
+            bool live = p.mask ? (p.mask[r] != 0) : true;
+            bool bad = false;
+            if (live) {
+                const long long y = p.tokens[r];
+                if (y < 0 || y >= p.vocab) {
+                    live = false;
+                    bad = true;
+                }
+            }
+            if (!live) {
+                write_row_outputs(p, r, (bad && !p.bwd) ? NAN : 0.f, 0.f, 0);
+                if (bad && p.bwd) atomicOr(&p.hdr->error, 1);
+            }
+            return live;
+        },
+        [&](int pos, long long r) {
+            w.rows[pos] = (int)r;
+            w.tokens32[pos] = (int)p.tokens[r];
+        });
+    if (threadIdx.x == 0) *w.n_live = total;
+}
+
+// Compact rows with a gradient -> rows2[], orig2[], *n_grad.
+__global__ void __launch_bounds__(1024) lm_select_grad_rows(LmRows w)
+{
+    const int total = lm_ordered_select(
+        *w.n_live, [&](long long i) { return w.q[i] != 0.f; },
+        [&](int pos, long long i) {
+            w.rows2[pos] = (int)i;
+            w.orig2[pos] = w.rows[i];
+        });
+    if (threadIdx.x == 0) *w.n_grad = total;
+}
+
+// out[i][:] = in[rowmap[i]][:] for i < *count: d bf16 values per row, 16 bytes per lane.
+__global__ void __launch_bounds__(256) lm_gather_rows(const __bf16 *in, long long ldi, const int *rowmap,
+                                                      const int *count, int d, __bf16 *out, long long ldo)
+{
+    const int n = *count;
+    for (int i = blockIdx.x; i < n; i += gridDim.x) {
+        const u32x4 *src = (const u32x4 *)(in + (long long)rowmap[i] * ldi);
+        u32x4 *dst = (u32x4 *)(out + (long long)i * ldo);
+        for (int c = threadIdx.x; c < d / 8; c += 256) dst[c] = src[c];
+    }
+}
+
+// Merges the tile partials of each compact row, then the objective's once-per-row arithmetic.
 __global__ void __launch_bounds__(256) lm_combine(RowParams p, LmRows w)
 {
-    const long long row = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (row >= p.n_tokens) return;
-    bool live = p.mask ? (p.mask[row] != 0) : true;
-    bool bad = false;
-    if (live) {
-        const long long y = p.tokens[row];
-        if (y < 0 || y >= p.vocab) {
-            live = false;
-            bad = true;
-        }
-    }
-    if (!live) {
-        write_row_outputs(p, row, (bad && !p.bwd) ? NAN : 0.f, 0.f, 0);
-        if (bad && p.bwd) atomicOr(&p.hdr->error, 1);
-        if (p.bwd) {
-            w.q[row] = 0.f;
-            w.gy[row] = 0.f;
-            w.shift[row] = 0.f;
-        }
-        return;
-    }
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= *w.n_live) return;
+    const long long row = w.rows[i];
     float m = -INFINITY;
-    for (int t = 0; t < w.tiles_n; ++t) m = fmaxf(m, w.part_m[(long long)t * p.n_tokens + row]);
-    const float zy = w.zy[row];
+    for (int t = 0; t < w.tiles_n; ++t) m = fmaxf(m, w.part_m[(long long)t * w.part_stride + i]);
+    const float zy = w.zy[i];
     const float mk = fmaxf(m, zy * p.k);  // the sampled token may be the row's maximum
     float s_excl = 0.f;
     for (int t = 0; t < w.tiles_n; ++t) {
-        const float mt = w.part_m[(long long)t * p.n_tokens + row];
+        const float mt = w.part_m[(long long)t * w.part_stride + i];
         if (mt != -INFINITY)
-            s_excl += w.part_s[(long long)t * p.n_tokens + row] * __builtin_amdgcn_exp2f(mt - mk);
+            s_excl += w.part_s[(long long)t * w.part_stride + i] * __builtin_amdgcn_exp2f(mt - mk);
     }
     const RowScalars o = row_scalars(p, row, zy, mk, s_excl);
     write_row_outputs(p, row, o.logp, o.J, o.flags);
     if (p.bwd) {
         const float q = o.c * p.inv_T;
-        w.q[row] = q;
-        w.gy[row] = q * (o.s_excl / o.s);
-        w.shift[row] = o.shift;
+        w.q[i] = q;
+        w.gy[i] = q * (o.s_excl / o.s);
+        w.shift[i] = o.shift;
     }
 }
 
-// G = dL/dz in bf16, row-major [M][ldg] and transposed [V][ldgt], from the fp32 logits:
-// g_j = -q p_j, g_y = q (1 - p_y).  64 x 64 tiles; padding columns of both (up to ldg,
-// ldgt) are written as zeros so that the products can run over whole K steps.
-__global__ void __launch_bounds__(256) lm_grad_logits(const float *Z, long long ldz, int M, int V,
-                                                      const long long *tokens, LmRows w, float k,
-                                                      __bf16 *G, long long ldg, __bf16 *Gt,
+// G = dL/dz in bf16 for the gradient rows, row-major [n_grad][ldg] and transposed
+// [V][ldgt], from the fp32 logits: g_j = -q p_j, g_y = q (1 - p_y).  64 x 64 tiles, four
+// consecutive elements per lane on both sides.  Padding (columns V .. ldg of G, columns
+// n_grad .. the next multiple of 64 of G^T) is written as zeros so that the products can
+// run over whole K steps.
+__global__ void __launch_bounds__(256) lm_grad_logits(const float *Z, long long ldz, int V, LmRows w,
+                                                      float k, __bf16 *G, long long ldg, __bf16 *Gt,
                                                       long long ldgt)
 {
     __shared__ float tile[64][65];
+    const int n2 = *w.n_grad;
     const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;  // 64 columns x 4 rows per pass
-#pragma unroll 4
-    for (int i = 0; i < 16; ++i) {
-        const int r = r0 + ty + 4 * i, c = c0 + tx;
-        float gv = 0.f;
-        if (r < M && c < V) {
-            const float q = w.q[r];
-            if (q != 0.f) {
-                const long long y = tokens[r];
-                gv = c == y ? w.gy[r]
-                            : -q * __builtin_amdgcn_exp2f(fmaf(Z[(long long)r * ldz + c], k, -w.shift[r]));
+    if (r0 >= (n2 + 63) / 64 * 64) return;
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;  // 16 x 4 columns, 16 rows per pass
+    const int c = c0 + tx * 4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int rl = ty + 16 * i, r = r0 + rl;
+        float gv[4] = {0.f, 0.f, 0.f, 0.f};
+        if (r < n2 && c < V) {
+            const int ci = w.rows2[r];
+            const float q = w.q[ci], sh = w.shift[ci];
+            const int y = w.tokens32[ci];
+            const float *zrow = Z + (long long)ci * ldz + c;
+            float z[4];
+            if (c + 3 < V) {
+                const f32x4 zv = *(const f32x4 *)zrow;
+                z[0] = zv[0], z[1] = zv[1], z[2] = zv[2], z[3] = zv[3];
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) z[e] = c + e < V ? zrow[e] : -INFINITY;
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                gv[e] = -q * __builtin_amdgcn_exp2f(fmaf(z[e], k, -sh));
+                if (c + e == y) gv[e] = w.gy[ci];
+                if (c + e >= V) gv[e] = 0.f;
             }
         }
-        if (r < M && c < ldg) G[(long long)r * ldg + c] = (__bf16)gv;
-        tile[ty + 4 * i][tx] = gv;
+        if (r < n2 && c < ldg) {  // ldg is a multiple of 64: whole groups of four
+            bf16x2 lo = __builtin_convertvector((f32x2){gv[0], gv[1]}, bf16x2);
+            bf16x2 hi = __builtin_convertvector((f32x2){gv[2], gv[3]}, bf16x2);
+            unsigned *dst = (unsigned *)(G + (long long)r * ldg + c);
+            dst[0] = __builtin_bit_cast(unsigned, lo);
+            dst[1] = __builtin_bit_cast(unsigned, hi);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) tile[rl][tx * 4 + e] = gv[e];
     }
     __syncthreads();
-#pragma unroll 4
-    for (int i = 0; i < 16; ++i) {
-        const int c = c0 + ty + 4 * i, r = r0 + tx;
-        if (c < V && r < ldgt) Gt[(long long)c * ldgt + r] = (__bf16)tile[tx][ty + 4 * i];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int cl2 = ty + 16 * i, cc = c0 + cl2;  // vocabulary entry: a row of G^T
+        const int r = r0 + tx * 4;                   // four consecutive gradient rows
+        if (cc < V && r < ldgt) {
+            bf16x2 lo = __builtin_convertvector((f32x2){tile[tx * 4][cl2], tile[tx * 4 + 1][cl2]}, bf16x2);
+            bf16x2 hi = __builtin_convertvector((f32x2){tile[tx * 4 + 2][cl2], tile[tx * 4 + 3][cl2]}, bf16x2);
+            unsigned *dst = (unsigned *)(Gt + (long long)cc * ldgt + r);
+            dst[0] = __builtin_bit_cast(unsigned, lo);
+            dst[1] = __builtin_bit_cast(unsigned, hi);
+        }
     }
 }
 
-// out[c][r] = in[r][c] for r < R, c < C; columns R .. ldo of out are zero-filled.
-__global__ void __launch_bounds__(256) lm_transpose(const __bf16 *in, long long ldi, int R, int C,
-                                                    __bf16 *out, long long ldo)
+// out[c][r] = in[rowmap ? rowmap[r] : r][c] for r < R (R = *R_dev when given), c < C; the
+// columns R .. ldo of out are zero-filled.
+__global__ void __launch_bounds__(256) lm_transpose(const __bf16 *in, long long ldi, int R, const int *R_dev,
+                                                    const int *rowmap, int C, __bf16 *out, long long ldo)
 {
     __shared__ unsigned short tile[64][66];
+    if (R_dev) R = min(R, *R_dev);
     const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     const unsigned short *src = (const unsigned short *)in;
@@ -450,7 +569,9 @@ __global__ void __launch_bounds__(256) lm_transpose(const __bf16 *in, long long 
 #pragma unroll 4
     for (int i = 0; i < 16; ++i) {
         const int r = r0 + ty + 4 * i, c = c0 + tx;
-        tile[ty + 4 * i][tx] = (r < R && c < C) ? src[(long long)r * ldi + c] : (unsigned short)0;
+        unsigned short v = 0;
+        if (r < R && c < C) v = src[(long long)(rowmap ? rowmap[r] : r) * ldi + c];
+        tile[ty + 4 * i][tx] = v;
     }
     __syncthreads();
 #pragma unroll 4
@@ -460,13 +581,14 @@ __global__ void __launch_bounds__(256) lm_transpose(const __bf16 *in, long long 
     }
 }
 
-// rows x cols zeros into a row-strided fp32 matrix (a fill kernel rather than a memset, so
-// that the call can be captured into a graph)
-__global__ void __launch_bounds__(256) lm_zero_f32(float *out, long long rows, long long cols, long long ld)
+// rows x cols zeros into a row-strided matrix (fill kernels rather than memsets, so that
+// the call can be captured into a graph)
+template <typename T>
+__global__ void __launch_bounds__(256) lm_zero(T *out, long long rows, long long cols, long long ld)
 {
     const long long total = rows * cols;
     for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256)
-        out[(i / cols) * ld + i % cols] = 0.f;
+        out[(i / cols) * ld + i % cols] = (T)0;
 }
 
 // ---------------------------------------------------------------------------
@@ -486,17 +608,15 @@ hipError_t lm_launch_gemm(GemmParams p, hipStream_t st)
         if (e != hipSuccess) return e;
         attr_done[dev] = true;
     }
-    p.tiles_m = (p.M + LM_BM - 1) / LM_BM;
     p.tiles_n = (p.N + LM_BN - 1) / LM_BN;
-    const long long total = (long long)p.tiles_m * p.tiles_n;
+    const long long total = (long long)((p.M + LM_BM - 1) / LM_BM) * p.tiles_n;  // upper bound
     const long long grid = (total + 7) / 8 * 8;
     hipLaunchKernelGGL((lm_gemm_nt<EPI, STORE_Z>), dim3((unsigned)grid), dim3(LM_THREADS), LM_LDS_BYTES, st, p);
     return hipGetLastError();
 }
 
 struct LmLayout {
-    size_t rows_bytes;  // the objective's own workspace (header, J, flags, ...)
-    size_t zy, shift, q, gy, part_m, part_s, Z, G, Gt, Wt, Ht, total;
+    size_t rows, tokens32, rows2, orig2, counts, zy, shift, q, gy, part_m, part_s, Hc, Z, G, Gt, Wt, Ht, total;
     long long ldz, ldg, ldgt;  // vocab and token counts rounded up to whole K steps
     int tiles_n;
 };
@@ -508,16 +628,21 @@ LmLayout lm_layout(int64_t n, int64_t V, int64_t d, bool bwd)
     L.ldz = L.ldg = (long long)align_up((size_t)V, 64);  // whole K steps, 128-byte rows
     L.ldgt = (long long)align_up((size_t)n, 64);
     size_t off = align_up(grpo_workspace_bytes(n), 256);
-    L.rows_bytes = off;
     auto take = [&](size_t bytes) {
         const size_t at = off;
         off += align_up(bytes, 256);
         return at;
     };
+    L.counts = take(256);
+    L.rows = take((size_t)n * 4);
+    L.tokens32 = take((size_t)n * 4);
     L.zy = take((size_t)n * 4);
     L.part_m = take((size_t)L.tiles_n * n * 4);
     L.part_s = take((size_t)L.tiles_n * n * 4);
+    L.Hc = take((size_t)n * d * 2);
     if (bwd) {
+        L.rows2 = take((size_t)n * 4);
+        L.orig2 = take((size_t)n * 4);
         L.shift = take((size_t)n * 4);
         L.q = take((size_t)n * 4);
         L.gy = take((size_t)n * 4);
@@ -545,8 +670,7 @@ grpo_status lm_check_common(const void *hidden, int64_t hidden_stride, const voi
         ((weight_stride * 2) & 15))
         return GRPO_ERR_ALIGN;
     // byte offsets inside one 256-row operand tile must fit 32 bits
-    if (hidden_stride * 2 * LM_BM >= (1ll << 32) || weight_stride * 2 * LM_BN >= (1ll << 32))
-        return GRPO_ERR_SHAPE;
+    if (weight_stride * 2 * LM_BN >= (1ll << 32)) return GRPO_ERR_SHAPE;
     return GRPO_OK;
 }
 
@@ -590,36 +714,25 @@ grpo_status lm_impl(bool bwd, const void *hidden, int64_t hidden_stride, const v
         hipLaunchKernelGGL(grpo_prepare, dim3(1), dim3(1024), 0, st, mask, (const float *)nullptr,
                            (long long)n_tokens, denom, hdr);
     if (n_tokens > 0) {
+        const int M = (int)n_tokens, V = (int)vocab, D = (int)d_model;
         LmRows w = {};
+        w.n_live = (int *)(ws + L.counts);
+        w.n_grad = w.n_live + 1;
+        w.rows = (int *)(ws + L.rows);
+        w.tokens32 = (int *)(ws + L.tokens32);
         w.zy = (float *)(ws + L.zy);
         w.part_m = (float *)(ws + L.part_m);
         w.part_s = (float *)(ws + L.part_s);
+        w.part_stride = n_tokens;
         w.tiles_n = L.tiles_n;
         if (bwd) {
+            w.rows2 = (int *)(ws + L.rows2);
+            w.orig2 = (int *)(ws + L.orig2);
             w.shift = (float *)(ws + L.shift);
             w.q = (float *)(ws + L.q);
             w.gy = (float *)(ws + L.gy);
         }
         const float k = (float)((double)kLog2e / (double)temperature);
-
-        GemmParams g = {};
-        g.A = (const __bf16 *)hidden;
-        g.lda = hidden_stride;
-        g.B = (const __bf16 *)weight;
-        g.ldb = weight_stride;
-        g.M = (int)n_tokens;
-        g.N = (int)vocab;
-        g.K = (int)d_model;
-        g.tokens = (const long long *)tokens;
-        g.mask = mask;
-        g.k = k;
-        g.part_m = w.part_m;
-        g.part_s = w.part_s;
-        g.zy = w.zy;
-        g.Z = bwd ? (float *)(ws + L.Z) : nullptr;
-        g.ldz = L.ldz;
-        hipError_t e = bwd ? lm_launch_gemm<LM_EPI_LSE, true>(g, st) : lm_launch_gemm<LM_EPI_LSE, false>(g, st);
-        if (e != hipSuccess) return GRPO_ERR_HIP;
 
         RowParams p = {};
         p.tokens = (const long long *)tokens;
@@ -639,35 +752,69 @@ grpo_status lm_impl(bool bwd, const void *hidden, int64_t hidden_stride, const v
         p.delta = delta;
         p.grad_scale = grad_scale;
         p.bwd = bwd ? 1 : 0;
+
+        // rows that take part, and their hidden states side by side
+        __bf16 *Hc = (__bf16 *)(ws + L.Hc);
+        hipLaunchKernelGGL(lm_select_rows, dim3(1), dim3(1024), 0, st, p, w);
+        hipLaunchKernelGGL(lm_gather_rows, dim3((unsigned)(M < 8192 ? M : 8192)), dim3(256), 0, st,
+                           (const __bf16 *)hidden, (long long)hidden_stride, (const int *)w.rows,
+                           (const int *)w.n_live, D, Hc, (long long)d_model);
+
+        GemmParams g = {};  // logits of the compact rows: softmax partials, z_y, fp32 copy for the backward
+        g.A = Hc;
+        g.lda = d_model;
+        g.B = (const __bf16 *)weight;
+        g.ldb = weight_stride;
+        g.M = M;
+        g.M_dev = w.n_live;
+        g.N = V;
+        g.K = D;
+        g.tokens32 = w.tokens32;
+        g.k = k;
+        g.part_m = w.part_m;
+        g.part_s = w.part_s;
+        g.part_stride = n_tokens;
+        g.zy = w.zy;
+        g.Z = bwd ? (float *)(ws + L.Z) : nullptr;
+        g.ldz = L.ldz;
+        hipError_t e = bwd ? lm_launch_gemm<LM_EPI_LSE, true>(g, st) : lm_launch_gemm<LM_EPI_LSE, false>(g, st);
+        if (e != hipSuccess) return GRPO_ERR_HIP;
+
         hipLaunchKernelGGL(lm_combine, dim3((unsigned)((n_tokens + 255) / 256)), dim3(256), 0, st, p, w);
 
         if (bwd) {
             __bf16 *G = (__bf16 *)(ws + L.G), *Gt = (__bf16 *)(ws + L.Gt);
             __bf16 *Wt = (__bf16 *)(ws + L.Wt), *Ht = (__bf16 *)(ws + L.Ht);
-            const int M = (int)n_tokens, V = (int)vocab, D = (int)d_model;
+            hipLaunchKernelGGL(lm_select_grad_rows, dim3(1), dim3(1024), 0, st, w);
             hipLaunchKernelGGL(lm_grad_logits, dim3((unsigned)(L.ldg / 64), (unsigned)(L.ldgt / 64)), dim3(256),
-                               0, st, (const float *)(ws + L.Z), L.ldz, M, V, (const long long *)tokens, w, k,
-                               G, L.ldg, Gt, L.ldgt);
-            // W^T [d][ldg] and H^T [d][ldgt]
-            hipLaunchKernelGGL(lm_transpose, dim3((unsigned)((D + 63) / 64), (unsigned)(L.ldg / 64)), dim3(256), 0, st,
-                               (const __bf16 *)weight, (long long)weight_stride, V, D, Wt, L.ldg);
-            hipLaunchKernelGGL(lm_transpose, dim3((unsigned)((D + 63) / 64), (unsigned)(L.ldgt / 64)), dim3(256), 0, st,
-                               (const __bf16 *)hidden, (long long)hidden_stride, M, D, Ht, L.ldgt);
+                               0, st, (const float *)(ws + L.Z), L.ldz, V, w, k, G, L.ldg, Gt, L.ldgt);
+            // W^T [d][ldg]; H^T of the gradient rows [d][ldgt]
+            hipLaunchKernelGGL(lm_transpose, dim3((unsigned)((D + 63) / 64), (unsigned)(L.ldg / 64)), dim3(256), 0,
+                               st, (const __bf16 *)weight, (long long)weight_stride, V, (const int *)nullptr,
+                               (const int *)nullptr, D, Wt, L.ldg);
+            hipLaunchKernelGGL(lm_transpose, dim3((unsigned)((D + 63) / 64), (unsigned)(L.ldgt / 64)), dim3(256), 0,
+                               st, (const __bf16 *)hidden, (long long)hidden_stride, M, (const int *)w.n_grad,
+                               (const int *)w.orig2, D, Ht, L.ldgt);
+            // rows without gradient keep the zeros written here
+            hipLaunchKernelGGL(lm_zero<unsigned short>, dim3(2048), dim3(256), 0, st, (unsigned short *)grad_hidden,
+                               (long long)n_tokens, (long long)d_model, (long long)grad_hidden_stride);
 
-            GemmParams gh = {};  // dL/dH [M][d] = G [M][V] . W [V][d]
+            GemmParams gh = {};  // dL/dH [gradient rows][d] = G . W, scattered to the original rows
             gh.A = G;
             gh.lda = L.ldg;
             gh.B = Wt;
             gh.ldb = L.ldg;
             gh.M = M;
+            gh.M_dev = w.n_grad;
             gh.N = D;
             gh.K = (int)L.ldg;
             gh.C = grad_hidden;
             gh.ldc = grad_hidden_stride;
+            gh.c_rows = w.orig2;
             e = lm_launch_gemm<LM_EPI_BF16, false>(gh, st);
             if (e != hipSuccess) return GRPO_ERR_HIP;
 
-            GemmParams gw = {};  // dL/dW [V][d] = G^T [V][M] . H [M][d]
+            GemmParams gw = {};  // dL/dW [V][d] = G^T . H over the gradient rows
             gw.A = Gt;
             gw.lda = L.ldgt;
             gw.B = Ht;
@@ -675,6 +822,7 @@ grpo_status lm_impl(bool bwd, const void *hidden, int64_t hidden_stride, const v
             gw.M = V;
             gw.N = D;
             gw.K = (int)L.ldgt;
+            gw.K_dev = w.n_grad;
             gw.C = grad_weight;
             gw.ldc = grad_weight_stride;
             gw.accumulate = accumulate_grad_weight ? 1 : 0;
@@ -683,7 +831,7 @@ grpo_status lm_impl(bool bwd, const void *hidden, int64_t hidden_stride, const v
         }
     } else if (bwd && !accumulate_grad_weight && vocab > 0) {
         // no tokens: the weight gradient is zero
-        hipLaunchKernelGGL(lm_zero_f32, dim3(4096), dim3(256), 0, st, grad_weight, (long long)vocab,
+        hipLaunchKernelGGL(lm_zero<float>, dim3(4096), dim3(256), 0, st, grad_weight, (long long)vocab,
                            (long long)d_model, (long long)grad_weight_stride);
     }
     if (bwd)
