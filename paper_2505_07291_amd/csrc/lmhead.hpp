@@ -42,6 +42,7 @@ constexpr int LM_SLOTS = 5;                          // operand tiles resident i
 constexpr int LM_LPT = LM_BM * LM_CPR / LM_THREADS;  // 16-byte loads per lane and operand tile: 4
 constexpr int LM_LDS_BYTES = LM_SLOTS * LM_TILE_BYTES;
 constexpr int LM_GROUP_M = 8;                        // tile rows that share a sweep along N
+constexpr int LM_SPLIT_MAX = 4;                      // parts the contraction of dL/dH may be cut into
 
 enum { LM_EPI_LSE = 0, LM_EPI_BF16 = 1, LM_EPI_F32 = 2 };
 
@@ -58,6 +59,11 @@ struct GemmParams {
     void *C;
     long long ldc;
     const int *c_rows;   // LM_EPI_BF16, optional: row i of the result goes to row c_rows[i] of C
+    // LM_EPI_BF16, optional split of the contraction (split_max > 1): the kernel picks a number of
+    // parts S <= split_max from the live tile count (lm_choose_split); with S > 1 part s of a tile
+    // goes as fp32 to split_ws[s][row][col] (rows of M, N columns) and lm_split_reduce finishes
+    int split_max, n_cu;
+    float *split_ws;
     int accumulate;      // LM_EPI_F32: C += result
     // LM_EPI_LSE
     const int *tokens32; // [M]: sampled token of each row of A
@@ -76,12 +82,15 @@ struct GemmParams {
 // panels and most operand traffic is served by that XCD's L2.  The number of tile rows
 // comes from the device-side row count, so that the live tiles are spread over all XCDs
 // whatever part of the launched grid they are.
-__device__ __forceinline__ bool lm_map_tile(int tiles_m, int tiles_n, int &tm, int &tn)
+__device__ __forceinline__ bool lm_map_tile(int tiles_m, int tiles_n, int splits, int &tm, int &tn, int &part)
 {
-    const int total = tiles_m * tiles_n;
+    const int tiles = tiles_m * tiles_n;
+    const int total = tiles * splits;
     const int per_xcd = (total + 7) / 8;
-    const int L = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    int L = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
     if ((int)(blockIdx.x >> 3) >= per_xcd || L >= total) return false;
+    part = L / tiles;  // the parts of the contraction one after the other: an XCD stays inside one part
+    L -= part * tiles;
     const int group_tiles = LM_GROUP_M * tiles_n;
     const int grp = L / group_tiles;
     const int in_grp = L - grp * group_tiles;
@@ -89,6 +98,25 @@ __device__ __forceinline__ bool lm_map_tile(int tiles_m, int tiles_n, int &tm, i
     tm = grp * LM_GROUP_M + in_grp % rows_here;
     tn = in_grp / rows_here;
     return true;
+}
+
+// Into how many parts the contraction is cut when the tiles alone fill the CUs badly (a product
+// with 780 tiles on 256 CUs runs four rounds, the last one on twelve CUs): the S <= split_max
+// with the fewest rounds of work per CU, counted in whole tiles, plus 3 % of a tile per extra part
+// for the fp32 partial results and their sum.  Every workgroup, and lm_split_reduce, computes the
+// same value from the same numbers.
+__device__ __forceinline__ int lm_choose_split(int tiles, int k_tiles, int split_max, int n_cu)
+{
+    int best = 1;
+    float best_cost = (float)((tiles + n_cu - 1) / n_cu);
+    for (int S = 2; S <= split_max && k_tiles / S >= 8; ++S) {
+        const float cost = (float)((tiles * S + n_cu - 1) / n_cu) / (float)S + 0.03f * (float)(S - 1);
+        if (cost < best_cost) {
+            best_cost = cost;
+            best = S;
+        }
+    }
+    return best;
 }
 
 template <int CTRL>
@@ -122,8 +150,13 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
     extern __shared__ __attribute__((aligned(1024))) char lm_smem[];
     const int M = p.M_dev ? min(*p.M_dev, p.M) : p.M;
     const int K = p.K_dev ? min((*p.K_dev + LM_BK - 1) / LM_BK * LM_BK, p.K) : p.K;
-    int tm, tn;
-    if (!lm_map_tile((M + LM_BM - 1) / LM_BM, p.tiles_n, tm, tn)) return;  // whole workgroup alike, before any barrier
+    int tm, tn, part = 0, parts = 1;
+    {
+        const int tiles_m = (M + LM_BM - 1) / LM_BM;
+        if (EPI == LM_EPI_BF16 && p.split_max > 1)
+            parts = lm_choose_split(tiles_m * p.tiles_n, K / LM_BK, p.split_max, p.n_cu);
+        if (!lm_map_tile(tiles_m, p.tiles_n, parts, tm, tn, part)) return;  // whole workgroup alike, before any barrier
+    }
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / LM_WN, wn = wave % LM_WN;  // this wavefront's 128 x 64 part of the tile
@@ -145,9 +178,11 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
         a_off[i] = (unsigned)(((long long)ra * p.lda + lc * 8) * 2);
         b_off[i] = (unsigned)(((long long)rb * p.ldb + lc * 8) * 2);
     }
-    const char *a_tile = (const char *)p.A + (long long)row0 * p.lda * 2;
-    const char *b_tile = (const char *)p.B + (long long)col0 * p.ldb * 2;
-    const int KT = K / LM_BK;
+    // this workgroup's part of the contraction: K steps [kt0, kt0 + KT)
+    const int kt0 = (int)((long long)(K / LM_BK) * part / parts);
+    const int KT = (int)((long long)(K / LM_BK) * (part + 1) / parts) - kt0;
+    const char *a_tile = (const char *)p.A + ((long long)row0 * p.lda + (long long)kt0 * LM_BK) * 2;
+    const char *b_tile = (const char *)p.B + ((long long)col0 * p.ldb + (long long)kt0 * LM_BK) * 2;
 
     // LDS is a ring of five 32 KB slots that operand tiles pass through in the order
     // A(0), B(0), A(1), B(1), ...: entry q = 2 kt + (0 for A, 1 for B) lives in slot q % 5.
@@ -206,22 +241,26 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
             for (int j = 0; j < LM_FB; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i], f[LM_FA + j], acc[i][j], 0, 0, 0);
     };
-    // one k-step: 6 LDS reads, 8 products, 2 global -> LDS loads: a read with each of the
-    // first six products, then the two loads after a product each
-    auto interleave = [&]() {
-#pragma unroll
-        for (int i = 0; i < LM_FA + LM_FB; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-#pragma unroll
-        for (int i = 0; i < LM_LPT / 2; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-        }
+    // One k-step: wait for the fragments read during the previous k-step (they had all of its
+    // products' time to arrive), issue the six reads of the next k-step's fragments, then the
+    // eight products with the two global -> LDS loads behind the second and the fourth.  The
+    // wait is written out so that it sits in front of the new reads: left to itself the
+    // compiler puts one wait for everything between the reads and the first product.
+    auto lds_landed = [&]() {
+        __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0) and nothing else
         __builtin_amdgcn_sched_barrier(0);
     };
-    static_assert(LM_BK / 16 == 4 && LM_SLOTS == 5 && LM_LPT == 4 && LM_FA * LM_FB >= LM_FA + LM_FB + LM_LPT / 2,
+    auto interleave = [&]() {
+        __builtin_amdgcn_sched_group_barrier(0x100, LM_FA + LM_FB, 0);
+#pragma unroll
+        for (int i = 0; i < LM_LPT / 2; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, LM_FA * LM_FB - LM_LPT, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    static_assert(LM_BK / 16 == 4 && LM_SLOTS == 5 && LM_LPT == 4 && LM_FA * LM_FB >= LM_LPT,
                   "the pipeline and its wait counts are written for 4 k-steps, 5 slots, 4 loads per operand tile");
 
     // Memory loads return in order, so "at most n outstanding" means that everything older
@@ -238,20 +277,24 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
     asm volatile("s_waitcnt vmcnt(6) lgkmcnt(0)\n\ts_barrier" ::: "memory");  // A(0), B(0) are there
     read_frags(F[0], 0, 0);
     for (int kt = 0; kt < KT; ++kt) {
+        lds_landed();
         read_frags(F[1], kt, 1);
         products(F[0]);
         issue_half(2 * kt + 3, true, 1);   // rest of B(kt + 1)
         interleave();
+        lds_landed();
         read_frags(F[0], kt, 2);
         products(F[1]);
         issue_half(2 * kt + 4, false, 0);  // A(kt + 2)
         interleave();
+        lds_landed();
         read_frags(F[1], kt, 3);
         products(F[0]);
         issue_half(2 * kt + 4, false, 1);
         interleave();
         // outstanding, oldest first: ..., B(kt + 1), A(kt + 2): 4 left = tile kt + 1 landed
         asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        lds_landed();
         read_frags(F[0], kt + 1, 0);
         products(F[1]);
         issue_half(2 * kt + 5, true, 0);   // B(kt + 2) into the slot A(kt) just left
@@ -276,7 +319,9 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
                 for (int j = 0; j < LM_FB; ++j) {
                     const int col = col0 + wcol + j * 32 + cl;
                     if (col >= p.N) continue;
-                    if (EPI == LM_EPI_BF16) {
+                    if (EPI == LM_EPI_BF16 && parts > 1) {
+                        p.split_ws[((long long)part * p.M + row) * p.N + col] = acc[i][j][v];
+                    } else if (EPI == LM_EPI_BF16) {
                         ((__bf16 *)p.C)[orow * p.ldc + col] = (__bf16)acc[i][j][v];
                     } else {
                         float *c = (float *)p.C + orow * p.ldc + col;
@@ -466,21 +511,38 @@ __global__ void __launch_bounds__(256) lm_gather_rows(const __bf16 *in, long lon
 }
 
 // Merges the tile partials of each compact row, then the objective's once-per-row arithmetic.
-__global__ void __launch_bounds__(256) lm_combine(RowParams p, LmRows w)
+// A workgroup takes 16 compact rows; 16 lanes share a row, each merging every 16th tile, and
+// their results meet in LDS in lane order (fixed order: the bits repeat from run to run).
+constexpr int LM_CMB_ROWS = 16, LM_CMB_LANES = 16;
+__global__ void __launch_bounds__(LM_CMB_ROWS * LM_CMB_LANES) lm_combine(RowParams p, LmRows w)
 {
-    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= *w.n_live) return;
-    const long long row = w.rows[i];
+    __shared__ float sh_m[LM_CMB_LANES][LM_CMB_ROWS + 1], sh_s[LM_CMB_LANES][LM_CMB_ROWS + 1];
+    const int rl = threadIdx.x % LM_CMB_ROWS, tl = threadIdx.x / LM_CMB_ROWS;
+    const long long i = (long long)blockIdx.x * LM_CMB_ROWS + rl;
+    const bool live = i < *w.n_live;
     float m = -INFINITY;
-    for (int t = 0; t < w.tiles_n; ++t) m = fmaxf(m, w.part_m[(long long)t * w.part_stride + i]);
-    const float zy = w.zy[i];
+    if (live)
+        for (int t = tl; t < w.tiles_n; t += LM_CMB_LANES) m = fmaxf(m, w.part_m[(long long)t * w.part_stride + i]);
+    sh_m[tl][rl] = m;
+    __syncthreads();
+#pragma unroll
+    for (int l = 0; l < LM_CMB_LANES; ++l) m = fmaxf(m, sh_m[l][rl]);
+    const float zy = live ? w.zy[i] : 0.f;
     const float mk = fmaxf(m, zy * p.k);  // the sampled token may be the row's maximum
+    float s = 0.f;
+    if (live)
+        for (int t = tl; t < w.tiles_n; t += LM_CMB_LANES) {
+            const float mt = w.part_m[(long long)t * w.part_stride + i];
+            if (mt != -INFINITY)
+                s += w.part_s[(long long)t * w.part_stride + i] * __builtin_amdgcn_exp2f(mt - mk);
+        }
+    sh_s[tl][rl] = s;
+    __syncthreads();
+    if (tl != 0 || !live) return;
     float s_excl = 0.f;
-    for (int t = 0; t < w.tiles_n; ++t) {
-        const float mt = w.part_m[(long long)t * w.part_stride + i];
-        if (mt != -INFINITY)
-            s_excl += w.part_s[(long long)t * w.part_stride + i] * __builtin_amdgcn_exp2f(mt - mk);
-    }
+#pragma unroll
+    for (int l = 0; l < LM_CMB_LANES; ++l) s_excl += sh_s[l][rl];
+    const long long row = w.rows[i];
     const RowScalars o = row_scalars(p, row, zy, mk, s_excl);
     write_row_outputs(p, row, o.logp, o.J, o.flags);
     if (p.bwd) {
@@ -581,6 +643,29 @@ __global__ void __launch_bounds__(256) lm_transpose(const __bf16 *in, long long 
     }
 }
 
+// Sum of the parts of a split product: C[c_rows[r]][:] = bf16(sum over s of ws[s][r][:]) for the
+// rows present, parts in order.  Does nothing when lm_gemm_nt chose not to split.
+__global__ void __launch_bounds__(256) lm_split_reduce(const float *ws, const int *M_dev, int M, int N, int tiles_n,
+                                                       int k_tiles, int split_max, int n_cu, const int *c_rows,
+                                                       __bf16 *C, long long ldc)
+{
+    const int rows = M_dev ? min(*M_dev, M) : M;
+    const int parts = lm_choose_split((rows + LM_BM - 1) / LM_BM * tiles_n, k_tiles, split_max, n_cu);
+    if (parts == 1) return;
+    const int quads = N / 4;  // N is a multiple of LM_BK
+    const long long total = (long long)rows * quads;
+    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long long)gridDim.x * 256) {
+        const int r = (int)(e / quads), c = (int)(e % quads) * 4;
+        f32x4 a = *(const f32x4 *)(ws + (long long)r * N + c);
+        for (int sp = 1; sp < parts; ++sp) a += *(const f32x4 *)(ws + ((long long)sp * M + r) * N + c);
+        const bf16x2 lo = __builtin_convertvector((f32x2){a[0], a[1]}, bf16x2);
+        const bf16x2 hi = __builtin_convertvector((f32x2){a[2], a[3]}, bf16x2);
+        unsigned *dst = (unsigned *)(C + (long long)(c_rows ? c_rows[r] : r) * ldc + c);
+        dst[0] = __builtin_bit_cast(unsigned, lo);
+        dst[1] = __builtin_bit_cast(unsigned, hi);
+    }
+}
+
 // rows x cols zeros into a row-strided matrix (fill kernels rather than memsets, so that
 // the call can be captured into a graph)
 template <typename T>
@@ -609,7 +694,8 @@ hipError_t lm_launch_gemm(GemmParams p, hipStream_t st)
         attr_done[dev] = true;
     }
     p.tiles_n = (p.N + LM_BN - 1) / LM_BN;
-    const long long total = (long long)((p.M + LM_BM - 1) / LM_BM) * p.tiles_n;  // upper bound
+    const long long total = (long long)((p.M + LM_BM - 1) / LM_BM) * p.tiles_n *
+                            (EPI == LM_EPI_BF16 && p.split_max > 1 ? p.split_max : 1);  // upper bound
     const long long grid = (total + 7) / 8 * 8;
     hipLaunchKernelGGL((lm_gemm_nt<EPI, STORE_Z>), dim3((unsigned)grid), dim3(LM_THREADS), LM_LDS_BYTES, st, p);
     return hipGetLastError();
@@ -780,7 +866,8 @@ grpo_status lm_impl(bool bwd, const void *hidden, int64_t hidden_stride, const v
         hipError_t e = bwd ? lm_launch_gemm<LM_EPI_LSE, true>(g, st) : lm_launch_gemm<LM_EPI_LSE, false>(g, st);
         if (e != hipSuccess) return GRPO_ERR_HIP;
 
-        hipLaunchKernelGGL(lm_combine, dim3((unsigned)((n_tokens + 255) / 256)), dim3(256), 0, st, p, w);
+        hipLaunchKernelGGL(lm_combine, dim3((unsigned)((n_tokens + LM_CMB_ROWS - 1) / LM_CMB_ROWS)),
+                           dim3(LM_CMB_ROWS * LM_CMB_LANES), 0, st, p, w);
 
         if (bwd) {
             __bf16 *G = (__bf16 *)(ws + L.G), *Gt = (__bf16 *)(ws + L.Gt);
@@ -811,8 +898,23 @@ grpo_status lm_impl(bool bwd, const void *hidden, int64_t hidden_stride, const v
             gh.C = grad_hidden;
             gh.ldc = grad_hidden_stride;
             gh.c_rows = w.orig2;
+            // The fp32 logits are no longer needed: their space takes the partial results when the
+            // contraction over the vocabulary is split (d_model is a multiple of 4 columns: the
+            // partial rows stay 16-byte aligned).
+            gh.split_max = (int)(L.ldz / d_model < LM_SPLIT_MAX ? L.ldz / d_model : LM_SPLIT_MAX);
+            gh.split_ws = (float *)(ws + L.Z);
+            int dev = 0, n_cu = 0;
+            if (hipGetDevice(&dev) != hipSuccess ||
+                hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0)
+                return GRPO_ERR_HIP;
+            gh.n_cu = n_cu;
             e = lm_launch_gemm<LM_EPI_BF16, false>(gh, st);
             if (e != hipSuccess) return GRPO_ERR_HIP;
+            if (gh.split_max > 1)
+                hipLaunchKernelGGL(lm_split_reduce, dim3(2048), dim3(256), 0, st, (const float *)gh.split_ws,
+                                   (const int *)w.n_grad, M, D, (D + LM_BN - 1) / LM_BN, (int)(L.ldg / LM_BK),
+                                   gh.split_max, n_cu, (const int *)w.orig2, (__bf16 *)grad_hidden,
+                                   (long long)grad_hidden_stride);
 
             GemmParams gw = {};  // dL/dW [V][d] = G^T . H over the gradient rows
             gw.A = Gt;
