@@ -158,7 +158,8 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
         if (!lm_map_tile(tiles_m, p.tiles_n, parts, tm, tn, part)) return;  // whole workgroup alike, before any barrier
     }
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // in a scalar register: LDS targets are uniform
     const int wm = wave / LM_WN, wn = wave % LM_WN;  // this wavefront's 128 x 64 part of the tile
     const int row0 = tm * LM_BM, col0 = tn * LM_BN;
 
@@ -191,15 +192,21 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
     // again, into a slot nobody reads any more: every iteration then issues the same number
     // of loads and "landed" is a fixed vmcnt value.
     auto slot_of = [&](int q) { return lm_smem + (q % LM_SLOTS) * LM_TILE_BYTES; };
+    // The loads are buffer loads with LDS as their target: the tile's first row at this
+    // workgroup's first K step is the buffer's base, the lane's offset inside the tile a
+    // vector register, the K position a scalar one, the LDS address goes through M0 - no
+    // vector arithmetic per load.  The range check of the buffer is left wide open (rows are
+    // clamped above and K steps below, so every address is inside the operand).
+    const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)a_tile, 0, -1, 0x00020000);
+    const __amdgpu_buffer_rsrc_t b_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)b_tile, 0, -1, 0x00020000);
     auto issue_half = [&](int q, bool b_operand, int half) {
-        const long long k0 = (long long)min(q >> 1, KT - 1) * (LM_BK * 2);
+        const int k0 = min(q >> 1, KT - 1) * (LM_BK * 2);
         char *sd = slot_of(q) + wave * 1024;
-        const char *src = (b_operand ? b_tile : a_tile) + k0;
 #pragma unroll
         for (int i = half * (LM_LPT / 2); i < (half + 1) * (LM_LPT / 2); ++i)
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void *)(src + (b_operand ? b_off[i] : a_off[i])),
-                (__attribute__((address_space(3))) void *)(sd + i * (LM_THREADS * 16)), 16, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(b_operand ? b_rsrc : a_rsrc,
+                                                     (__attribute__((address_space(3))) void *)(sd + i * (LM_THREADS * 16)),
+                                                     16, (int)(b_operand ? b_off[i] : a_off[i]), k0, 0, 0);
     };
 
     // Fragment addresses: lane (r = lane % 32, half = lane / 32) reads, for k-step ks, the
