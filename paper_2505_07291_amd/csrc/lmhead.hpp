@@ -910,10 +910,7 @@ grpo_status lm_impl(bool bwd, const void *hidden, int64_t hidden_stride, const v
             // partial rows stay 16-byte aligned).
             gh.split_max = (int)(L.ldz / d_model < LM_SPLIT_MAX ? L.ldz / d_model : LM_SPLIT_MAX);
             gh.split_ws = (float *)(ws + L.Z);
-            int dev = 0, n_cu = 0;
-            if (hipGetDevice(&dev) != hipSuccess ||
-                hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0)
-                return GRPO_ERR_HIP;
+            const int n_cu = cu_count();
             gh.n_cu = n_cu;
             e = lm_launch_gemm<LM_EPI_BF16, false>(gh, st);
             if (e != hipSuccess) return GRPO_ERR_HIP;
