@@ -71,3 +71,60 @@ def test_graph_capture_and_replay():
         torch.cuda.synchronize()
         for k, v in ref.items():
             assert torch.equal(v, bufs[k]), "%s differs on replay %d" % (k, i)
+
+
+def _lm_setup():
+    cfg = wl.CONFIGS["qwen_short"].scaled(n_prompts=2, seq_len=40, vocab=2600, group_size=4)
+    d = 192
+    b = wl.make_lmhead_batch(cfg, d, device=DEV)
+    N, V = b["n_tokens"], b["vocab"]
+    lp0 = grpo.grpo_lmhead_logprobs_fwd(b["hidden"], b["weight"], b["tokens"], b["mask"])
+    torch.cuda.synchronize()
+    old = wl.make_old_logprobs(cfg, lp0).to(DEV)
+    _, adv_tok = grpo.grpo_group_advantages(b["rewards"], group_size=cfg.group_size,
+                                            rollout_of_token=b["rollout_of_token"])
+    bufs = dict(dH=torch.empty((N, d), dtype=torch.bfloat16, device=DEV),
+                dW=torch.empty((V, d), dtype=torch.float32, device=DEV), loss=torch.empty(1, device=DEV),
+                lp=torch.empty(N, device=DEV), counts=torch.empty(5, dtype=torch.int64, device=DEV),
+                ws=torch.empty(grpo.grpo_lmhead_workspace_bytes(N, V, d, True), dtype=torch.uint8, device=DEV))
+    return b, old, adv_tok, bufs
+
+
+def _lm_step(b, old, adv_tok, bufs, stream):
+    grpo.grpo_lmhead_loss_fwd_bwd(b["hidden"], b["weight"], b["tokens"], old, adv_tok, b["mask"],
+                                  grad_hidden=bufs["dH"], grad_weight=bufs["dW"], loss_out=bufs["loss"],
+                                  logprobs_out=bufs["lp"], counts_out=bufs["counts"], workspace=bufs["ws"],
+                                  stream=stream)
+
+
+def test_lmhead_side_stream_and_graph_replay():
+    """The fused language-model-head call (a dozen kernels, the split contraction among them) on a
+    side stream and as a captured graph replayed with eager work in between: the eager bits."""
+    b, old, adv_tok, bufs = _lm_setup()
+    keys = ("loss", "lp", "counts", "dH", "dW")
+    _lm_step(b, old, adv_tok, bufs, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    ref = {k: bufs[k].clone() for k in keys}
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    for k in keys:
+        bufs[k].zero_()
+    torch.cuda.synchronize()
+    _lm_step(b, old, adv_tok, bufs, side)
+    side.synchronize()
+    for k, v in ref.items():
+        assert torch.equal(v, bufs[k]), k
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            _lm_step(b, old, adv_tok, bufs, side)
+    torch.cuda.synchronize()
+    for i in range(3):
+        for k in keys:
+            bufs[k].zero_()
+        bufs["ws"].fill_(0x5a)                                # the workspace carries nothing between calls
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k, v in ref.items():
+            assert torch.equal(v, bufs[k]), "%s differs on replay %d" % (k, i)
