@@ -342,8 +342,20 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
     // Softmax partials of this tile: for every row the maximum of z k over the tile's
     // columns and the sum of exp2(z k - max), the sampled token's column left out of both
     // (its accumulator goes to zy instead) so that 1 - p_y keeps its precision later.
-    __syncthreads();  // the operand slots are free now: reuse their start as scratch
-    float *red_m = (float *)lm_smem;  // [LM_WN][256]
+    //
+    // An accumulator block spreads a row over 32 lanes; reducing it there costs ten cross-lane
+    // steps per row.  Instead every wavefront turns its part of the tile round through LDS
+    // (free now), 64 rows at a time: written as accumulators, read back one whole row per
+    // lane, so that maximum and sum are plain loops with every lane busy, and the fp32 copy of
+    // the logits leaves in 16-byte pieces.  Rows are LM_EPI_PITCH floats apart: 16-byte aligned,
+    // and neither the row-per-lane reads nor the 16-lanes-per-row reads collide on banks.
+    constexpr int LM_EPI_PITCH = 68;
+    constexpr int LM_EPI_WAVE_BYTES = 64 * LM_EPI_PITCH * 4;
+    static_assert(8 * LM_EPI_WAVE_BYTES + (2 * LM_WN * LM_BM + LM_BM) * 4 <= LM_LDS_BYTES, "epilogue staging fits LDS");
+    static_assert(LM_FA == 4 && LM_FB == 2 && LM_WM * LM_WN == 8, "the staging below is written for 128 x 64 parts");
+    __syncthreads();  // the operand slots are free now
+    float *stage = (float *)(lm_smem + wave * LM_EPI_WAVE_BYTES);
+    float *red_m = (float *)(lm_smem + 8 * LM_EPI_WAVE_BYTES);  // [LM_WN][256]
     float *red_s = red_m + LM_WN * LM_BM;
     int *ycol_s = (int *)(red_s + LM_WN * LM_BM);
     if (tid < LM_BM) {
@@ -357,42 +369,57 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
         ycol_s[tid] = yc;
     }
     __syncthreads();
+    const int ncols = min(64, p.N - col0 - wcol);  // columns of this wavefront's part inside the matrix
 #pragma unroll
-    for (int i = 0; i < LM_FA; ++i)
+    for (int h = 0; h < 2; ++h) {
+        // accumulators of block rows 2h, 2h + 1 -> stage[64][pitch]
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int rl0 = wrow + i * 32 + q * 8 + g * 4;
-            const i32x4 yv = *(const i32x4 *)(ycol_s + rl0);
+        for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int rl = rl0 + e;
-                const int row = row0 + rl;
-                float a[LM_FB];
+            for (int v = 0; v < 16; ++v)
 #pragma unroll
-                for (int j = 0; j < LM_FB; ++j) {
-                    const int cloc = wcol + j * 32 + cl;
-                    const float z = acc[i][j][q * 4 + e];
-                    const bool in = col0 + cloc < p.N;
-                    if (STORE_Z && in && row < M) p.Z[(long long)row * p.ldz + col0 + cloc] = z;
-                    const bool is_y = cloc == yv[e];
-                    if (is_y) p.zy[row] = z;
-                    a[j] = (is_y || !in) ? -INFINITY : z * p.k;
-                }
-                float m = a[0];
+                for (int j = 0; j < LM_FB; ++j)
+                    stage[(ii * 32 + 8 * (v >> 2) + 4 * g + (v & 3)) * LM_EPI_PITCH + j * 32 + cl] = acc[2 * h + ii][j][v];
+        // LDS serves a wavefront's accesses in order: what follows sees these writes
+        const int rbase = wrow + h * 64;  // first of the 64 rows inside the tile
+        if (STORE_Z && col0 + wcol < p.ldz) {
+            // 16 lanes per row, four rows per instruction; the columns between N and the row
+            // pitch of Z receive the products with the clamped operand rows: never read
+            const int rr = lane >> 4, c4 = (lane & 15) * 4;
 #pragma unroll
-                for (int j = 1; j < LM_FB; ++j) m = fmaxf(m, a[j]);
-                m = lm_row32_max(m);
-                const float ref = m == -INFINITY ? 0.f : m;  // a row of the tile with nothing to sum
-                float s = 0.f;
-#pragma unroll
-                for (int j = 0; j < LM_FB; ++j) s += __builtin_amdgcn_exp2f(a[j] - ref);
-                s = lm_row32_sum(s);
-                if (cl == 0) {
-                    red_m[wn * LM_BM + rl] = m;
-                    red_s[wn * LM_BM + rl] = s;
-                }
+            for (int it = 0; it < 16; ++it) {
+                const int rl = it * 4 + rr;
+                const int row = row0 + rbase + rl;
+                const f32x4 zq = *(const f32x4 *)(stage + rl * LM_EPI_PITCH + c4);
+                if (row < M) *(f32x4 *)(p.Z + (long long)row * p.ldz + col0 + wcol + c4) = zq;
             }
         }
+        // lane = row: take the sampled token's logit out, blank what lies outside the matrix
+        float *myrow = stage + lane * LM_EPI_PITCH;
+        const int yc = ycol_s[rbase + lane] - wcol;
+        if (yc >= 0 && yc < 64) {
+            p.zy[row0 + rbase + lane] = myrow[yc];
+            myrow[yc] = -INFINITY;
+        }
+        if (ncols < 64)
+            for (int c = max(ncols, 0); c < 64; ++c) myrow[c] = -INFINITY;
+        f32x4 zv[16];
+#pragma unroll
+        for (int c = 0; c < 16; ++c) zv[c] = *(const f32x4 *)(myrow + 4 * c);
+        float mz = -INFINITY;
+#pragma unroll
+        for (int c = 0; c < 16; ++c) mz = fmaxf(fmaxf(fmaxf(mz, zv[c][0]), fmaxf(zv[c][1], zv[c][2])), zv[c][3]);
+        const float m = mz * p.k;                    // k > 0: the maximum of z k
+        const float ref = mz == -INFINITY ? 0.f : m;  // a row with nothing to sum
+        float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+            s0 += __builtin_amdgcn_exp2f(fmaf(zv[c][0], p.k, -ref)) + __builtin_amdgcn_exp2f(fmaf(zv[c][1], p.k, -ref));
+            s1 += __builtin_amdgcn_exp2f(fmaf(zv[c][2], p.k, -ref)) + __builtin_amdgcn_exp2f(fmaf(zv[c][3], p.k, -ref));
+        }
+        red_m[wn * LM_BM + rbase + lane] = m;
+        red_s[wn * LM_BM + rbase + lane] = s0 + s1;
+    }
     __syncthreads();
     if (tid < LM_BM) {
         const int row = row0 + tid;
