@@ -213,11 +213,14 @@ def main():
             step(ev=evs[i], **kw)
         torch.cuda.synchronize()
         wall = (time.perf_counter() - t0) / K
-        kern = sum(a.elapsed_time(b) for a, b in evs) / K * 1e-3
+        per_step = sorted(a.elapsed_time(b) for a, b in evs)
+        timed.last = {"median": per_step[len(per_step) // 2], "min": per_step[0], "max": per_step[-1]}
+        kern = sum(per_step) / K * 1e-3
         return wall, kern
 
     log("[bench] timing %d steps after %d warm-up steps" % (args.steps, args.warmup))
     wall, kern = timed(args.steps, args.warmup)
+    kern_spread = dict(timed.last)
     assert grpo.grpo_workspace_error(ws) == 0
     c = counts.cpu().tolist()
     loss_value = float(loss.cpu())
@@ -295,7 +298,9 @@ def main():
                      "unit": "GB/s", "frac": alg_bytes / kern / 1e9 / HBM_PEAK_GBPS,
                      "traffic": traffic_from_profiles(cfg.name),
                      "kernel": "grpo_rows_cached (inside grpo_loss_fwd_bwd)",
-                     "kernel_ms": kern * 1e3, "algorithmic_bytes": alg_bytes,
+                     "kernel_ms": kern * 1e3, "kernel_ms_median": kern_spread["median"],
+                     "kernel_ms_min": kern_spread["min"], "kernel_ms_max": kern_spread["max"],
+                     "algorithmic_bytes": alg_bytes,
                      "gbps_2r1w_all_rows_convention": conv_bytes / kern / 1e9,
                      "gbps_design_traffic_1r1w": design_bytes / kern / 1e9},
         "full_rows": {"note": "same logits, every row unmasked and live: the kernel's worst case",

@@ -652,28 +652,41 @@ __global__ void __launch_bounds__(256) lm_grad_logits(const float *Z, long long 
 }
 
 // out[c][r] = in[rowmap ? rowmap[r] : r][c] for r < R (R = *R_dev when given), c < C; the
-// columns R .. ldo of out are zero-filled.
+// columns R .. ldo of out are zero-filled.  64 x 64 tiles through LDS, four consecutive
+// elements (8 bytes) per lane on both sides; C and ldo are multiples of 4 and both matrices
+// 8-byte aligned (the operands of this path: d_model is a multiple of 64, rows 16-byte aligned).
 __global__ void __launch_bounds__(256) lm_transpose(const __bf16 *in, long long ldi, int R, const int *R_dev,
                                                     const int *rowmap, int C, __bf16 *out, long long ldo)
 {
     __shared__ unsigned short tile[64][66];
     if (R_dev) R = min(R, *R_dev);
     const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;  // 16 lanes x 4 elements across, 16 down
     const unsigned short *src = (const unsigned short *)in;
     unsigned short *dst = (unsigned short *)out;
-#pragma unroll 4
-    for (int i = 0; i < 16; ++i) {
-        const int r = r0 + ty + 4 * i, c = c0 + tx;
-        unsigned short v = 0;
-        if (r < R && c < C) v = src[(long long)(rowmap ? rowmap[r] : r) * ldi + c];
-        tile[ty + 4 * i][tx] = v;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int rl = ty + 16 * i, r = r0 + rl, c = c0 + tx * 4;
+        unsigned lo = 0, hi = 0;
+        if (r < R && c < C) {
+            const unsigned *q = (const unsigned *)(src + (long long)(rowmap ? rowmap[r] : r) * ldi + c);
+            lo = q[0];
+            hi = q[1];
+        }
+        tile[rl][tx * 4 + 0] = (unsigned short)lo;
+        tile[rl][tx * 4 + 1] = (unsigned short)(lo >> 16);
+        tile[rl][tx * 4 + 2] = (unsigned short)hi;
+        tile[rl][tx * 4 + 3] = (unsigned short)(hi >> 16);
     }
     __syncthreads();
-#pragma unroll 4
-    for (int i = 0; i < 16; ++i) {
-        const int c = c0 + ty + 4 * i, r = r0 + tx;
-        if (c < C && r < ldo) dst[(long long)c * ldo + r] = tile[tx][ty + 4 * i];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int cl2 = ty + 16 * i, c = c0 + cl2, r = r0 + tx * 4;  // a row of the output, four of its columns
+        if (c < C && r < ldo) {
+            unsigned *q = (unsigned *)(dst + (long long)c * ldo + r);
+            q[0] = (unsigned)tile[tx * 4][cl2] | ((unsigned)tile[tx * 4 + 1][cl2] << 16);
+            q[1] = (unsigned)tile[tx * 4 + 2][cl2] | ((unsigned)tile[tx * 4 + 3][cl2] << 16);
+        }
     }
 }
 
