@@ -19,11 +19,13 @@
 // wavefronts rather than four because one wavefront sustains only about one 16-byte-per-lane
 // load every 170 cycles and one ds_read_b128 every 58 (measured, whatever is in flight):
 // at four wavefronts the tile's operand loads take longer than its products.  Operand
-// tiles go from global memory straight into LDS (global_load_lds_dwordx4, no register
-// staging) through a ring of five 32 KB slots, all 160 KB of a CU.  Inside a tile row
-// the eight 16-byte chunks are stored at chunk ^ ((row >> 1) & 7), applied on the
-// global-address side, so that 16 consecutive rows of one logical chunk (a quarter of a
-// ds_read_b128 fragment read) fall on 16 different groups of four banks.
+// tiles go from global memory straight into LDS (buffer_load_dwordx4 ... lds, no register
+// staging, no vector address arithmetic) through a ring of five 32 KB slots, all 160 KB of a
+// CU.  Inside a tile row the eight 16-byte chunks are stored at chunk ^ ((row >> 1) & 7),
+// applied on the global-address side, so that 16 consecutive rows of one logical chunk (a
+// quarter of a ds_read_b128 fragment read) fall on 16 different groups of four banks.
+// After the last K step the same LDS serves the epilogue: the accumulators are turned round
+// through it so that the per-row softmax partials are plain loops, one row per lane.
 
 namespace {
 
