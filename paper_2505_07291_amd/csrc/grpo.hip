@@ -243,19 +243,39 @@ __device__ __forceinline__ void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-// ---- reductions: butterflies inside the 64-lane wavefront, LDS across waves,
-// always in the same order, so results are bitwise reproducible ----
+// ---- reductions: data-parallel-primitive (DPP) steps inside the 64-lane wavefront, LDS
+// across waves, always in the same order, so results are bitwise reproducible ----
+// A DPP step costs a few cycles; the same reduction through ds_bpermute took six round
+// trips to LDS of about a hundred cycles each, in front of a workgroup barrier every time.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_move(float identity, float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, identity),
+                                                                   __builtin_bit_cast(int, v), CTRL, ROW_MASK,
+                                                                   0xf, false));
+}
+// Quad swaps, mirror inside 8, mirror inside 16: every lane of a row of 16 holds the row's
+// result; then lane 15 of a row is added into the next row (rows 1 and 3), lane 31 into
+// rows 2 and 3, and lane 63, which has seen everything, is read out for all.
 __device__ __forceinline__ float wave_max(float v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    return v;
+    v = fmaxf(v, dpp_move<0xB1, 0xf>(v, v));
+    v = fmaxf(v, dpp_move<0x4E, 0xf>(v, v));
+    v = fmaxf(v, dpp_move<0x141, 0xf>(v, v));
+    v = fmaxf(v, dpp_move<0x140, 0xf>(v, v));
+    v = fmaxf(v, dpp_move<0x142, 0xa>(-INFINITY, v));
+    v = fmaxf(v, dpp_move<0x143, 0xc>(-INFINITY, v));
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 __device__ __forceinline__ float wave_sum(float v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
+    v += dpp_move<0xB1, 0xf>(0.f, v);
+    v += dpp_move<0x4E, 0xf>(0.f, v);
+    v += dpp_move<0x141, 0xf>(0.f, v);
+    v += dpp_move<0x140, 0xf>(0.f, v);
+    v += dpp_move<0x142, 0xa>(0.f, v);
+    v += dpp_move<0x143, 0xc>(0.f, v);
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 __device__ __forceinline__ double wave_sum(double v)
 {
