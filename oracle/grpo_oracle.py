@@ -447,3 +447,22 @@ def lmhead_loss_fwd_bwd(hidden, weight, tokens, old_logprobs, advantages, mask=N
         res["grad_hidden"] = lmhead_grad_hidden(res["grad"], weight)
         res["grad_weight"] = lmhead_grad_weight(res["grad"], hidden)
     return res
+
+
+def lmhead_aux_loss_fwd_bwd(hidden, weight, tokens, old_logprobs, ref_logprobs, advantages, mask=None, *,
+                            token_weights=None, eps_low=0.2, eps_high=0.2, delta=4.0, temperature=1.0,
+                            kl_coef=0.0, ent_coef=0.0, denom=0.0, grad_scale=1.0, want_grads=True):
+    """The objective of ``aux_loss_fwd_bwd`` (policy term, sampled-token KL against a reference
+    policy, entropy bonus, per-token weights) on logits z = h W^T that are never rounded, and
+    its gradient with respect to the hidden states and the head's weights (chain rule through
+    the same two products as ``lmhead_loss_fwd_bwd``)."""
+    z = lmhead_logits(hidden, weight)
+    res = aux_loss_fwd_bwd(z, tokens, old_logprobs, ref_logprobs, advantages, mask,
+                           token_weights=token_weights, eps_low=eps_low, eps_high=eps_high, delta=delta,
+                           temperature=temperature, kl_coef=kl_coef, ent_coef=ent_coef, denom=denom,
+                           grad_scale=grad_scale, grad_rows="all" if want_grads else None)
+    res["logits"] = z
+    if want_grads:
+        res["grad_hidden"] = lmhead_grad_hidden(res["grad"], weight)
+        res["grad_weight"] = lmhead_grad_weight(res["grad"], hidden)
+    return res

@@ -143,3 +143,97 @@ def test_gradients_match_central_differences():
         wm[v, k] -= step
         fd = (loss_at(h, wp) - loss_at(h, wm)) / (2 * step)
         assert abs(fd - res["grad_weight"][v, k]) < 1e-8, (v, k)
+
+
+# ---- the head in front of the objective with the auxiliary terms ----
+
+def _torch_total(H, W, tokens, old, ref, adv, mask, tw, eps_low, eps_high, delta, T, klc, enc, denom):
+    z = H @ W.T / T
+    lp = torch.log_softmax(z, dim=-1).gather(1, tokens[:, None])[:, 0]
+    r = torch.exp(lp - old)
+    J = torch.minimum(torch.clamp(r, max=delta) * adv, torch.clamp(r, 1 - eps_low, 1 + eps_high) * adv)
+    d = ref - lp
+    kl = torch.exp(d) - d - 1
+    ent = torch.distributions.Categorical(logits=z).entropy()
+    w = mask * tw
+    D = denom if denom > 0 else mask.sum()
+    return (-(J * w).sum() + klc * (kl * w).sum() - enc * (ent * w).sum()) / D
+
+
+def test_aux_identity_weight_reduces_to_the_logits_objective():
+    rng, h, _, tokens, adv, mask = _problem(31, N=8, d=12, V=12, dtype="bf16")
+    w = to_bf16_bits(np.eye(12, dtype=np.float32))
+    old = (rng.standard_normal(8) * 0.3 - 2.5).astype(np.float32)
+    ref = (rng.standard_normal(8) * 0.3 - 2.5).astype(np.float32)
+    kw = dict(temperature=0.7, kl_coef=0.05, ent_coef=0.02, grad_scale=1.3)
+    a = orc.lmhead_aux_loss_fwd_bwd(h, w, tokens, old, ref, adv, mask, **kw)
+    b = orc.aux_loss_fwd_bwd(h, tokens, old, ref, adv, mask, grad_rows="all", **kw)
+    for key in ("total", "policy", "kl", "entropy"):
+        assert a[key] == b[key], key
+    assert np.array_equal(a["logprobs"], b["logprobs"]) and np.array_equal(a["entropies"], b["entropies"])
+    assert np.array_equal(a["grad_hidden"], b["grad"])
+    assert np.abs(a["grad_weight"] - b["grad"].T @ bf16_bits_to_f64(h)).max() < 1e-15
+
+
+def test_aux_zero_coefficients_reduce_to_the_plain_head_objective():
+    rng, h, w, tokens, adv, mask = _problem(32, N=12, d=6, V=15)
+    new = orc.logprobs(orc.lmhead_logits(h, w), tokens)
+    old = (new + rng.uniform(-1.5, 1.5, 12)).astype(np.float32)
+    a = orc.lmhead_aux_loss_fwd_bwd(h, w, tokens, old, None, adv, mask, grad_scale=0.9)
+    b = orc.lmhead_loss_fwd_bwd(h, w, tokens, old, adv, mask, grad_scale=0.9)
+    assert abs(a["total"] - b["loss"]) < 1e-15 and a["policy"] == a["total"]
+    assert np.abs(a["grad_hidden"] - b["grad_hidden"]).max() < 1e-15
+    assert np.abs(a["grad_weight"] - b["grad_weight"]).max() < 1e-15
+    assert np.array_equal(a["counts"], b["counts"])
+
+
+@pytest.mark.parametrize("seed,T,weighted", [(41, 1.0, False), (42, 0.7, True)])
+def test_aux_gradients_match_autograd(seed, T, weighted):
+    rng, h, w, tokens, adv, mask = _problem(seed, N=24, d=8, V=17)
+    new = orc.logprobs(orc.lmhead_logits(h, w), tokens, temperature=T)
+    old = (new + rng.uniform(-1.8, 1.8, 24)).astype(np.float32)
+    ref = (new + rng.standard_normal(24) * 0.4).astype(np.float32)
+    tw = rng.uniform(0.2, 1.5, 24).astype(np.float32) if weighted else None
+    if weighted:
+        tw[5] = 0.0                                   # a zero weight takes the row out
+    kw = dict(eps_low=0.2, eps_high=0.3, delta=4.0)
+    res = orc.lmhead_aux_loss_fwd_bwd(h, w, tokens, old, ref, adv, mask, token_weights=tw, temperature=T,
+                                      kl_coef=0.07, ent_coef=0.03, denom=13.0, **kw)
+    H = torch.tensor(h, requires_grad=True)
+    W = torch.tensor(w, requires_grad=True)
+    f64 = lambda a: torch.tensor(np.asarray(a), dtype=torch.float64)
+    total = _torch_total(H, W, torch.tensor(tokens), f64(old), f64(ref), f64(adv), f64(mask),
+                         f64(tw) if weighted else torch.ones(24, dtype=torch.float64),
+                         T=T, klc=0.07, enc=0.03, denom=13.0, **kw)
+    total.backward()
+    assert abs(res["total"] - total.item()) < 1e-13
+    assert np.abs(res["grad_hidden"] - H.grad.numpy()).max() < 1e-13
+    assert np.abs(res["grad_weight"] - W.grad.numpy()).max() < 1e-13
+    assert np.abs(res["grad_weight"].sum(axis=0)).max() < 1e-14      # rows of G still sum to zero
+    if weighted:
+        assert not res["grad_hidden"][5].any()
+    assert res["counts"][1] > 0 and res["counts"][2] > 0
+
+
+def test_aux_gradients_match_central_differences():
+    rng, h, w, tokens, adv, mask = _problem(51, N=10, d=4, V=7)
+    new = orc.logprobs(orc.lmhead_logits(h, w), tokens)
+    old = (new + rng.choice([-0.1, 0.05, 0.12], 10)).astype(np.float32)
+    ref = (new + rng.standard_normal(10) * 0.3).astype(np.float32)
+    kw = dict(kl_coef=0.2, ent_coef=0.1)
+    res = orc.lmhead_aux_loss_fwd_bwd(h, w, tokens, old, ref, adv, mask, **kw)
+    step = 1e-6
+
+    def total_at(hh, ww):
+        return orc.lmhead_aux_loss_fwd_bwd(hh, ww, tokens, old, ref, adv, mask, want_grads=False, **kw)["total"]
+
+    for (t, k) in [(0, 0), (4, 3), (9, 1)]:
+        hp, hm = h.copy(), h.copy()
+        hp[t, k] += step
+        hm[t, k] -= step
+        assert abs((total_at(hp, w) - total_at(hm, w)) / (2 * step) - res["grad_hidden"][t, k]) < 1e-8, (t, k)
+    for (v, k) in [(0, 0), (6, 2), (int(tokens[0]), 1)]:
+        wp, wm = w.copy(), w.copy()
+        wp[v, k] += step
+        wm[v, k] -= step
+        assert abs((total_at(h, wp) - total_at(h, wm)) / (2 * step) - res["grad_weight"][v, k]) < 1e-8, (v, k)
