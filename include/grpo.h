@@ -358,6 +358,30 @@ grpo_status grpo_lmhead_loss_fwd_bwd(const void *hidden, int64_t hidden_stride, 
                                      int accumulate_grad_weight, void *workspace, size_t workspace_bytes,
                                      void *stream);
 
+/*
+ * The total objective of grpo_loss_aux_fwd_bwd (policy term of section 3.4, sampled-token
+ * KL against a reference policy and entropy bonus with the coefficients of section 4.1,
+ * per-token weights for packed batches and the sample-level normalisation) on z = h W^T,
+ * and its gradient with respect to h and W.  Arguments as grpo_lmhead_loss_fwd_bwd, plus
+ * ref_logprobs, token_weights, kl_coef, entropy_coef, entropy_out and the four-entry
+ * loss_out exactly as documented for grpo_loss_aux_fwd_bwd; G = grad_scale * dtotal/dz as
+ * defined there, rounded to bf16 before the two products.  A row with weight 0 is treated
+ * like a masked row and costs no matrix work.  With entropy_coef != 0 every row that takes
+ * part has a gradient.  The same workspace size as grpo_lmhead_loss_fwd_bwd
+ * (grpo_lmhead_workspace_bytes with with_backward != 0).
+ */
+grpo_status grpo_lmhead_loss_aux_fwd_bwd(const void *hidden, int64_t hidden_stride, const void *weight,
+                                         int64_t weight_stride, int64_t n_tokens, int64_t vocab,
+                                         int64_t d_model, const int64_t *tokens, const float *old_logprobs,
+                                         const float *ref_logprobs, const float *advantages,
+                                         const uint8_t *mask, const float *token_weights, float eps_low,
+                                         float eps_high, float delta, float temperature, float kl_coef,
+                                         float entropy_coef, double denom, float grad_scale, float *loss_out,
+                                         float *logprobs_out, float *entropy_out, int64_t *counts_out,
+                                         void *grad_hidden, int64_t grad_hidden_stride, float *grad_weight,
+                                         int64_t grad_weight_stride, int accumulate_grad_weight,
+                                         void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -7,6 +7,7 @@ from .binding import (COUNT_NAMES, GRPO_BF16, GRPO_F32, GrpoError, grpo_filter_g
                       grpo_logprobs_fwd, grpo_loss_aux_fwd_bwd, grpo_loss_fwd_bwd, grpo_packed_layout,
                       grpo_workspace_bytes,
                       grpo_workspace_error, lib, status_string,
-                      grpo_lmhead_workspace_bytes, grpo_lmhead_logprobs_fwd, grpo_lmhead_loss_fwd_bwd)
+                      grpo_lmhead_workspace_bytes, grpo_lmhead_logprobs_fwd, grpo_lmhead_loss_fwd_bwd,
+                      grpo_lmhead_loss_aux_fwd_bwd)
 from .build import build_library  # noqa: F401
 from . import workloads  # noqa: F401

@@ -66,6 +66,10 @@ def lib():
         L.grpo_lmhead_loss_fwd_bwd.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, vp, vp, vp, f32, f32,
                                                f32, f32, f64, f32, vp, vp, vp, vp, i64, vp, i64, i32,
                                                vp, sz, vp]
+        L.grpo_lmhead_loss_aux_fwd_bwd.restype = i32
+        L.grpo_lmhead_loss_aux_fwd_bwd.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, vp, vp, vp, vp, vp,
+                                                   f32, f32, f32, f32, f32, f32, f64, f32, vp, vp, vp, vp,
+                                                   vp, i64, vp, i64, i32, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -404,3 +408,58 @@ def grpo_lmhead_loss_fwd_bwd(hidden, weight, tokens, old_logprobs, advantages, m
     if rc != GRPO_OK:
         raise GrpoError(rc, "grpo_lmhead_loss_fwd_bwd")
     return loss_out, logprobs_out, counts_out, grad_hidden, grad_weight
+
+
+def grpo_lmhead_loss_aux_fwd_bwd(hidden, weight, tokens, old_logprobs, ref_logprobs, advantages, mask=None,
+                                 eps_low=0.2, eps_high=0.2, delta=4.0, temperature=1.0, kl_coef=0.0,
+                                 entropy_coef=0.0, denom=0.0, grad_scale=1.0, *, token_weights=None,
+                                 grad_hidden=None, grad_weight=None, accumulate_grad_weight=False,
+                                 loss_out=None, logprobs_out=None, entropy_out=None, want_entropy=True,
+                                 counts_out=None, workspace=None, stream=None):
+    """Total objective (policy + KL - entropy bonus, per-token weights) on hidden @ weight.T with
+    gradients for both operands; see grpo_lmhead_loss_aux_fwd_bwd in grpo.h.  Returns (loss [4]:
+    total, policy, mean kl, mean entropy; logprobs [n]; entropy [n] or None; counts [5];
+    grad_hidden bf16 [n, d]; grad_weight f32 [vocab, d])."""
+    n, v, d, hs, ws = _lmhead_args(hidden, weight)
+    dev = hidden.device
+    _check(tokens, torch.int64, n, "tokens", dev)
+    _check(old_logprobs, torch.float32, n, "old_logprobs", dev)
+    _check(advantages, torch.float32, n, "advantages", dev)
+    if ref_logprobs is not None:
+        _check(ref_logprobs, torch.float32, n, "ref_logprobs", dev)
+    if token_weights is not None:
+        _check(token_weights, torch.float32, n, "token_weights", dev)
+    if mask is not None:
+        _check(mask, torch.uint8, n, "mask", dev)
+    if grad_hidden is None:
+        grad_hidden = torch.empty((n, d), dtype=torch.bfloat16, device=dev)
+    if grad_weight is None:
+        if accumulate_grad_weight:
+            raise ValueError("accumulate_grad_weight needs the grad_weight tensor to add to")
+        grad_weight = torch.empty((v, d), dtype=torch.float32, device=dev)
+    if grad_hidden.dtype != torch.bfloat16 or grad_hidden.shape != (n, d) or grad_hidden.stride(1) != 1:
+        raise ValueError("grad_hidden must be bfloat16 [n_tokens, d_model] with unit inner stride")
+    if grad_weight.dtype != torch.float32 or grad_weight.shape != (v, d) or grad_weight.stride(1) != 1:
+        raise ValueError("grad_weight must be float32 [vocab, d_model] with unit inner stride")
+    if loss_out is None:
+        loss_out = torch.empty(4, dtype=torch.float32, device=dev)
+    if logprobs_out is None:
+        logprobs_out = torch.empty(n, dtype=torch.float32, device=dev)
+    if entropy_out is None and want_entropy:
+        entropy_out = torch.empty(n, dtype=torch.float32, device=dev)
+    if counts_out is None:
+        counts_out = torch.empty(5, dtype=torch.int64, device=dev)
+    if workspace is None:
+        workspace = torch.empty(grpo_lmhead_workspace_bytes(n, v, d, True), dtype=torch.uint8, device=dev)
+    ghs = grad_hidden.stride(0) if n > 1 else max(grad_hidden.stride(0), d)
+    gws = grad_weight.stride(0) if v > 1 else max(grad_weight.stride(0), d)
+    rc = lib().grpo_lmhead_loss_aux_fwd_bwd(
+        _ptr(hidden), hs, _ptr(weight), ws, n, v, d, _ptr(tokens), _ptr(old_logprobs), _ptr(ref_logprobs),
+        _ptr(advantages), _ptr(mask), _ptr(token_weights), float(eps_low), float(eps_high), float(delta),
+        float(temperature), float(kl_coef), float(entropy_coef), float(denom), float(grad_scale),
+        _ptr(loss_out), _ptr(logprobs_out), _ptr(entropy_out), _ptr(counts_out), _ptr(grad_hidden), ghs,
+        _ptr(grad_weight), gws, 1 if accumulate_grad_weight else 0, _ptr(workspace), workspace.numel(),
+        _stream(stream))
+    if rc != GRPO_OK:
+        raise GrpoError(rc, "grpo_lmhead_loss_aux_fwd_bwd")
+    return loss_out, logprobs_out, entropy_out, counts_out, grad_hidden, grad_weight

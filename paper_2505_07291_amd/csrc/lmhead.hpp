@@ -70,7 +70,8 @@ struct GemmParams {
     // LM_EPI_LSE
     const int *tokens32; // [M]: sampled token of each row of A
     float k;             // log2(e) / T
-    float *part_m, *part_s;  // [tiles_n][part_stride]: max and sum of exp2(z k - max) over the tile's columns, y left out
+    float *part_m, *part_s;  // [tiles_n][part_stride]: max of z over the tile's columns and sum of exp2((z - max) k), y left out
+    float *part_w;           // with the auxiliary terms: sum of exp2(a) a, a = (z - max) k, over the same columns
     long long part_stride;
     float *zy;               // [M]: the accumulator at the sampled token's column
     float *Z;                // optional fp32 copy of the logits, [M][ldz]
@@ -146,7 +147,7 @@ __device__ __forceinline__ float lm_row32_sum(float v)
     return v + __shfl_xor(v, 16, 64);
 }
 
-template <int EPI, bool STORE_Z>
+template <int EPI, bool STORE_Z, bool AUX = false>
 __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
 {
     extern __shared__ __attribute__((aligned(1024))) char lm_smem[];
@@ -353,13 +354,14 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
     // and neither the row-per-lane reads nor the 16-lanes-per-row reads collide on banks.
     constexpr int LM_EPI_PITCH = 68;
     constexpr int LM_EPI_WAVE_BYTES = 64 * LM_EPI_PITCH * 4;
-    static_assert(8 * LM_EPI_WAVE_BYTES + (2 * LM_WN * LM_BM + LM_BM) * 4 <= LM_LDS_BYTES, "epilogue staging fits LDS");
+    static_assert(8 * LM_EPI_WAVE_BYTES + (3 * LM_WN * LM_BM + LM_BM) * 4 <= LM_LDS_BYTES, "epilogue staging fits LDS");
     static_assert(LM_FA == 4 && LM_FB == 2 && LM_WM * LM_WN == 8, "the staging below is written for 128 x 64 parts");
     __syncthreads();  // the operand slots are free now
     float *stage = (float *)(lm_smem + wave * LM_EPI_WAVE_BYTES);
     float *red_m = (float *)(lm_smem + 8 * LM_EPI_WAVE_BYTES);  // [LM_WN][256]
     float *red_s = red_m + LM_WN * LM_BM;
-    int *ycol_s = (int *)(red_s + LM_WN * LM_BM);
+    float *red_w = red_s + LM_WN * LM_BM;
+    int *ycol_s = (int *)(red_w + LM_WN * LM_BM);
     if (tid < LM_BM) {
         // column of the sampled token inside this tile, -1 when it is elsewhere
         const int r = row0 + tid;
@@ -411,15 +413,33 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
         float mz = -INFINITY;
 #pragma unroll
         for (int c = 0; c < 16; ++c) mz = fmaxf(fmaxf(fmaxf(mz, zv[c][0]), fmaxf(zv[c][1], zv[c][2])), zv[c][3]);
-        const float m = mz * p.k;                    // k > 0: the maximum of z k
-        const float ref = mz == -INFINITY ? 0.f : m;  // a row with nothing to sum
         float s0 = 0.f, s1 = 0.f;
+        if constexpr (AUX) {
+            // exponents (z - max) k, exactly 0 at the maximum: the entropy gradient of a near-one-hot
+            // row depends on it (see row_scalars_aux); elements at -inf contribute 0, not 0 * inf
+            const float refz = mz == -INFINITY ? 0.f : mz;
+            float w0 = 0.f, w1 = 0.f;
 #pragma unroll
-        for (int c = 0; c < 16; ++c) {
-            s0 += __builtin_amdgcn_exp2f(fmaf(zv[c][0], p.k, -ref)) + __builtin_amdgcn_exp2f(fmaf(zv[c][1], p.k, -ref));
-            s1 += __builtin_amdgcn_exp2f(fmaf(zv[c][2], p.k, -ref)) + __builtin_amdgcn_exp2f(fmaf(zv[c][3], p.k, -ref));
+            for (int c = 0; c < 16; ++c)
+#pragma unroll
+                for (int e = 0; e < 4; e += 2) {
+                    const float a0 = (zv[c][e] - refz) * p.k, a1 = (zv[c][e + 1] - refz) * p.k;
+                    const float e0 = __builtin_amdgcn_exp2f(a0), e1 = __builtin_amdgcn_exp2f(a1);
+                    s0 += e0;
+                    s1 += e1;
+                    w0 = fmaf(e0, fmaxf(a0, kExpFloor), w0);
+                    w1 = fmaf(e1, fmaxf(a1, kExpFloor), w1);
+                }
+            red_w[wn * LM_BM + rbase + lane] = w0 + w1;
+        } else {
+            const float ref = mz == -INFINITY ? 0.f : mz * p.k;  // 0 for a row with nothing to sum
+#pragma unroll
+            for (int c = 0; c < 16; ++c) {
+                s0 += __builtin_amdgcn_exp2f(fmaf(zv[c][0], p.k, -ref)) + __builtin_amdgcn_exp2f(fmaf(zv[c][1], p.k, -ref));
+                s1 += __builtin_amdgcn_exp2f(fmaf(zv[c][2], p.k, -ref)) + __builtin_amdgcn_exp2f(fmaf(zv[c][3], p.k, -ref));
+            }
         }
-        red_m[wn * LM_BM + rbase + lane] = m;
+        red_m[wn * LM_BM + rbase + lane] = mz;  // in units of z
         red_s[wn * LM_BM + rbase + lane] = s0 + s1;
     }
     __syncthreads();
@@ -429,14 +449,21 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
             float m = -INFINITY;
 #pragma unroll
             for (int w = 0; w < LM_WN; ++w) m = fmaxf(m, red_m[w * LM_BM + tid]);
-            float s = 0.f;
+            float s = 0.f, ws = 0.f;
 #pragma unroll
             for (int w = 0; w < LM_WN; ++w) {
                 const float mw = red_m[w * LM_BM + tid];
-                if (mw != -INFINITY) s += red_s[w * LM_BM + tid] * __builtin_amdgcn_exp2f(mw - m);
+                if (mw != -INFINITY) {
+                    const float d = (mw - m) * p.k;  // <= 0; exactly 0 for the part that holds the maximum
+                    const float f = __builtin_amdgcn_exp2f(d);
+                    const float sw = red_s[w * LM_BM + tid];
+                    s = fmaf(sw, f, s);
+                    if constexpr (AUX) ws = fmaf(f, fmaf(d, sw, red_w[w * LM_BM + tid]), ws);
+                }
             }
             p.part_m[(long long)tn * p.part_stride + row] = m;
             p.part_s[(long long)tn * p.part_stride + row] = s;
+            if constexpr (AUX) p.part_w[(long long)tn * p.part_stride + row] = ws;
         }
     }
 }
@@ -453,7 +480,9 @@ struct LmRows {
     float *shift;  // max k + log2(sum): p_j = exp2(z_j k - shift)
     float *q;      // c / T
     float *gy;     // gradient at the sampled token: q (1 - p_y), from the sum without y
-    float *part_m, *part_s;
+    // with the auxiliary terms: g_j = p_j (q2 + bq a_j), a_j = (z_j - mx) k - log2s = log2 p_j
+    float *mx, *log2s, *q2, *bq;
+    float *part_m, *part_s, *part_w;
     long long part_stride;
     int tiles_n;
 };
@@ -501,6 +530,7 @@ __global__ void __launch_bounds__(1024) lm_select_rows(RowParams p, LmRows w)
         p.n_tokens,
         [&](long long r) {
             bool live = p.mask ? (p.mask[r] != 0) : true;
+            if (live && p.token_w && p.token_w[r] == 0.f) live = false;  // a zero weight masks the row
             bool bad = false;
             if (live) {
                 const long long y = p.tokens[r];
@@ -511,6 +541,7 @@ __global__ void __launch_bounds__(1024) lm_select_rows(RowParams p, LmRows w)
             }
             if (!live) {
                 write_row_outputs(p, r, (bad && !p.bwd) ? NAN : 0.f, 0.f, 0);
+                write_row_aux(p, r, 0.f, 0.f);
                 if (bad && p.bwd) atomicOr(&p.hdr->error, 1);
             }
             return live;
@@ -526,7 +557,7 @@ __global__ void __launch_bounds__(1024) lm_select_rows(RowParams p, LmRows w)
 __global__ void __launch_bounds__(1024) lm_select_grad_rows(LmRows w)
 {
     const int total = lm_ordered_select(
-        *w.n_live, [&](long long i) { return w.q[i] != 0.f; },
+        *w.n_live, [&](long long i) { return w.q[i] != 0.f || (w.bq && w.bq[i] != 0.f); },
         [&](int pos, long long i) {
             w.rows2[pos] = (int)i;
             w.orig2[pos] = w.rows[i];
@@ -550,42 +581,71 @@ __global__ void __launch_bounds__(256) lm_gather_rows(const __bf16 *in, long lon
 // A workgroup takes 16 compact rows; 16 lanes share a row, each merging every 16th tile, and
 // their results meet in LDS in lane order (fixed order: the bits repeat from run to run).
 constexpr int LM_CMB_ROWS = 16, LM_CMB_LANES = 16;
+template <bool AUX>
 __global__ void __launch_bounds__(LM_CMB_ROWS * LM_CMB_LANES) lm_combine(RowParams p, LmRows w)
 {
     __shared__ float sh_m[LM_CMB_LANES][LM_CMB_ROWS + 1], sh_s[LM_CMB_LANES][LM_CMB_ROWS + 1];
+    __shared__ float sh_w[LM_CMB_LANES][LM_CMB_ROWS + 1];
     const int rl = threadIdx.x % LM_CMB_ROWS, tl = threadIdx.x / LM_CMB_ROWS;
     const long long i = (long long)blockIdx.x * LM_CMB_ROWS + rl;
     const bool live = i < *w.n_live;
-    float m = -INFINITY;
+    float mz = -INFINITY;  // maximum over the tiles, in units of z
     if (live)
-        for (int t = tl; t < w.tiles_n; t += LM_CMB_LANES) m = fmaxf(m, w.part_m[(long long)t * w.part_stride + i]);
-    sh_m[tl][rl] = m;
+        for (int t = tl; t < w.tiles_n; t += LM_CMB_LANES) mz = fmaxf(mz, w.part_m[(long long)t * w.part_stride + i]);
+    sh_m[tl][rl] = mz;
     __syncthreads();
 #pragma unroll
-    for (int l = 0; l < LM_CMB_LANES; ++l) m = fmaxf(m, sh_m[l][rl]);
+    for (int l = 0; l < LM_CMB_LANES; ++l) mz = fmaxf(mz, sh_m[l][rl]);
     const float zy = live ? w.zy[i] : 0.f;
-    const float mk = fmaxf(m, zy * p.k);  // the sampled token may be the row's maximum
-    float s = 0.f;
+    const float mx = fmaxf(mz, zy);  // the sampled token may be the row's maximum
+    const float mk = mx * p.k;
+    float s = 0.f, ws = 0.f;
     if (live)
         for (int t = tl; t < w.tiles_n; t += LM_CMB_LANES) {
             const float mt = w.part_m[(long long)t * w.part_stride + i];
-            if (mt != -INFINITY)
-                s += w.part_s[(long long)t * w.part_stride + i] * __builtin_amdgcn_exp2f(mt - mk);
+            if (mt == -INFINITY) continue;
+            const float st = w.part_s[(long long)t * w.part_stride + i];
+            if constexpr (AUX) {
+                const float d = (mt - mx) * p.k;
+                const float f = __builtin_amdgcn_exp2f(d);
+                s = fmaf(st, f, s);
+                ws = fmaf(f, fmaf(d, st, w.part_w[(long long)t * w.part_stride + i]), ws);
+            } else {
+                s = fmaf(st, __builtin_amdgcn_exp2f(fmaf(mt, p.k, -mk)), s);
+            }
         }
     sh_s[tl][rl] = s;
+    if constexpr (AUX) sh_w[tl][rl] = ws;
     __syncthreads();
     if (tl != 0 || !live) return;
-    float s_excl = 0.f;
+    float s_excl = 0.f, w_excl = 0.f;
 #pragma unroll
-    for (int l = 0; l < LM_CMB_LANES; ++l) s_excl += sh_s[l][rl];
+    for (int l = 0; l < LM_CMB_LANES; ++l) {
+        s_excl += sh_s[l][rl];
+        if constexpr (AUX) w_excl += sh_w[l][rl];
+    }
     const long long row = w.rows[i];
-    const RowScalars o = row_scalars(p, row, zy, mk, s_excl);
-    write_row_outputs(p, row, o.logp, o.J, o.flags);
-    if (p.bwd) {
+    if constexpr (AUX) {
+        float kl, H;
+        const RowScalars o = row_scalars_aux(p, row, zy, mx, s_excl, w_excl, kl, H);
+        write_row_aux(p, row, kl, H);
+        write_row_outputs(p, row, o.logp, o.J, o.flags);
         const float q = o.c * p.inv_T;
         w.q[i] = q;
-        w.gy[i] = q * (o.s_excl / o.s);
-        w.shift[i] = o.shift;
+        w.gy[i] = q * (o.s_excl / o.s) + o.gy_ent;
+        w.mx[i] = o.mx;
+        w.log2s[i] = o.log2s;
+        w.q2[i] = o.q2;
+        w.bq[i] = o.bq;
+    } else {
+        const RowScalars o = row_scalars(p, row, zy, mk, s_excl);
+        write_row_outputs(p, row, o.logp, o.J, o.flags);
+        if (p.bwd) {
+            const float q = o.c * p.inv_T;
+            w.q[i] = q;
+            w.gy[i] = q * (o.s_excl / o.s);
+            w.shift[i] = o.shift;
+        }
     }
 }
 
@@ -594,6 +654,7 @@ __global__ void __launch_bounds__(LM_CMB_ROWS * LM_CMB_LANES) lm_combine(RowPara
 // consecutive elements per lane on both sides.  Padding (columns V .. ldg of G, columns
 // n_grad .. the next multiple of 64 of G^T) is written as zeros so that the products can
 // run over whole K steps.
+template <bool AUX>
 __global__ void __launch_bounds__(256) lm_grad_logits(const float *Z, long long ldz, int V, LmRows w,
                                                       float k, __bf16 *G, long long ldg, __bf16 *Gt,
                                                       long long ldgt)
@@ -610,7 +671,12 @@ __global__ void __launch_bounds__(256) lm_grad_logits(const float *Z, long long 
         float gv[4] = {0.f, 0.f, 0.f, 0.f};
         if (r < n2 && c < V) {
             const int ci = w.rows2[r];
-            const float q = w.q[ci], sh = w.shift[ci];
+            float q = 0.f, sh = 0.f, mxr = 0.f, l2s = 0.f, q2 = 0.f, bq = 0.f;
+            if constexpr (AUX) {
+                mxr = w.mx[ci], l2s = w.log2s[ci], q2 = w.q2[ci], bq = w.bq[ci];
+            } else {
+                q = w.q[ci], sh = w.shift[ci];
+            }
             const int y = w.tokens32[ci];
             const float *zrow = Z + (long long)ci * ldz + c;
             float z[4];
@@ -623,7 +689,13 @@ __global__ void __launch_bounds__(256) lm_grad_logits(const float *Z, long long 
             }
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                gv[e] = -q * __builtin_amdgcn_exp2f(fmaf(z[e], k, -sh));
+                if constexpr (AUX) {
+                    // g_j = p_j (q2 + bq log2 p_j): policy, KL and entropy parts in one (see grad_vec_aux)
+                    const float a = fmaxf(fmaf(z[e] - mxr, k, -l2s), kExpFloor);
+                    gv[e] = __builtin_amdgcn_exp2f(a) * fmaf(bq, a, q2);
+                } else {
+                    gv[e] = -q * __builtin_amdgcn_exp2f(fmaf(z[e], k, -sh));
+                }
                 if (c + e == y) gv[e] = w.gy[ci];
                 if (c + e >= V) gv[e] = 0.f;
             }
@@ -729,7 +801,7 @@ __global__ void __launch_bounds__(256) lm_zero(T *out, long long rows, long long
 // Host side
 // ---------------------------------------------------------------------------
 
-template <int EPI, bool STORE_Z>
+template <int EPI, bool STORE_Z, bool AUX = false>
 hipError_t lm_launch_gemm(GemmParams p, hipStream_t st)
 {
     static bool attr_done[64] = {false};
@@ -737,7 +809,7 @@ hipError_t lm_launch_gemm(GemmParams p, hipStream_t st)
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     if (dev >= 0 && dev < 64 && !attr_done[dev]) {
-        e = hipFuncSetAttribute((const void *)lm_gemm_nt<EPI, STORE_Z>,
+        e = hipFuncSetAttribute((const void *)lm_gemm_nt<EPI, STORE_Z, AUX>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, LM_LDS_BYTES);
         if (e != hipSuccess) return e;
         attr_done[dev] = true;
@@ -746,12 +818,13 @@ hipError_t lm_launch_gemm(GemmParams p, hipStream_t st)
     const long long total = (long long)((p.M + LM_BM - 1) / LM_BM) * p.tiles_n *
                             (EPI == LM_EPI_BF16 && p.split_max > 1 ? p.split_max : 1);  // upper bound
     const long long grid = (total + 7) / 8 * 8;
-    hipLaunchKernelGGL((lm_gemm_nt<EPI, STORE_Z>), dim3((unsigned)grid), dim3(LM_THREADS), LM_LDS_BYTES, st, p);
+    hipLaunchKernelGGL((lm_gemm_nt<EPI, STORE_Z, AUX>), dim3((unsigned)grid), dim3(LM_THREADS), LM_LDS_BYTES, st, p);
     return hipGetLastError();
 }
 
 struct LmLayout {
-    size_t rows, tokens32, rows2, orig2, counts, zy, shift, q, gy, part_m, part_s, Hc, Z, G, Gt, Wt, Ht, total;
+    size_t rows, tokens32, rows2, orig2, counts, zy, shift, q, gy, mx, log2s, q2, bq, part_m, part_s, part_w, Hc, Z, G, Gt,
+        Wt, Ht, total;
     long long ldz, ldg, ldgt;  // vocab and token counts rounded up to whole K steps
     int tiles_n;
 };
@@ -781,6 +854,11 @@ LmLayout lm_layout(int64_t n, int64_t V, int64_t d, bool bwd)
         L.shift = take((size_t)n * 4);
         L.q = take((size_t)n * 4);
         L.gy = take((size_t)n * 4);
+        L.mx = take((size_t)n * 4);  // these four and part_w: only the call with the auxiliary terms
+        L.log2s = take((size_t)n * 4);
+        L.q2 = take((size_t)n * 4);
+        L.bq = take((size_t)n * 4);
+        L.part_w = take((size_t)L.tiles_n * n * 4);
         L.Z = take((size_t)n * L.ldz * 4);
         L.G = take((size_t)n * L.ldg * 2);
         L.Gt = take((size_t)V * L.ldgt * 2);
@@ -809,11 +887,12 @@ grpo_status lm_check_common(const void *hidden, int64_t hidden_stride, const voi
     return GRPO_OK;
 }
 
-grpo_status lm_impl(bool bwd, const void *hidden, int64_t hidden_stride, const void *weight,
+grpo_status lm_impl(bool bwd, bool aux, const void *hidden, int64_t hidden_stride, const void *weight,
                     int64_t weight_stride, int64_t n_tokens, int64_t vocab, int64_t d_model,
-                    const int64_t *tokens, const float *old_logprobs, const float *advantages,
-                    const uint8_t *mask, float eps_low, float eps_high, float delta, float temperature,
-                    double denom, float grad_scale, float *loss_out, float *logprobs_out,
+                    const int64_t *tokens, const float *old_logprobs, const float *ref_logprobs,
+                    const float *advantages, const uint8_t *mask, const float *token_weights, float eps_low,
+                    float eps_high, float delta, float temperature, float kl_coef, float entropy_coef,
+                    double denom, float grad_scale, float *loss_out, float *logprobs_out, float *entropy_out,
                     int64_t *counts_out, void *grad_hidden, int64_t grad_hidden_stride,
                     float *grad_weight, int64_t grad_weight_stride, int accumulate_grad_weight,
                     void *workspace, size_t workspace_bytes, void *stream)
@@ -823,10 +902,12 @@ grpo_status lm_impl(bool bwd, const void *hidden, int64_t hidden_stride, const v
     if (rc != GRPO_OK) return rc;
     if (bwd) {
         if (!(eps_low >= 0.f && eps_low <= 1.f) || !(eps_high >= 0.f) || !std::isfinite(eps_high) ||
-            !(delta > 1.f + eps_high) || std::isnan(denom) || std::isnan(grad_scale))
+            !(delta > 1.f + eps_high) || std::isnan(denom) || std::isnan(grad_scale) ||
+            !std::isfinite(kl_coef) || !std::isfinite(entropy_coef))
             return GRPO_ERR_PARAM;
         if (!loss_out) return GRPO_ERR_NULL;
         if (n_tokens > 0 && (!old_logprobs || !advantages || !grad_hidden)) return GRPO_ERR_NULL;
+        if (n_tokens > 0 && kl_coef != 0.f && !ref_logprobs) return GRPO_ERR_NULL;
         if (!grad_weight) return GRPO_ERR_NULL;
         if (grad_hidden_stride < d_model || grad_weight_stride < d_model) return GRPO_ERR_SHAPE;
     } else {
@@ -842,11 +923,12 @@ grpo_status lm_impl(bool bwd, const void *hidden, int64_t hidden_stride, const v
     const size_t col = align_up((size_t)n_tokens * 4, 256);
     WsHeader *hdr = (WsHeader *)ws;
     float *J_ws = (float *)(ws + kHeaderBytes);
+    float *KL_ws = (float *)(ws + kHeaderBytes + col);
     float *H_ws = (float *)(ws + kHeaderBytes + 2 * col);
     unsigned char *flags_ws = (unsigned char *)(ws + kHeaderBytes + 3 * col);
 
     if (bwd)
-        hipLaunchKernelGGL(grpo_prepare, dim3(1), dim3(1024), 0, st, mask, (const float *)nullptr,
+        hipLaunchKernelGGL(grpo_prepare, dim3(1), dim3(1024), 0, st, mask, aux ? token_weights : (const float *)nullptr,
                            (long long)n_tokens, denom, hdr);
     if (n_tokens > 0) {
         const int M = (int)n_tokens, V = (int)vocab, D = (int)d_model;
@@ -860,6 +942,13 @@ grpo_status lm_impl(bool bwd, const void *hidden, int64_t hidden_stride, const v
         w.part_s = (float *)(ws + L.part_s);
         w.part_stride = n_tokens;
         w.tiles_n = L.tiles_n;
+        if (aux) {
+            w.part_w = (float *)(ws + L.part_w);
+            w.mx = (float *)(ws + L.mx);
+            w.log2s = (float *)(ws + L.log2s);
+            w.q2 = (float *)(ws + L.q2);
+            w.bq = (float *)(ws + L.bq);
+        }
         if (bwd) {
             w.rows2 = (int *)(ws + L.rows2);
             w.orig2 = (int *)(ws + L.orig2);
@@ -887,6 +976,15 @@ grpo_status lm_impl(bool bwd, const void *hidden, int64_t hidden_stride, const v
         p.delta = delta;
         p.grad_scale = grad_scale;
         p.bwd = bwd ? 1 : 0;
+        if (aux) {
+            p.ref_lp = kl_coef != 0.f ? ref_logprobs : nullptr;
+            p.token_w = token_weights;
+            p.KL_ws = KL_ws;
+            p.H_ws = H_ws;
+            p.entropy_out = entropy_out;
+            p.kl_coef = kl_coef;
+            p.ent_coef = entropy_coef;
+        }
 
         // rows that take part, and their hidden states side by side
         __bf16 *Hc = (__bf16 *)(ws + L.Hc);
@@ -908,22 +1006,33 @@ grpo_status lm_impl(bool bwd, const void *hidden, int64_t hidden_stride, const v
         g.k = k;
         g.part_m = w.part_m;
         g.part_s = w.part_s;
+        g.part_w = w.part_w;
         g.part_stride = n_tokens;
         g.zy = w.zy;
         g.Z = bwd ? (float *)(ws + L.Z) : nullptr;
         g.ldz = L.ldz;
-        hipError_t e = bwd ? lm_launch_gemm<LM_EPI_LSE, true>(g, st) : lm_launch_gemm<LM_EPI_LSE, false>(g, st);
+        hipError_t e = aux   ? lm_launch_gemm<LM_EPI_LSE, true, true>(g, st)
+                       : bwd ? lm_launch_gemm<LM_EPI_LSE, true>(g, st)
+                             : lm_launch_gemm<LM_EPI_LSE, false>(g, st);
         if (e != hipSuccess) return GRPO_ERR_HIP;
 
-        hipLaunchKernelGGL(lm_combine, dim3((unsigned)((n_tokens + LM_CMB_ROWS - 1) / LM_CMB_ROWS)),
-                           dim3(LM_CMB_ROWS * LM_CMB_LANES), 0, st, p, w);
+        const dim3 cmb_grid((unsigned)((n_tokens + LM_CMB_ROWS - 1) / LM_CMB_ROWS));
+        if (aux)
+            hipLaunchKernelGGL(lm_combine<true>, cmb_grid, dim3(LM_CMB_ROWS * LM_CMB_LANES), 0, st, p, w);
+        else
+            hipLaunchKernelGGL(lm_combine<false>, cmb_grid, dim3(LM_CMB_ROWS * LM_CMB_LANES), 0, st, p, w);
 
         if (bwd) {
             __bf16 *G = (__bf16 *)(ws + L.G), *Gt = (__bf16 *)(ws + L.Gt);
             __bf16 *Wt = (__bf16 *)(ws + L.Wt), *Ht = (__bf16 *)(ws + L.Ht);
             hipLaunchKernelGGL(lm_select_grad_rows, dim3(1), dim3(1024), 0, st, w);
-            hipLaunchKernelGGL(lm_grad_logits, dim3((unsigned)(L.ldg / 64), (unsigned)(L.ldgt / 64)), dim3(256),
-                               0, st, (const float *)(ws + L.Z), L.ldz, V, w, k, G, L.ldg, Gt, L.ldgt);
+            const dim3 gl_grid((unsigned)(L.ldg / 64), (unsigned)(L.ldgt / 64));
+            if (aux)
+                hipLaunchKernelGGL(lm_grad_logits<true>, gl_grid, dim3(256), 0, st, (const float *)(ws + L.Z), L.ldz,
+                                   V, w, k, G, L.ldg, Gt, L.ldgt);
+            else
+                hipLaunchKernelGGL(lm_grad_logits<false>, gl_grid, dim3(256), 0, st, (const float *)(ws + L.Z), L.ldz,
+                                   V, w, k, G, L.ldg, Gt, L.ldgt);
             // W^T [d][ldg]; H^T of the gradient rows [d][ldgt]
             hipLaunchKernelGGL(lm_transpose, dim3((unsigned)((D + 63) / 64), (unsigned)(L.ldg / 64)), dim3(256), 0,
                                st, (const __bf16 *)weight, (long long)weight_stride, V, (const int *)nullptr,
@@ -983,8 +1092,9 @@ grpo_status lm_impl(bool bwd, const void *hidden, int64_t hidden_stride, const v
                            (long long)d_model, (long long)grad_weight_stride);
     }
     if (bwd)
-        hipLaunchKernelGGL(grpo_finalize, dim3(1), dim3(1024), 0, st, J_ws, (const float *)nullptr, H_ws,
-                           flags_ws, (long long)n_tokens, hdr, 0.f, 0.f, loss_out, (long long *)counts_out);
+        hipLaunchKernelGGL(grpo_finalize, dim3(1), dim3(1024), 0, st, J_ws, aux ? KL_ws : (const float *)nullptr, H_ws,
+                           flags_ws, (long long)n_tokens, hdr, kl_coef, entropy_coef, loss_out,
+                           (long long *)counts_out);
     return hipGetLastError() == hipSuccess ? GRPO_OK : GRPO_ERR_HIP;
 }
 
@@ -1004,9 +1114,9 @@ grpo_status grpo_lmhead_logprobs_fwd(const void *hidden, int64_t hidden_stride, 
                                      float temperature, float *logprobs_out, void *workspace,
                                      size_t workspace_bytes, void *stream)
 {
-    return lm_impl(false, hidden, hidden_stride, weight, weight_stride, n_tokens, vocab, d_model, tokens,
-                   nullptr, nullptr, mask, 0.f, 0.f, 0.f, temperature, 0.0, 0.f, nullptr, logprobs_out,
-                   nullptr, nullptr, 0, nullptr, 0, 0, workspace, workspace_bytes, stream);
+    return lm_impl(false, false, hidden, hidden_stride, weight, weight_stride, n_tokens, vocab, d_model, tokens,
+                   nullptr, nullptr, nullptr, mask, nullptr, 0.f, 0.f, 0.f, temperature, 0.f, 0.f, 0.0, 0.f, nullptr,
+                   logprobs_out, nullptr, nullptr, nullptr, 0, nullptr, 0, 0, workspace, workspace_bytes, stream);
 }
 
 grpo_status grpo_lmhead_loss_fwd_bwd(const void *hidden, int64_t hidden_stride, const void *weight,
@@ -1020,10 +1130,29 @@ grpo_status grpo_lmhead_loss_fwd_bwd(const void *hidden, int64_t hidden_stride, 
                                      int accumulate_grad_weight, void *workspace, size_t workspace_bytes,
                                      void *stream)
 {
-    return lm_impl(true, hidden, hidden_stride, weight, weight_stride, n_tokens, vocab, d_model, tokens,
-                   old_logprobs, advantages, mask, eps_low, eps_high, delta, temperature, denom, grad_scale,
-                   loss_out, logprobs_out, counts_out, grad_hidden, grad_hidden_stride, grad_weight,
-                   grad_weight_stride, accumulate_grad_weight, workspace, workspace_bytes, stream);
+    return lm_impl(true, false, hidden, hidden_stride, weight, weight_stride, n_tokens, vocab, d_model, tokens,
+                   old_logprobs, nullptr, advantages, mask, nullptr, eps_low, eps_high, delta, temperature, 0.f, 0.f,
+                   denom, grad_scale, loss_out, logprobs_out, nullptr, counts_out, grad_hidden, grad_hidden_stride,
+                   grad_weight, grad_weight_stride, accumulate_grad_weight, workspace, workspace_bytes, stream);
+}
+
+grpo_status grpo_lmhead_loss_aux_fwd_bwd(const void *hidden, int64_t hidden_stride, const void *weight,
+                                         int64_t weight_stride, int64_t n_tokens, int64_t vocab,
+                                         int64_t d_model, const int64_t *tokens, const float *old_logprobs,
+                                         const float *ref_logprobs, const float *advantages,
+                                         const uint8_t *mask, const float *token_weights, float eps_low,
+                                         float eps_high, float delta, float temperature, float kl_coef,
+                                         float entropy_coef, double denom, float grad_scale, float *loss_out,
+                                         float *logprobs_out, float *entropy_out, int64_t *counts_out,
+                                         void *grad_hidden, int64_t grad_hidden_stride, float *grad_weight,
+                                         int64_t grad_weight_stride, int accumulate_grad_weight,
+                                         void *workspace, size_t workspace_bytes, void *stream)
+{
+    return lm_impl(true, true, hidden, hidden_stride, weight, weight_stride, n_tokens, vocab, d_model, tokens,
+                   old_logprobs, ref_logprobs, advantages, mask, token_weights, eps_low, eps_high, delta,
+                   temperature, kl_coef, entropy_coef, denom, grad_scale, loss_out, logprobs_out, entropy_out,
+                   counts_out, grad_hidden, grad_hidden_stride, grad_weight, grad_weight_stride,
+                   accumulate_grad_weight, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

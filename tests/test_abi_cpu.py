@@ -202,3 +202,27 @@ def test_lmhead_logprobs_rejects_bad_arguments_and_sizes_its_workspace():
     assert bwd >= 8 * n * V + 2 * V * d and bwd < 9 * n * V + 4 * V * d
     assert grpo.grpo_lmhead_workspace_bytes(-1, V, d, True) == 0
     assert grpo.grpo_lmhead_workspace_bytes(n, 0, d, True) == 0
+
+
+def lmhead_aux_args(**over):
+    a = dict(hidden=P, hs=128, weight=P, wstride=128, n=16, V=1000, d=128, tokens=P, old=P, ref=P, adv=P,
+             mask=P, tw=None, el=0.2, eh=0.2, delta=4.0, T=1.0, klc=0.001, enc=1e-4, denom=0.0, gs=1.0,
+             loss=P, lp=P, ent=None, counts=P, gh=P, ghs=128, gw=P, gws=128, acc=0, ws=P, ws_bytes=1 << 30,
+             stream=None)
+    a.update(over)
+    return [a[k] for k in ("hidden", "hs", "weight", "wstride", "n", "V", "d", "tokens", "old", "ref", "adv",
+                           "mask", "tw", "el", "eh", "delta", "T", "klc", "enc", "denom", "gs", "loss", "lp",
+                           "ent", "counts", "gh", "ghs", "gw", "gws", "acc", "ws", "ws_bytes", "stream")]
+
+
+@pytest.mark.parametrize("over,expect", [
+    (dict(hidden=None), NULL), (dict(old=None), NULL), (dict(loss=None), NULL), (dict(gw=None), NULL),
+    (dict(ref=None), NULL),                       # a KL coefficient needs the reference log-probs
+    (dict(n=-1), SHAPE), (dict(d=80, hs=80, wstride=80), SHAPE), (dict(ghs=64), SHAPE),
+    (dict(weight=P + 2), ALIGN),
+    (dict(T=0.0), PARAM), (dict(delta=1.2), PARAM), (dict(klc=float("inf")), PARAM),
+    (dict(enc=float("nan")), PARAM),
+    (dict(ws=None), WORKSPACE), (dict(ws_bytes=4096), WORKSPACE),
+])
+def test_lmhead_aux_loss_rejects_bad_arguments_before_any_launch(over, expect):
+    assert grpo.lib().grpo_lmhead_loss_aux_fwd_bwd(*lmhead_aux_args(**over)) == expect

@@ -1,0 +1,235 @@
+"""GPU parity of the fused language-model-head path with the auxiliary terms
+(grpo_lmhead_loss_aux_fwd_bwd: policy term, sampled-token KL, entropy bonus, per-token
+weights, on logits the library forms itself) against the fp64 oracle.
+
+Tolerances: scalars and per-token outputs as for the logits path with the auxiliary terms
+(log-probs 2e-4 abs, per-token entropy 2e-4 abs, total / policy 1e-4 rel, mean KL 1e-4 rel
++ 1e-9, mean entropy 1e-4 rel + 2e-7, counters exact); dL/dH and dL/dW as for the plain
+head path: G is rounded to bf16 (u = 2^-8) before the two fp32-accumulating products and
+dL/dH is rounded to bf16 on output, so element by element
+    |d dH[t,k]| <= u sum_v |G[t,v]| |W[v,k]| + u |dH[t,k]|,   |d dW[v,k]| <= u sum_t |G[t,v]| |H[t,k]|
+with 5 % slack, plus what the logits path's gradient bound adds for the two new terms, carried
+through the products: the KL part of a row's coefficient is known to two fp32 ulps of l
+(floor_kl = |kl_coef grad_scale omega / (D T)| 2^-22 max(|l|, 1) on every |G[t,v]| of the row via
+p_v, i.e. floor_kl * sum_v p_v |W[v,k]| <= floor_kl max|W|), and the entropy part to
+|ent_coef grad_scale omega / (D T)| p_max max(H, 1) 2^-20; and the error must look like
+rounding noise (Frobenius norm below 0.6 u of the norm of the bounds).
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2505_07291_amd as grpo
+from paper_2505_07291_amd import workloads as wl
+from oracle import grpo_oracle as orc
+from test_gpu_lmhead_parity import DEV, TOL_LOGP, TOL_LOSS_REL, U, bits, f32, say, wide
+
+pytestmark = pytest.mark.gpu
+
+
+def run_aux_case(cfg, d_model, kl_coef, ent_coef, *, denom=0.0, grad_scale=1.0, weighted=False, label="",
+                 batch=None):
+    if batch is None:
+        batch = wl.make_lmhead_batch(cfg, d_model, device=DEV)
+    N, V = batch["n_tokens"], batch["vocab"]
+    T = f32(cfg.temperature)
+    kw = dict(eps_low=f32(cfg.eps_low), eps_high=f32(cfg.eps_high), delta=f32(cfg.delta))
+    hb, wb = bits(batch["hidden"]), bits(batch["weight"])
+    tokens_np, mask_np = batch["tokens"].cpu().numpy(), batch["mask"].cpu().numpy()
+    adv = orc.group_advantages(batch["rewards"].cpu().numpy(), group_size=batch["group_size"])
+    adv_tok = orc.broadcast_advantages(adv, batch["rollout_of_token"].cpu().numpy()).astype(np.float32)
+    lp_orc = orc.logprobs(orc.lmhead_logits(hb, wb), tokens_np, mask_np, temperature=T)
+    old = wl.make_old_logprobs(cfg, lp_orc)
+    g = torch.Generator().manual_seed(1900 + cfg.index)
+    ref = (torch.as_tensor(lp_orc) + torch.randn(N, generator=g, dtype=torch.float64) * 0.1).float()
+    tw = None
+    if weighted:
+        tw = (torch.rand(N, generator=g) * 1.3 + 0.2).float()
+        tw[::7] = 0.0                                   # zero weight: the row drops out like a masked one
+    tw_np = None if tw is None else tw.numpy()
+    want = orc.lmhead_aux_loss_fwd_bwd(hb, wb, tokens_np, old.numpy(), ref.numpy(), adv_tok, mask_np,
+                                       token_weights=tw_np, temperature=T, kl_coef=f32(kl_coef),
+                                       ent_coef=f32(ent_coef), denom=denom, grad_scale=f32(grad_scale), **kw)
+    say("[gpu] %s grpo_lmhead_loss_aux_fwd_bwd N=%d V=%d d=%d kl=%g ent=%g" % (label, N, V, d_model, kl_coef, ent_coef))
+    loss, lp, ent, counts, dH, dW = grpo.grpo_lmhead_loss_aux_fwd_bwd(
+        batch["hidden"], batch["weight"], batch["tokens"], old.to(DEV), ref.to(DEV),
+        torch.as_tensor(adv_tok, device=DEV), batch["mask"], temperature=T, kl_coef=kl_coef,
+        entropy_coef=ent_coef, denom=denom, grad_scale=grad_scale,
+        token_weights=None if tw is None else tw.to(DEV), **kw)
+    torch.cuda.synchronize()
+    got = loss.cpu().numpy().astype(np.float64)
+    e_lp = np.abs(lp.cpu().numpy() - want["logprobs"]).max()
+    e_h = np.abs(ent.cpu().numpy() - want["entropies"]).max()
+    say("      |dl|=%.1e |dH_t|=%.1e total %.8g vs %.8g kl %.5g H %.6g counts %s" %
+        (e_lp, e_h, got[0], want["total"], got[2], got[3], counts.tolist()))
+    assert e_lp <= TOL_LOGP and e_h <= 2e-4
+    assert counts.cpu().numpy().tolist() == want["counts"].tolist()
+    assert abs(got[0] - want["total"]) <= TOL_LOSS_REL * abs(want["total"]) + 1e-7
+    assert abs(got[1] - want["policy"]) <= TOL_LOSS_REL * abs(want["policy"]) + 1e-7
+    assert abs(got[2] - want["kl"]) <= 1e-4 * want["kl"] + 1e-9
+    assert abs(got[3] - want["entropy"]) <= 1e-4 * want["entropy"] + 2e-7
+    # gradients
+    G = want["grad"]
+    H64, W64 = wide(hb), wide(wb)
+    M = int(want["counts"][0])
+    D = denom if denom > 0 else float(max(M, 1))
+    wrow = np.ones(N) if tw_np is None else np.abs(tw_np.astype(np.float64))
+    scale = wrow * abs(f32(grad_scale)) / (D * T)
+    z = want["logits"]
+    pmax = np.exp(z.max(axis=1) / T - z[np.arange(N), tokens_np] / T + want["logprobs"])
+    floor_row = scale * (abs(f32(kl_coef)) * 2.0 ** -22 * np.maximum(np.abs(want["logprobs"]), 1.0) +
+                         abs(f32(ent_coef)) * pmax * np.maximum(want["entropies"], 1.0) * 2.0 ** -20)
+    floor_row = np.where((mask_np == 1) & (wrow > 0), floor_row, 0.0)
+    bH = U * (np.abs(G) @ np.abs(W64) + np.abs(want["grad_hidden"])) + floor_row[:, None] * np.abs(W64).max()
+    bW = U * (np.abs(G).T @ np.abs(H64)) + (floor_row[:, None] * np.abs(H64)).sum(axis=0)[None, :]
+    eH = np.abs(dH.cpu().double().numpy() - want["grad_hidden"])
+    eW = np.abs(dW.cpu().double().numpy() - want["grad_weight"])
+    say("      dH err max %.3e (max %.3e)  dW err max %.3e (max %.3e)" %
+        (eH.max(), np.abs(want["grad_hidden"]).max(), eW.max(), np.abs(want["grad_weight"]).max()))
+    assert np.all(eH <= 1.05 * bH + 1e-30), "dH off by %g of its bound" % (eH / (bH + 1e-300)).max()
+    assert np.all(eW <= 1.05 * bW + 1e-30), "dW off by %g of its bound" % (eW / (bW + 1e-300)).max()
+    assert np.linalg.norm(eH) <= 0.6 * np.linalg.norm(bH) and np.linalg.norm(eW) <= 0.6 * np.linalg.norm(bW)
+    nograd = (want["coeff"] == 0) & (want["ent_coeff"] == 0)
+    assert not dH.cpu().float().numpy()[nograd].any()
+    return batch, want
+
+
+SHAPES = [
+    ("qwen_short", 2, 4, 64, 1000, 128),
+    ("qwen_medium", 2, 4, 100, 2600, 192),
+    ("long_reasoning", 4, 4, 40, 1300, 320),
+    ("numerics_stress", 2, 4, 64, 900, 128),
+]
+
+
+@pytest.mark.parametrize("name,P,G,L,V,D", SHAPES)
+@pytest.mark.parametrize("coefs", [(0.001, 1e-4), (0.05, 0.02)], ids=["paper_coefs", "large_coefs"])
+def test_reduced_configs_every_element(name, P, G, L, V, D, coefs):
+    cfg = wl.CONFIGS[name].scaled(n_prompts=P, seq_len=L, vocab=V, group_size=G)
+    if cfg.logits not in ("normal", "normal_boost"):
+        cfg = wl.replace(cfg, logits="normal", logit_std=3.0)
+    run_aux_case(cfg, D, coefs[0], coefs[1], label="%s %dx%dx%d" % (name, P * G * L, V, D))
+
+
+def test_near_one_hot_rows():
+    """Rows whose hidden state points along one weight row, so that one logit stands 40 to 50
+    above the rest: on the sampled token (p_y within 1e-15 of 1: the ln(1 + x) form of l, an
+    entropy of order 1e-14 and gradients that vanish) or on another token (l near -45)."""
+    cfg = wl.CONFIGS["qwen_short"].scaled(n_prompts=2, seq_len=32, vocab=1100, group_size=4)
+    d = 128
+    batch = wl.make_lmhead_batch(cfg, d, device=DEV)
+    N, V = batch["n_tokens"], batch["vocab"]
+    W = batch["weight"].float()
+    g = torch.Generator().manual_seed(4242)
+    other = torch.randint(0, V, (N,), generator=g).to(DEV)
+    target = torch.where(torch.arange(N, device=DEV) % 4 < 2, batch["tokens"], other)   # half on y, a quarter elsewhere
+    wy = W[target]
+    spike = 45.0 * wy / (wy * wy).sum(dim=1, keepdim=True)
+    noise = torch.randn((N, d), generator=g).to(DEV) * 0.05
+    spiked = (torch.arange(N, device=DEV) % 4 != 3)[:, None]
+    batch["hidden"] = torch.where(spiked, spike + noise, batch["hidden"].float()).to(torch.bfloat16).contiguous()
+    run_aux_case(cfg, d, 0.05, 0.02, label="near one-hot", batch=batch)
+
+
+def test_token_weights_denominator_and_grad_scale():
+    cfg = wl.CONFIGS["qwen_short"].scaled(n_prompts=2, seq_len=40, vocab=1500, group_size=4)
+    run_aux_case(cfg, 128, 0.05, 0.02, denom=8.0, grad_scale=2.5, weighted=True, label="weights/denom/scale")
+
+
+def test_zero_coefficients_match_the_plain_head_call_and_rows_without_gradient_stay_zero():
+    cfg = wl.CONFIGS["numerics_stress"].scaled(n_prompts=2, seq_len=48, vocab=700, group_size=4)
+    cfg = wl.replace(cfg, logits="normal", logit_std=3.0)
+    b = wl.make_lmhead_batch(cfg, 128, device=DEV)
+    lp0 = grpo.grpo_lmhead_logprobs_fwd(b["hidden"], b["weight"], b["tokens"], b["mask"])
+    torch.cuda.synchronize()
+    old = wl.make_old_logprobs(cfg, lp0).to(DEV)
+    _, adv = grpo.grpo_group_advantages(b["rewards"], group_size=cfg.group_size, rollout_of_token=b["rollout_of_token"])
+    kw = dict(eps_low=f32(cfg.eps_low), eps_high=f32(cfg.eps_high), delta=f32(cfg.delta))
+    a = grpo.grpo_lmhead_loss_fwd_bwd(b["hidden"], b["weight"], b["tokens"], old, adv, b["mask"], **kw)
+    c = grpo.grpo_lmhead_loss_aux_fwd_bwd(b["hidden"], b["weight"], b["tokens"], old, None, adv, b["mask"], **kw)
+    torch.cuda.synchronize()
+    assert torch.equal(a[2], c[3])                                   # counters
+    assert abs(float(a[0]) - float(c[0][0])) <= 1e-4 * abs(float(a[0])) and float(c[0][2]) == 0.0
+    assert float((a[1] - c[1]).abs().max()) <= TOL_LOGP
+    dHa, dHc = a[3].float(), c[4].float()
+    assert bool(((dHa == 0).all(dim=1) == (dHc == 0).all(dim=1)).all())   # the same rows have no gradient
+    tol = 2.0 * U * dHa.abs().amax() + 1e-12
+    assert float((dHa - dHc).abs().max()) <= tol
+    assert float((a[4] - c[5]).abs().max()) <= 2.0 * U * float(a[4].abs().max()) + 1e-12
+    # run to run: identical bits
+    c2 = grpo.grpo_lmhead_loss_aux_fwd_bwd(b["hidden"], b["weight"], b["tokens"], old, None, adv, b["mask"], **kw)
+    torch.cuda.synchronize()
+    assert all(torch.equal(x, y) for x, y in zip(c, c2) if x is not None)
+
+
+def test_full_size_qwen_short_sampled_rows():
+    """BASELINE configs[1] with a 5120-wide head and the coefficients of section 4.1: log-probs,
+    entropies and dL/dH rows against the oracle on sampled rows, the two scalars that need every
+    row (mean KL, mean entropy) against the library's own per-token outputs summed in fp64, dL/dW
+    through properties that hold at any size."""
+    cfg = wl.CONFIGS["qwen_short"]
+    d = 5120
+    batch = wl.make_lmhead_batch(cfg, d, device=DEV)
+    N, V = batch["n_tokens"], batch["vocab"]
+    T = f32(cfg.temperature)
+    kw = dict(eps_low=f32(cfg.eps_low), eps_high=f32(cfg.eps_high), delta=f32(cfg.delta))
+    klc, enc = 0.001, 1e-4
+    mask_np, tokens_np = batch["mask"].cpu().numpy(), batch["tokens"].cpu().numpy()
+    rng = np.random.default_rng(23)
+    rows = np.sort(np.concatenate([rng.choice(np.flatnonzero(mask_np == 1), 12, replace=False),
+                                   rng.choice(np.flatnonzero(mask_np == 0), 3, replace=False)]))
+    hb, wb = bits(batch["hidden"]), bits(batch["weight"])
+    say("[gpu] full-size lmhead aux: oracle logits for %d sampled rows" % len(rows))
+    z_rows = orc.lmhead_logits(hb, wb, rows=rows)
+    lp_rows = orc.logprobs(z_rows, tokens_np[rows], mask_np[rows], temperature=T)
+    H_rows = orc.entropies(z_rows, mask_np[rows], temperature=T)
+    adv = orc.group_advantages(batch["rewards"].cpu().numpy(), group_size=batch["group_size"])
+    adv_tok = orc.broadcast_advantages(adv, batch["rollout_of_token"].cpu().numpy()).astype(np.float32)
+    lp_g = grpo.grpo_lmhead_logprobs_fwd(batch["hidden"], batch["weight"], batch["tokens"], batch["mask"], T)
+    torch.cuda.synchronize()
+    gen = torch.Generator().manual_seed(78)
+    base = lp_g.cpu().double()
+    base[torch.as_tensor(rows)] = torch.as_tensor(lp_rows)
+    old = (base + (torch.randn(N, generator=gen) * 0.1).clamp(-0.15, 0.15).double()).float()
+    ref = (base + (torch.randn(N, generator=gen) * 0.1).double()).float()
+    M = int(mask_np.sum())
+    say("[gpu] full-size lmhead aux: grpo_lmhead_loss_aux_fwd_bwd N=%d V=%d d=%d" % (N, V, d))
+    loss, lp, ent, counts, dH, dW = grpo.grpo_lmhead_loss_aux_fwd_bwd(
+        batch["hidden"], batch["weight"], batch["tokens"], old.to(DEV), ref.to(DEV),
+        torch.as_tensor(adv_tok, device=DEV), batch["mask"], temperature=T, kl_coef=klc, entropy_coef=enc, **kw)
+    torch.cuda.synchronize()
+    assert int(counts[0]) == M
+    e_lp = np.abs(lp.cpu().numpy().astype(np.float64)[rows] - lp_rows).max()
+    e_h = np.abs(ent.cpu().numpy().astype(np.float64)[rows] - H_rows).max()
+    say("[gpu] full-size lmhead aux: |dl| %.2e |dH_t| %.2e on sampled rows" % (e_lp, e_h))
+    assert e_lp <= TOL_LOGP and e_h <= 2e-4
+    # scalars from the per-token outputs (each checked above on the sample)
+    lpd, entd = lp.cpu().double(), ent.cpu().double()
+    m = torch.as_tensor(mask_np, dtype=torch.float64)
+    dk = ref.double() - lpd
+    kl_mean = float(((torch.exp(dk) - dk - 1) * m).sum() / M)
+    h_mean = float((entd * m).sum() / M)
+    got = loss.cpu().numpy().astype(np.float64)
+    assert abs(got[2] - kl_mean) <= 1e-4 * kl_mean + 1e-9 and abs(got[3] - h_mean) <= 1e-4 * h_mean + 2e-7
+    assert abs(got[0] - (got[1] + klc * got[2] - enc * got[3])) <= 1e-6 * abs(got[0]) + 1e-7
+    obj = orc.aux_objective_from_logprobs(lp_rows, H_rows, old.numpy()[rows], ref.numpy()[rows], adv_tok[rows],
+                                          mask_np[rows], kl_coef=f32(klc), ent_coef=f32(enc), denom=float(M), **kw)
+    G_rows = orc.aux_grad_rows(z_rows, tokens_np[rows], obj["coeff"], obj["ent_coeff"], temperature=T)
+    dH_o = orc.lmhead_grad_hidden(G_rows, wb)
+    Ww_max = float(np.abs(wide(wb[:4096])).max())
+    bound = np.abs(G_rows) @ np.abs(wide(wb))
+    eH = np.abs(dH.cpu().double().numpy()[rows] - dH_o)
+    pmax = np.exp(z_rows.max(axis=1) / T - z_rows[np.arange(len(rows)), tokens_np[rows]] / T + lp_rows)
+    floor = (np.abs(obj["coeff"] / T) * 2.0 ** -22 +
+             (klc * 2.0 ** -22 * np.maximum(np.abs(lp_rows), 1.0) +
+              enc * pmax * np.maximum(H_rows, 1.0) * 2.0 ** -20) / (M * T))[:, None] * Ww_max
+    say("[gpu] full-size lmhead aux: dH err max %.3e (max|dH| %.3e)" % (eH.max(), np.abs(dH_o).max()))
+    assert np.all(eH <= 1.05 * U * (bound + np.abs(dH_o)) + floor)
+    assert np.all(dH.cpu().float().numpy()[rows][mask_np[rows] == 0] == 0.0)
+    inner_W = (dW.double() * batch["weight"].double()).sum().item()
+    inner_H = (dH.double() * batch["hidden"].double()).sum().item()
+    scale = (dW.double().abs() * batch["weight"].double().abs()).sum().item()
+    say("[gpu] full-size lmhead aux: <dW,W> %.6e <dH,H> %.6e (scale %.3e)" % (inner_W, inner_H, scale))
+    assert abs(inner_W - inner_H) <= U * scale
+    col = dW.double().sum(dim=0).abs().max().item()
+    assert col <= U * dW.double().abs().sum(dim=0).max().item()
