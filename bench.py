@@ -112,7 +112,18 @@ def lmhead_leg(grpo, wl, cfg, d_model, dev, stream, reps):
             evs.append((a, e))
         torch.cuda.synchronize()
         return sum(a.elapsed_time(e) for a, e in evs) / reps
+    ref = wl.make_old_logprobs(cfg, lp, seed=cfg.index + 77).to(dev)
+    loss4 = torch.empty(4, dtype=torch.float32, device=dev)
+
+    def fwd_bwd_aux():   # the coefficients of section 4.1
+        grpo.grpo_lmhead_loss_aux_fwd_bwd(b["hidden"], b["weight"], b["tokens"], old, ref, adv_tok, b["mask"],
+                                          cfg.eps_low, cfg.eps_high, cfg.delta, cfg.temperature, 0.001, 1e-4,
+                                          0.0, 1.0, grad_hidden=dH, grad_weight=dW, loss_out=loss4,
+                                          logprobs_out=lp, want_entropy=False, counts_out=counts,
+                                          workspace=ws_b, stream=stream)
     ms_f = timed(fwd)
+    ms_x = timed(fwd_bwd_aux)
+    aux_vals = loss4.cpu().tolist()
     ms_b = timed(fwd_bwd)
     c = counts.cpu().tolist()
     n_unmasked = c[0]
@@ -128,6 +139,11 @@ def lmhead_leg(grpo, wl, cfg, d_model, dev, stream, reps):
             "d_model": d_model, "rows": N, "rows_unmasked": n_unmasked, "rows_with_gradient": n_grad,
             "fwd_ms": ms_f, "fwd_tokens_per_s": N / (ms_f * 1e-3),
             "fwd_bwd_ms": ms_b, "fwd_bwd_tokens_per_s": N / (ms_b * 1e-3), "loss": float(loss.cpu()),
+            "aux": {"note": "grpo_lmhead_loss_aux_fwd_bwd, KL 0.001 and entropy 1e-4: every unmasked row has a "
+                            "gradient", "fwd_bwd_ms": ms_x, "fwd_bwd_tokens_per_s": N / (ms_x * 1e-3),
+                    "tflops": (flops_f + 4.0 * n_unmasked * V * d_model) / (ms_x * 1e-3) / 1e12,
+                    "total": aux_vals[0], "policy": aux_vals[1], "mean_kl": aux_vals[2],
+                    "mean_entropy": aux_vals[3]},
             "roofline": {"bound": "mfma", "achieved": flops_f / (ms_f * 1e-3) / 1e12, "peak": 2500.0,
                          "unit": "TFLOP/s", "frac": flops_f / (ms_f * 1e-3) / 1e12 / 2500.0,
                          "kernel": "lm_gemm_nt (forward: logits + softmax partials)",
