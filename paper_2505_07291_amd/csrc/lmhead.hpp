@@ -44,6 +44,8 @@ constexpr int LM_SLOTS = 5;                          // operand tiles resident i
 constexpr int LM_LPT = LM_BM * LM_CPR / LM_THREADS;  // 16-byte loads per lane and operand tile: 4
 constexpr int LM_LDS_BYTES = LM_SLOTS * LM_TILE_BYTES;
 constexpr int LM_GROUP_M = 8;                        // tile rows that share a sweep along N
+constexpr int LM_GM_BWD = 4;                         // the same for the two gradient products: their A panels (G, G^T)
+                                                     // come from HBM, and a lower group re-reads them less often
 constexpr int LM_SPLIT_MAX = 4;                      // parts the contraction of dL/dH may be cut into
 
 enum { LM_EPI_LSE = 0, LM_EPI_BF16 = 1, LM_EPI_F32 = 2 };
@@ -57,6 +59,7 @@ struct GemmParams {
     const int *K_dev;    // optional: length of the contraction actually present, rounded up to LM_BK
                          // in the kernel (the padding must hold zeros); 0 gives a zero result
     int tiles_n;
+    int group_m;         // tile rows that share a sweep along N (0: LM_GROUP_M)
     // LM_EPI_BF16 / LM_EPI_F32
     void *C;
     long long ldc;
@@ -85,7 +88,7 @@ struct GemmParams {
 // panels and most operand traffic is served by that XCD's L2.  The number of tile rows
 // comes from the device-side row count, so that the live tiles are spread over all XCDs
 // whatever part of the launched grid they are.
-__device__ __forceinline__ bool lm_map_tile(int tiles_m, int tiles_n, int splits, int &tm, int &tn, int &part)
+__device__ __forceinline__ bool lm_map_tile(int tiles_m, int tiles_n, int splits, int group_m, int &tm, int &tn, int &part)
 {
     const int tiles = tiles_m * tiles_n;
     const int total = tiles * splits;
@@ -94,11 +97,11 @@ __device__ __forceinline__ bool lm_map_tile(int tiles_m, int tiles_n, int splits
     if ((int)(blockIdx.x >> 3) >= per_xcd || L >= total) return false;
     part = L / tiles;  // the parts of the contraction one after the other: an XCD stays inside one part
     L -= part * tiles;
-    const int group_tiles = LM_GROUP_M * tiles_n;
+    const int group_tiles = group_m * tiles_n;
     const int grp = L / group_tiles;
     const int in_grp = L - grp * group_tiles;
-    const int rows_here = min(LM_GROUP_M, tiles_m - grp * LM_GROUP_M);
-    tm = grp * LM_GROUP_M + in_grp % rows_here;
+    const int rows_here = min(group_m, tiles_m - grp * group_m);
+    tm = grp * group_m + in_grp % rows_here;
     tn = in_grp / rows_here;
     return true;
 }
@@ -158,7 +161,7 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
         const int tiles_m = (M + LM_BM - 1) / LM_BM;
         if (EPI == LM_EPI_BF16 && p.split_max > 1)
             parts = lm_choose_split(tiles_m * p.tiles_n, K / LM_BK, p.split_max, p.n_cu);
-        if (!lm_map_tile(tiles_m, p.tiles_n, parts, tm, tn, part)) return;  // whole workgroup alike, before any barrier
+        if (!lm_map_tile(tiles_m, p.tiles_n, parts, p.group_m, tm, tn, part)) return;  // whole workgroup alike, before any barrier
     }
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -815,6 +818,7 @@ hipError_t lm_launch_gemm(GemmParams p, hipStream_t st)
         attr_done[dev] = true;
     }
     p.tiles_n = (p.N + LM_BN - 1) / LM_BN;
+    if (p.group_m <= 0) p.group_m = LM_GROUP_M;
     const long long total = (long long)((p.M + LM_BM - 1) / LM_BM) * p.tiles_n *
                             (EPI == LM_EPI_BF16 && p.split_max > 1 ? p.split_max : 1);  // upper bound
     const long long grid = (total + 7) / 8 * 8;
@@ -1056,6 +1060,7 @@ grpo_status lm_impl(bool bwd, bool aux, const void *hidden, int64_t hidden_strid
             gh.C = grad_hidden;
             gh.ldc = grad_hidden_stride;
             gh.c_rows = w.orig2;
+            gh.group_m = LM_GM_BWD;
             // The fp32 logits are no longer needed: their space takes the partial results when the
             // contraction over the vocabulary is split (d_model is a multiple of 4 columns: the
             // partial rows stay 16-byte aligned).
@@ -1083,6 +1088,7 @@ grpo_status lm_impl(bool bwd, bool aux, const void *hidden, int64_t hidden_strid
             gw.C = grad_weight;
             gw.ldc = grad_weight_stride;
             gw.accumulate = accumulate_grad_weight ? 1 : 0;
+            gw.group_m = LM_GM_BWD;
             e = lm_launch_gemm<LM_EPI_F32, false>(gw, st);
             if (e != hipSuccess) return GRPO_ERR_HIP;
         }
