@@ -226,3 +226,29 @@ def lmhead_aux_args(**over):
 ])
 def test_lmhead_aux_loss_rejects_bad_arguments_before_any_launch(over, expect):
     assert grpo.lib().grpo_lmhead_loss_aux_fwd_bwd(*lmhead_aux_args(**over)) == expect
+
+
+def test_product_and_oracle_do_not_know_each_other():
+    """The package imports nothing from oracle/ (and would have nothing to fall back on), the
+    oracle imports nothing from the package, and the library's sources include no oracle file."""
+    import ast
+    import glob
+
+    def imported(path):
+        mods = set()
+        for node in ast.walk(ast.parse(open(path).read())):
+            if isinstance(node, ast.Import):
+                mods.update(a.name.split(".")[0] for a in node.names)
+            elif isinstance(node, ast.ImportFrom) and node.module and node.level == 0:
+                mods.add(node.module.split(".")[0])
+        return mods
+    for f in glob.glob(os.path.join(ROOT, "paper_2505_07291_amd", "*.py")):
+        assert "oracle" not in imported(f), f
+    for f in glob.glob(os.path.join(ROOT, "oracle", "*.py")):
+        assert "paper_2505_07291_amd" not in imported(f), f
+    for f in glob.glob(os.path.join(ROOT, "paper_2505_07291_amd", "csrc", "*")) + \
+            glob.glob(os.path.join(ROOT, "include", "*")):
+        assert "oracle" not in open(f).read().lower(), f
+    for f in glob.glob(os.path.join(ROOT, "oracle", "*.c")):
+        includes = re.findall(r'#\s*include\s*[<"]([^>"]+)[>"]', open(f).read())
+        assert includes and all("grpo" not in i and "hip" not in i for i in includes), (f, includes)
