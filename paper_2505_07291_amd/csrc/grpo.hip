@@ -713,6 +713,25 @@ __device__ __forceinline__ void order_after(unsigned &off, X &x)
 }
 
 
+// How many gradient slots of a row wait in LDS before they are stored (see the kernel): as
+// many as an equal share of 144 KB of the CU's LDS holds for each of the workgroups that run
+// on a CU together (a slot is 16 bytes per lane), at most all of them.
+#ifndef GRPO_ROW_STASH_KB
+#define GRPO_ROW_STASH_KB 144
+#endif
+#ifndef GRPO_ROW_LOADFIRST
+#define GRPO_ROW_LOADFIRST 1  // per slot: the next row's load in front of this row's store
+#endif
+constexpr int row_blocks_per_cu(int block, int nv)
+{
+    return block == 1024 ? 1 : block == 512 ? 2 : nv >= 16 ? 4 : 8;
+}
+constexpr int row_stash_slots(int block, int nv)
+{
+    const int fit = GRPO_ROW_STASH_KB * 1024 / row_blocks_per_cu(block, nv) / (block * 16);
+    return fit < nv ? fit : nv;
+}
+
 // ---------------------------------------------------------------------------
 // Register-resident row kernel: requires ceil(vocab / EPV) <= BLOCK * NV.
 // One workgroup per row at a time, rows strided over a persistent grid.
@@ -723,6 +742,15 @@ __global__ void __launch_bounds__(BLOCK, 4) grpo_rows_cached(RowParams p)  // 4 
     constexpr int EPV = Elem<DT>::EPV;
     constexpr int BYTES = Elem<DT>::BYTES;
     constexpr unsigned SLAB = BLOCK * 16u;  // bytes one pass of the workgroup covers
+    // Gradient vectors of the first STASH slots wait in LDS (each lane its own 16 bytes per
+    // slot, no sharing) and are stored after the loop over the slots, so that the next row's
+    // loads stand in front of them in the memory queue.  Loads and stores retire in issue
+    // order: with every store in front of a load the last load returns when everything is
+    // done, and the row statistics that follow run with nothing in flight; with a third of the
+    // stores behind the loads they drain during that arithmetic (what a row whose gradient is
+    // zero gets for free: it issues all loads, then all stores).
+    constexpr int STASH = row_stash_slots(BLOCK, NV);
+    extern __shared__ __attribute__((aligned(16))) char row_stash[];
     __shared__ float lds_max[BLOCK / 64];
     __shared__ float lds_sum[BLOCK / 64];
     __shared__ float lds_sumw[BLOCK / 64];
@@ -913,9 +941,18 @@ __global__ void __launch_bounds__(BLOCK, 4) grpo_rows_cached(RowParams p)  // 4 
                         packed = pack<DT>(g);
                     }
                     order_after(noff, packed);
-                    if (v < nvec_full) st16(grow + (size_t)i * SLAB + toff, packed);
+#if GRPO_ROW_LOADFIRST
+                    if (i < STASH) *(u32x4 *)(row_stash + (size_t)i * SLAB + toff) = packed;
+                    if (has_next) fetch_slot(zrow_next, i);
+                    if (i >= STASH && v < nvec_full) st16(grow + (size_t)i * SLAB + toff, packed);
+#else
+                    if (i < STASH)
+                        *(u32x4 *)(row_stash + (size_t)i * SLAB + toff) = packed;
+                    else if (v < nvec_full)
+                        st16(grow + (size_t)i * SLAB + toff, packed);
 #if GRPO_BWD_INTERLEAVE
                     if (has_next) fetch_slot(zrow_next, i);
+#endif
 #endif
                     VECTOR_FENCE();
                 }
@@ -936,6 +973,11 @@ __global__ void __launch_bounds__(BLOCK, 4) grpo_rows_cached(RowParams p)  // 4 
                 }
 #endif
                 if (has_next) fetch_rest(zrow_next, y_next);
+#pragma unroll
+                for (int i = 0; i < STASH; ++i) {
+                    const u32x4 packed = *(const u32x4 *)(row_stash + (size_t)i * SLAB + toff);
+                    if (i * BLOCK + tid < nvec_full) st16(grow + (size_t)i * SLAB + toff, packed);
+                }
             }
         }
         row = next;
@@ -1317,7 +1359,17 @@ void launch_cached(const RowParams &p, int blocks_per_cu, hipStream_t st)
 {
     long long grid = (long long)cu_count() * blocks_per_cu;
     if (grid > p.n_tokens) grid = p.n_tokens;
-    hipLaunchKernelGGL((grpo_rows_cached<DT, BLOCK, NV, AUX, TAIL>), dim3((unsigned)grid), dim3(BLOCK), 0,
+    constexpr unsigned lds_bytes = (unsigned)row_stash_slots(BLOCK, NV) * BLOCK * 16u;
+    if constexpr (lds_bytes > 0) {
+        static bool attr_done[64] = {false};
+        int dev = 0;
+        if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64 && !attr_done[dev]) {
+            if (hipFuncSetAttribute((const void *)grpo_rows_cached<DT, BLOCK, NV, AUX, TAIL>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) == hipSuccess)
+                attr_done[dev] = true;
+        }
+    }
+    hipLaunchKernelGGL((grpo_rows_cached<DT, BLOCK, NV, AUX, TAIL>), dim3((unsigned)grid), dim3(BLOCK), lds_bytes,
                        st, p);
 }
 
@@ -1338,17 +1390,17 @@ void launch_rows(const RowParams &p_in, hipStream_t st)
     // (queue, three barriers, scalar arithmetic) is hidden.  Only rows too wide for that
     // use one 1024-lane workgroup per CU.
     if (nvec <= 256 * 1)
-        launch_cached<DT, 256, 1, AUX, true>(p, 8, st);
+        launch_cached<DT, 256, 1, AUX, true>(p, row_blocks_per_cu(256, 1), st);
     else if (nvec <= 256 * 4)
-        launch_cached<DT, 256, 4, AUX, true>(p, 8, st);
+        launch_cached<DT, 256, 4, AUX, true>(p, row_blocks_per_cu(256, 4), st);
     else if (nvec <= 256 * 16)
-        launch_cached<DT, 256, 16, AUX, true>(p, 4, st);
+        launch_cached<DT, 256, 16, AUX, true>(p, row_blocks_per_cu(256, 16), st);
     else if (nvec <= 512 * 16)
-        launch_cached<DT, 512, 16, AUX, true>(p, 2, st);
+        launch_cached<DT, 512, 16, AUX, true>(p, row_blocks_per_cu(512, 16), st);
     else if (nvec <= 1024 * 10)
-        launch_cached<DT, 1024, 10, AUX, true>(p, 1, st);
+        launch_cached<DT, 1024, 10, AUX, true>(p, row_blocks_per_cu(1024, 10), st);
     else if (nvec <= 1024 * 19 && !ragged)
-        launch_cached<DT, 1024, 19, AUX, false>(p, 1, st);
+        launch_cached<DT, 1024, 19, AUX, false>(p, row_blocks_per_cu(1024, 19), st);
     else {
         long long grid = (long long)cu_count() * 2;
         if (grid > p.n_tokens) grid = p.n_tokens;
