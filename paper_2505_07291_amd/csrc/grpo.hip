@@ -713,19 +713,26 @@ __device__ __forceinline__ void order_after(unsigned &off, X &x)
 }
 
 
-// How many gradient slots of a row wait in LDS before they are stored (see the kernel): as
-// many as an equal share of 144 KB of the CU's LDS holds for each of the workgroups that run
-// on a CU together (a slot is 16 bytes per lane), at most all of them.
+// Workgroups that share a CU, by instantiation.
+constexpr int row_blocks_per_cu(int block, int nv)
+{
+    return block == 1024 || nv > 19 ? 1 : block == 512 ? 2 : nv >= 16 ? 4 : 8;
+}
+// How many gradient slots of a row wait before they are stored (see the kernel).  In LDS: as
+// many as an equal share of 144 KB of the CU's LDS holds for each workgroup on the CU (a slot
+// is 16 bytes per lane), at most all of them.  In registers: only the widest instantiation,
+// eight wavefronts with 256 registers each, of which the row takes 152; 16 slots is the most
+// the compiler fits without spilling.
 #ifndef GRPO_ROW_STASH_KB
 #define GRPO_ROW_STASH_KB 144
+#endif
+#ifndef GRPO_ROW_RSTASH
+#define GRPO_ROW_RSTASH 16
 #endif
 #ifndef GRPO_ROW_LOADFIRST
 #define GRPO_ROW_LOADFIRST 1  // per slot: the next row's load in front of this row's store
 #endif
-constexpr int row_blocks_per_cu(int block, int nv)
-{
-    return block == 1024 ? 1 : block == 512 ? 2 : nv >= 16 ? 4 : 8;
-}
+constexpr int row_reg_stash_slots(int block, int nv) { return nv > 19 ? GRPO_ROW_RSTASH : 0; }
 constexpr int row_stash_slots(int block, int nv)
 {
     const int fit = GRPO_ROW_STASH_KB * 1024 / row_blocks_per_cu(block, nv) / (block * 16);
@@ -737,19 +744,22 @@ constexpr int row_stash_slots(int block, int nv)
 // One workgroup per row at a time, rows strided over a persistent grid.
 // ---------------------------------------------------------------------------
 template <grpo_dtype DT, int BLOCK, int NV, bool AUX, bool TAIL>
-__global__ void __launch_bounds__(BLOCK, 4) grpo_rows_cached(RowParams p)  // 4 waves per SIMD: 128 VGPRs
+// 4 wavefronts per SIMD and 128 registers each; the widest instantiation 2 and 256
+__global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowParams p)
 {
     constexpr int EPV = Elem<DT>::EPV;
     constexpr int BYTES = Elem<DT>::BYTES;
     constexpr unsigned SLAB = BLOCK * 16u;  // bytes one pass of the workgroup covers
     // Gradient vectors of the first STASH slots wait in LDS (each lane its own 16 bytes per
-    // slot, no sharing) and are stored after the loop over the slots, so that the next row's
-    // loads stand in front of them in the memory queue.  Loads and stores retire in issue
-    // order: with every store in front of a load the last load returns when everything is
-    // done, and the row statistics that follow run with nothing in flight; with a third of the
-    // stores behind the loads they drain during that arithmetic (what a row whose gradient is
-    // zero gets for free: it issues all loads, then all stores).
+    // slot, no sharing), those of the next RSTASH slots in registers, and all of them are
+    // stored after the loop over the slots, so that the next row's loads stand in front of
+    // them in the memory queue.  Loads and stores retire in issue order: with a store in
+    // front of every load the last load returns when everything is done, and the row
+    // statistics that follow run with nothing in flight; with the stores behind the loads
+    // they drain during that arithmetic (what a row whose gradient is zero gets for free: it
+    // issues all loads, then all stores).
     constexpr int STASH = row_stash_slots(BLOCK, NV);
+    constexpr int RSTASH = row_reg_stash_slots(BLOCK, NV);  // further slots that wait in registers
     extern __shared__ __attribute__((aligned(16))) char row_stash[];
     __shared__ float lds_max[BLOCK / 64];
     __shared__ float lds_sum[BLOCK / 64];
@@ -928,6 +938,7 @@ __global__ void __launch_bounds__(BLOCK, 4) grpo_rows_cached(RowParams p)  // 4 
             } else {
                 const float q = -sc.c * p.inv_T;
                 const float gy = (sc.c * p.inv_T) * (sc.s_excl / sc.s) + (AUX ? sc.gy_ent : 0.f);
+                u32x4 rstash[RSTASH > 0 ? RSTASH : 1];
 #pragma unroll
                 for (int i = 0; i < NV; ++i) {
                     const int v = i * BLOCK + tid;
@@ -944,7 +955,8 @@ __global__ void __launch_bounds__(BLOCK, 4) grpo_rows_cached(RowParams p)  // 4 
 #if GRPO_ROW_LOADFIRST
                     if (i < STASH) *(u32x4 *)(row_stash + (size_t)i * SLAB + toff) = packed;
                     if (has_next) fetch_slot(zrow_next, i);
-                    if (i >= STASH && v < nvec_full) st16(grow + (size_t)i * SLAB + toff, packed);
+                    if (i >= STASH && i < STASH + RSTASH) rstash[i - STASH < 0 ? 0 : i - STASH] = packed;
+                    if (i >= STASH + RSTASH && v < nvec_full) st16(grow + (size_t)i * SLAB + toff, packed);
 #else
                     if (i < STASH)
                         *(u32x4 *)(row_stash + (size_t)i * SLAB + toff) = packed;
@@ -978,6 +990,9 @@ __global__ void __launch_bounds__(BLOCK, 4) grpo_rows_cached(RowParams p)  // 4 
                     const u32x4 packed = *(const u32x4 *)(row_stash + (size_t)i * SLAB + toff);
                     if (i * BLOCK + tid < nvec_full) st16(grow + (size_t)i * SLAB + toff, packed);
                 }
+#pragma unroll
+                for (int i = STASH; i < STASH + RSTASH; ++i)
+                    if (i * BLOCK + tid < nvec_full) st16(grow + (size_t)i * SLAB + toff, rstash[i - STASH]);
             }
         }
         row = next;
@@ -1388,7 +1403,9 @@ void launch_rows(const RowParams &p_in, hipStream_t st)
     // Narrow rows take small workgroups, several per CU (each around 16 slots per lane): the
     // phases of different rows then overlap inside a CU and the per-row bookkeeping
     // (queue, three barriers, scalar arithmetic) is hidden.  Only rows too wide for that
-    // use one 1024-lane workgroup per CU.
+    // use one workgroup per CU: 1024 lanes with up to 10 slots, and for the widest rows 512
+    // lanes with 38 slots and twice the registers, the spare ones holding gradient vectors
+    // back behind the next row's loads.
     if (nvec <= 256 * 1)
         launch_cached<DT, 256, 1, AUX, true>(p, row_blocks_per_cu(256, 1), st);
     else if (nvec <= 256 * 4)
@@ -1399,8 +1416,8 @@ void launch_rows(const RowParams &p_in, hipStream_t st)
         launch_cached<DT, 512, 16, AUX, true>(p, row_blocks_per_cu(512, 16), st);
     else if (nvec <= 1024 * 10)
         launch_cached<DT, 1024, 10, AUX, true>(p, row_blocks_per_cu(1024, 10), st);
-    else if (nvec <= 1024 * 19 && !ragged)
-        launch_cached<DT, 1024, 19, AUX, false>(p, row_blocks_per_cu(1024, 19), st);
+    else if (nvec <= 512 * 38 && !ragged)
+        launch_cached<DT, 512, 38, AUX, false>(p, row_blocks_per_cu(512, 38), st);
     else {
         long long grid = (long long)cu_count() * 2;
         if (grid > p.n_tokens) grid = p.n_tokens;
