@@ -93,12 +93,7 @@ struct Elem<GRPO_F32> {
 // Tunables, with the settings measured best on MI355X (5 GB to 20 GB of logits):
 //  - non-temporal loads and stores for the two row streams: every byte is touched
 //    once, so nothing is gained by keeping it in L2 / Infinity Cache
-//    (log-probs pass 5.5 -> 6.3 TB/s, mixed batches about 4% faster);
-//  - the next row's loads are issued slot by slot behind the gradient stores of the
-//    current row rather than in one burst after them (within noise of each other).
-#ifndef GRPO_BWD_INTERLEAVE
-#define GRPO_BWD_INTERLEAVE 1
-#endif
+//    (log-probs pass 5.5 -> 6.3 TB/s, mixed batches about 4% faster).
 #ifndef GRPO_NT_LOAD
 #define GRPO_NT_LOAD 1
 #endif
@@ -729,9 +724,6 @@ constexpr int row_blocks_per_cu(int block, int nv)
 #ifndef GRPO_ROW_RSTASH
 #define GRPO_ROW_RSTASH 16
 #endif
-#ifndef GRPO_ROW_LOADFIRST
-#define GRPO_ROW_LOADFIRST 1  // per slot: the next row's load in front of this row's store
-#endif
 constexpr int row_reg_stash_slots(int block, int nv) { return nv > 19 ? GRPO_ROW_RSTASH : 0; }
 constexpr int row_stash_slots(int block, int nv)
 {
@@ -952,20 +944,12 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
                         packed = pack<DT>(g);
                     }
                     order_after(noff, packed);
-#if GRPO_ROW_LOADFIRST
+                    // the slot's gradient waits (LDS, then registers) or, for the last slots, is
+                    // stored at once, but in every case behind the next row's load into the slot
                     if (i < STASH) *(u32x4 *)(row_stash + (size_t)i * SLAB + toff) = packed;
                     if (has_next) fetch_slot(zrow_next, i);
                     if (i >= STASH && i < STASH + RSTASH) rstash[i - STASH < 0 ? 0 : i - STASH] = packed;
                     if (i >= STASH + RSTASH && v < nvec_full) st16(grow + (size_t)i * SLAB + toff, packed);
-#else
-                    if (i < STASH)
-                        *(u32x4 *)(row_stash + (size_t)i * SLAB + toff) = packed;
-                    else if (v < nvec_full)
-                        st16(grow + (size_t)i * SLAB + toff, packed);
-#if GRPO_BWD_INTERLEAVE
-                    if (has_next) fetch_slot(zrow_next, i);
-#endif
-#endif
                     VECTOR_FENCE();
                 }
                 if (tail_wave && tid == 0) {
@@ -978,12 +962,6 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
                     }
                     store_vec<DT>(grow, nvec_full, nvec_full, tail, g);
                 }
-#if !GRPO_BWD_INTERLEAVE
-                if (has_next) {
-#pragma unroll
-                    for (int i = 0; i < NV; ++i) fetch_slot(zrow_next, i);
-                }
-#endif
                 if (has_next) fetch_rest(zrow_next, y_next);
 #pragma unroll
                 for (int i = 0; i < STASH; ++i) {
