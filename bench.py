@@ -337,7 +337,15 @@ def main():
                          "frac": N * row_bytes / (fwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS},
     }
     if not args.no_lmhead and cfg.logits in ("normal", "normal_boost") and cfg.dtype == "bf16":
-        out["lmhead"] = lmhead_leg(grpo, wl, cfg, args.d_model, dev, stream, max(3, args.steps // 6))
+        # the leg needs its own operands, gradients and two workspaces next to the batch
+        need = (grpo.grpo_lmhead_workspace_bytes(N, V, args.d_model, True) +
+                grpo.grpo_lmhead_workspace_bytes(N, V, args.d_model, False) +
+                6 * V * args.d_model + 4 * N * args.d_model)
+        free = torch.cuda.mem_get_info()[0]
+        if need < 0.9 * free:
+            out["lmhead"] = lmhead_leg(grpo, wl, cfg, args.d_model, dev, stream, max(3, args.steps // 6))
+        else:
+            out["lmhead"] = {"skipped": "needs %.0f GB of device memory, %.0f GB free" % (need / 1e9, free / 1e9)}
     if not args.no_cpu_baseline:
         log("[bench] timing the fp64 oracle on a sample of the batch (about 12 s)")
         step()
