@@ -11,6 +11,7 @@
 // traffic per row instead of 2 reads + 1 write.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdint>
 
@@ -725,6 +726,13 @@ constexpr int row_blocks_per_cu(int block, int nv)
 #define GRPO_ROW_RSTASH 16
 #endif
 constexpr int row_reg_stash_slots(int block, int nv) { return nv > 19 ? GRPO_ROW_RSTASH : 0; }
+// Rows wider than 38 slots of 512 lanes: this many slots in registers and this many (8 KB each)
+// in LDS, 544 KB together.
+#ifndef GRPO_WIDE_REG_SLOTS
+#define GRPO_WIDE_REG_SLOTS 50
+#endif
+constexpr int kWideRegSlots = GRPO_WIDE_REG_SLOTS;
+constexpr int kWideLdsSlots = 18;
 constexpr int row_stash_slots(int block, int nv)
 {
     const int fit = GRPO_ROW_STASH_KB * 1024 / row_blocks_per_cu(block, nv) / (block * 16);
@@ -732,16 +740,21 @@ constexpr int row_stash_slots(int block, int nv)
 }
 
 // ---------------------------------------------------------------------------
-// Register-resident row kernel: requires ceil(vocab / EPV) <= BLOCK * NV.
+// Register-resident row kernel: requires ceil(vocab / EPV) <= BLOCK * (NV + NL).
 // One workgroup per row at a time, rows strided over a persistent grid.
+// NL > 0: the row is wider than the registers hold and its last NL slots live in LDS, which
+// the loads fill directly (buffer loads with LDS as their target); no gradient waits then.
+// SKIP: slots wholly past the end of the row are skipped (one scalar branch per slot and pass),
+// for vocabularies well below the instantiation's width.
 // ---------------------------------------------------------------------------
-template <grpo_dtype DT, int BLOCK, int NV, bool AUX, bool TAIL>
-// 4 wavefronts per SIMD and 128 registers each; the widest instantiation 2 and 256
+template <grpo_dtype DT, int BLOCK, int NV, bool AUX, bool TAIL, int NL = 0, bool SKIP = false>
+// 4 wavefronts per SIMD and 128 registers each; the widest instantiations 2 and 256
 __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowParams p)
 {
     constexpr int EPV = Elem<DT>::EPV;
     constexpr int BYTES = Elem<DT>::BYTES;
     constexpr unsigned SLAB = BLOCK * 16u;  // bytes one pass of the workgroup covers
+    static_assert(NL == 0 || !TAIL, "LDS-resident slots come without the ragged-tail slot");
     // Gradient vectors of the first STASH slots wait in LDS (each lane its own 16 bytes per
     // slot, no sharing), those of the next RSTASH slots in registers, and all of them are
     // stored after the loop over the slots, so that the next row's loads stand in front of
@@ -750,8 +763,9 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
     // statistics that follow run with nothing in flight; with the stores behind the loads
     // they drain during that arithmetic (what a row whose gradient is zero gets for free: it
     // issues all loads, then all stores).
-    constexpr int STASH = row_stash_slots(BLOCK, NV);
-    constexpr int RSTASH = row_reg_stash_slots(BLOCK, NV);  // further slots that wait in registers
+    constexpr int STASH = NL > 0 ? 0 : row_stash_slots(BLOCK, NV);
+    // further slots that wait in registers (the branches of SKIP cost a few registers)
+    constexpr int RSTASH = NL > 0 ? 0 : row_reg_stash_slots(BLOCK, NV) - (SKIP ? 4 : 0);
     extern __shared__ __attribute__((aligned(16))) char row_stash[];
     __shared__ float lds_max[BLOCK / 64];
     __shared__ float lds_sum[BLOCK / 64];
@@ -767,6 +781,8 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
     // (The widest instantiation has no registers to spare for that slot and is built
     // without it; ragged rows of that width take the streaming kernel.)
     const bool tail_wave = TAIL && tail != 0 && tid < 64;
+    // slot i holds something of this row (always true without SKIP); uniform
+    auto used = [&](int i) { return !SKIP || i * BLOCK < nvec_full; };
 
     // ---- which row next ----
     // With a workspace (objective + gradient) rows are handed out through a counter in
@@ -835,6 +851,41 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
     auto fetch_slot = [&](const char *zrow, int i) {
         if (i * BLOCK + tid < nvec_full) buf[i] = ld16(zrow + (size_t)i * SLAB + noff);
     };
+    // LDS-resident slot j (slot NV + j of the row): lane tid owns the 16 bytes at j * SLAB + toff,
+    // which is also where the load puts them (wavefront base in M0, 16 bytes per lane).  Lanes
+    // past the end of the row load nothing and read their piece as -inf.
+    const int wave_lds = __builtin_amdgcn_readfirstlane(tid >> 6) * 1024;
+    auto fetch_lds_slot = [&](const char *zrow, int j) {
+        if constexpr (NL > 0) {
+            if ((NV + j) * BLOCK + tid < nvec_full) {
+                const __amdgpu_buffer_rsrc_t rsrc =
+                    __builtin_amdgcn_make_buffer_rsrc((void *)zrow, 0, -1, 0x00020000);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    rsrc, (__attribute__((address_space(3))) void *)(row_stash + (size_t)j * SLAB + wave_lds), 16,
+                    (int)((unsigned)(NV + j) * SLAB + noff), 0, 0, GRPO_NT_LOAD ? 2 : 0);
+            }
+        }
+    };
+    auto lds_slot = [&](int j, int vy_, int ey_) -> u32x4 {
+        u32x4 z = *(const u32x4 *)(row_stash + (size_t)j * SLAB + toff);
+        const int v = (NV + j) * BLOCK + tid;
+        if (v >= nvec_full) z = neg_inf_vec<DT>();
+        if (v == vy_) set_neg_inf<DT>(z, ey_);  // the sampled token's logit stays out of the sums
+        return z;
+    };
+    // every load of the row has landed (they retire in order, the LDS-bound ones last)
+    auto lds_slots_landed = [&]() {
+        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto fetch_all = [&](const char *zrow) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i)
+            if (used(i)) fetch_slot(zrow, i);
+#pragma unroll
+        for (int j = 0; j < NL; ++j)
+            if (used(NV + j)) fetch_lds_slot(zrow, j);
+    };
     auto fetch_rest = [&](const char *zrow, long long y) {
         if (tail_wave && tid == 0) tbuf = load_vec<DT>(zrow, nvec_full, nvec_full, tail);
         zy = load_elem<DT>(zrow, y);
@@ -844,8 +895,7 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
     long long row = acquire(y);
     if (row < p.n_tokens) {
         const char *zrow = (const char *)p.logits + row * p.row_stride * BYTES;
-#pragma unroll
-        for (int i = 0; i < NV; ++i) fetch_slot(zrow, i);
+        fetch_all(zrow);
         fetch_rest(zrow, y);
     }
 
@@ -873,9 +923,20 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
         float mx = -INFINITY;
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
+            if (!used(i)) continue;
             forget(buf[i]);
             mx = fmaxf(mx, vec_max_ref<DT, AUX>(buf[i]));
             VECTOR_FENCE();
+        }
+        if constexpr (NL > 0) {
+            if (used(NV)) lds_slots_landed();
+#pragma unroll
+            for (int j = 0; j < NL; ++j) {
+                if (!used(NV + j)) continue;
+                const u32x4 z = lds_slot(j, vy, ey);
+                mx = fmaxf(mx, vec_max_ref<DT, AUX>(z));
+                VECTOR_FENCE();
+            }
         }
         if (tail_wave) mx = fmaxf(mx, vec_max_ref<DT, AUX>(tbuf));
         mx = fmaxf(block_max<BLOCK>(mx, lds_max), zy);
@@ -886,6 +947,7 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
         float acc = 0.f, accw = 0.f;
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
+            if (!used(i)) continue;
             forget(buf[i]);
             if constexpr (AUX)
                 acc += exp_sum_vec_aux<DT>(buf[i], p.k, mx, accw);
@@ -894,6 +956,20 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
             if (!p.bwd && has_next) {
                 order_after(noff, acc);
                 fetch_slot(zrow_next, i);
+            }
+            VECTOR_FENCE();
+        }
+#pragma unroll
+        for (int j = 0; j < NL; ++j) {
+            if (!used(NV + j)) continue;
+            u32x4 z = lds_slot(j, vy, ey);
+            if constexpr (AUX)
+                acc += exp_sum_vec_aux<DT>(z, p.k, mx, accw);
+            else
+                acc += exp_sum_vec<DT>(z, p.k, mk);
+            if (!p.bwd && has_next) {
+                order_after(noff, acc);  // the slot has been read: its refill may start
+                fetch_lds_slot(zrow_next, j);
             }
             VECTOR_FENCE();
         }
@@ -922,8 +998,7 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
             if (sc.c == 0.f && (!AUX || sc.b == 0.f)) {
                 // the gradient of this row is cut: fetch the next row, then zero-fill
                 if (has_next) {
-#pragma unroll
-                    for (int i = 0; i < NV; ++i) fetch_slot(zrow_next, i);
+                    fetch_all(zrow_next);
                     fetch_rest(zrow_next, y_next);
                 }
                 zero_row<DT, BLOCK>(grow, nvec_full, tail, tid);
@@ -933,6 +1008,7 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
                 u32x4 rstash[RSTASH > 0 ? RSTASH : 1];
 #pragma unroll
                 for (int i = 0; i < NV; ++i) {
+                    if (!used(i)) continue;
                     const int v = i * BLOCK + tid;
                     forget(buf[i]);
                     u32x4 packed;
@@ -950,6 +1026,24 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
                     if (has_next) fetch_slot(zrow_next, i);
                     if (i >= STASH && i < STASH + RSTASH) rstash[i - STASH < 0 ? 0 : i - STASH] = packed;
                     if (i >= STASH + RSTASH && v < nvec_full) st16(grow + (size_t)i * SLAB + toff, packed);
+                    VECTOR_FENCE();
+                }
+#pragma unroll
+                for (int j = 0; j < NL; ++j) {
+                    if (!used(NV + j)) continue;
+                    const int v = (NV + j) * BLOCK + tid;
+                    u32x4 z = lds_slot(j, -1, 0);
+                    u32x4 packed;
+                    if constexpr (AUX) {
+                        packed = grad_vec_aux<DT>(z, p.k, sc.mx, sc.log2s, sc.q2, sc.bq, v == vy, ey, gy);
+                    } else {
+                        float g[EPV];
+                        grad_vec<DT>(z, p.k, sc.shift, q, v == vy, ey, gy, g);
+                        packed = pack<DT>(g);
+                    }
+                    order_after(noff, packed);  // the slot has been read: its refill may start
+                    if (has_next) fetch_lds_slot(zrow_next, j);
+                    if (v < nvec_full) st16(grow + (size_t)(NV + j) * SLAB + toff, packed);
                     VECTOR_FENCE();
                 }
                 if (tail_wave && tid == 0) {
@@ -1335,35 +1429,36 @@ __global__ void __launch_bounds__(256) grpo_packed_stamp(const long long *cu, lo
 
 int cu_count()
 {
-    static int cached[64] = {0};
+    static std::atomic<int> cached[64];          // zero-initialised; host threads may race here
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-    if (cached[dev] == 0) {
-        int n = 0;
+    int n = cached[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
             n = 256;
-        cached[dev] = n;
+        cached[dev].store(n, std::memory_order_relaxed);
     }
-    return cached[dev];
+    return n;
 }
 
-template <grpo_dtype DT, int BLOCK, int NV, bool AUX, bool TAIL>
+template <grpo_dtype DT, int BLOCK, int NV, bool AUX, bool TAIL, int NL = 0, bool SKIP = false>
 void launch_cached(const RowParams &p, int blocks_per_cu, hipStream_t st)
 {
     long long grid = (long long)cu_count() * blocks_per_cu;
     if (grid > p.n_tokens) grid = p.n_tokens;
-    constexpr unsigned lds_bytes = (unsigned)row_stash_slots(BLOCK, NV) * BLOCK * 16u;
+    // dynamic LDS: the waiting gradient slots, or the LDS-resident part of the row
+    constexpr unsigned lds_bytes = (unsigned)(NL > 0 ? NL : row_stash_slots(BLOCK, NV)) * BLOCK * 16u;
     if constexpr (lds_bytes > 0) {
-        static bool attr_done[64] = {false};
+        static std::atomic<bool> attr_done[64];  // setting the attribute twice is harmless
         int dev = 0;
-        if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64 && !attr_done[dev]) {
-            if (hipFuncSetAttribute((const void *)grpo_rows_cached<DT, BLOCK, NV, AUX, TAIL>,
+        if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64 && !attr_done[dev].load()) {
+            if (hipFuncSetAttribute((const void *)grpo_rows_cached<DT, BLOCK, NV, AUX, TAIL, NL, SKIP>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) == hipSuccess)
-                attr_done[dev] = true;
+                attr_done[dev].store(true);
         }
     }
-    hipLaunchKernelGGL((grpo_rows_cached<DT, BLOCK, NV, AUX, TAIL>), dim3((unsigned)grid), dim3(BLOCK), lds_bytes,
-                       st, p);
+    hipLaunchKernelGGL((grpo_rows_cached<DT, BLOCK, NV, AUX, TAIL, NL, SKIP>), dim3((unsigned)grid), dim3(BLOCK),
+                       lds_bytes, st, p);
 }
 
 template <grpo_dtype DT, bool AUX>
@@ -1394,8 +1489,15 @@ void launch_rows(const RowParams &p_in, hipStream_t st)
         launch_cached<DT, 512, 16, AUX, true>(p, row_blocks_per_cu(512, 16), st);
     else if (nvec <= 1024 * 10)
         launch_cached<DT, 1024, 10, AUX, true>(p, row_blocks_per_cu(1024, 10), st);
-    else if (nvec <= 512 * 38 && !ragged)
-        launch_cached<DT, 512, 38, AUX, false>(p, row_blocks_per_cu(512, 38), st);
+    else if (nvec <= 512 * 38 && !ragged) {
+        if (nvec > 512 * 32)
+            launch_cached<DT, 512, 38, AUX, false>(p, row_blocks_per_cu(512, 38), st);
+        else  // well below the width: the empty slots are skipped
+            launch_cached<DT, 512, 38, AUX, false, 0, true>(p, row_blocks_per_cu(512, 38), st);
+    } else if (nvec <= 512 * (kWideRegSlots - (AUX ? 2 : 0) + kWideLdsSlots) && !ragged)
+        // wider than the registers: the last slots of the row live in LDS (the auxiliary terms
+        // take two slots' worth of registers for themselves)
+        launch_cached<DT, 512, kWideRegSlots - (AUX ? 2 : 0), AUX, false, kWideLdsSlots, true>(p, 1, st);
     else {
         long long grid = (long long)cu_count() * 2;
         if (grid > p.n_tokens) grid = p.n_tokens;

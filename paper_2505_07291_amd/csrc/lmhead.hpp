@@ -807,15 +807,15 @@ __global__ void __launch_bounds__(256) lm_zero(T *out, long long rows, long long
 template <int EPI, bool STORE_Z, bool AUX = false>
 hipError_t lm_launch_gemm(GemmParams p, hipStream_t st)
 {
-    static bool attr_done[64] = {false};
+    static std::atomic<bool> attr_done[64];      // setting the attribute twice is harmless
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
-    if (dev >= 0 && dev < 64 && !attr_done[dev]) {
+    if (dev >= 0 && dev < 64 && !attr_done[dev].load()) {
         e = hipFuncSetAttribute((const void *)lm_gemm_nt<EPI, STORE_Z, AUX>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, LM_LDS_BYTES);
         if (e != hipSuccess) return e;
-        attr_done[dev] = true;
+        attr_done[dev].store(true);
     }
     p.tiles_n = (p.N + LM_BN - 1) / LM_BN;
     if (p.group_m <= 0) p.group_m = LM_GROUP_M;

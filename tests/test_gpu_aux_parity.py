@@ -126,8 +126,18 @@ def test_aux_with_zero_coefficients_equals_the_plain_objective():
                                                 ("bf16", 152069, 152072), ("bf16", 200003, 200008),
                                                 ("f32", 1000, 1004), ("f32", 100003, 100004)])
 def test_aux_ragged_shapes(dtype, vocab, stride):
-    N = 29
-    say("\n[case] aux ragged dtype=%s V=%d stride=%d" % (dtype, vocab, stride))
+    run_aux_shape_case(dtype, vocab, stride, 29)
+
+
+@pytest.mark.parametrize("vocab,rows", [(100352, 420), (262144, 420), (270336, 300)])
+def test_aux_wide_rows_several_per_workgroup(vocab, rows):
+    """Rows that leave register slots empty, and rows whose last slots live in LDS, with more rows
+    than workgroups; every element compared."""
+    run_aux_shape_case("bf16", vocab, vocab, rows)
+
+
+def run_aux_shape_case(dtype, vocab, stride, N):
+    say("\n[case] aux shape dtype=%s V=%d stride=%d N=%d" % (dtype, vocab, stride, N))
     g = torch.Generator().manual_seed(vocab * 3 + 1)
     dt = torch.bfloat16 if dtype == "bf16" else torch.float32
     store = torch.full((N, stride), 7.0, dtype=dt)

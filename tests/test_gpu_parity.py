@@ -152,13 +152,8 @@ RAGGED = [
 ]
 
 
-@pytest.mark.parametrize("dtype,vocab,stride", RAGGED)
-def test_ragged_shapes_and_strides(dtype, vocab, stride):
-    """Row widths that end inside a 16-byte vector, padded row pitches, a row count that
-    does not divide the grid, asymmetric clipping, an imposed denominator and a
-    non-unit upstream gradient; every element compared."""
-    N = 37
-    say("\n[case] ragged dtype=%s V=%d stride=%d N=%d" % (dtype, vocab, stride, N))
+def run_shape_case(dtype, vocab, stride, N, grad_rows="all"):
+    say("\n[case] shape dtype=%s V=%d stride=%d N=%d" % (dtype, vocab, stride, N))
     g = torch.Generator().manual_seed(vocab * 7 + (dtype == "f32"))
     dt = torch.bfloat16 if dtype == "bf16" else torch.float32
     store = torch.full((N, stride), 7.0, dtype=dt)            # padding holds a sentinel
@@ -180,7 +175,8 @@ def test_ragged_shapes_and_strides(dtype, vocab, stride):
     old = (torch.as_tensor(lp_orc) + noise).to(torch.float32)
     adv = torch.randn(N, generator=g).numpy().astype(np.float32)
     adv[3] = 0.0
-    out = check_against_oracle(batch, old, lp_orc, adv, denom=50.0, grad_scale=2.5, label="ragged")
+    out = check_against_oracle(batch, old, lp_orc, adv, denom=50.0, grad_scale=2.5, label="shape",
+                               grad_rows=grad_rows)
     pad = store[:, vocab:]
     assert bool((pad == 7.0).all()), "logits padding was written"
     # gradient buffer padding must be left alone too: run into a pre-filled buffer
@@ -192,6 +188,39 @@ def test_ragged_shapes_and_strides(dtype, vocab, stride):
     torch.cuda.synchronize()
     assert bool((gbuf[:, vocab:] == 3.0).all()), "gradient padding was written"
     assert torch.equal(gview, out["grad"])
+    lp_fwd = grpo.grpo_logprobs_fwd(logits, batch["tokens"], batch["mask"], temperature=f32(0.9))
+    torch.cuda.synchronize()
+    assert torch.equal(lp_fwd, out["logprobs"])
+
+
+@pytest.mark.parametrize("dtype,vocab,stride", RAGGED)
+def test_ragged_shapes_and_strides(dtype, vocab, stride):
+    """Row widths that end inside a 16-byte vector, padded row pitches, a row count that
+    does not divide the grid, asymmetric clipping, an imposed denominator and a
+    non-unit upstream gradient; every element compared."""
+    run_shape_case(dtype, vocab, stride, 37)
+
+
+WIDE = [
+    # (vocab, row_stride, rows): more rows than workgroups, so that each workgroup takes several
+    # in turn and refills its registers and LDS from the next row while it finishes the current one
+    (100352, 100352, 800),   # 25 of the 38 register slots: the instantiation that skips empty slots
+    (163840, 163848, 800),   # wider than 38 slots, still registers only
+    (204808, 204808, 800),   # one lane reaches into the first LDS-resident slot
+    (262144, 262144, 800),   # 14 LDS-resident slots
+    (278528, 278528, 600),   # the widest row that is read once
+]
+
+
+@pytest.mark.parametrize("vocab,stride,rows", WIDE)
+def test_wide_rows_several_per_workgroup(vocab, stride, rows):
+    """Vocabularies beside the benchmark's: rows that leave register slots empty and rows wider
+    than the registers, whose last slots live in LDS.  All log-probs, the loss and the counters;
+    gradients of the first and last rows and of a seeded sample in between."""
+    rng = np.random.default_rng(vocab)
+    pick = np.unique(np.concatenate([np.arange(12), np.arange(rows - 12, rows),
+                                     rng.choice(rows, size=120, replace=False)]))
+    run_shape_case("bf16", vocab, stride, rows, grad_rows=pick)
 
 
 def test_inplace_gradient_and_bitwise_determinism():

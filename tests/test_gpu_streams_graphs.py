@@ -128,3 +128,37 @@ def test_lmhead_side_stream_and_graph_replay():
         torch.cuda.synchronize()
         for k, v in ref.items():
             assert torch.equal(v, bufs[k]), "%s differs on replay %d" % (k, i)
+
+
+def test_two_host_threads_on_two_streams():
+    """Two host threads call the library at the same time, each on a stream and with buffers of its
+    own (the foreign-function call releases the interpreter lock): both get the single-thread bits."""
+    import threading
+    cfg, b, old, bufs0 = _setup()
+    _step(cfg, b, old, bufs0, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    ref = _snapshot(bufs0)
+    sets = [{k: torch.zeros_like(v) for k, v in bufs0.items()} for _ in range(2)]
+    streams = [torch.cuda.Stream() for _ in range(2)]
+    for s in streams:
+        s.wait_stream(torch.cuda.current_stream())
+    errors = []
+
+    def work(i):
+        try:
+            for _ in range(20):
+                _step(cfg, b, old, sets[i], streams[i])
+            streams[i].synchronize()
+        except Exception as exc:                              # surfaced below, in the main thread
+            errors.append(exc)
+
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    torch.cuda.synchronize()
+    for i in range(2):
+        for k, v in ref.items():
+            assert torch.equal(v, sets[i][k]), "thread %d: %s" % (i, k)
