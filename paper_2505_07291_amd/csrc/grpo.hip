@@ -726,28 +726,33 @@ constexpr int row_blocks_per_cu(int block, int nv)
 #define GRPO_ROW_RSTASH 16
 #endif
 constexpr int row_reg_stash_slots(int block, int nv) { return nv > 19 ? GRPO_ROW_RSTASH : 0; }
-// Rows wider than 38 slots of 512 lanes: this many slots in registers and this many (8 KB each)
-// in LDS, 544 KB together.
-#ifndef GRPO_WIDE_REG_SLOTS
-#define GRPO_WIDE_REG_SLOTS 50
+// Rows wider than 44 slots of 512 lanes keep 50 slots in registers and up to 18 (8 KB each) in
+// LDS, 544 KB together.
+#ifndef GRPO_WIDE_NV
+#define GRPO_WIDE_NV 50
 #endif
-constexpr int kWideRegSlots = GRPO_WIDE_REG_SLOTS;
-constexpr int kWideLdsSlots = 18;
-constexpr int row_stash_slots(int block, int nv)
+#ifndef GRPO_WIDE_RST
+#define GRPO_WIDE_RST 0
+#endif
+constexpr int kWideRegSlots = GRPO_WIDE_NV;
+constexpr int row_stash_slots(int block, int nv, int nl = 0)
 {
-    const int fit = GRPO_ROW_STASH_KB * 1024 / row_blocks_per_cu(block, nv) / (block * 16);
-    return fit < nv ? fit : nv;
+    const int fit = GRPO_ROW_STASH_KB * 1024 / row_blocks_per_cu(block, nv) / (block * 16) - nl;
+    return fit < 0 ? 0 : fit < nv ? fit : nv;
 }
 
 // ---------------------------------------------------------------------------
 // Register-resident row kernel: requires ceil(vocab / EPV) <= BLOCK * (NV + NL).
 // One workgroup per row at a time, rows strided over a persistent grid.
 // NL > 0: the row is wider than the registers hold and its last NL slots live in LDS, which
-// the loads fill directly (buffer loads with LDS as their target); no gradient waits then.
-// SKIP: slots wholly past the end of the row are skipped (one scalar branch per slot and pass),
-// for vocabularies well below the instantiation's width.
+// the loads fill directly (buffer loads with LDS as their target).
+// RST >= 0: the number of gradient slots that wait in registers, for the instantiations of 512
+// lanes beside the benchmark's width; what LDS the row leaves free holds waiting slots too.
+// (Skipping the empty slots of a narrower row with a branch per slot was tried instead of
+// several widths: the wait counters are then reset to zero at every join and the gradient
+// pass ran 1.5 times as long.)
 // ---------------------------------------------------------------------------
-template <grpo_dtype DT, int BLOCK, int NV, bool AUX, bool TAIL, int NL = 0, bool SKIP = false>
+template <grpo_dtype DT, int BLOCK, int NV, bool AUX, bool TAIL, int NL = 0, int RST = -1>
 // 4 wavefronts per SIMD and 128 registers each; the widest instantiations 2 and 256
 __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowParams p)
 {
@@ -763,10 +768,11 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
     // statistics that follow run with nothing in flight; with the stores behind the loads
     // they drain during that arithmetic (what a row whose gradient is zero gets for free: it
     // issues all loads, then all stores).
-    constexpr int STASH = NL > 0 ? 0 : row_stash_slots(BLOCK, NV);
-    // further slots that wait in registers (the branches of SKIP cost a few registers)
-    constexpr int RSTASH = NL > 0 ? 0 : row_reg_stash_slots(BLOCK, NV) - (SKIP ? 4 : 0);
+    constexpr int STASH = row_stash_slots(BLOCK, NV, NL);
+    constexpr int RSTASH = RST >= 0 ? RST : row_reg_stash_slots(BLOCK, NV);  // further slots that wait in registers
+    static_assert(STASH + RSTASH <= NV, "more waiting slots than register slots");
     extern __shared__ __attribute__((aligned(16))) char row_stash[];
+    char *const grad_stash = row_stash + (size_t)NL * SLAB;  // behind the LDS-resident part of the row
     __shared__ float lds_max[BLOCK / 64];
     __shared__ float lds_sum[BLOCK / 64];
     __shared__ float lds_sumw[BLOCK / 64];
@@ -781,8 +787,6 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
     // (The widest instantiation has no registers to spare for that slot and is built
     // without it; ragged rows of that width take the streaming kernel.)
     const bool tail_wave = TAIL && tail != 0 && tid < 64;
-    // slot i holds something of this row (always true without SKIP); uniform
-    auto used = [&](int i) { return !SKIP || i * BLOCK < nvec_full; };
 
     // ---- which row next ----
     // With a workspace (objective + gradient) rows are handed out through a counter in
@@ -847,17 +851,31 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
     u32x4 tbuf = neg_inf_vec<DT>();
     float zy = 0.f;
 
+    // The lane's number and byte offset as the slot loops use them.  In the instantiations with
+    // LDS-resident slots they are made opaque at every use: otherwise the compiler keeps the
+    // vector number, the store offset and the in-range mask of each of the 60 to 68 slots in
+    // registers of their own across the whole row loop, and the row spills.
+    auto lane = [&]() __attribute__((always_inline)) {
+        int t = tid;
+        if constexpr (NL > 0) asm volatile("" : "+v"(t));
+        return t;
+    };
+    auto lane_off = [&]() __attribute__((always_inline)) {
+        unsigned o = toff;
+        if constexpr (NL > 0) asm volatile("" : "+v"(o));
+        return o;
+    };
     unsigned noff = toff;  // byte offset of this lane inside a slab, as used by the refills
-    auto fetch_slot = [&](const char *zrow, int i) {
-        if (i * BLOCK + tid < nvec_full) buf[i] = ld16(zrow + (size_t)i * SLAB + noff);
+    auto fetch_slot = [&](const char *zrow, int i) __attribute__((always_inline)) {
+        if (i * BLOCK + lane() < nvec_full) buf[i] = ld16(zrow + (size_t)i * SLAB + noff);
     };
     // LDS-resident slot j (slot NV + j of the row): lane tid owns the 16 bytes at j * SLAB + toff,
     // which is also where the load puts them (wavefront base in M0, 16 bytes per lane).  Lanes
     // past the end of the row load nothing and read their piece as -inf.
     const int wave_lds = __builtin_amdgcn_readfirstlane(tid >> 6) * 1024;
-    auto fetch_lds_slot = [&](const char *zrow, int j) {
+    auto fetch_lds_slot = [&](const char *zrow, int j) __attribute__((always_inline)) {
         if constexpr (NL > 0) {
-            if ((NV + j) * BLOCK + tid < nvec_full) {
+            if ((NV + j) * BLOCK + lane() < nvec_full) {
                 const __amdgpu_buffer_rsrc_t rsrc =
                     __builtin_amdgcn_make_buffer_rsrc((void *)zrow, 0, -1, 0x00020000);
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(
@@ -866,9 +884,13 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
             }
         }
     };
-    auto lds_slot = [&](int j, int vy_, int ey_) -> u32x4 {
-        u32x4 z = *(const u32x4 *)(row_stash + (size_t)j * SLAB + toff);
-        const int v = (NV + j) * BLOCK + tid;
+    auto lds_slot = [&](int j, int vy_, int ey_) __attribute__((always_inline)) -> u32x4 {
+        // each pass reads the slot anew: with an address the compiler can recognise it keeps the
+        // first pass's values of all slots in registers for the later passes, and the row spills
+        unsigned off = toff;
+        asm volatile("" : "+v"(off));
+        u32x4 z = *(const u32x4 *)(row_stash + (size_t)j * SLAB + off);
+        const int v = (NV + j) * BLOCK + lane();
         if (v >= nvec_full) z = neg_inf_vec<DT>();
         if (v == vy_) set_neg_inf<DT>(z, ey_);  // the sampled token's logit stays out of the sums
         return z;
@@ -878,13 +900,12 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
         __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
         __builtin_amdgcn_sched_barrier(0);
     };
-    auto fetch_all = [&](const char *zrow) {
+    // (always inlined: as a function of its own it would take the row out of the registers)
+    auto fetch_all = [&](const char *zrow) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < NV; ++i)
-            if (used(i)) fetch_slot(zrow, i);
+        for (int i = 0; i < NV; ++i) fetch_slot(zrow, i);
 #pragma unroll
-        for (int j = 0; j < NL; ++j)
-            if (used(NV + j)) fetch_lds_slot(zrow, j);
+        for (int j = 0; j < NL; ++j) fetch_lds_slot(zrow, j);
     };
     auto fetch_rest = [&](const char *zrow, long long y) {
         if (tail_wave && tid == 0) tbuf = load_vec<DT>(zrow, nvec_full, nvec_full, tail);
@@ -923,18 +944,17 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
         float mx = -INFINITY;
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
-            if (!used(i)) continue;
             forget(buf[i]);
             mx = fmaxf(mx, vec_max_ref<DT, AUX>(buf[i]));
             VECTOR_FENCE();
         }
         if constexpr (NL > 0) {
-            if (used(NV)) lds_slots_landed();
+            lds_slots_landed();
 #pragma unroll
             for (int j = 0; j < NL; ++j) {
-                if (!used(NV + j)) continue;
-                const u32x4 z = lds_slot(j, vy, ey);
+                    const u32x4 z = lds_slot(j, vy, ey);
                 mx = fmaxf(mx, vec_max_ref<DT, AUX>(z));
+                asm volatile("" : "+v"(mx));  // done with this slot before the next one is read
                 VECTOR_FENCE();
             }
         }
@@ -947,7 +967,6 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
         float acc = 0.f, accw = 0.f;
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
-            if (!used(i)) continue;
             forget(buf[i]);
             if constexpr (AUX)
                 acc += exp_sum_vec_aux<DT>(buf[i], p.k, mx, accw);
@@ -961,12 +980,12 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
         }
 #pragma unroll
         for (int j = 0; j < NL; ++j) {
-            if (!used(NV + j)) continue;
             u32x4 z = lds_slot(j, vy, ey);
             if constexpr (AUX)
                 acc += exp_sum_vec_aux<DT>(z, p.k, mx, accw);
             else
                 acc += exp_sum_vec<DT>(z, p.k, mk);
+            asm volatile("" : "+v"(acc));  // done with this slot before the next one is read
             if (!p.bwd && has_next) {
                 order_after(noff, acc);  // the slot has been read: its refill may start
                 fetch_lds_slot(zrow_next, j);
@@ -1008,8 +1027,7 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
                 u32x4 rstash[RSTASH > 0 ? RSTASH : 1];
 #pragma unroll
                 for (int i = 0; i < NV; ++i) {
-                    if (!used(i)) continue;
-                    const int v = i * BLOCK + tid;
+                            const int v = i * BLOCK + lane();
                     forget(buf[i]);
                     u32x4 packed;
                     if constexpr (AUX) {
@@ -1022,16 +1040,15 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
                     order_after(noff, packed);
                     // the slot's gradient waits (LDS, then registers) or, for the last slots, is
                     // stored at once, but in every case behind the next row's load into the slot
-                    if (i < STASH) *(u32x4 *)(row_stash + (size_t)i * SLAB + toff) = packed;
+                    if (i < STASH) *(u32x4 *)(grad_stash + (size_t)i * SLAB + lane_off()) = packed;
                     if (has_next) fetch_slot(zrow_next, i);
                     if (i >= STASH && i < STASH + RSTASH) rstash[i - STASH < 0 ? 0 : i - STASH] = packed;
-                    if (i >= STASH + RSTASH && v < nvec_full) st16(grow + (size_t)i * SLAB + toff, packed);
+                    if (i >= STASH + RSTASH && v < nvec_full) st16(grow + (size_t)i * SLAB + lane_off(), packed);
                     VECTOR_FENCE();
                 }
 #pragma unroll
                 for (int j = 0; j < NL; ++j) {
-                    if (!used(NV + j)) continue;
-                    const int v = (NV + j) * BLOCK + tid;
+                            const int v = (NV + j) * BLOCK + lane();
                     u32x4 z = lds_slot(j, -1, 0);
                     u32x4 packed;
                     if constexpr (AUX) {
@@ -1043,7 +1060,7 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
                     }
                     order_after(noff, packed);  // the slot has been read: its refill may start
                     if (has_next) fetch_lds_slot(zrow_next, j);
-                    if (v < nvec_full) st16(grow + (size_t)(NV + j) * SLAB + toff, packed);
+                    if (v < nvec_full) st16(grow + (size_t)(NV + j) * SLAB + lane_off(), packed);
                     VECTOR_FENCE();
                 }
                 if (tail_wave && tid == 0) {
@@ -1059,12 +1076,12 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
                 if (has_next) fetch_rest(zrow_next, y_next);
 #pragma unroll
                 for (int i = 0; i < STASH; ++i) {
-                    const u32x4 packed = *(const u32x4 *)(row_stash + (size_t)i * SLAB + toff);
-                    if (i * BLOCK + tid < nvec_full) st16(grow + (size_t)i * SLAB + toff, packed);
+                    const u32x4 packed = *(const u32x4 *)(grad_stash + (size_t)i * SLAB + lane_off());
+                    if (i * BLOCK + lane() < nvec_full) st16(grow + (size_t)i * SLAB + lane_off(), packed);
                 }
 #pragma unroll
                 for (int i = STASH; i < STASH + RSTASH; ++i)
-                    if (i * BLOCK + tid < nvec_full) st16(grow + (size_t)i * SLAB + toff, rstash[i - STASH]);
+                    if (i * BLOCK + lane() < nvec_full) st16(grow + (size_t)i * SLAB + lane_off(), rstash[i - STASH]);
             }
         }
         row = next;
@@ -1441,23 +1458,23 @@ int cu_count()
     return n;
 }
 
-template <grpo_dtype DT, int BLOCK, int NV, bool AUX, bool TAIL, int NL = 0, bool SKIP = false>
+template <grpo_dtype DT, int BLOCK, int NV, bool AUX, bool TAIL, int NL = 0, int RST = -1>
 void launch_cached(const RowParams &p, int blocks_per_cu, hipStream_t st)
 {
     long long grid = (long long)cu_count() * blocks_per_cu;
     if (grid > p.n_tokens) grid = p.n_tokens;
     // dynamic LDS: the waiting gradient slots, or the LDS-resident part of the row
-    constexpr unsigned lds_bytes = (unsigned)(NL > 0 ? NL : row_stash_slots(BLOCK, NV)) * BLOCK * 16u;
+    constexpr unsigned lds_bytes = (unsigned)(NL + row_stash_slots(BLOCK, NV, NL)) * BLOCK * 16u;
     if constexpr (lds_bytes > 0) {
         static std::atomic<bool> attr_done[64];  // setting the attribute twice is harmless
         int dev = 0;
         if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64 && !attr_done[dev].load()) {
-            if (hipFuncSetAttribute((const void *)grpo_rows_cached<DT, BLOCK, NV, AUX, TAIL, NL, SKIP>,
+            if (hipFuncSetAttribute((const void *)grpo_rows_cached<DT, BLOCK, NV, AUX, TAIL, NL, RST>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) == hipSuccess)
                 attr_done[dev].store(true);
         }
     }
-    hipLaunchKernelGGL((grpo_rows_cached<DT, BLOCK, NV, AUX, TAIL, NL, SKIP>), dim3((unsigned)grid), dim3(BLOCK),
+    hipLaunchKernelGGL((grpo_rows_cached<DT, BLOCK, NV, AUX, TAIL, NL, RST>), dim3((unsigned)grid), dim3(BLOCK),
                        lds_bytes, st, p);
 }
 
@@ -1473,6 +1490,11 @@ void launch_rows(const RowParams &p_in, hipStream_t st)
     }
     const long long nvec = (p.vocab + Elem<DT>::EPV - 1) / Elem<DT>::EPV;
     const bool ragged = p.vocab % Elem<DT>::EPV != 0;
+    auto launch_streamed = [&]() {
+        long long grid = (long long)cu_count() * 2;
+        if (grid > p.n_tokens) grid = p.n_tokens;
+        hipLaunchKernelGGL((grpo_rows_streamed<DT, 1024, AUX>), dim3((unsigned)grid), dim3(1024), 0, st, p);
+    };
     // Narrow rows take small workgroups, several per CU (each around 16 slots per lane): the
     // phases of different rows then overlap inside a CU and the per-row bookkeeping
     // (queue, three barriers, scalar arithmetic) is hidden.  Only rows too wide for that
@@ -1489,20 +1511,29 @@ void launch_rows(const RowParams &p_in, hipStream_t st)
         launch_cached<DT, 512, 16, AUX, true>(p, row_blocks_per_cu(512, 16), st);
     else if (nvec <= 1024 * 10)
         launch_cached<DT, 1024, 10, AUX, true>(p, row_blocks_per_cu(1024, 10), st);
-    else if (nvec <= 512 * 38 && !ragged) {
-        if (nvec > 512 * 32)
-            launch_cached<DT, 512, 38, AUX, false>(p, row_blocks_per_cu(512, 38), st);
-        else  // well below the width: the empty slots are skipped
-            launch_cached<DT, 512, 38, AUX, false, 0, true>(p, row_blocks_per_cu(512, 38), st);
-    } else if (nvec <= 512 * (kWideRegSlots - (AUX ? 2 : 0) + kWideLdsSlots) && !ragged)
-        // wider than the registers: the last slots of the row live in LDS (the auxiliary terms
-        // take two slots' worth of registers for themselves)
-        launch_cached<DT, 512, kWideRegSlots - (AUX ? 2 : 0), AUX, false, kWideLdsSlots, true>(p, 1, st);
-    else {
-        long long grid = (long long)cu_count() * 2;
-        if (grid > p.n_tokens) grid = p.n_tokens;
-        hipLaunchKernelGGL((grpo_rows_streamed<DT, 1024, AUX>), dim3((unsigned)grid), dim3(1024), 0, st, p);
-    }
+    else if (ragged)
+        launch_streamed();
+    // 512 lanes with twice the registers, in several widths: the arithmetic of a pass runs over
+    // every slot of the instantiation, used or not.  The trailing number is the count of
+    // gradient slots that wait in registers: what fits beside the row (fewer with the auxiliary
+    // terms, which need a few registers more).
+    else if (nvec <= 512 * 26)
+        launch_cached<DT, 512, 26, AUX, false, 0, 8>(p, 1, st);
+    else if (nvec <= 512 * 32)
+        launch_cached<DT, 512, 32, AUX, false, 0, 14>(p, 1, st);
+    else if (nvec <= 512 * 38)
+        launch_cached<DT, 512, 38, AUX, false>(p, 1, st);
+    else if (nvec <= 512 * 44)
+        launch_cached<DT, 512, 44, AUX, false, 0, AUX ? 8 : 10>(p, 1, st);
+    // wider than the registers: the last slots of the row live in LDS
+    else if (nvec <= 512 * (kWideRegSlots + 4))
+        launch_cached<DT, 512, kWideRegSlots, AUX, false, 4, GRPO_WIDE_RST>(p, 1, st);
+    else if (nvec <= 512 * (kWideRegSlots + 10))
+        launch_cached<DT, 512, kWideRegSlots, AUX, false, 10, GRPO_WIDE_RST>(p, 1, st);
+    else if (nvec <= 512 * (kWideRegSlots + 18))
+        launch_cached<DT, 512, kWideRegSlots, AUX, false, 18, GRPO_WIDE_RST>(p, 1, st);
+    else
+        launch_streamed();
 }
 
 grpo_status check_logits_args(const void *logits, grpo_dtype dtype, int64_t n_tokens, int64_t vocab,
