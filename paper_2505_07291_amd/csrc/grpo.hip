@@ -769,7 +769,8 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
     // they drain during that arithmetic (what a row whose gradient is zero gets for free: it
     // issues all loads, then all stores).
     constexpr int STASH = row_stash_slots(BLOCK, NV, NL);
-    constexpr int RSTASH = RST >= 0 ? RST : row_reg_stash_slots(BLOCK, NV);  // further slots that wait in registers
+    // further slots that wait in registers
+    constexpr int RSTASH = RST < 0 ? row_reg_stash_slots(BLOCK, NV) : RST < NV - STASH ? RST : NV - STASH;
     static_assert(STASH + RSTASH <= NV, "more waiting slots than register slots");
     extern __shared__ __attribute__((aligned(16))) char row_stash[];
     char *const grad_stash = row_stash + (size_t)NL * SLAB;  // behind the LDS-resident part of the row
