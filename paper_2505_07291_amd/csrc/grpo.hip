@@ -4,8 +4,9 @@
 //
 // The path is a streaming reduction over rows of 152k logits: it is bound by HBM
 // bandwidth, not by arithmetic, so there is no MFMA here.  The design keeps one
-// whole row resident in the vector registers of a 1024-lane workgroup (304 KB of
-// the CU's 512 KB register file for a 152064-wide bf16 row), so that the row is
+// whole row resident in the vector registers of one workgroup (304 KB of the CU's
+// 512 KB register file for a 152064-wide bf16 row: 512 lanes with 256 registers each,
+// 152 of them the row), so that the row is
 // read from HBM once, reduced twice (max, sum of exponentials) out of registers,
 // and the gradient is produced from the same registers: 1 read + 1 write of HBM
 // traffic per row instead of 2 reads + 1 write.
@@ -1499,9 +1500,9 @@ void launch_rows(const RowParams &p_in, hipStream_t st)
     // Narrow rows take small workgroups, several per CU (each around 16 slots per lane): the
     // phases of different rows then overlap inside a CU and the per-row bookkeeping
     // (queue, three barriers, scalar arithmetic) is hidden.  Only rows too wide for that
-    // use one workgroup per CU: 1024 lanes with up to 10 slots, and for the widest rows 512
-    // lanes with 38 slots and twice the registers, the spare ones holding gradient vectors
-    // back behind the next row's loads.
+    // use one workgroup per CU: 512 lanes with twice the registers, the spare ones holding
+    // gradient vectors back behind the next row's loads (1024 lanes with up to 10 slots where
+    // the ragged-tail slot is needed, which those are built without).
     if (nvec <= 256 * 1)
         launch_cached<DT, 256, 1, AUX, true>(p, row_blocks_per_cu(256, 1), st);
     else if (nvec <= 256 * 4)
@@ -1510,6 +1511,8 @@ void launch_rows(const RowParams &p_in, hipStream_t st)
         launch_cached<DT, 256, 16, AUX, true>(p, row_blocks_per_cu(256, 16), st);
     else if (nvec <= 512 * 16)
         launch_cached<DT, 512, 16, AUX, true>(p, row_blocks_per_cu(512, 16), st);
+    else if (nvec <= 512 * 20 && !ragged)  // all 20 gradient slots wait: 18 in LDS, 2 in registers
+        launch_cached<DT, 512, 20, AUX, false, 0, 2>(p, 1, st);
     else if (nvec <= 1024 * 10)
         launch_cached<DT, 1024, 10, AUX, true>(p, row_blocks_per_cu(1024, 10), st);
     else if (ragged)

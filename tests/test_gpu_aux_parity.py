@@ -129,10 +129,10 @@ def test_aux_ragged_shapes(dtype, vocab, stride):
     run_aux_shape_case(dtype, vocab, stride, 29)
 
 
-@pytest.mark.parametrize("vocab,rows", [(100352, 420), (262144, 420), (270336, 300)])
+@pytest.mark.parametrize("vocab,rows", [(81920, 420), (100352, 420), (128256, 420), (163840, 420), (204808, 420), (262144, 420), (278528, 300)])
 def test_aux_wide_rows_several_per_workgroup(vocab, rows):
-    """Rows that leave register slots empty, and rows whose last slots live in LDS, with more rows
-    than workgroups; every element compared."""
+    """Every width of the 512-lane instantiations, up to rows whose last slots live in LDS, with more
+    rows than workgroups; every element compared."""
     run_aux_shape_case("bf16", vocab, vocab, rows)
 
 

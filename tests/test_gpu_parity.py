@@ -148,7 +148,7 @@ RAGGED = [
     ("bf16", 8200, 8208), ("bf16", 50257, 50264), ("bf16", 81921, 81928),
     ("bf16", 152064, 152064), ("bf16", 152069, 152072), ("bf16", 155649, 155656), ("bf16", 200003, 200008),
     ("f32", 1, 4), ("f32", 3, 4), ("f32", 1000, 1004), ("f32", 4099, 4100), ("f32", 40001, 40004),
-    ("f32", 77824, 77824), ("f32", 100003, 100004),
+    ("f32", 40000, 40000), ("f32", 77824, 77824), ("f32", 100003, 100004),
 ]
 
 
@@ -204,17 +204,21 @@ def test_ragged_shapes_and_strides(dtype, vocab, stride):
 WIDE = [
     # (vocab, row_stride, rows): more rows than workgroups, so that each workgroup takes several
     # in turn and refills its registers and LDS from the next row while it finishes the current one
-    (100352, 100352, 800),   # 25 of the 38 register slots: the instantiation that skips empty slots
-    (163840, 163848, 800),   # wider than 38 slots, still registers only
+    (65544, 65552, 800),     # the narrowest row on 512 lanes with 256 registers (20 slots)
+    (81920, 81920, 800),     # ... and the widest: all 20 slots used, every store behind the loads
+    (100352, 100352, 800),   # 26 register slots
+    (128256, 128256, 800),   # 32 register slots
+    (163840, 163848, 800),   # 44 register slots
     (204808, 204808, 800),   # one lane reaches into the first LDS-resident slot
-    (262144, 262144, 800),   # 14 LDS-resident slots
+    (230400, 230400, 700),   # the instantiation with 10 LDS-resident slots
+    (262144, 262144, 800),   # 14 of 18 LDS-resident slots used
     (278528, 278528, 600),   # the widest row that is read once
 ]
 
 
 @pytest.mark.parametrize("vocab,stride,rows", WIDE)
 def test_wide_rows_several_per_workgroup(vocab, stride, rows):
-    """Vocabularies beside the benchmark's: rows that leave register slots empty and rows wider
+    """Vocabularies beside the benchmark's, each on the instantiation of its width, up to rows wider
     than the registers, whose last slots live in LDS.  All log-probs, the loss and the counters;
     gradients of the first and last rows and of a seeded sample in between."""
     rng = np.random.default_rng(vocab)
