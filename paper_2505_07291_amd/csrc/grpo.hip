@@ -710,6 +710,54 @@ __device__ __forceinline__ void order_after(unsigned &off, X &x)
 }
 
 
+// One vector of an online softmax pass: running maximum m (in logit units), sum s of the
+// exponentials relative to it and, for the entropy, w = sum e a with a the exponent in log2
+// units.  The sampled token's element (has_y, ey) takes part in the maximum only.
+template <grpo_dtype DT, bool AUX>
+__device__ __forceinline__ void online_vec(const u32x4 &z, bool has_y, int ey, float k, float &m, float &s,
+                                           float &w)
+{
+    constexpr int EPV = Elem<DT>::EPV;
+    float f[EPV];
+    unpack<DT>(z, f);
+    float vm = f[0];
+#pragma unroll
+    for (int e = 1; e < EPV; ++e) vm = fmaxf(vm, f[e]);
+    if (vm > m) {
+        // new reference: every exponent so far moves by dlt, every term by 2^dlt
+        const float dlt = (m - vm) * k;  // -inf the first time: s and w are 0 and stay 0
+        const float sc_ = __builtin_amdgcn_exp2f(dlt);
+        if constexpr (AUX) w = (s > 0.f) ? sc_ * fmaf(dlt, s, w) : 0.f;
+        s *= sc_;
+        m = vm;
+    }
+    const float mk_t = m * k;
+    float part = 0.f, partw = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) {
+        const float a = AUX ? fmaxf((f[e] - m) * k, kExpFloor) : fmaf(f[e], k, -mk_t);
+        float ex = __builtin_amdgcn_exp2f(a);
+        if (has_y && e == ey) ex = 0.f;
+        part += ex;
+        if constexpr (AUX) partw = fmaf(ex, a, partw);
+    }
+    if (m > -INFINITY) {  // all -inf so far: exponents would be NaN
+        s += part;
+        w += partw;
+    }
+}
+
+// The online partials (m, s, w) of one lane moved to the row's reference maximum mx.
+template <bool AUX>
+__device__ __forceinline__ void online_rescale(float m, float s, float w, float mx, float k, float &scaled,
+                                               float &scaledw)
+{
+    const float dlt = (m - mx) * k;
+    const float sc_ = __builtin_amdgcn_exp2f(dlt);
+    scaled = (m > -INFINITY) ? s * sc_ : 0.f;
+    scaledw = (AUX && m > -INFINITY && s > 0.f) ? sc_ * fmaf(dlt, s, w) : 0.f;
+}
+
 // Workgroups that share a CU, by instantiation.
 constexpr int row_blocks_per_cu(int block, int nv)
 {
@@ -736,6 +784,10 @@ constexpr int row_reg_stash_slots(int block, int nv) { return nv > 19 ? GRPO_ROW
 #define GRPO_WIDE_RST 0
 #endif
 constexpr int kWideRegSlots = GRPO_WIDE_NV;
+#ifndef GRPO_REM_NV
+#define GRPO_REM_NV 48
+#endif
+constexpr int kRemRegSlots = GRPO_REM_NV;  // with a streamed remainder: its loop needs registers too
 constexpr int row_stash_slots(int block, int nv, int nl = 0)
 {
     const int fit = GRPO_ROW_STASH_KB * 1024 / row_blocks_per_cu(block, nv) / (block * 16) - nl;
@@ -752,8 +804,11 @@ constexpr int row_stash_slots(int block, int nv, int nl = 0)
 // (Skipping the empty slots of a narrower row with a branch per slot was tried instead of
 // several widths: the wait counters are then reset to zero at every join and the gradient
 // pass ran 1.5 times as long.)
+// REM: the row may be wider still; what lies beyond slot NV + NL is streamed from memory, once
+// for an online (max, sum) pass that is merged into the resident part's statistics and once
+// more for the gradient: 2 reads + 1 write for that remainder only.
 // ---------------------------------------------------------------------------
-template <grpo_dtype DT, int BLOCK, int NV, bool AUX, bool TAIL, int NL = 0, int RST = -1>
+template <grpo_dtype DT, int BLOCK, int NV, bool AUX, bool TAIL, int NL = 0, int RST = -1, bool REM = false>
 // 4 wavefronts per SIMD and 128 registers each; the widest instantiations 2 and 256
 __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowParams p)
 {
@@ -761,6 +816,8 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
     constexpr int BYTES = Elem<DT>::BYTES;
     constexpr unsigned SLAB = BLOCK * 16u;  // bytes one pass of the workgroup covers
     static_assert(NL == 0 || !TAIL, "LDS-resident slots come without the ragged-tail slot");
+    static_assert(!REM || !TAIL, "the streamed remainder comes without the ragged-tail slot");
+    constexpr int RU = 4;  // vectors per lane in flight in the remainder loops
     // Gradient vectors of the first STASH slots wait in LDS (each lane its own 16 bytes per
     // slot, no sharing), those of the next RSTASH slots in registers, and all of them are
     // stored after the loop over the slots, so that the next row's loads stand in front of
@@ -961,6 +1018,26 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
             }
         }
         if (tail_wave) mx = fmaxf(mx, vec_max_ref<DT, AUX>(tbuf));
+        // the part of the row that is not resident: online statistics, first read
+        const char *zrow_cur = (const char *)p.logits + row * p.row_stride * BYTES;
+        float rem_m = -INFINITY, rem_s = 0.f, rem_w = 0.f;
+        if constexpr (REM) {
+            for (int base = (NV + NL) * BLOCK; base < nvec_full; base += RU * BLOCK) {
+                u32x4 z[RU];
+#pragma unroll
+                for (int u = 0; u < RU; ++u) {
+                    const int v = base + u * BLOCK + tid;
+                    z[u] = neg_inf_vec<DT>();
+                    if (v < nvec_full) z[u] = ld16(zrow_cur + (size_t)v * 16);
+                }
+#pragma unroll
+                for (int u = 0; u < RU; ++u) {
+                    online_vec<DT, AUX>(z[u], base + u * BLOCK + tid == vy, ey, p.k, rem_m, rem_s, rem_w);
+                    VECTOR_FENCE();
+                }
+            }
+            mx = fmaxf(mx, rem_m);
+        }
         mx = fmaxf(block_max<BLOCK>(mx, lds_max), zy);
         const float mk = mx * p.k;
 
@@ -1000,6 +1077,12 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
             else
                 acc += exp_sum_vec<DT>(tbuf, p.k, mk);
         }
+        if constexpr (REM) {
+            float scaled, scaledw;
+            online_rescale<AUX>(rem_m, rem_s, rem_w, mx, p.k, scaled, scaledw);
+            acc += scaled;
+            accw += scaledw;
+        }
         const float zy_row = zy;
         if (!p.bwd && has_next) fetch_rest(zrow_next, y_next);
         RowScalars sc;
@@ -1026,6 +1109,33 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
             } else {
                 const float q = -sc.c * p.inv_T;
                 const float gy = (sc.c * p.inv_T) * (sc.s_excl / sc.s) + (AUX ? sc.gy_ent : 0.f);
+                if constexpr (REM) {
+                    // second read of the remainder, before the resident slots: behind their
+                    // refills these loads would wait for the whole next row
+                    for (int base = (NV + NL) * BLOCK; base < nvec_full; base += RU * BLOCK) {
+                        u32x4 z[RU];
+#pragma unroll
+                        for (int u = 0; u < RU; ++u) {
+                            const int v = base + u * BLOCK + tid;
+                            z[u] = neg_inf_vec<DT>();
+                            if (v < nvec_full) z[u] = ld16(zrow_cur + (size_t)v * 16);
+                        }
+#pragma unroll
+                        for (int u = 0; u < RU; ++u) {
+                            const int v = base + u * BLOCK + tid;
+                            u32x4 packed;
+                            if constexpr (AUX) {
+                                packed = grad_vec_aux<DT>(z[u], p.k, sc.mx, sc.log2s, sc.q2, sc.bq, v == vy, ey, gy);
+                            } else {
+                                float g[EPV];
+                                grad_vec<DT>(z[u], p.k, sc.shift, q, v == vy, ey, gy, g);
+                                packed = pack<DT>(g);
+                            }
+                            if (v < nvec_full) st16(grow + (size_t)v * 16, packed);
+                            VECTOR_FENCE();
+                        }
+                    }
+                }
                 u32x4 rstash[RSTASH > 0 ? RSTASH : 1];
 #pragma unroll
                 for (int i = 0; i < NV; ++i) {
@@ -1116,45 +1226,15 @@ __global__ void __launch_bounds__(BLOCK) grpo_rows_streamed(RowParams p)
         const int vy = (int)(y / EPV);
         const int ey = (int)(y % EPV);
 
-        // online pass: running maximum m (in logit units), sum s of exponentials relative
-        // to it and, for the entropy, w = sum e a with a the exponent in log2 units
         float m = -INFINITY, s = 0.f, w = 0.f;
         for (int v = tid; v < nvec; v += BLOCK) {
             const u32x4 z = load_vec<DT>(zrow, v, nvec_full, tail);
-            float f[EPV];
-            unpack<DT>(z, f);
-            float vm = f[0];
-#pragma unroll
-            for (int e = 1; e < EPV; ++e) vm = fmaxf(vm, f[e]);
-            if (vm > m) {
-                // new reference: every exponent so far moves by dlt, every term by 2^dlt
-                const float dlt = (m - vm) * p.k;  // -inf the first time: s and w are 0 and stay 0
-                const float sc_ = __builtin_amdgcn_exp2f(dlt);
-                if constexpr (AUX) w = (s > 0.f) ? sc_ * fmaf(dlt, s, w) : 0.f;
-                s *= sc_;
-                m = vm;
-            }
-            const float mk_t = m * p.k;
-            float part = 0.f, partw = 0.f;
-#pragma unroll
-            for (int e = 0; e < EPV; ++e) {
-                const float a = AUX ? fmaxf((f[e] - m) * p.k, kExpFloor) : fmaf(f[e], p.k, -mk_t);
-                float ex = __builtin_amdgcn_exp2f(a);
-                if (v == vy && e == ey) ex = 0.f;
-                part += ex;
-                if constexpr (AUX) partw = fmaf(ex, a, partw);
-            }
-            if (m > -INFINITY) {  // all -inf so far: exponents would be NaN
-                s += part;
-                w += partw;
-            }
+            online_vec<DT, AUX>(z, v == vy, ey, p.k, m, s, w);
         }
         const float mx = fmaxf(block_max<BLOCK>(m, lds_max), zy);
         const float mk = mx * p.k;
-        const float dlt = (m - mx) * p.k;
-        const float sc_ = __builtin_amdgcn_exp2f(dlt);
-        float scaled = (m > -INFINITY) ? s * sc_ : 0.f;
-        float scaledw = (AUX && m > -INFINITY && s > 0.f) ? sc_ * fmaf(dlt, s, w) : 0.f;
+        float scaled, scaledw;
+        online_rescale<AUX>(m, s, w, mx, p.k, scaled, scaledw);
         RowScalars sc;
         if constexpr (AUX) {
             block_sum2<BLOCK>(scaled, scaledw, lds_sum, lds_sumw);
@@ -1460,7 +1540,7 @@ int cu_count()
     return n;
 }
 
-template <grpo_dtype DT, int BLOCK, int NV, bool AUX, bool TAIL, int NL = 0, int RST = -1>
+template <grpo_dtype DT, int BLOCK, int NV, bool AUX, bool TAIL, int NL = 0, int RST = -1, bool REM = false>
 void launch_cached(const RowParams &p, int blocks_per_cu, hipStream_t st)
 {
     long long grid = (long long)cu_count() * blocks_per_cu;
@@ -1471,12 +1551,12 @@ void launch_cached(const RowParams &p, int blocks_per_cu, hipStream_t st)
         static std::atomic<bool> attr_done[64];  // setting the attribute twice is harmless
         int dev = 0;
         if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64 && !attr_done[dev].load()) {
-            if (hipFuncSetAttribute((const void *)grpo_rows_cached<DT, BLOCK, NV, AUX, TAIL, NL, RST>,
+            if (hipFuncSetAttribute((const void *)grpo_rows_cached<DT, BLOCK, NV, AUX, TAIL, NL, RST, REM>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) == hipSuccess)
                 attr_done[dev].store(true);
         }
     }
-    hipLaunchKernelGGL((grpo_rows_cached<DT, BLOCK, NV, AUX, TAIL, NL, RST>), dim3((unsigned)grid), dim3(BLOCK),
+    hipLaunchKernelGGL((grpo_rows_cached<DT, BLOCK, NV, AUX, TAIL, NL, RST, REM>), dim3((unsigned)grid), dim3(BLOCK),
                        lds_bytes, st, p);
 }
 
@@ -1536,6 +1616,9 @@ void launch_rows(const RowParams &p_in, hipStream_t st)
         launch_cached<DT, 512, kWideRegSlots, AUX, false, 10, GRPO_WIDE_RST>(p, 1, st);
     else if (nvec <= 512 * (kWideRegSlots + 18))
         launch_cached<DT, 512, kWideRegSlots, AUX, false, 18, GRPO_WIDE_RST>(p, 1, st);
+    // wider than registers and LDS together: the remainder is read twice, up to as much again
+    else if (nvec <= 512 * 2 * (kRemRegSlots + 18))
+        launch_cached<DT, 512, kRemRegSlots, AUX, false, 18, 0, true>(p, 1, st);
     else
         launch_streamed();
 }

@@ -129,11 +129,13 @@ def test_aux_ragged_shapes(dtype, vocab, stride):
     run_aux_shape_case(dtype, vocab, stride, 29)
 
 
-@pytest.mark.parametrize("vocab,rows", [(81920, 420), (100352, 420), (128256, 420), (163840, 420), (204808, 420), (262144, 420), (278528, 300)])
-def test_aux_wide_rows_several_per_workgroup(vocab, rows):
-    """Every width of the 512-lane instantiations, up to rows whose last slots live in LDS, with more
-    rows than workgroups; every element compared."""
-    run_aux_shape_case("bf16", vocab, vocab, rows)
+@pytest.mark.parametrize("dtype,vocab,rows", [("bf16", 81920, 420), ("bf16", 100352, 420), ("bf16", 128256, 420),
+                                              ("bf16", 163840, 420), ("bf16", 204808, 420), ("bf16", 262144, 420),
+                                              ("bf16", 278528, 300), ("bf16", 300000, 300), ("f32", 152064, 300)])
+def test_aux_wide_rows_several_per_workgroup(dtype, vocab, rows):
+    """Every width of the 512-lane instantiations, up to rows whose last slots live in LDS and rows with a streamed
+    remainder, with more rows than workgroups; every element compared."""
+    run_aux_shape_case(dtype, vocab, vocab, rows)
 
 
 def run_aux_shape_case(dtype, vocab, stride, N):

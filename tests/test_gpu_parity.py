@@ -202,29 +202,35 @@ def test_ragged_shapes_and_strides(dtype, vocab, stride):
 
 
 WIDE = [
-    # (vocab, row_stride, rows): more rows than workgroups, so that each workgroup takes several
+    # (dtype, vocab, row_stride, rows): more rows than workgroups, so that each workgroup takes several
     # in turn and refills its registers and LDS from the next row while it finishes the current one
-    (65544, 65552, 800),     # the narrowest row on 512 lanes with 256 registers (20 slots)
-    (81920, 81920, 800),     # ... and the widest: all 20 slots used, every store behind the loads
-    (100352, 100352, 800),   # 26 register slots
-    (128256, 128256, 800),   # 32 register slots
-    (163840, 163848, 800),   # 44 register slots
-    (204808, 204808, 800),   # one lane reaches into the first LDS-resident slot
-    (230400, 230400, 700),   # the instantiation with 10 LDS-resident slots
-    (262144, 262144, 800),   # 14 of 18 LDS-resident slots used
-    (278528, 278528, 600),   # the widest row that is read once
+    ("bf16", 65544, 65552, 800),     # the narrowest row on 512 lanes with 256 registers (20 slots)
+    ("bf16", 81920, 81920, 800),     # ... and the widest: all 20 slots used, every store behind the loads
+    ("bf16", 100352, 100352, 800),   # 26 register slots
+    ("bf16", 128256, 128256, 800),   # 32 register slots
+    ("bf16", 163840, 163848, 800),   # 44 register slots
+    ("bf16", 204808, 204808, 800),   # one lane reaches into the first LDS-resident slot
+    ("bf16", 230400, 230400, 700),   # the instantiation with 10 LDS-resident slots
+    ("bf16", 262144, 262144, 800),   # 14 of 18 LDS-resident slots used
+    ("bf16", 278528, 278528, 600),   # the widest row that is read once
+    ("bf16", 270344, 270344, 600),   # one vector beyond registers + LDS of the instantiation with a remainder
+    ("bf16", 300000, 300000, 600),   # a streamed remainder of a few slots
+    ("bf16", 540672, 540672, 300),   # the widest row with a streamed remainder: half of it
+    ("f32", 135172, 135172, 600),    # the same in fp32: one vector of remainder
+    ("f32", 152064, 152064, 600),    # the benchmark's vocabulary in fp32: 8 slots of remainder
 ]
 
 
-@pytest.mark.parametrize("vocab,stride,rows", WIDE)
-def test_wide_rows_several_per_workgroup(vocab, stride, rows):
+@pytest.mark.parametrize("dtype,vocab,stride,rows", WIDE)
+def test_wide_rows_several_per_workgroup(dtype, vocab, stride, rows):
     """Vocabularies beside the benchmark's, each on the instantiation of its width, up to rows wider
-    than the registers, whose last slots live in LDS.  All log-probs, the loss and the counters;
-    gradients of the first and last rows and of a seeded sample in between."""
+    than the registers, whose last slots live in LDS, and rows wider than both, whose remainder is
+    streamed.  All log-probs, the loss and the counters; gradients of the first and last rows and
+    of a seeded sample in between."""
     rng = np.random.default_rng(vocab)
     pick = np.unique(np.concatenate([np.arange(12), np.arange(rows - 12, rows),
-                                     rng.choice(rows, size=120, replace=False)]))
-    run_shape_case("bf16", vocab, stride, rows, grad_rows=pick)
+                                     rng.choice(rows, size=100, replace=False)]))
+    run_shape_case(dtype, vocab, stride, rows, grad_rows=pick)
 
 
 def test_inplace_gradient_and_bitwise_determinism():
