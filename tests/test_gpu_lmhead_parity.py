@@ -153,6 +153,45 @@ def test_denominator_grad_scale_accumulate_and_determinism():
     assert torch.equal(acc, dW + dW)
 
 
+def test_micro_batches_accumulate_into_the_weight_gradient():
+    """Token micro-batches with the whole batch's token count as `denom` and dL/dW accumulated from
+    call to call bound the workspace (logits of one micro-batch at a time): log-probs are the whole
+    batch's bits, losses and counters add up, gradients agree to rounding."""
+    cfg = wl.CONFIGS["qwen_short"].scaled(n_prompts=3, seq_len=50, vocab=3000, group_size=4)
+    d = 256
+    batch = wl.make_lmhead_batch(cfg, d, device=DEV)
+    hb, wb, adv_tok, lp_o, old = oracle_inputs(batch)
+    N = batch["n_tokens"]
+    kw = dict(eps_low=f32(cfg.eps_low), eps_high=f32(cfg.eps_high), delta=f32(cfg.delta),
+              temperature=f32(cfg.temperature))
+    old_d, adv_d = old.to(DEV), torch.as_tensor(adv_tok, device=DEV)
+    say("\n[gpu] lmhead micro-batches N=%d V=%d d=%d" % (N, batch["vocab"], d))
+    loss, lp, counts, dH, dW = grpo.grpo_lmhead_loss_fwd_bwd(batch["hidden"], batch["weight"], batch["tokens"],
+                                                             old_d, adv_d, batch["mask"], **kw)
+    torch.cuda.synchronize()
+    M = int(counts[0].item())
+    cuts = [0, 70, 71, 333, N]
+    dW_acc = torch.zeros_like(dW)
+    dH_all = torch.empty_like(dH)
+    loss_sum, counts_sum = 0.0, torch.zeros_like(counts)
+    for b, e in zip(cuts[:-1], cuts[1:]):
+        l_i, lp_i, c_i, dH_i, _ = grpo.grpo_lmhead_loss_fwd_bwd(
+            batch["hidden"][b:e], batch["weight"], batch["tokens"][b:e], old_d[b:e], adv_d[b:e],
+            batch["mask"][b:e], denom=float(M), grad_weight=dW_acc, accumulate_grad_weight=True, **kw)
+        torch.cuda.synchronize()
+        assert torch.equal(lp_i, lp[b:e]), (b, e)
+        dH_all[b:e] = dH_i
+        loss_sum += float(l_i.item())
+        counts_sum += c_i
+    assert torch.equal(counts_sum, counts)
+    assert abs(loss_sum - float(loss.item())) <= 1e-6 * abs(float(loss.item())) + 1e-9
+    # dL/dH rows: the same products, possibly cut differently along the vocabulary, then rounded to bf16
+    a, b_ = dH_all.float(), dH.float()
+    assert float((a - b_).abs().max()) <= 2.0 ** -7 * float(b_.abs().max())
+    # dL/dW: fp32 sums over the tokens in another order
+    assert float((dW_acc - dW).abs().max()) <= 1e-5 * float(dW.abs().max())
+
+
 def test_strided_operands():
     cfg = wl.CONFIGS["qwen_short"].scaled(n_prompts=1, seq_len=70, vocab=600, group_size=4)
     batch = wl.make_lmhead_batch(cfg, 128, device=DEV)

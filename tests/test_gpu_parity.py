@@ -250,6 +250,35 @@ def test_inplace_gradient_and_bitwise_determinism():
         assert torch.equal(first[k], third[k]), k + " differs in place"
 
 
+def test_micro_batches_add_up():
+    """A batch cut into micro-batches that all receive the whole batch's token count as `denom`
+    (what a trainer with gradient accumulation, or one rank of several, does): per-row outputs
+    are the whole batch's bits, losses and counters add up."""
+    cfg = wl.CONFIGS["qwen_medium"].scaled(n_prompts=2, seq_len=7)
+    batch = wl.make_batch(cfg, DEV)
+    N = cfg.n_tokens
+    say("\n[case] micro-batches: N=%d V=%d" % (N, cfg.vocab))
+    adv, adv_tok, lp_orc = oracle_side(batch)
+    old = wl.make_old_logprobs(cfg, lp_orc).to(DEV)
+    a_dev = torch.as_tensor(adv_tok.astype(np.float32), device=DEV)
+    kw = dict(eps_low=f32(cfg.eps_low), eps_high=f32(cfg.eps_high), delta=f32(cfg.delta),
+              temperature=f32(cfg.temperature))
+    loss, lp, counts, grad = grpo.grpo_loss_fwd_bwd(batch["logits"], batch["tokens"], old, a_dev, batch["mask"], **kw)
+    torch.cuda.synchronize()
+    M = int(counts[0].item())
+    cuts = [0, N // 5, N // 5 + 1, N // 2, N]                 # uneven pieces, one of a single row
+    loss_sum, counts_sum = 0.0, torch.zeros_like(counts)
+    for b, e in zip(cuts[:-1], cuts[1:]):
+        l_i, lp_i, c_i, g_i = grpo.grpo_loss_fwd_bwd(batch["logits"][b:e], batch["tokens"][b:e], old[b:e],
+                                                     a_dev[b:e], batch["mask"][b:e], denom=float(M), **kw)
+        torch.cuda.synchronize()
+        assert torch.equal(lp_i, lp[b:e]) and torch.equal(g_i, grad[b:e]), (b, e)
+        loss_sum += float(l_i.item())
+        counts_sum += c_i
+    assert torch.equal(counts_sum, counts)
+    assert abs(loss_sum - float(loss.item())) <= 1e-6 * abs(float(loss.item())) + 1e-9
+
+
 def test_edge_cases():
     V, N = 4096, 24
     g = torch.Generator().manual_seed(3)
