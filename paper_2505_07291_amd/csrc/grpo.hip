@@ -761,7 +761,8 @@ __device__ __forceinline__ void online_rescale(float m, float s, float w, float 
 // Workgroups that share a CU, by instantiation.
 constexpr int row_blocks_per_cu(int block, int nv)
 {
-    return block == 1024 || nv > 19 ? 1 : block == 512 ? 2 : nv >= 16 ? 4 : 8;
+    // more than 19 slots: the instantiations with 256 registers per lane, 512 lanes per CU
+    return block == 1024 ? 1 : nv > 19 ? 512 / block : block == 512 ? 2 : nv >= 16 ? 4 : 8;
 }
 // How many gradient slots of a row wait before they are stored (see the kernel).  In LDS: as
 // many as an equal share of 144 KB of the CU's LDS holds for each workgroup on the CU (a slot
@@ -1589,6 +1590,14 @@ void launch_rows(const RowParams &p_in, hipStream_t st)
         launch_cached<DT, 256, 4, AUX, true>(p, row_blocks_per_cu(256, 4), st);
     else if (nvec <= 256 * 16)
         launch_cached<DT, 256, 16, AUX, true>(p, row_blocks_per_cu(256, 16), st);
+    // two workgroups of 256 lanes with 256 registers each, every gradient slot waiting behind
+    // the loads, are 3 % ahead of two of 512 lanes with 128.  (The log-probs pass alone gains
+    // nothing, but it takes the same instantiation: the two entry points then give the same
+    // bits, and the ratio of an unchanged policy to itself is exactly 1.)
+    else if (nvec <= 256 * 26 && !ragged)
+        launch_cached<DT, 256, 26, AUX, false, 0, 8>(p, 2, st);
+    else if (nvec <= 256 * 32 && !ragged)
+        launch_cached<DT, 256, 32, AUX, false, 0, 14>(p, 2, st);
     else if (nvec <= 512 * 16)
         launch_cached<DT, 512, 16, AUX, true>(p, row_blocks_per_cu(512, 16), st);
     else if (nvec <= 512 * 20 && !ragged)  // all 20 gradient slots wait: 18 in LDS, 2 in registers

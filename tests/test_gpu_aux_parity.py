@@ -129,7 +129,7 @@ def test_aux_ragged_shapes(dtype, vocab, stride):
     run_aux_shape_case(dtype, vocab, stride, 29)
 
 
-@pytest.mark.parametrize("dtype,vocab,rows", [("bf16", 81920, 420), ("bf16", 100352, 420), ("bf16", 128256, 420),
+@pytest.mark.parametrize("dtype,vocab,rows", [("bf16", 50304, 600), ("bf16", 65536, 600), ("bf16", 81920, 420), ("bf16", 100352, 420), ("bf16", 128256, 420),
                                               ("bf16", 163840, 420), ("bf16", 204808, 420), ("bf16", 262144, 420),
                                               ("bf16", 278528, 300), ("bf16", 300000, 300), ("f32", 152064, 300)])
 def test_aux_wide_rows_several_per_workgroup(dtype, vocab, rows):

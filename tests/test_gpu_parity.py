@@ -204,6 +204,9 @@ def test_ragged_shapes_and_strides(dtype, vocab, stride):
 WIDE = [
     # (dtype, vocab, row_stride, rows): more rows than workgroups, so that each workgroup takes several
     # in turn and refills its registers and LDS from the next row while it finishes the current one
+    ("bf16", 50304, 50304, 900),     # 256 lanes with 256 registers, 26 slots, two workgroups per CU
+    ("bf16", 65536, 65536, 900),     # ... 32 slots
+    ("f32", 32768, 32768, 900),      # ... the same in fp32
     ("bf16", 65544, 65552, 800),     # the narrowest row on 512 lanes with 256 registers (20 slots)
     ("bf16", 81920, 81920, 800),     # ... and the widest: all 20 slots used, every store behind the loads
     ("bf16", 100352, 100352, 800),   # 26 register slots
