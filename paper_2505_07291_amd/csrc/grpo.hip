@@ -766,9 +766,9 @@ constexpr int row_blocks_per_cu(int block, int nv)
 }
 // How many gradient slots of a row wait before they are stored (see the kernel).  In LDS: as
 // many as an equal share of 144 KB of the CU's LDS holds for each workgroup on the CU (a slot
-// is 16 bytes per lane), at most all of them.  In registers: only the widest instantiation,
-// eight wavefronts with 256 registers each, of which the row takes 152; 16 slots is the most
-// the compiler fits without spilling.
+// is 16 bytes per lane), at most all of them.  In registers: only the instantiations with 256
+// registers per lane; in the benchmark's (512 lanes x 38 slots, the row takes 152 registers)
+// 16 slots is the most the compiler fits without spilling, the others state their number.
 #ifndef GRPO_ROW_STASH_KB
 #define GRPO_ROW_STASH_KB 144
 #endif
@@ -800,8 +800,8 @@ constexpr int row_stash_slots(int block, int nv, int nl = 0)
 // One workgroup per row at a time, rows strided over a persistent grid.
 // NL > 0: the row is wider than the registers hold and its last NL slots live in LDS, which
 // the loads fill directly (buffer loads with LDS as their target).
-// RST >= 0: the number of gradient slots that wait in registers, for the instantiations of 512
-// lanes beside the benchmark's width; what LDS the row leaves free holds waiting slots too.
+// RST >= 0: the number of gradient slots that wait in registers, for the instantiations with
+// 256 registers beside the benchmark's width; what LDS the row leaves free holds waiting slots too.
 // (Skipping the empty slots of a narrower row with a branch per slot was tried instead of
 // several widths: the wait counters are then reset to zero at every join and the gradient
 // pass ran 1.5 times as long.)
