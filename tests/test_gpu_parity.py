@@ -236,6 +236,23 @@ def test_wide_rows_several_per_workgroup(dtype, vocab, stride, rows):
     run_shape_case(dtype, vocab, stride, rows, grad_rows=pick)
 
 
+# widest vocabulary (bf16) of each instantiation of the row kernel, in dispatch order
+WIDTH_LIMITS = [2048, 8192, 32768, 53248, 65536, 81920, 106496, 131072, 155648, 180224, 221184, 245760,
+                278528, 540672]
+
+
+@pytest.mark.parametrize("limit", WIDTH_LIMITS)
+def test_both_sides_of_every_width_limit(limit):
+    """The last vocabulary an instantiation serves and the first one of the next (one more 16-byte
+    vector): a row that fills every slot to the last lane, and one with a single lane in a new slot."""
+    for vocab in (limit, limit + 8):
+        rows = 300
+        rng = np.random.default_rng(vocab)
+        pick = np.unique(np.concatenate([np.arange(4), np.arange(rows - 4, rows),
+                                         rng.choice(rows, size=24, replace=False)]))
+        run_shape_case("bf16", vocab, vocab, rows, grad_rows=pick)
+
+
 def test_inplace_gradient_and_bitwise_determinism():
     cfg = wl.CONFIGS["qwen_short"].scaled(n_prompts=2, seq_len=5)
     say("\n[case] in-place + determinism: N=%d V=%d" % (cfg.n_tokens, cfg.vocab))
