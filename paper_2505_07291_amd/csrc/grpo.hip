@@ -1561,13 +1561,16 @@ void launch_cached(const RowParams &p, int blocks_per_cu, hipStream_t st)
                        lds_bytes, st, p);
 }
 
+#ifndef GRPO_QUEUE_CHUNK_BYTES
+#define GRPO_QUEUE_CHUNK_BYTES 32768
+#endif
 template <grpo_dtype DT, bool AUX>
 void launch_rows(const RowParams &p_in, hipStream_t st)
 {
     RowParams p = p_in;
     {   // rows per queue increment: 1 from 32 KB per row upwards, more for narrower rows
         const long long row_bytes = p.vocab * Elem<DT>::BYTES;
-        long long c = (32768 + row_bytes - 1) / row_bytes;
+        long long c = (GRPO_QUEUE_CHUNK_BYTES + row_bytes - 1) / row_bytes;
         p.queue_chunk = (int)(c < 1 ? 1 : (c > 64 ? 64 : c));
         p.queue_parts = row_bytes < 200 * 1024 ? kQueueParts : 1;
     }
