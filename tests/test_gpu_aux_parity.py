@@ -123,7 +123,7 @@ def test_aux_with_zero_coefficients_equals_the_plain_objective():
 
 
 @pytest.mark.parametrize("dtype,vocab,stride", [("bf16", 5, 8), ("bf16", 2047, 2048), ("bf16", 50257, 50264),
-                                                ("bf16", 152069, 152072), ("bf16", 200003, 200008),
+                                                ("bf16", 152069, 152072), ("bf16", 200003, 200008), ("bf16", 600000, 600000),
                                                 ("f32", 1000, 1004), ("f32", 100003, 100004)])
 def test_aux_ragged_shapes(dtype, vocab, stride):
     run_aux_shape_case(dtype, vocab, stride, 29)

@@ -147,8 +147,9 @@ RAGGED = [
     ("bf16", 1, 8), ("bf16", 5, 8), ("bf16", 8, 8), ("bf16", 2047, 2048), ("bf16", 2048, 2048),
     ("bf16", 8200, 8208), ("bf16", 50257, 50264), ("bf16", 81921, 81928),
     ("bf16", 152064, 152064), ("bf16", 152069, 152072), ("bf16", 155649, 155656), ("bf16", 200003, 200008),
+    ("bf16", 600000, 600000),                    # too wide to keep half of it resident: streamed
     ("f32", 1, 4), ("f32", 3, 4), ("f32", 1000, 1004), ("f32", 4099, 4100), ("f32", 40001, 40004),
-    ("f32", 40000, 40000), ("f32", 77824, 77824), ("f32", 100003, 100004),
+    ("f32", 40000, 40000), ("f32", 77824, 77824), ("f32", 100003, 100004), ("f32", 300000, 300000),
 ]
 
 
