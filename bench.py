@@ -165,6 +165,11 @@ def main():
                     help="skip the fused language-model-head leg (hidden states and head weights in)")
     ap.add_argument("--d-model", type=int, default=5120,
                     help="hidden size of the language-model-head leg (5120: a 32B Qwen-family model)")
+    ap.add_argument("--vocab", type=int, default=0,
+                    help="another vocabulary size for the workload's recipe (rows scaled to keep the "
+                         "bytes of logits); not the headline configuration, no language-model-head leg")
+    ap.add_argument("--logits-dtype", choices=["bf16", "f32"], default=None,
+                    help="another storage type for the logits, as --vocab")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 1 GiB device copies (reference for HBM counters)")
     args = ap.parse_args()
@@ -182,6 +187,17 @@ def main():
     torch.cuda.set_device(0)
     dev = "cuda:0"
     cfg = wl.CONFIGS[args.workload]
+    variant = ""
+    if args.vocab or args.logits_dtype:
+        # the same recipe at another row width: the sequence length takes up the difference
+        import dataclasses
+        esz0 = 2 if cfg.dtype == "bf16" else 4
+        dt = args.logits_dtype or cfg.dtype
+        vocab = args.vocab or cfg.vocab
+        L = max(1, round(cfg.seq_len * cfg.vocab * esz0 / (vocab * (2 if dt == "bf16" else 4))))
+        cfg = dataclasses.replace(cfg.scaled(seq_len=L, vocab=vocab), dtype=dt)
+        variant = "@V=%d,%s" % (vocab, dt)
+        args.no_lmhead = True
     N, V = cfg.n_tokens, cfg.vocab
     log("[bench] generating %s: N=%d V=%d %s (%.2f GB of logits)" %
         (cfg.name, N, V, cfg.dtype, N * V * (2 if cfg.dtype == "bf16" else 4) / 1e9))
@@ -300,11 +316,12 @@ def main():
         torch.cuda.synchronize()
 
     out = {
-        "metric": "GRPO loss fwd+bwd tokens/s (V=152064 bf16)" if V == 152064 else "GRPO loss fwd+bwd tokens/s",
+        "metric": "GRPO loss fwd+bwd tokens/s (V=152064 bf16)" if V == 152064 and cfg.dtype == "bf16" else
+                  "GRPO loss fwd+bwd tokens/s (V=%d %s)" % (V, cfg.dtype),
         "value": N / wall, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": wall * 1e3, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": cfg.name, "n_tokens": N, "vocab": V, "logits_dtype": cfg.dtype,
+        "config": {"workload": cfg.name + variant, "n_tokens": N, "vocab": V, "logits_dtype": cfg.dtype,
                    "group_size": cfg.group_size, "n_rollouts": cfg.n_rollouts,
                    "rows_live": n_full, "rows_zero_coeff": n_zero_coeff, "rows_masked": n_masked,
                    "eps_low": cfg.eps_low, "eps_high": cfg.eps_high, "delta": cfg.delta,
@@ -312,7 +329,7 @@ def main():
         "counts": dict(zip(grpo.COUNT_NAMES, c)), "loss": loss_value,
         "roofline": {"bound": "hbm", "achieved": alg_bytes / kern / 1e9, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": alg_bytes / kern / 1e9 / HBM_PEAK_GBPS,
-                     "traffic": traffic_from_profiles(cfg.name),
+                     "traffic": None if variant else traffic_from_profiles(cfg.name),
                      "kernel": "grpo_rows_cached (inside grpo_loss_fwd_bwd)",
                      "kernel_ms": kern * 1e3, "kernel_ms_median": kern_spread["median"],
                      "kernel_ms_min": kern_spread["min"], "kernel_ms_max": kern_spread["max"],
