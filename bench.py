@@ -64,9 +64,23 @@ def cpu_baseline(batch, old, adv_tok, budget_s=10.0, block=512):
         done += r1 - r0
         live += int(mask[r0:r1].sum())
         r0 = r1 % N
-    return dict(value=done / t_used, unit="tokens/s", cores=orc.num_threads(), kind="oracle",
+    # the same on one thread, on the first rows of the batch (about a second)
+    threads = orc.num_threads()
+    n1 = min(N, 256)
+    z = batch["logits"][:n1].cpu()
+    z = z.view(torch.int16).numpy().view(np.uint16) if z.dtype == torch.bfloat16 else z.numpy()
+    orc.set_num_threads(1)
+    try:
+        t0 = time.perf_counter()
+        orc.loss_fwd_bwd(z, tokens[:n1], oldn[:n1], advn[:n1], mask[:n1], eps_low=cfg.eps_low,
+                         eps_high=cfg.eps_high, delta=cfg.delta, temperature=cfg.temperature, grad_rows="all")
+        t1 = time.perf_counter() - t0
+    finally:
+        orc.set_num_threads(threads)
+    return dict(value=done / t_used, unit="tokens/s", cores=threads, kind="oracle",
                 sample="%d rows of the batch in order from row 0, wrapping (%d unmasked), fp64 "
-                       "forward+backward in blocks of %d rows, %.1f s" % (done, live, block, t_used))
+                       "forward+backward in blocks of %d rows, %.1f s" % (done, live, block, t_used),
+                single_thread_value=n1 / t1, single_thread_sample="the first %d rows, %.1f s" % (n1, t1))
 
 
 def lmhead_leg(grpo, wl, cfg, d_model, dev, stream, reps):

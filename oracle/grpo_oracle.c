@@ -736,6 +736,9 @@ int oracle_lmhead_grad_weight(const double *G, int64_t n_rows, int64_t V,
 #ifdef _OPENMP
 #include <omp.h>
 int oracle_num_threads(void) { return omp_get_max_threads(); }
+/* Threads for the "for each row" loops from here on (the benchmark also reports one thread). */
+void oracle_set_num_threads(int n) { omp_set_num_threads(n > 0 ? n : 1); }
 #else
 int oracle_num_threads(void) { return 1; }
+void oracle_set_num_threads(int n) { (void)n; }
 #endif

@@ -91,6 +91,8 @@ def lib():
         L.oracle_lmhead_grad_weight.argtypes = [vp, i64, i64, vp, i32, i64, i64, vp, i64, vp]
         L.oracle_num_threads.restype = i32
         L.oracle_num_threads.argtypes = []
+        L.oracle_set_num_threads.restype = None
+        L.oracle_set_num_threads.argtypes = [i32]
         _lib = L
     return _lib
 
@@ -119,6 +121,11 @@ def _logits_view(logits):
 
 def num_threads() -> int:
     return int(lib().oracle_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    """Threads used by the row loops from now on (results do not depend on it)."""
+    lib().oracle_set_num_threads(int(n))
 
 
 def group_advantages(rewards, group_size=None, group_offsets=None, eps_std=1e-6, ddof=0):
