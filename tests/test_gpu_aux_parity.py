@@ -181,7 +181,8 @@ def test_aux_only_entropy_no_reference():
 @pytest.mark.parametrize("name", ["qwen_short", "numerics_stress"])
 def test_aux_full_size(name):
     """Benchmark shapes: log-probs, entropies, the four loss scalars and the counters for every
-    row; gradients element by element on sampled rows of every class."""
+    row; gradients element by element on sampled rows of every class and on the unmasked rows of a
+    seeded sample of 8192 rows; masked rows zero throughout."""
     from helpers import sample_rows_by_class
     cfg = wl.CONFIGS[name]
     klc, enc = 0.001, 1e-4                                     # section 4.1
@@ -218,25 +219,41 @@ def test_aux_full_size(name):
     assert abs(got[1] - want["policy"]) <= TOL_LOSS_REL * abs(want["policy"])
     assert abs(got[2] - want["kl"]) <= 1e-4 * want["kl"] + 1e-9
     assert abs(got[3] - want["entropy"]) <= 1e-4 * want["entropy"] + 2e-7
-    rows = sample_rows_by_class(want["coeff"], mask_np, np.random.default_rng(7), 40)
-    rows_t = torch.as_tensor(rows, device=DEV)
-    z_rows = logits_to_numpy(batch["logits"][rows_t])
-    g_orc = orc.aux_grad_rows(z_rows, tokens_np[rows], want["coeff"][rows], want["ent_coeff"][rows], T, vocab=V)
-    g_gpu = grads_to_f64(grad[rows_t])
     M = int(mask_np.sum())
-    zf = batch["logits"][rows_t].float().cpu().numpy().astype(np.float64)
-    pmax = np.exp(zf.max(axis=1) / T - zf[np.arange(len(rows)), tokens_np[rows]] / T + lp_orc[rows])
-    floor = (klc / (M * T) * 2.0 ** -22 * np.maximum(np.abs(lp_orc[rows]), 1.0) +
-             enc / (M * T) * pmax * np.maximum(H_orc[rows], 1.0) * 2.0 ** -20)
-    rowmax = np.max(np.abs(g_orc), axis=1)
-    err = np.max(np.abs(g_gpu - g_orc), axis=1) - floor
-    masked = mask_np[rows] == 0
-    assert not g_gpu[masked].any()
-    live = rowmax > 0
-    worst = float(np.max(err[live] / rowmax[live]))
+
+    def worst_error(rows):
+        """Largest gradient error of these rows in units of their row maximum, beyond the floors."""
+        rows_t = torch.as_tensor(rows, device=DEV)
+        z_rows = logits_to_numpy(batch["logits"][rows_t])
+        g_orc = orc.aux_grad_rows(z_rows, tokens_np[rows], want["coeff"][rows], want["ent_coeff"][rows], T, vocab=V)
+        g_gpu = grads_to_f64(grad[rows_t])
+        zf = batch["logits"][rows_t].float().cpu().numpy().astype(np.float64)
+        pmax = np.exp(zf.max(axis=1) / T - zf[np.arange(len(rows)), tokens_np[rows]] / T + lp_orc[rows])
+        assert np.all(pmax[mask_np[rows] != 0] <= 1.0 + 1e-9)      # a probability where the row takes part
+        floor = (klc / (M * T) * 2.0 ** -22 * np.maximum(np.abs(lp_orc[rows]), 1.0) +
+                 enc / (M * T) * pmax * np.maximum(H_orc[rows], 1.0) * 2.0 ** -20)
+        rowmax = np.max(np.abs(g_orc), axis=1)
+        err = np.max(np.abs(g_gpu - g_orc), axis=1) - floor
+        assert not g_gpu[mask_np[rows] == 0].any()
+        live = rowmax > 0
+        return float(np.max(err[live] / rowmax[live])) if live.any() else 0.0
+
+    rows = sample_rows_by_class(want["coeff"], mask_np, np.random.default_rng(7), 40)
+    worst = worst_error(rows)
     assert worst <= TOL_GRAD, worst
-    say("  ok: total=%.6g policy=%.6g kl=%.4g H=%.5g grad=%.2e x rowmax on %d rows" %
-        (got[0], got[1], got[2], got[3], worst, len(rows)))
+    # ... and on a seeded sample of 8192 rows, in blocks (with an entropy term every unmasked row
+    # has a gradient); masked rows of the whole batch must be zero
+    sample = np.sort(np.random.default_rng(2000 + cfg.index).choice(N, size=min(N, 8192), replace=False))
+    sample = sample[mask_np[sample] != 0]
+    for b in range(0, len(sample), 256):
+        worst = max(worst, worst_error(sample[b:b + 256]))
+    assert worst <= TOL_GRAD, worst
+    masked_t = torch.as_tensor(mask_np == 0, device=DEV)
+    for r0 in range(0, N, 8192):
+        blk = grad[r0:r0 + 8192][masked_t[r0:r0 + 8192]]
+        assert not bool(blk.any()), "a masked row is not zero"
+    say("  ok: total=%.6g policy=%.6g kl=%.4g H=%.5g grad=%.2e x rowmax on %d + %d rows" %
+        (got[0], got[1], got[2], got[3], worst, len(rows), len(sample)))
 
 
 @pytest.mark.parametrize("sample_level", [True, False])

@@ -404,7 +404,8 @@ FULL = ["qwen_short", "qwen_medium", "long_reasoning", "numerics_stress"]
 def test_full_size_configs(name):
     """The benchmark's own shapes and launch configuration.  Log-probs, loss and counters
     are compared for every row (the oracle streams the logits in blocks); gradients are
-    compared element by element on sampled rows of every row class, and for all rows
+    compared element by element on sampled rows of every row class and on a seeded sample of
+    8192 rows, and for all rows
     through two properties that hold at any size: rows with zero coefficient are exactly
     zero, and the largest |gradient| of a row sits on the sampled token, where it equals
     (c/T)(1 - p_y)."""
@@ -447,5 +448,22 @@ def test_full_size_configs(name):
     slack = (coeff[live] / T).abs() * 1.5e-14
     assert bool(((g_y[live] - expect[live]).abs() <= TOL_GRAD * scale + slack).all())
     assert bool(((rowmax[live].double() - scale).abs() <= TOL_GRAD * scale + slack).all())
+    # element by element on a seeded sample of 8192 rows of the batch.  Every class occurs in it;
+    # its rows with a zero coefficient were compared exactly above (all of them are zero), the
+    # live ones go through the oracle in blocks
+    sample = np.sort(np.random.default_rng(1000 + cfg.index).choice(N, size=min(N, 8192), replace=False))
+    live_s = sample[pre["coeff"][sample] != 0]
+    tokens_np = batch["tokens"].cpu().numpy()
+    worst = 0.0
+    for b in range(0, len(live_s), 256):
+        rows_b = live_s[b:b + 256]
+        rt = torch.as_tensor(rows_b, device=DEV)
+        g_orc = orc.grad_rows(logits_to_numpy(batch["logits"][rt]), tokens_np[rows_b], pre["coeff"][rows_b],
+                              temperature=T, vocab=cfg.vocab)
+        top = np.abs(g_orc).max(axis=1)
+        assert (top > 0).all()
+        worst = max(worst, float((np.abs(grads_to_f64(grad[rt]) - g_orc).max(axis=1) / top).max()))
+    say("  sample of %d rows (%d live): grad=%.2e x rowmax" % (len(sample), len(live_s), worst))
+    assert worst <= TOL_GRAD, "grad error %g x row max on the large sample" % worst
     del batch, out, grad
     torch.cuda.empty_cache()
