@@ -153,30 +153,33 @@ RAGGED = [
 ]
 
 
-def run_shape_case(dtype, vocab, stride, N, grad_rows="all"):
-    say("\n[case] shape dtype=%s V=%d stride=%d N=%d" % (dtype, vocab, stride, N))
-    g = torch.Generator().manual_seed(vocab * 7 + (dtype == "f32"))
+def run_shape_case(dtype, vocab, stride, N, grad_rows="all", *, temperature=0.9, eps_low=0.2, eps_high=0.28,
+                   delta=3.0, denom=50.0, grad_scale=2.5, masked=0.25, seed=None):
+    say("\n[case] shape dtype=%s V=%d stride=%d N=%d T=%g eps=%g/%g delta=%g denom=%g scale=%g" %
+        (dtype, vocab, stride, N, temperature, eps_low, eps_high, delta, denom, grad_scale))
+    g = torch.Generator().manual_seed(vocab * 7 + (dtype == "f32") if seed is None else seed)
     dt = torch.bfloat16 if dtype == "bf16" else torch.float32
     store = torch.full((N, stride), 7.0, dtype=dt)            # padding holds a sentinel
     store[:, :vocab] = (torch.randn((N, vocab), generator=g) * 3).to(dt)
     store = store.to(DEV)
     logits = store[:, :vocab]
     tokens = torch.randint(0, vocab, (N,), generator=g)
-    tokens[0], tokens[1] = vocab - 1, 0                        # first and last element of a row
-    mask = (torch.rand(N, generator=g) > 0.25).to(torch.uint8)
+    tokens[0], tokens[-1] = vocab - 1, 0                       # last and first element of a row
+    mask = (torch.rand(N, generator=g) > masked).to(torch.uint8)
     mask[:2] = 1
     batch = dict(logits=logits, tokens=tokens.to(DEV), mask=mask.to(DEV), n_tokens=N, vocab=vocab,
-                 temperature=0.9, eps_low=0.2, eps_high=0.28, delta=3.0)
+                 temperature=temperature, eps_low=eps_low, eps_high=eps_high, delta=delta)
     lp_orc = oracle_logprobs_blocked(batch)
     noise = torch.rand(N, generator=g, dtype=torch.float64) * 4 - 2
-    kinks = np.log([0.8, 1.28, 3.0])
+    kinks = np.log([1.0 - f32(eps_low), 1.0 + f32(eps_high), f32(delta)]) if eps_low < 1 else \
+        np.log([1.0 + f32(eps_high), f32(delta)])
     for t in range(N):                                         # keep clear of the kinks
         while np.min(np.abs(-float(noise[t]) - kinks)) < 1e-3:
             noise[t] = torch.rand(1, generator=g, dtype=torch.float64)[0] * 4 - 2
     old = (torch.as_tensor(lp_orc) + noise).to(torch.float32)
     adv = torch.randn(N, generator=g).numpy().astype(np.float32)
-    adv[3] = 0.0
-    out = check_against_oracle(batch, old, lp_orc, adv, denom=50.0, grad_scale=2.5, label="shape",
+    adv[N // 2] = 0.0
+    out = check_against_oracle(batch, old, lp_orc, adv, denom=denom, grad_scale=grad_scale, label="shape",
                                grad_rows=grad_rows)
     pad = store[:, vocab:]
     assert bool((pad == 7.0).all()), "logits padding was written"
@@ -184,14 +187,37 @@ def run_shape_case(dtype, vocab, stride, N, grad_rows="all"):
     gbuf = torch.full((N, stride), 3.0, dtype=dt, device=DEV)
     gview = gbuf[:, :vocab]
     grpo.grpo_loss_fwd_bwd(logits, batch["tokens"], old.to(DEV), torch.as_tensor(adv, device=DEV),
-                           batch["mask"], f32(0.2), f32(0.28), f32(3.0), f32(0.9), 50.0, 2.5,
-                           grad_logits=gview)
+                           batch["mask"], f32(eps_low), f32(eps_high), f32(delta), f32(temperature), denom,
+                           grad_scale, grad_logits=gview)
     torch.cuda.synchronize()
     assert bool((gbuf[:, vocab:] == 3.0).all()), "gradient padding was written"
     assert torch.equal(gview, out["grad"])
-    lp_fwd = grpo.grpo_logprobs_fwd(logits, batch["tokens"], batch["mask"], temperature=f32(0.9))
+    lp_fwd = grpo.grpo_logprobs_fwd(logits, batch["tokens"], batch["mask"], temperature=f32(temperature))
     torch.cuda.synchronize()
     assert torch.equal(lp_fwd, out["logprobs"])
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes_and_parameters(seed):
+    """Seeded draws over the whole argument space at once: storage type, vocabulary from a handful of
+    entries to 300000 (half of them ending inside a 16-byte vector), padded row pitch, row count,
+    share of masked rows, temperature, both clip widths, the cap, denominator and upstream gradient."""
+    rng = np.random.default_rng(4242 + seed)
+    dtype = "bf16" if rng.random() < 0.7 else "f32"
+    epv = 8 if dtype == "bf16" else 4
+    vocab = int(np.exp(rng.uniform(np.log(2), np.log(300000 if dtype == "bf16" else 150000))))
+    if rng.random() < 0.5:
+        vocab = max(epv, vocab // epv * epv)
+    stride = (vocab + epv - 1) // epv * epv + epv * int(rng.integers(0, 3))
+    N = int(min(rng.integers(2, 700), max(2, 120_000_000 // vocab)))
+    eps_high = float(rng.uniform(0.05, 0.5))
+    kw = dict(temperature=float(rng.uniform(0.5, 1.5)), eps_low=float(rng.uniform(0.05, 0.5)), eps_high=eps_high,
+              delta=1.0 + eps_high + float(rng.uniform(0.2, 4.0)),
+              denom=0.0 if rng.random() < 0.3 else float(rng.uniform(10, 1000)),
+              grad_scale=f32(rng.uniform(0.1, 4.0)), masked=float(rng.uniform(0.0, 0.9)), seed=977 * seed + 1)
+    rows = "all" if N * vocab <= 20_000_000 else np.unique(np.concatenate(
+        [[0, 1, N - 1], rng.choice(N, size=min(N, 24), replace=False)]))
+    run_shape_case(dtype, vocab, stride, N, grad_rows=rows, **kw)
 
 
 @pytest.mark.parametrize("dtype,vocab,stride", RAGGED)
