@@ -297,7 +297,7 @@ grpo_status grpo_workspace_error(const void *workspace, int32_t *flag_out, void 
  *           elements (>= d_model), base and pitch 16-byte aligned.
  *  weight   [vocab, d_model] bf16, device, read; row v holds the d_model weights of
  *           vocabulary entry v; row pitch weight_stride, aligned like hidden.
- *  d_model  a multiple of 32, at most 2^20.  vocab in [1, 2^28].
+ *  d_model  a multiple of 64 (one step of the contraction), at most 2^20.  vocab in [1, 2^28].
  *  tokens, mask, temperature, old_logprobs, advantages, eps_low, eps_high, delta,
  *  denom, grad_scale, loss_out, logprobs_out, counts_out: as in
  *           grpo_logprobs_fwd / grpo_loss_fwd_bwd.
@@ -314,7 +314,7 @@ grpo_status grpo_workspace_error(const void *workspace, int32_t *flag_out, void 
  * objective has no gradient (clipped, delta-capped, zero advantage): the rows that
  * take part are compacted on the device first.
  * Errors as for grpo_loss_fwd_bwd; additionally GRPO_ERR_SHAPE when d_model is not
- * a multiple of 32 or a pitch is smaller than d_model.  All work is enqueued on
+ * a multiple of 64 or a pitch is smaller than d_model.  All work is enqueued on
  * `stream`; nothing is allocated.
  * ------------------------------------------------------------------------- */
 

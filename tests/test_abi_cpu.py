@@ -163,7 +163,7 @@ def lmhead_args(**over):
 @pytest.mark.parametrize("over,expect", [
     (dict(hidden=None), NULL), (dict(weight=None), NULL), (dict(tokens=None), NULL), (dict(old=None), NULL),
     (dict(adv=None), NULL), (dict(loss=None), NULL), (dict(gh=None), NULL), (dict(gw=None), NULL),
-    (dict(n=-1), SHAPE), (dict(V=0), SHAPE), (dict(d=0), SHAPE), (dict(d=80, hs=80, wstride=80), SHAPE),
+    (dict(n=-1), SHAPE), (dict(V=0), SHAPE), (dict(d=0), SHAPE), (dict(d=80, hs=80, wstride=80), SHAPE), (dict(d=96, hs=96, wstride=96), SHAPE),
     (dict(hs=64), SHAPE), (dict(wstride=120), SHAPE), (dict(ghs=64), SHAPE), (dict(gws=100), SHAPE),
     (dict(V=(1 << 28) + 1), SHAPE), (dict(d=1 << 21, hs=1 << 21, wstride=1 << 21), SHAPE),
     (dict(hidden=P + 8), ALIGN), (dict(weight=P + 2), ALIGN), (dict(hs=132), ALIGN), (dict(wstride=129), ALIGN),
@@ -218,7 +218,7 @@ def lmhead_aux_args(**over):
 @pytest.mark.parametrize("over,expect", [
     (dict(hidden=None), NULL), (dict(old=None), NULL), (dict(loss=None), NULL), (dict(gw=None), NULL),
     (dict(ref=None), NULL),                       # a KL coefficient needs the reference log-probs
-    (dict(n=-1), SHAPE), (dict(d=80, hs=80, wstride=80), SHAPE), (dict(ghs=64), SHAPE),
+    (dict(n=-1), SHAPE), (dict(d=80, hs=80, wstride=80), SHAPE), (dict(d=96, hs=96, wstride=96), SHAPE), (dict(ghs=64), SHAPE),
     (dict(weight=P + 2), ALIGN),
     (dict(T=0.0), PARAM), (dict(delta=1.2), PARAM), (dict(klc=float("inf")), PARAM),
     (dict(enc=float("nan")), PARAM),

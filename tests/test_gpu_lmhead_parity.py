@@ -134,6 +134,23 @@ def test_reduced_configs_every_element(name, P, G, L, V, D):
     run_case(cfg, D, label="%s %dx%dx%d" % (name, P * G * L, V, D))
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_random_shapes_and_parameters(seed):
+    """Seeded draws over recipe, row count, vocabulary, hidden size (any multiple of 64), denominator
+    and upstream gradient; every element compared."""
+    rng = np.random.default_rng(777 + seed)
+    name = ["qwen_short", "long_reasoning", "numerics_stress"][int(rng.integers(0, 3))]
+    G = int(rng.choice([2, 4, 8]))
+    cfg = wl.CONFIGS[name].scaled(n_prompts=int(rng.integers(2, 5)), seq_len=int(rng.integers(3, 70)),
+                                  vocab=int(rng.integers(2, 4000)), group_size=G)
+    if cfg.logits not in ("normal", "normal_boost"):
+        cfg = wl.replace(cfg, logits="normal", logit_std=3.0)
+    d = 64 * int(rng.integers(1, 9))
+    denom = 0.0 if rng.random() < 0.4 else float(rng.uniform(20, 2000))
+    say("\n[case] lmhead random %d: %s N=%d V=%d d=%d" % (seed, name, cfg.n_tokens, cfg.vocab, d))
+    run_case(cfg, d, denom=denom, grad_scale=f32(rng.uniform(0.2, 3.0)), label="random %d" % seed)
+
+
 def test_denominator_grad_scale_accumulate_and_determinism():
     cfg = wl.CONFIGS["qwen_short"].scaled(n_prompts=2, seq_len=40, vocab=1500, group_size=4)
     batch, old, adv_tok, out = run_case(cfg, 128, denom=1000.0, grad_scale=2.5, label="denom/scale")
@@ -254,7 +271,7 @@ def test_edge_cases():
     assert abs(loss.item() + 1.0) < 1e-6      # r = 1, A = 1: loss = -1
     # argument errors are reported, not launched
     with pytest.raises(grpo.GrpoError):
-        grpo.grpo_lmhead_logprobs_fwd(h[:, :48], w[:, :48], tok)        # d_model not a multiple of 32
+        grpo.grpo_lmhead_logprobs_fwd(h[:, :48], w[:, :48], tok)        # d_model not a multiple of 64
     with pytest.raises(grpo.GrpoError):
         grpo.grpo_lmhead_loss_fwd_bwd(h, w, tok, z, z, m1, delta=1.1)    # delta <= 1 + eps_high
     with pytest.raises(grpo.GrpoError):
