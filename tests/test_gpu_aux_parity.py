@@ -138,33 +138,69 @@ def test_aux_wide_rows_several_per_workgroup(dtype, vocab, rows):
     run_aux_shape_case(dtype, vocab, vocab, rows)
 
 
-def run_aux_shape_case(dtype, vocab, stride, N):
-    say("\n[case] aux shape dtype=%s V=%d stride=%d N=%d" % (dtype, vocab, stride, N))
-    g = torch.Generator().manual_seed(vocab * 3 + 1)
+def run_aux_shape_case(dtype, vocab, stride, N, *, temperature=0.8, eps_low=0.2, eps_high=0.28, delta=3.0,
+                       kl_coef=0.04, ent_coef=0.03, denom=40.0, grad_scale=1.5, masked=0.2, weights=False,
+                       seed=None):
+    say("\n[case] aux shape dtype=%s V=%d stride=%d N=%d T=%g eps=%g/%g delta=%g kl=%g ent=%g denom=%g scale=%g%s"
+        % (dtype, vocab, stride, N, temperature, eps_low, eps_high, delta, kl_coef, ent_coef, denom, grad_scale,
+           " weights" if weights else ""))
+    g = torch.Generator().manual_seed(vocab * 3 + 1 if seed is None else seed)
     dt = torch.bfloat16 if dtype == "bf16" else torch.float32
     store = torch.full((N, stride), 7.0, dtype=dt)
     store[:, :vocab] = (torch.randn((N, vocab), generator=g) * 3).to(dt)
-    if vocab > 100:
+    if vocab > 100 and N > 3:
         store[3, 10:60] = float("-inf")                       # masked vocabulary entries
     store = store.to(DEV)
     tokens = torch.randint(0, vocab, (N,), generator=g)
-    tokens[3] = 0
-    mask = (torch.rand(N, generator=g) > 0.2).to(torch.uint8)
+    tokens[min(3, N - 1)] = 0
+    mask = (torch.rand(N, generator=g) > masked).to(torch.uint8)
     mask[:4] = 1
     batch = dict(logits=store[:, :vocab], tokens=tokens.to(DEV), mask=mask.to(DEV), n_tokens=N,
-                 vocab=vocab, temperature=0.8, eps_low=0.2, eps_high=0.28, delta=3.0)
+                 vocab=vocab, temperature=temperature, eps_low=eps_low, eps_high=eps_high, delta=delta)
     lp_orc = oracle_logprobs_blocked(batch)
     noise = torch.rand(N, generator=g, dtype=torch.float64) * 3 - 1.5
-    kinks = np.log([0.8, 1.28, 3.0])
+    kinks = np.log([1.0 - f32(eps_low), 1.0 + f32(eps_high), f32(delta)])
     for t in range(N):
         while np.min(np.abs(-float(noise[t]) - kinks)) < 1e-3:
             noise[t] = torch.rand(1, generator=g, dtype=torch.float64)[0] * 3 - 1.5
     old = (torch.as_tensor(lp_orc) + noise).float()
-    ref = (torch.as_tensor(lp_orc) + torch.randn(N, generator=g, dtype=torch.float64) * 0.3).float()
+    ref = None
+    if kl_coef != 0.0:
+        ref = (torch.as_tensor(lp_orc) + torch.randn(N, generator=g, dtype=torch.float64) * 0.3).float()
     adv = torch.randn(N, generator=g).numpy().astype(np.float32)
-    adv[2] = 0.0
-    run_aux_case(batch, old, ref, adv, 0.04, 0.03, denom=40.0, grad_scale=1.5, label="ragged")
+    adv[N // 2] = 0.0
+    tw = None
+    if weights:                                               # per-token weights, a few of them zero
+        tw = (torch.rand(N, generator=g) * 2).float()
+        tw[torch.rand(N, generator=g) < 0.1] = 0.0
+        tw = tw.to(DEV)
+    run_aux_case(batch, old, ref, adv, kl_coef, ent_coef, denom=denom, grad_scale=grad_scale, label="shape",
+                 token_weights=tw)
     assert bool((store[:, vocab:] == 7.0).all())
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_aux_random_shapes_and_parameters(seed):
+    """Seeded draws over storage type, vocabulary (half of them ending inside a 16-byte vector), pitch,
+    row count, mask share, per-token weights, both coefficients (either may be zero) and every scalar
+    parameter; every element compared."""
+    rng = np.random.default_rng(9090 + seed)
+    dtype = "bf16" if rng.random() < 0.7 else "f32"
+    epv = 8 if dtype == "bf16" else 4
+    vocab = int(np.exp(rng.uniform(np.log(2), np.log(300000 if dtype == "bf16" else 150000))))
+    if rng.random() < 0.5:
+        vocab = max(epv, vocab // epv * epv)
+    stride = (vocab + epv - 1) // epv * epv + epv * int(rng.integers(0, 3))
+    N = int(min(rng.integers(4, 400), max(4, 30_000_000 // vocab)))
+    eps_high = float(rng.uniform(0.05, 0.5))
+    kl = 0.0 if rng.random() < 0.25 else float(rng.uniform(0.001, 0.1))
+    ent = 0.0 if rng.random() < 0.25 else float(rng.uniform(1e-4, 0.05))
+    run_aux_shape_case(dtype, vocab, stride, N, temperature=float(rng.uniform(0.5, 1.5)),
+                       eps_low=float(rng.uniform(0.05, 0.5)), eps_high=eps_high,
+                       delta=1.0 + eps_high + float(rng.uniform(0.2, 4.0)), kl_coef=f32(kl), ent_coef=f32(ent),
+                       denom=0.0 if rng.random() < 0.3 else float(rng.uniform(10, 1000)),
+                       grad_scale=f32(rng.uniform(0.1, 4.0)), masked=float(rng.uniform(0.0, 0.8)),
+                       weights=bool(rng.random() < 0.5), seed=313 * seed + 5)
 
 
 def test_aux_only_entropy_no_reference():
