@@ -508,3 +508,28 @@ def test_staged_entry_points_agree_with_one_call_form():
     pick = np.array([3, 0, 17, 49])
     g = orc.grad_rows(z[pick], tokens[pick], obj["coeff"][pick], temperature=T)
     assert np.array_equal(g, one["grad"][pick])
+
+
+def test_results_do_not_depend_on_the_thread_count():
+    """The row loops are the only parallel part and the reductions over rows run in row order:
+    one thread, three threads and all of them give the same bits."""
+    rng = np.random.default_rng(5)
+    N, V = 300, 1000
+    z = rng.normal(0, 3, (N, V)).astype(np.float32)
+    tok = rng.integers(0, V, N)
+    old = rng.normal(-7, 0.3, N).astype(np.float32)
+    adv = rng.normal(0, 1, N).astype(np.float32)
+    mask = (rng.random(N) > 0.2).astype(np.uint8)
+    threads = orc.num_threads()
+    outs = []
+    try:
+        for n in (1, 3, threads):
+            orc.set_num_threads(n)
+            assert orc.num_threads() == n
+            outs.append(orc.loss_fwd_bwd(z, tok, old, adv, mask, eps_low=0.2, eps_high=0.2, delta=4.0,
+                                         temperature=1.0, grad_rows="all"))
+    finally:
+        orc.set_num_threads(threads)
+    for o in outs[1:]:
+        for k in ("loss", "logprobs", "counts", "J", "coeff", "grad"):
+            assert np.array_equal(np.asarray(outs[0][k]), np.asarray(o[k])), k
