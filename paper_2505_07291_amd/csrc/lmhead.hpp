@@ -46,7 +46,7 @@ constexpr int LM_LDS_BYTES = LM_SLOTS * LM_TILE_BYTES;
 constexpr int LM_GROUP_M = 8;                        // tile rows that share a sweep along N
 constexpr int LM_GM_BWD = 4;                         // the same for the two gradient products: their A panels (G, G^T)
                                                      // come from HBM, and a lower group re-reads them less often
-constexpr int LM_SPLIT_MAX = 4;                      // parts the contraction of dL/dH may be cut into
+constexpr int LM_SPLIT_MAX = 32;                     // parts the contraction of one tile of dL/dH may be cut into
 
 enum { LM_EPI_LSE = 0, LM_EPI_BF16 = 1, LM_EPI_F32 = 2 };
 
@@ -64,10 +64,11 @@ struct GemmParams {
     void *C;
     long long ldc;
     const int *c_rows;   // LM_EPI_BF16, optional: row i of the result goes to row c_rows[i] of C
-    // LM_EPI_BF16, optional split of the contraction (split_max > 1): the kernel picks a number of
-    // parts S <= split_max from the live tile count (lm_choose_split); with S > 1 part s of a tile
-    // goes as fp32 to split_ws[s][row][col] (rows of M, N columns) and lm_split_reduce finishes
-    int split_max, n_cu;
+    // LM_EPI_BF16, optional split of the contraction (split_items > 0): the tiles that do not fill
+    // a whole round of the CUs are cut into parts along K (lm_plan_split, from the live tile count);
+    // part s of the t-th such tile goes as a 256 x 256 fp32 block to split_ws[t * parts + s] and
+    // lm_split_reduce finishes.  split_items: how many such blocks split_ws holds.
+    int split_items, n_cu;
     float *split_ws;
     int accumulate;      // LM_EPI_F32: C += result
     // LM_EPI_LSE
@@ -88,41 +89,70 @@ struct GemmParams {
 // panels and most operand traffic is served by that XCD's L2.  The number of tile rows
 // comes from the device-side row count, so that the live tiles are spread over all XCDs
 // whatever part of the launched grid they are.
-__device__ __forceinline__ bool lm_map_tile(int tiles_m, int tiles_n, int splits, int group_m, int &tm, int &tn, int &part)
+__device__ __forceinline__ void lm_tile_of(int L, int tiles_m, int tiles_n, int group_m, int &tm, int &tn)
 {
-    const int tiles = tiles_m * tiles_n;
-    const int total = tiles * splits;
-    const int per_xcd = (total + 7) / 8;
-    int L = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
-    if ((int)(blockIdx.x >> 3) >= per_xcd || L >= total) return false;
-    part = L / tiles;  // the parts of the contraction one after the other: an XCD stays inside one part
-    L -= part * tiles;
     const int group_tiles = group_m * tiles_n;
     const int grp = L / group_tiles;
     const int in_grp = L - grp * group_tiles;
     const int rows_here = min(group_m, tiles_m - grp * group_m);
     tm = grp * group_m + in_grp % rows_here;
     tn = in_grp / rows_here;
-    return true;
 }
 
-// Into how many parts the contraction is cut when the tiles alone fill the CUs badly (a product
-// with 780 tiles on 256 CUs runs four rounds, the last one on twelve CUs): the S <= split_max
-// with the fewest rounds of work per CU, counted in whole tiles, plus 3 % of a tile per extra part
-// for the fp32 partial results and their sum.  Every workgroup, and lm_split_reduce, computes the
-// same value from the same numbers.
-__device__ __forceinline__ int lm_choose_split(int tiles, int k_tiles, int split_max, int n_cu)
+// A product whose tiles do not fill whole rounds of the CUs (780 tiles on 256 CUs: three rounds
+// and twelve tiles) would run its last round on a few CUs, each for a whole tile's time.  The
+// first `full` tiles of the order above (whole rounds) are therefore computed as they are, and
+// each of the `rest` that remain is cut into s2 parts along the contraction, so that the last
+// round is s2 times shorter and spread over all CUs: s2 minimises the rounds of parts, counted in
+// tile times, with a small charge per part for the fp32 partial results and their sum.  Every
+// workgroup, and lm_split_reduce, computes the same plan from the same numbers.
+struct LmSplit {
+    int full, rest, s2;
+};
+__device__ __forceinline__ LmSplit lm_plan_split(int tiles, int k_tiles, int max_items, int n_cu)
 {
-    int best = 1;
-    float best_cost = (float)((tiles + n_cu - 1) / n_cu);
-    for (int S = 2; S <= split_max && k_tiles / S >= 8; ++S) {
-        const float cost = (float)((tiles * S + n_cu - 1) / n_cu) / (float)S + 0.03f * (float)(S - 1);
-        if (cost < best_cost) {
-            best_cost = cost;
-            best = S;
+    LmSplit sp;
+    sp.rest = max_items > 0 ? tiles % n_cu : 0;
+    sp.full = tiles - sp.rest;
+    sp.s2 = 1;
+    if (sp.rest == 0) return sp;
+    const int lim = min(min(LM_SPLIT_MAX, k_tiles / 8), max_items / sp.rest);
+    float best = 1.f;
+    for (int S = 2; S <= lim; ++S) {
+        const float cost = (float)((sp.rest * S + n_cu - 1) / n_cu) / (float)S + 0.002f * (float)S;
+        if (cost < best) {
+            best = cost;
+            sp.s2 = S;
         }
     }
-    return best;
+    return sp;
+}
+
+// Workgroup -> tile (and part).  Each XCD takes a contiguous run of the whole tiles, then a
+// contiguous run of the parts, so that both kinds of work are spread evenly over the XCDs; the
+// parts are ordered part by part (the same K range of neighbouring tiles shares operand panels).
+// rest_index: which of the cut tiles this is, -1 for a whole tile.
+__device__ __forceinline__ bool lm_map_tile(int tiles_m, int tiles_n, const LmSplit &sp, int group_m, int &tm, int &tn,
+                                            int &part, int &rest_index)
+{
+    const int xcd = (int)(blockIdx.x & 7), idx = (int)(blockIdx.x >> 3);
+    const int per_xcd = (sp.full + 7) / 8;
+    int L;
+    part = 0;
+    rest_index = -1;
+    if (idx < per_xcd) {
+        L = xcd * per_xcd + idx;
+        if (L >= sp.full) return false;
+    } else {
+        const int items = sp.rest * sp.s2, items_per_xcd = (items + 7) / 8;
+        const int j = xcd * items_per_xcd + (idx - per_xcd);
+        if (idx - per_xcd >= items_per_xcd || j >= items) return false;
+        part = j / sp.rest;
+        rest_index = j - part * sp.rest;
+        L = sp.full + rest_index;
+    }
+    lm_tile_of(L, tiles_m, tiles_n, group_m, tm, tn);
+    return true;
 }
 
 template <int CTRL>
@@ -156,12 +186,14 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
     extern __shared__ __attribute__((aligned(1024))) char lm_smem[];
     const int M = p.M_dev ? min(*p.M_dev, p.M) : p.M;
     const int K = p.K_dev ? min((*p.K_dev + LM_BK - 1) / LM_BK * LM_BK, p.K) : p.K;
-    int tm, tn, part = 0, parts = 1;
+    int tm, tn, part = 0, parts = 1, rest_index = -1;
     {
         const int tiles_m = (M + LM_BM - 1) / LM_BM;
-        if (EPI == LM_EPI_BF16 && p.split_max > 1)
-            parts = lm_choose_split(tiles_m * p.tiles_n, K / LM_BK, p.split_max, p.n_cu);
-        if (!lm_map_tile(tiles_m, p.tiles_n, parts, p.group_m, tm, tn, part)) return;  // whole workgroup alike, before any barrier
+        const LmSplit sp = lm_plan_split(tiles_m * p.tiles_n, K / LM_BK, EPI == LM_EPI_BF16 ? p.split_items : 0,
+                                         p.n_cu > 0 ? p.n_cu : 256);
+        if (!lm_map_tile(tiles_m, p.tiles_n, sp, p.group_m, tm, tn, part, rest_index))
+            return;  // whole workgroup alike, before any barrier
+        if (rest_index >= 0) parts = sp.s2;
     }
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -333,7 +365,8 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
                     const int col = col0 + wcol + j * 32 + cl;
                     if (col >= p.N) continue;
                     if (EPI == LM_EPI_BF16 && parts > 1) {
-                        p.split_ws[((long long)part * p.M + row) * p.N + col] = acc[i][j][v];
+                        p.split_ws[(((long long)rest_index * parts + part) << 16) + (row - row0) * LM_BN + (col - col0)] =
+                            acc[i][j][v];
                     } else if (EPI == LM_EPI_BF16) {
                         ((__bf16 *)p.C)[orow * p.ldc + col] = (__bf16)acc[i][j][v];
                     } else {
@@ -767,24 +800,31 @@ __global__ void __launch_bounds__(256) lm_transpose(const __bf16 *in, long long 
     }
 }
 
-// Sum of the parts of a split product: C[c_rows[r]][:] = bf16(sum over s of ws[s][r][:]) for the
-// rows present, parts in order.  Does nothing when lm_gemm_nt chose not to split.
+// Sum of the parts of the tiles lm_gemm_nt has cut: C[c_rows[r]][:] = bf16(sum over s of the
+// tile's partial blocks) for the rows present, parts in order.  Does nothing when no tile was cut.
 __global__ void __launch_bounds__(256) lm_split_reduce(const float *ws, const int *M_dev, int M, int N, int tiles_n,
-                                                       int k_tiles, int split_max, int n_cu, const int *c_rows,
-                                                       __bf16 *C, long long ldc)
+                                                       int k_tiles, int max_items, int n_cu, int group_m,
+                                                       const int *c_rows, __bf16 *C, long long ldc)
 {
     const int rows = M_dev ? min(*M_dev, M) : M;
-    const int parts = lm_choose_split((rows + LM_BM - 1) / LM_BM * tiles_n, k_tiles, split_max, n_cu);
-    if (parts == 1) return;
-    const int quads = N / 4;  // N is a multiple of LM_BK
-    const long long total = (long long)rows * quads;
+    const int tiles_m = (rows + LM_BM - 1) / LM_BM;
+    const LmSplit sp = lm_plan_split(tiles_m * tiles_n, k_tiles, max_items, n_cu);
+    if (sp.s2 == 1) return;
+    constexpr int quads = LM_BN / 4;
+    const long long total = (long long)sp.rest * LM_BM * quads;
     for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long long)gridDim.x * 256) {
-        const int r = (int)(e / quads), c = (int)(e % quads) * 4;
-        f32x4 a = *(const f32x4 *)(ws + (long long)r * N + c);
-        for (int sp = 1; sp < parts; ++sp) a += *(const f32x4 *)(ws + ((long long)sp * M + r) * N + c);
+        const int t = (int)(e / (LM_BM * quads)), in_tile = (int)(e % (LM_BM * quads));
+        const int r = in_tile / quads, c = in_tile % quads * 4;
+        int tm, tn;
+        lm_tile_of(sp.full + t, tiles_m, tiles_n, group_m, tm, tn);
+        const int row = tm * LM_BM + r, col = tn * LM_BN + c;
+        if (row >= rows || col >= N) continue;  // N is a multiple of LM_BK: a quad is inside or outside
+        const float *src = ws + (((long long)t * sp.s2) << 16) + r * LM_BN + c;
+        f32x4 a = *(const f32x4 *)src;
+        for (int s = 1; s < sp.s2; ++s) a += *(const f32x4 *)(src + ((long long)s << 16));
         const bf16x2 lo = __builtin_convertvector((f32x2){a[0], a[1]}, bf16x2);
         const bf16x2 hi = __builtin_convertvector((f32x2){a[2], a[3]}, bf16x2);
-        unsigned *dst = (unsigned *)(C + (long long)(c_rows ? c_rows[r] : r) * ldc + c);
+        unsigned *dst = (unsigned *)(C + (long long)(c_rows ? c_rows[row] : row) * ldc + col);
         dst[0] = __builtin_bit_cast(unsigned, lo);
         dst[1] = __builtin_bit_cast(unsigned, hi);
     }
@@ -819,9 +859,11 @@ hipError_t lm_launch_gemm(GemmParams p, hipStream_t st)
     }
     p.tiles_n = (p.N + LM_BN - 1) / LM_BN;
     if (p.group_m <= 0) p.group_m = LM_GROUP_M;
-    const long long total = (long long)((p.M + LM_BM - 1) / LM_BM) * p.tiles_n *
-                            (EPI == LM_EPI_BF16 && p.split_max > 1 ? p.split_max : 1);  // upper bound
-    const long long grid = (total + 7) / 8 * 8;
+    // upper bound: every tile whole, plus the most parts a plan can have (fewer than n_cu tiles cut)
+    const long long tiles = (long long)((p.M + LM_BM - 1) / LM_BM) * p.tiles_n;
+    const long long items = EPI == LM_EPI_BF16 && p.split_items > 0
+                                ? (long long)(p.n_cu > 0 ? p.n_cu : 256) * LM_SPLIT_MAX : 0;
+    const long long grid = ((tiles + 7) / 8 + (items + 7) / 8) * 8;
     hipLaunchKernelGGL((lm_gemm_nt<EPI, STORE_Z, AUX>), dim3((unsigned)grid), dim3(LM_THREADS), LM_LDS_BYTES, st, p);
     return hipGetLastError();
 }
@@ -1061,19 +1103,19 @@ grpo_status lm_impl(bool bwd, bool aux, const void *hidden, int64_t hidden_strid
             gh.ldc = grad_hidden_stride;
             gh.c_rows = w.orig2;
             gh.group_m = LM_GM_BWD;
-            // The fp32 logits are no longer needed: their space takes the partial results when the
-            // contraction over the vocabulary is split (d_model is a multiple of 4 columns: the
-            // partial rows stay 16-byte aligned).
-            gh.split_max = (int)(L.ldz / d_model < LM_SPLIT_MAX ? L.ldz / d_model : LM_SPLIT_MAX);
+            // The fp32 logits are no longer needed: their space takes the partial results (blocks of
+            // 256 x 256 fp32) of the tiles whose contraction over the vocabulary is cut into parts.
+            const size_t z_blocks = (size_t)n_tokens * (size_t)L.ldz * 4 / ((size_t)LM_BM * LM_BN * 4);
+            gh.split_items = (int)(z_blocks < 0x7fffffffu ? z_blocks : 0x7fffffffu);
             gh.split_ws = (float *)(ws + L.Z);
             const int n_cu = cu_count();
             gh.n_cu = n_cu;
             e = lm_launch_gemm<LM_EPI_BF16, false>(gh, st);
             if (e != hipSuccess) return GRPO_ERR_HIP;
-            if (gh.split_max > 1)
+            if (gh.split_items > 0)
                 hipLaunchKernelGGL(lm_split_reduce, dim3(2048), dim3(256), 0, st, (const float *)gh.split_ws,
                                    (const int *)w.n_grad, M, D, (D + LM_BN - 1) / LM_BN, (int)(L.ldg / LM_BK),
-                                   gh.split_max, n_cu, (const int *)w.orig2, (__bf16 *)grad_hidden,
+                                   gh.split_items, n_cu, LM_GM_BWD, (const int *)w.orig2, (__bf16 *)grad_hidden,
                                    (long long)grad_hidden_stride);
 
             GemmParams gw = {};  // dL/dW [V][d] = G^T . H over the gradient rows
