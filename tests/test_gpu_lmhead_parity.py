@@ -170,14 +170,30 @@ def test_denominator_grad_scale_accumulate_and_determinism():
     assert torch.equal(acc, dW + dW)
 
 
-def test_micro_batches_accumulate_into_the_weight_gradient():
+@pytest.mark.parametrize("shape", ["small", "many tiles"])
+def test_micro_batches_accumulate_into_the_weight_gradient(shape):
     """Token micro-batches with the whole batch's token count as `denom` and dL/dW accumulated from
     call to call bound the workspace (logits of one micro-batch at a time): log-probs are the whole
-    batch's bits, losses and counters add up, gradients agree to rounding."""
-    cfg = wl.CONFIGS["qwen_short"].scaled(n_prompts=3, seq_len=50, vocab=3000, group_size=4)
-    d = 256
-    batch = wl.make_lmhead_batch(cfg, d, device=DEV)
-    hb, wb, adv_tok, lp_o, old = oracle_inputs(batch)
+    batch's bits, losses and counters add up, gradients agree to rounding.  The second shape has
+    about a hundred tiles of dL/dH over a contraction of 128 steps, so that the whole batch cuts its
+    tiles into many parts that take several rounds, and every micro-batch plans differently."""
+    if shape == "small":
+        cfg = wl.CONFIGS["qwen_short"].scaled(n_prompts=3, seq_len=50, vocab=3000, group_size=4)
+        d = 256
+        batch = wl.make_lmhead_batch(cfg, d, device=DEV)
+        hb, wb, adv_tok, lp_o, old = oracle_inputs(batch)
+    else:
+        # too large for the oracle's plain loops: this case compares the library with itself,
+        # old log-probs from its own forward pass
+        cfg = wl.CONFIGS["qwen_short"].scaled(n_prompts=6, seq_len=120, vocab=8192, group_size=8)
+        d = 2048
+        batch = wl.make_lmhead_batch(cfg, d, device=DEV)
+        lp0 = grpo.grpo_lmhead_logprobs_fwd(batch["hidden"], batch["weight"], batch["tokens"], batch["mask"],
+                                            f32(cfg.temperature))
+        torch.cuda.synchronize()
+        old = wl.make_old_logprobs(cfg, lp0.cpu().numpy().astype(np.float64))
+        adv = orc.group_advantages(batch["rewards"].cpu().numpy(), group_size=batch["group_size"])
+        adv_tok = orc.broadcast_advantages(adv, batch["rollout_of_token"].cpu().numpy()).astype(np.float32)
     N = batch["n_tokens"]
     kw = dict(eps_low=f32(cfg.eps_low), eps_high=f32(cfg.eps_high), delta=f32(cfg.delta),
               temperature=f32(cfg.temperature))
@@ -187,7 +203,7 @@ def test_micro_batches_accumulate_into_the_weight_gradient():
                                                              old_d, adv_d, batch["mask"], **kw)
     torch.cuda.synchronize()
     M = int(counts[0].item())
-    cuts = [0, 70, 71, 333, N]
+    cuts = [0, 70, 71, 333, N] if shape == "small" else [0, 700, 701, 2900, N]
     dW_acc = torch.zeros_like(dW)
     dH_all = torch.empty_like(dH)
     loss_sum, counts_sum = 0.0, torch.zeros_like(counts)
