@@ -149,7 +149,8 @@ def run_aux_shape_case(dtype, vocab, stride, N, *, temperature=0.8, eps_low=0.2,
     store = torch.full((N, stride), 7.0, dtype=dt)
     store[:, :vocab] = (torch.randn((N, vocab), generator=g) * 3).to(dt)
     if vocab > 100 and N > 3:
-        store[3, 10:60] = float("-inf")                       # masked vocabulary entries
+        store[3, 10:60] = float("-inf")                       # masked vocabulary entries ...
+        store[3, vocab - 60:vocab - 10] = float("-inf")       # ... at both ends of the row
     store = store.to(DEV)
     tokens = torch.randint(0, vocab, (N,), generator=g)
     tokens[min(3, N - 1)] = 0

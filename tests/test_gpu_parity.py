@@ -326,8 +326,13 @@ def test_micro_batches_add_up():
     assert abs(loss_sum - float(loss.item())) <= 1e-6 * abs(float(loss.item())) + 1e-9
 
 
-def test_edge_cases():
-    V, N = 4096, 24
+@pytest.mark.parametrize("V", [4096, 152064, 262144, 300000, 600000])
+def test_edge_cases(V):
+    """Degenerate inputs on every kind of row kernel: rows in registers (narrow, and the benchmark's
+    width with waiting gradient slots), rows partly in LDS, rows with a streamed remainder, and
+    the streaming kernel.  The poisoned entries sit at the far end of the row, i.e. in the LDS-resident
+    slots or the remainder where there are such."""
+    N = 24
     g = torch.Generator().manual_seed(3)
     logits = (torch.randn((N, V), generator=g) * 2).to(torch.bfloat16).to(DEV)
     tokens = torch.randint(0, V, (N,), generator=g).to(DEV)
@@ -375,7 +380,7 @@ def test_edge_cases():
 
     say("[case] edge: NaN in one row's logits reaches that row's outputs and the loss, nothing else")
     z3 = logits.clone()
-    z3[7, 100] = float("nan")
+    z3[7, V - 100] = float("nan")
     loss3, lp3, counts3, grad3 = grpo.grpo_loss_fwd_bwd(z3, tokens, old, adv, ones)
     torch.cuda.synchronize()
     assert bool(torch.isnan(loss3)) and bool(torch.isnan(lp3[7]))
@@ -384,9 +389,11 @@ def test_edge_cases():
 
     say("[case] edge: -inf logits (vocabulary masking) are legal")
     z4 = logits.clone()
-    z4[:, 1000:3000] = float("-inf")
+    z4[:, V // 4:3 * V // 4] = float("-inf")
+    z4[:, V - V // 50:] = float("-inf")
     tok4 = tokens.clone()
-    tok4[(tok4 >= 1000) & (tok4 < 3000)] = 5
+    tok4[((tok4 >= V // 4) & (tok4 < 3 * V // 4)) | (tok4 >= V - V // 50)] = 5
+    tok4[1] = V - V // 50 - 1                                   # the last entry that is not masked
     batch = dict(logits=z4, tokens=tok4, mask=ones, n_tokens=N, vocab=V, temperature=1.0,
                  eps_low=0.2, eps_high=0.2, delta=4.0)
     lp_orc = oracle_logprobs_blocked(batch)
