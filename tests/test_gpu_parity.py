@@ -401,6 +401,27 @@ def test_edge_cases(V):
     check_against_oracle(batch, old4, lp_orc, adv.cpu().numpy(), label="-inf entries")
 
 
+def test_maximum_vocabulary():
+    """The widest row the library accepts, 2^28 entries (512 MB in bf16): three rows, one of them
+    masked; log-probs, loss and counters of all, the gradient of one row element by element."""
+    V, N = 1 << 28, 3
+    say("\n[case] maximum vocabulary: N=%d V=%d" % (N, V))
+    g = torch.Generator(device=DEV).manual_seed(99)
+    logits = torch.empty((N, V), dtype=torch.bfloat16, device=DEV)
+    for r in range(N):
+        for c0 in range(0, V, 1 << 26):
+            logits[r, c0:c0 + (1 << 26)] = (torch.randn(1 << 26, generator=g, device=DEV) * 3).to(torch.bfloat16)
+    tokens = torch.tensor([V - 1, 12345, 7], device=DEV)
+    mask = torch.tensor([1, 0, 1], dtype=torch.uint8, device=DEV)
+    batch = dict(logits=logits, tokens=tokens, mask=mask, n_tokens=N, vocab=V, temperature=1.0,
+                 eps_low=0.2, eps_high=0.2, delta=4.0)
+    lp_orc = oracle_logprobs_blocked(batch)
+    old = (torch.as_tensor(lp_orc) + torch.tensor([0.05, 0.0, -0.1], dtype=torch.float64)).to(torch.float32)
+    adv = np.array([1.0, 1.0, -0.5], dtype=np.float32)
+    check_against_oracle(batch, old, lp_orc, adv, grad_rows=np.array([0]), label="maximum vocabulary")
+    assert grpo.lib().grpo_workspace_bytes(N) > 0
+
+
 @pytest.mark.parametrize("ddof", [0, 1])
 def test_group_advantages(ddof):
     say("\n[case] group advantages ddof=%d" % ddof)
