@@ -401,6 +401,13 @@ def test_edge_cases(V):
     check_against_oracle(batch, old4, lp_orc, adv.cpu().numpy(), label="-inf entries")
 
 
+@pytest.mark.parametrize("vocab,rows", [(24, 300000), (1000, 100000)])
+def test_many_narrow_rows(vocab, rows):
+    """Row counts far above the grid with rows of a few bytes: the row queue hands them out in
+    chunks over its eight partitions, and every workgroup takes hundreds of rows."""
+    run_shape_case("bf16", vocab, vocab, rows)
+
+
 def test_maximum_vocabulary():
     """The widest row the library accepts, 2^28 entries (512 MB in bf16): three rows, one of them
     masked; log-probs, loss and counters of all, the gradient of one row element by element."""
