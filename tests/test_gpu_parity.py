@@ -297,6 +297,30 @@ def test_inplace_gradient_and_bitwise_determinism():
         assert torch.equal(first[k], third[k]), k + " differs in place"
 
 
+def test_the_comparison_rejects_a_wrong_oracle():
+    """The comparator itself can fail: with a mistake planted on the oracle's side (never in the
+    library) the same check that passes above raises."""
+    cfg = wl.CONFIGS["numerics_stress"].scaled(n_prompts=2, seq_len=6)
+    batch = wl.make_batch(cfg, DEV)
+    adv, adv_tok, lp_orc = oracle_side(batch)
+    old = wl.make_old_logprobs(cfg, lp_orc)
+    a32 = adv_tok.astype(np.float32)
+    check_against_oracle(batch, old, lp_orc, a32, label="as it is")
+    live = int(np.flatnonzero(batch["mask"].cpu().numpy())[3])
+    wrong_lp = lp_orc.copy()
+    wrong_lp[live] += 3e-4                                      # one log-prob off by 1.5 tolerances
+    with pytest.raises(AssertionError, match="log-prob error"):
+        check_against_oracle(batch, old, wrong_lp, a32, label="log-prob off")
+    hot = dict(batch, temperature=batch["temperature"] * 1.001)  # the oracle's softmax at another temperature
+    with pytest.raises(AssertionError, match="log-prob error"):
+        check_against_oracle(batch, old, oracle_logprobs_blocked(hot), a32, label="temperature off")
+    flipped = a32.copy()
+    flipped[live] = -flipped[live] if flipped[live] != 0 else 1.0  # the oracle with one advantage of the other sign
+    with pytest.raises(AssertionError):
+        check_against_oracle(batch, old, lp_orc, flipped, gpu_adv=torch.as_tensor(a32, device=DEV),
+                             label="one advantage off")
+
+
 def test_micro_batches_add_up():
     """A batch cut into micro-batches that all receive the whole batch's token count as `denom`
     (what a trainer with gradient accumulation, or one rank of several, does): per-row outputs
