@@ -74,6 +74,35 @@ const char *grpo_status_string(grpo_status status);
 size_t grpo_workspace_bytes(int64_t n_tokens);
 
 /*
+ * Which row kernel serves logits rows of a given width (a pure host function, for
+ * reading profiles and for sizing expectations; it launches nothing).  The path of
+ * section 3.4 reads every logit at least once and writes every gradient once; how
+ * often a row is read a second time depends on whether it stays on the chip between
+ * the softmax statistics and the gradient:
+ *   streaming = 0: one workgroup of `lanes` lanes holds `register_slots` 16-byte
+ *     vectors per lane in registers and `lds_slots` more per lane in LDS
+ *     (`resident_vectors` of the row's `vectors` in all); these are read once.
+ *     With streamed_remainder = 1 the vectors beyond them are read twice.
+ *     ragged_tail_slot = 1: the instantiation also serves a vocabulary that ends
+ *     inside a 16-byte vector.  workgroups_per_cu of them share a compute unit.
+ *   streaming = 1: the row is read twice (online maximum and sum, then the gradient).
+ * Errors: GRPO_ERR_DTYPE, GRPO_ERR_SHAPE (vocab outside [1, 2^28]), GRPO_ERR_NULL.
+ */
+typedef struct grpo_row_plan {
+    int64_t vectors;           /* ceil(vocab / 8) for bf16, ceil(vocab / 4) for f32 */
+    int64_t resident_vectors;  /* of those, how many stay on the chip between the passes */
+    int32_t streaming;
+    int32_t lanes;
+    int32_t register_slots;
+    int32_t lds_slots;
+    int32_t workgroups_per_cu;
+    int32_t ragged_tail_slot;
+    int32_t streamed_remainder;
+    int32_t reserved;
+} grpo_row_plan;
+grpo_status grpo_row_kernel_plan(grpo_dtype dtype, int64_t vocab, grpo_row_plan *plan_out /* host */);
+
+/*
  * Group-relative advantages (section 3.4: each prompt's G sampled outputs are
  * scored relative to one another; section 3.3: a group whose rewards are all
  * equal has zero advantages).  The paper gives no formula; this library uses

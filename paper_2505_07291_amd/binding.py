@@ -40,6 +40,8 @@ def lib():
         L.grpo_status_string.argtypes = [i32]
         L.grpo_workspace_bytes.restype = sz
         L.grpo_workspace_bytes.argtypes = [i64]
+        L.grpo_row_kernel_plan.restype = i32
+        L.grpo_row_kernel_plan.argtypes = [i32, i64, ctypes.POINTER(RowPlan)]
         L.grpo_group_advantages.restype = i32
         L.grpo_group_advantages.argtypes = [vp, i64, vp, i64, i64, f32, i32, vp, vp, i64, vp, vp]
         L.grpo_logprobs_fwd.restype = i32
@@ -80,6 +82,23 @@ def status_string(status) -> str:
 
 def grpo_workspace_bytes(n_tokens: int) -> int:
     return int(lib().grpo_workspace_bytes(int(n_tokens)))
+
+
+class RowPlan(ctypes.Structure):
+    """grpo_row_plan of grpo.h."""
+    _fields_ = [("vectors", ctypes.c_int64), ("resident_vectors", ctypes.c_int64), ("streaming", ctypes.c_int32),
+                ("lanes", ctypes.c_int32), ("register_slots", ctypes.c_int32), ("lds_slots", ctypes.c_int32),
+                ("workgroups_per_cu", ctypes.c_int32), ("ragged_tail_slot", ctypes.c_int32),
+                ("streamed_remainder", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+def grpo_row_kernel_plan(dtype: int, vocab: int) -> dict:
+    """Which row kernel serves rows of this width; see grpo_row_kernel_plan in grpo.h."""
+    plan = RowPlan()
+    rc = lib().grpo_row_kernel_plan(int(dtype), int(vocab), ctypes.byref(plan))
+    if rc != 0:
+        raise GrpoError(rc, "grpo_row_kernel_plan")
+    return {name: int(getattr(plan, name)) for name, _ in RowPlan._fields_ if name != "reserved"}
 
 
 def _ptr(t):

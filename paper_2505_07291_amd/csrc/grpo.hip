@@ -1564,6 +1564,67 @@ void launch_cached(const RowParams &p, int blocks_per_cu, hipStream_t st)
 #ifndef GRPO_QUEUE_CHUNK_BYTES
 #define GRPO_QUEUE_CHUNK_BYTES 32768
 #endif
+// One line per instantiation of the register-resident row kernel:
+//   X(id, BLOCK, NV, TAIL, NL, RST without / with the auxiliary terms, REM, workgroups per CU)
+// RST: gradient slots that wait in registers (-1: the instantiation's own rule), what fits beside
+// the row; the auxiliary terms need a few registers more.
+#define GRPO_ROW_KERNELS(X)                                   \
+    X(0, 256, 1, true, 0, -1, -1, false, 8)                   \
+    X(1, 256, 4, true, 0, -1, -1, false, 8)                   \
+    X(2, 256, 16, true, 0, -1, -1, false, 4)                  \
+    X(3, 256, 26, false, 0, 8, 8, false, 2)                   \
+    X(4, 256, 32, false, 0, 14, 14, false, 2)                 \
+    X(5, 512, 16, true, 0, -1, -1, false, 2)                  \
+    X(6, 512, 20, false, 0, 2, 2, false, 1)                   \
+    X(7, 1024, 10, true, 0, -1, -1, false, 1)                 \
+    X(8, 512, 26, false, 0, 8, 8, false, 1)                   \
+    X(9, 512, 32, false, 0, 14, 14, false, 1)                 \
+    X(10, 512, 38, false, 0, -1, -1, false, 1)                \
+    X(11, 512, 44, false, 0, 10, 8, false, 1)                 \
+    X(12, 512, kWideRegSlots, false, 4, GRPO_WIDE_RST, GRPO_WIDE_RST, false, 1)  \
+    X(13, 512, kWideRegSlots, false, 10, GRPO_WIDE_RST, GRPO_WIDE_RST, false, 1) \
+    X(14, 512, kWideRegSlots, false, 18, GRPO_WIDE_RST, GRPO_WIDE_RST, false, 1) \
+    X(15, 512, kRemRegSlots, false, 18, 0, 0, true, 1)
+constexpr int kRowStreaming = -1;  // the plan's id for grpo_rows_streamed
+
+// Which kernel serves rows of nvec 16-byte vectors (the last one ragged or not).  Host logic only.
+//
+// Narrow rows take small workgroups, several per CU (each around 16 slots per lane): the
+// phases of different rows then overlap inside a CU and the per-row bookkeeping
+// (queue, three barriers, scalar arithmetic) is hidden.  Only rows too wide for that
+// use one workgroup per CU: 512 lanes with twice the registers, the spare ones holding
+// gradient vectors back behind the next row's loads (1024 lanes with up to 10 slots where
+// the ragged-tail slot is needed, which those are built without).
+int plan_rows(long long nvec, bool ragged)
+{
+    if (nvec <= 256 * 1) return 0;
+    if (nvec <= 256 * 4) return 1;
+    if (nvec <= 256 * 16) return 2;
+    // two workgroups of 256 lanes with 256 registers each, every gradient slot waiting behind
+    // the loads, are 3 % ahead of two of 512 lanes with 128.  (The log-probs pass alone gains
+    // nothing, but it takes the same instantiation: the two entry points then give the same
+    // bits, and the ratio of an unchanged policy to itself is exactly 1.)
+    if (nvec <= 256 * 26 && !ragged) return 3;
+    if (nvec <= 256 * 32 && !ragged) return 4;
+    if (nvec <= 512 * 16) return 5;
+    if (nvec <= 512 * 20 && !ragged) return 6;  // all 20 gradient slots wait: 18 in LDS, 2 in registers
+    if (nvec <= 1024 * 10) return 7;
+    if (ragged) return kRowStreaming;
+    // 512 lanes with twice the registers, in several widths: the arithmetic of a pass runs over
+    // every slot of the instantiation, used or not
+    if (nvec <= 512 * 26) return 8;
+    if (nvec <= 512 * 32) return 9;
+    if (nvec <= 512 * 38) return 10;
+    if (nvec <= 512 * 44) return 11;
+    // wider than the registers: the last slots of the row live in LDS
+    if (nvec <= 512 * (kWideRegSlots + 4)) return 12;
+    if (nvec <= 512 * (kWideRegSlots + 10)) return 13;
+    if (nvec <= 512 * (kWideRegSlots + 18)) return 14;
+    // wider than registers and LDS together: the remainder is read twice, up to as much again
+    if (nvec <= 512 * 2 * (kRemRegSlots + 18)) return 15;
+    return kRowStreaming;
+}
+
 template <grpo_dtype DT, bool AUX>
 void launch_rows(const RowParams &p_in, hipStream_t st)
 {
@@ -1575,64 +1636,20 @@ void launch_rows(const RowParams &p_in, hipStream_t st)
         p.queue_parts = row_bytes < 200 * 1024 ? kQueueParts : 1;
     }
     const long long nvec = (p.vocab + Elem<DT>::EPV - 1) / Elem<DT>::EPV;
-    const bool ragged = p.vocab % Elem<DT>::EPV != 0;
-    auto launch_streamed = [&]() {
+    switch (plan_rows(nvec, p.vocab % Elem<DT>::EPV != 0)) {
+#define GRPO_ROW_CASE(ID, BLOCK, NV, TAIL, NL, RSTP, RSTA, REM, PERCU)                              \
+    case ID:                                                                                       \
+        static_assert(PERCU == row_blocks_per_cu(BLOCK, NV), "workgroups per CU");                \
+        launch_cached<DT, BLOCK, NV, AUX, TAIL, NL, (AUX ? RSTA : RSTP), REM>(p, PERCU, st);      \
+        break;
+        GRPO_ROW_KERNELS(GRPO_ROW_CASE)
+#undef GRPO_ROW_CASE
+    default: {
         long long grid = (long long)cu_count() * 2;
         if (grid > p.n_tokens) grid = p.n_tokens;
         hipLaunchKernelGGL((grpo_rows_streamed<DT, 1024, AUX>), dim3((unsigned)grid), dim3(1024), 0, st, p);
-    };
-    // Narrow rows take small workgroups, several per CU (each around 16 slots per lane): the
-    // phases of different rows then overlap inside a CU and the per-row bookkeeping
-    // (queue, three barriers, scalar arithmetic) is hidden.  Only rows too wide for that
-    // use one workgroup per CU: 512 lanes with twice the registers, the spare ones holding
-    // gradient vectors back behind the next row's loads (1024 lanes with up to 10 slots where
-    // the ragged-tail slot is needed, which those are built without).
-    if (nvec <= 256 * 1)
-        launch_cached<DT, 256, 1, AUX, true>(p, row_blocks_per_cu(256, 1), st);
-    else if (nvec <= 256 * 4)
-        launch_cached<DT, 256, 4, AUX, true>(p, row_blocks_per_cu(256, 4), st);
-    else if (nvec <= 256 * 16)
-        launch_cached<DT, 256, 16, AUX, true>(p, row_blocks_per_cu(256, 16), st);
-    // two workgroups of 256 lanes with 256 registers each, every gradient slot waiting behind
-    // the loads, are 3 % ahead of two of 512 lanes with 128.  (The log-probs pass alone gains
-    // nothing, but it takes the same instantiation: the two entry points then give the same
-    // bits, and the ratio of an unchanged policy to itself is exactly 1.)
-    else if (nvec <= 256 * 26 && !ragged)
-        launch_cached<DT, 256, 26, AUX, false, 0, 8>(p, 2, st);
-    else if (nvec <= 256 * 32 && !ragged)
-        launch_cached<DT, 256, 32, AUX, false, 0, 14>(p, 2, st);
-    else if (nvec <= 512 * 16)
-        launch_cached<DT, 512, 16, AUX, true>(p, row_blocks_per_cu(512, 16), st);
-    else if (nvec <= 512 * 20 && !ragged)  // all 20 gradient slots wait: 18 in LDS, 2 in registers
-        launch_cached<DT, 512, 20, AUX, false, 0, 2>(p, 1, st);
-    else if (nvec <= 1024 * 10)
-        launch_cached<DT, 1024, 10, AUX, true>(p, row_blocks_per_cu(1024, 10), st);
-    else if (ragged)
-        launch_streamed();
-    // 512 lanes with twice the registers, in several widths: the arithmetic of a pass runs over
-    // every slot of the instantiation, used or not.  The trailing number is the count of
-    // gradient slots that wait in registers: what fits beside the row (fewer with the auxiliary
-    // terms, which need a few registers more).
-    else if (nvec <= 512 * 26)
-        launch_cached<DT, 512, 26, AUX, false, 0, 8>(p, 1, st);
-    else if (nvec <= 512 * 32)
-        launch_cached<DT, 512, 32, AUX, false, 0, 14>(p, 1, st);
-    else if (nvec <= 512 * 38)
-        launch_cached<DT, 512, 38, AUX, false>(p, 1, st);
-    else if (nvec <= 512 * 44)
-        launch_cached<DT, 512, 44, AUX, false, 0, AUX ? 8 : 10>(p, 1, st);
-    // wider than the registers: the last slots of the row live in LDS
-    else if (nvec <= 512 * (kWideRegSlots + 4))
-        launch_cached<DT, 512, kWideRegSlots, AUX, false, 4, GRPO_WIDE_RST>(p, 1, st);
-    else if (nvec <= 512 * (kWideRegSlots + 10))
-        launch_cached<DT, 512, kWideRegSlots, AUX, false, 10, GRPO_WIDE_RST>(p, 1, st);
-    else if (nvec <= 512 * (kWideRegSlots + 18))
-        launch_cached<DT, 512, kWideRegSlots, AUX, false, 18, GRPO_WIDE_RST>(p, 1, st);
-    // wider than registers and LDS together: the remainder is read twice, up to as much again
-    else if (nvec <= 512 * 2 * (kRemRegSlots + 18))
-        launch_cached<DT, 512, kRemRegSlots, AUX, false, 18, 0, true>(p, 1, st);
-    else
-        launch_streamed();
+    }
+    }
 }
 
 grpo_status check_logits_args(const void *logits, grpo_dtype dtype, int64_t n_tokens, int64_t vocab,
@@ -1750,6 +1767,37 @@ const char *grpo_status_string(grpo_status status)
         case GRPO_ERR_HIP: return "HIP runtime error at kernel launch";
     }
     return "unknown status";
+}
+
+grpo_status grpo_row_kernel_plan(grpo_dtype dtype, int64_t vocab, grpo_row_plan *plan_out)
+{
+    if (dtype != GRPO_F32 && dtype != GRPO_BF16) return GRPO_ERR_DTYPE;
+    if (vocab <= 0 || vocab > kMaxVocab) return GRPO_ERR_SHAPE;
+    if (!plan_out) return GRPO_ERR_NULL;
+    const int epv = dtype == GRPO_BF16 ? 8 : 4;
+    grpo_row_plan r = {};
+    r.vectors = (vocab + epv - 1) / epv;
+    switch (plan_rows(r.vectors, vocab % epv != 0)) {
+#define GRPO_ROW_CASE(ID, BLOCK, NV, TAIL, NL, RSTP, RSTA, REM, PERCU) \
+    case ID:                                                          \
+        r.lanes = BLOCK;                                              \
+        r.register_slots = NV;                                        \
+        r.lds_slots = NL;                                             \
+        r.workgroups_per_cu = PERCU;                                  \
+        r.ragged_tail_slot = TAIL ? 1 : 0;                            \
+        r.streamed_remainder = REM ? 1 : 0;                           \
+        break;
+        GRPO_ROW_KERNELS(GRPO_ROW_CASE)
+#undef GRPO_ROW_CASE
+    default:
+        r.streaming = 1;
+        r.lanes = 1024;
+        r.workgroups_per_cu = 2;
+    }
+    const int64_t capacity = (int64_t)r.lanes * (r.register_slots + r.lds_slots);
+    r.resident_vectors = r.streaming ? 0 : (r.vectors < capacity ? r.vectors : capacity);
+    *plan_out = r;
+    return GRPO_OK;
 }
 
 size_t grpo_workspace_bytes(int64_t n_tokens)

@@ -4,6 +4,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 import paper_2505_07291_amd as grpo
@@ -38,6 +39,53 @@ def test_status_strings_and_workspace_size():
     for n in (1, 255, 256, 257, 131072):
         b = grpo.grpo_workspace_bytes(n)
         assert b % 256 == 0 and b >= 256 + 13 * n
+
+
+def test_row_kernel_plan_covers_every_width():
+    """The host logic that picks a row kernel: every width gets a kernel that can hold or stream
+    it, ragged rows only kernels that handle a ragged tail, and what is held fits the chip."""
+    import ctypes
+    from paper_2505_07291_amd.binding import RowPlan
+    L = grpo.lib()
+    out = RowPlan()
+    assert L.grpo_row_kernel_plan(7, 1000, ctypes.byref(out)) == DTYPE
+    assert L.grpo_row_kernel_plan(1, 0, ctypes.byref(out)) == SHAPE
+    assert L.grpo_row_kernel_plan(1, (1 << 28) + 1, ctypes.byref(out)) == SHAPE
+    assert L.grpo_row_kernel_plan(1, 1000, None) == NULL
+    rng = np.random.default_rng(1)
+    limits = [256, 1024, 4096, 6656, 8192, 10240, 13312, 16384, 19456, 22528, 27648, 30720, 34816, 67584]
+    for dtype, epv in ((grpo.GRPO_BF16, 8), (grpo.GRPO_F32, 4)):
+        vocabs = set(range(1, 70)) | {int(v) for v in np.exp(rng.uniform(0, np.log(2.0 ** 28), 400))} | {1 << 28}
+        for lim in limits:                                      # both sides of every limit, ragged or not
+            vocabs |= {lim * epv - 1, lim * epv, lim * epv + 1, lim * epv + epv}
+        for vocab in sorted(vocabs):
+            p = grpo.grpo_row_kernel_plan(dtype, vocab)
+            nvec, ragged = (vocab + epv - 1) // epv, vocab % epv != 0
+            assert p["vectors"] == nvec
+            if p["streaming"]:
+                assert p["resident_vectors"] == 0
+                assert (ragged and nvec > 10240) or nvec > 67584, (dtype, vocab)
+                continue
+            cap = p["lanes"] * (p["register_slots"] + p["lds_slots"])
+            assert p["resident_vectors"] == min(nvec, cap)
+            if p["streamed_remainder"]:
+                assert cap < nvec <= 2 * cap
+            else:
+                assert nvec <= cap, (dtype, vocab, p)
+            assert not ragged or p["ragged_tail_slot"], (dtype, vocab, p)
+            # what is held fits: 512 KB of registers and 160 KB of LDS per CU
+            lanes_per_cu = p["lanes"] * p["workgroups_per_cu"]
+            assert lanes_per_cu <= 2048
+            assert p["register_slots"] * 16 * lanes_per_cu <= 432 * 1024
+            assert p["lds_slots"] * 16 * lanes_per_cu <= 160 * 1024
+    bench = grpo.grpo_row_kernel_plan(grpo.GRPO_BF16, 152064)
+    assert (bench["lanes"], bench["register_slots"], bench["lds_slots"], bench["streaming"]) == (512, 38, 0, 0)
+    assert bench["resident_vectors"] == bench["vectors"] == 19008
+    wide = grpo.grpo_row_kernel_plan(grpo.GRPO_BF16, 262144)
+    assert wide["lds_slots"] == 18 and wide["resident_vectors"] == wide["vectors"] and not wide["streamed_remainder"]
+    f32 = grpo.grpo_row_kernel_plan(grpo.GRPO_F32, 152064)
+    assert f32["streamed_remainder"] == 1 and f32["resident_vectors"] == 512 * 66 < f32["vectors"]
+    assert grpo.grpo_row_kernel_plan(grpo.GRPO_BF16, 152069)["streaming"] == 1   # ragged and wide
 
 
 def loss_args(**over):
