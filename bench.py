@@ -339,7 +339,8 @@ def main():
                    "group_size": cfg.group_size, "n_rollouts": cfg.n_rollouts,
                    "rows_live": n_full, "rows_zero_coeff": n_zero_coeff, "rows_masked": n_masked,
                    "eps_low": cfg.eps_low, "eps_high": cfg.eps_high, "delta": cfg.delta,
-                   "temperature": cfg.temperature},
+                   "temperature": cfg.temperature,
+                   "row_kernel": grpo.grpo_row_kernel_plan(grpo.GRPO_BF16 if cfg.dtype == "bf16" else grpo.GRPO_F32, V)},
         "counts": dict(zip(grpo.COUNT_NAMES, c)), "loss": loss_value,
         "roofline": {"bound": "hbm", "achieved": alg_bytes / kern / 1e9, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": alg_bytes / kern / 1e9 / HBM_PEAK_GBPS,
