@@ -818,7 +818,7 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
     constexpr unsigned SLAB = BLOCK * 16u;  // bytes one pass of the workgroup covers
     static_assert(NL == 0 || !TAIL, "LDS-resident slots come without the ragged-tail slot");
     static_assert(!REM || !TAIL, "the streamed remainder comes without the ragged-tail slot");
-    constexpr int RU = 4;  // vectors per lane in flight in the remainder loops
+    constexpr int RU = AUX ? 2 : 4;  // vectors per lane in flight in the remainder loops (what the registers leave)
     // Gradient vectors of the first STASH slots wait in LDS (each lane its own 16 bytes per
     // slot, no sharing), those of the next RSTASH slots in registers, and all of them are
     // stored after the loop over the slots, so that the next row's loads stand in front of
@@ -1357,8 +1357,11 @@ __global__ void __launch_bounds__(1024) grpo_finalize(const float *J_ws, const f
     if (threadIdx.x == 0) {
         double tot[3] = {0.0, 0.0, 0.0};
         long long t[4] = {0, 0, 0, 0};
-        for (int w = 0; w < 16; ++w) {
+#pragma unroll 2  // all 16 at once would read 224 registers' worth of partial sums first, and spill
+        for (int w = 0; w < 16; ++w) {  // wavefront by wavefront, in order
+#pragma unroll
             for (int q = 0; q < 3; ++q) tot[q] += lds_j[w][q];
+#pragma unroll
             for (int q = 0; q < 4; ++q) t[q] += lds_c[w][q];
         }
         const double policy = 0.0 - tot[0] * hdr->inv_D;
