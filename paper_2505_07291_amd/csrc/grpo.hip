@@ -1331,17 +1331,43 @@ __global__ void __launch_bounds__(1024) grpo_finalize(const float *J_ws, const f
     const bool aux = KL_ws != nullptr;
     double sj[3] = {0.0, 0.0, 0.0};
     long long c[4] = {0, 0, 0, 0};
-    for (long long i = threadIdx.x; i < n; i += 1024) {
+    auto count = [&](int fl) {
+        c[0] += (fl & kFlagClipHigh) ? 1 : 0;
+        c[1] += (fl & kFlagClipLow) ? 1 : 0;
+        c[2] += (fl & kFlagDelta) ? 1 : 0;
+        c[3] += (fl & kFlagOutOfBand) ? 1 : 0;
+    };
+    // four rows per lane and step (the arrays start on 256-byte boundaries), then the last n % 4
+    // rows one by one: a fixed assignment of rows to lanes, so the sums are reproducible
+    const long long n4 = n & ~3ll;
+    for (long long i = threadIdx.x * 4ll; i < n4; i += 4096) {
+        const float4 j = *(const float4 *)(J_ws + i);
+        sj[0] += (double)j.x;
+        sj[0] += (double)j.y;
+        sj[0] += (double)j.z;
+        sj[0] += (double)j.w;
+        if (aux) {
+            const float4 kl = *(const float4 *)(KL_ws + i), h = *(const float4 *)(H_ws + i);
+            sj[1] += (double)kl.x;
+            sj[1] += (double)kl.y;
+            sj[1] += (double)kl.z;
+            sj[1] += (double)kl.w;
+            sj[2] += (double)h.x;
+            sj[2] += (double)h.y;
+            sj[2] += (double)h.z;
+            sj[2] += (double)h.w;
+        }
+        const unsigned fl4 = *(const unsigned *)(flags_ws + i);
+#pragma unroll
+        for (int b = 0; b < 4; ++b) count((int)((fl4 >> (8 * b)) & 0xffu));
+    }
+    for (long long i = n4 + threadIdx.x; i < n; i += 1024) {
         sj[0] += (double)J_ws[i];
         if (aux) {
             sj[1] += (double)KL_ws[i];
             sj[2] += (double)H_ws[i];
         }
-        const int fl = flags_ws[i];
-        c[0] += (fl & kFlagClipHigh) ? 1 : 0;
-        c[1] += (fl & kFlagClipLow) ? 1 : 0;
-        c[2] += (fl & kFlagDelta) ? 1 : 0;
-        c[3] += (fl & kFlagOutOfBand) ? 1 : 0;
+        count(flags_ws[i]);
     }
 #pragma unroll
     for (int q = 0; q < 3; ++q) sj[q] = wave_sum(sj[q]);
