@@ -195,6 +195,15 @@ def run_shape_case(dtype, vocab, stride, N, grad_rows="all", *, temperature=0.9,
     lp_fwd = grpo.grpo_logprobs_fwd(logits, batch["tokens"], batch["mask"], temperature=f32(temperature))
     torch.cuda.synchronize()
     assert torch.equal(lp_fwd, out["logprobs"])
+    # in place: the gradient over the logits it was computed from, same bits, padding left alone
+    store2 = store.clone()
+    res = grpo.grpo_loss_fwd_bwd(store2[:, :vocab], batch["tokens"], old.to(DEV), torch.as_tensor(adv, device=DEV),
+                                 batch["mask"], f32(eps_low), f32(eps_high), f32(delta), f32(temperature), denom,
+                                 grad_scale, inplace=True)
+    torch.cuda.synchronize()
+    assert res[3].data_ptr() == store2.data_ptr()
+    assert torch.equal(store2[:, :vocab], out["grad"]) and torch.equal(res[0], out["loss"])
+    assert bool((store2[:, vocab:] == 7.0).all()), "padding was written by the in-place call"
 
 
 @pytest.mark.parametrize("seed", range(24))
