@@ -175,9 +175,19 @@ def run_aux_shape_case(dtype, vocab, stride, N, *, temperature=0.8, eps_low=0.2,
         tw = (torch.rand(N, generator=g) * 2).float()
         tw[torch.rand(N, generator=g) < 0.1] = 0.0
         tw = tw.to(DEV)
-    run_aux_case(batch, old, ref, adv, kl_coef, ent_coef, denom=denom, grad_scale=grad_scale, label="shape",
-                 token_weights=tw)
+    out = run_aux_case(batch, old, ref, adv, kl_coef, ent_coef, denom=denom, grad_scale=grad_scale, label="shape",
+                       token_weights=tw)
     assert bool((store[:, vocab:] == 7.0).all())
+    # in place: the gradient over the logits it was computed from, same bits, padding left alone
+    store2 = store.clone()
+    res = grpo.grpo_loss_aux_fwd_bwd(
+        store2[:, :vocab], batch["tokens"], old.to(DEV), None if ref is None else ref.to(DEV),
+        torch.as_tensor(adv, device=DEV), batch["mask"], f32(eps_low), f32(eps_high), f32(delta), f32(temperature),
+        kl_coef, ent_coef, denom, grad_scale, token_weights=tw, inplace=True)
+    torch.cuda.synchronize()
+    assert res[4].data_ptr() == store2.data_ptr()
+    assert torch.equal(store2[:, :vocab], out["grad"]) and torch.equal(res[0], out["loss"])
+    assert bool((store2[:, vocab:] == 7.0).all())
 
 
 @pytest.mark.parametrize("seed", range(16))
