@@ -1286,7 +1286,21 @@ __global__ void __launch_bounds__(1024) grpo_prepare(const unsigned char *mask,
 {
     __shared__ long long lds[16];
     long long cnt = 0;
-    if (mask || token_w) {
+    if (mask && !token_w) {
+        // the mask alone: 16 bytes per lane and step between the first and the last 16-byte
+        // boundary inside it, single bytes before and after (the counts are integers: any order)
+        const long long head = ((16 - (long long)((unsigned long long)mask & 15u)) & 15);
+        const long long lead = head < n ? head : n;
+        const long long nvec = (n - lead) / 16;
+        for (long long i = threadIdx.x; i < lead; i += 1024) cnt += mask[i] ? 1 : 0;
+        for (long long v = threadIdx.x; v < nvec; v += 1024) {
+            const u32x4 w = *(const u32x4 *)(mask + lead + 16 * v);
+#pragma unroll
+            for (int d = 0; d < 4; ++d)  // bit 7 of every byte that is not zero, then count them
+                cnt += __builtin_popcount((w[d] | ((w[d] & 0x7f7f7f7fu) + 0x7f7f7f7fu)) & 0x80808080u);
+        }
+        for (long long i = lead + 16 * nvec + threadIdx.x; i < n; i += 1024) cnt += mask[i] ? 1 : 0;
+    } else if (mask || token_w) {
         for (long long i = threadIdx.x; i < n; i += 1024)
             cnt += ((!mask || mask[i]) && (!token_w || token_w[i] != 0.f)) ? 1 : 0;
     }

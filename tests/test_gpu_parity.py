@@ -441,6 +441,27 @@ def test_many_narrow_rows(vocab, rows):
     run_shape_case("bf16", vocab, vocab, rows)
 
 
+def test_mask_at_any_alignment_and_length():
+    """The unmasked rows are counted 16 mask bytes at a time between the 16-byte boundaries inside the
+    mask: every offset of the mask's first byte, lengths around the vector width, any non-zero byte."""
+    V = 16
+    g = torch.Generator().manual_seed(21)
+    for N in (1, 2, 15, 16, 17, 31, 33, 1000, 4099, 70001):
+        logits = (torch.randn((N, V), generator=g) * 2).to(torch.bfloat16).to(DEV)
+        tokens = torch.randint(0, V, (N,), generator=g).to(DEV)
+        old = torch.full((N,), -3.0, device=DEV)
+        adv = torch.randn(N, generator=g).to(DEV)
+        for offset in (0, 1, 3, 8, 15, 16, 17):
+            raw = torch.randint(0, 256, (N + 64,), generator=g).to(torch.uint8)
+            raw[torch.rand(N + 64, generator=g) < 0.4] = 0
+            buf = raw.to(DEV)
+            mask = buf[offset:offset + N]
+            assert mask.data_ptr() % 16 == offset % 16
+            counts = grpo.grpo_loss_fwd_bwd(logits, tokens, old, adv, mask)[2]
+            torch.cuda.synchronize()
+            assert int(counts[0]) == int((raw[offset:offset + N] != 0).sum()), (N, offset)
+
+
 def test_maximum_vocabulary():
     """The widest row the library accepts, 2^28 entries (512 MB in bf16): three rows, one of them
     masked; log-probs, loss and counters of all, the gradient of one row element by element."""
