@@ -4,15 +4,26 @@
 One "step" is the whole hot path over one synthetic batch that is already resident
 in HBM: group advantages (+ broadcast to tokens), then the objective forward and the
 fused backward over the full vocabulary (grpo_group_advantages + grpo_loss_fwd_bwd).
-Prints ONE JSON line: whole-job tokens/s, the HBM roofline of the dominant (row)
-kernel measured with events on the launch stream, and the fp64 CPU oracle timed on a
-bounded sample of the same batch as a reported baseline.
+Prints ONE JSON line.  The headline (`value`, `roofline`) is the qwen_short batch; the
+`workloads` object carries the same measurement for every 152064-vocabulary batch
+(qwen_short, qwen_medium, long_reasoning, numerics_stress), each generated, timed and
+freed in turn; the fp64 CPU oracle is timed on a bounded sample of the headline batch
+as a reported baseline.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+Two bandwidth figures per workload, both from the row kernel's event-bracketed time:
+  frac        algorithmic bytes (2 reads + 1 write of a live row, 1 read + 1 zero-fill of a
+              row whose gradient is cut, 1 zero-fill of a masked row) / time / 8 TB/s;
+  frac_moved  bytes this design moves through HBM (live rows are read ONCE: 1 read +
+              1 write) / time / 8 TB/s: the physical share of the peak.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME|all]
 """
 import argparse
+import gc
+import hashlib
 import json
 import os
+import re
 import sys
 import time
 
@@ -21,23 +32,43 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak, 8 TB/s
+BF16_MFMA_PEAK_TFLOPS = 2500.0
+QWEN_WORKLOADS = ["qwen_short", "qwen_medium", "long_reasoning", "numerics_stress"]
+KERNEL_SOURCES = {"grpo_rows_cached": "paper_2505_07291_amd/csrc/grpo.hip",
+                  "lm_gemm_nt": "paper_2505_07291_amd/csrc/lmhead.hpp"}
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def traffic_from_profiles(workload):
-    """Measured HBM bytes per row-kernel launch, if a counter summary was committed for
-    this workload (profiles/hbm_traffic_<workload>.txt, line 'traffic_bytes_per_launch = N')."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % workload)
+def source_hash(kernel):
+    """First 16 hex digits of the SHA-256 of the source file that holds a kernel."""
+    with open(os.path.join(ROOT, KERNEL_SOURCES[kernel]), "rb") as f:
+        return hashlib.sha256(f.read()).hexdigest()[:16]
+
+
+def traffic_from_profile(name, kernel):
+    """Measured HBM bytes per launch from a committed counter summary, profiles/<name>.txt
+    (lines 'traffic_bytes_per_launch = N', 'kernel_source_sha256 = H', 'git_commit = C').
+    The figure is only handed on when the summary was taken with the kernel source that is
+    in the tree now; otherwise the traffic is reported as unmeasured."""
+    path = os.path.join(ROOT, "profiles", name + ".txt")
+    found = {}
     try:
         for line in open(path):
-            if line.startswith("traffic_bytes_per_launch"):
-                return float(line.split("=")[1])
+            m = re.match(r"\s*(traffic_bytes_per_launch|kernel_source_sha256|git_commit)\s*=\s*(\S+)", line)
+            if m:
+                found[m.group(1)] = m.group(2)
     except OSError:
-        pass
-    return None
+        return None, {"profile": None}
+    stamp = {"profile": "profiles/%s.txt" % name, "profile_git_commit": found.get("git_commit"),
+             "profile_kernel_source_sha256": found.get("kernel_source_sha256"),
+             "current_kernel_source_sha256": source_hash(kernel)}
+    stamp["current"] = stamp["profile_kernel_source_sha256"] == stamp["current_kernel_source_sha256"]
+    if not stamp["current"] or "traffic_bytes_per_launch" not in found:
+        return None, stamp
+    return float(found["traffic_bytes_per_launch"]), stamp
 
 
 def cpu_baseline(batch, old, adv_tok, budget_s=10.0, block=512):
@@ -83,7 +114,25 @@ def cpu_baseline(batch, old, adv_tok, budget_s=10.0, block=512):
                 single_thread_value=n1 / t1, single_thread_sample="the first %d rows, %.1f s" % (n1, t1))
 
 
-def lmhead_leg(grpo, wl, cfg, d_model, dev, stream, reps):
+def timed_calls(fn, stream, reps, warmup):
+    """Mean / median / min / max milliseconds of `reps` calls of fn after `warmup` untimed ones,
+    each bracketed by events on the launch stream."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    evs = []
+    for _ in range(reps):
+        a, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        fn()
+        e.record(stream)
+        evs.append((a, e))
+    torch.cuda.synchronize()
+    ms = sorted(a.elapsed_time(e) for a, e in evs)
+    return {"mean": sum(ms) / len(ms), "median": ms[len(ms) // 2], "min": ms[0], "max": ms[-1]}
+
+
+def lmhead_leg(grpo, wl, cfg, d_model, dev, stream, reps, warmup):
     """The fused language-model-head path on the same recipe: hidden states [N, d_model] and head
     weights [V, d_model] instead of logits.  A dense contraction, so its roofline is the bf16
     matrix-core peak; flops are the algorithmic 2 N V d per product (one product forward,
@@ -93,8 +142,10 @@ def lmhead_leg(grpo, wl, cfg, d_model, dev, stream, reps):
     log("[bench] language-model-head leg: N=%d V=%d d=%d" % (N, V, d_model))
     b = wl.make_lmhead_batch(cfg, d_model, dev)
     lp = torch.empty(N, dtype=torch.float32, device=dev)
-    ws_f = torch.empty(grpo.grpo_lmhead_workspace_bytes(N, V, d_model, False), dtype=torch.uint8, device=dev)
-    ws_b = torch.empty(grpo.grpo_lmhead_workspace_bytes(N, V, d_model, True), dtype=torch.uint8, device=dev)
+    ws_f_bytes = grpo.grpo_lmhead_workspace_bytes(N, V, d_model, False)
+    ws_b_bytes = grpo.grpo_lmhead_workspace_bytes(N, V, d_model, True)
+    ws_f = torch.empty(ws_f_bytes, dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(ws_b_bytes, dtype=torch.uint8, device=dev)
     dH = torch.empty((N, d_model), dtype=torch.bfloat16, device=dev)
     dW = torch.empty((V, d_model), dtype=torch.float32, device=dev)
     loss = torch.empty(1, dtype=torch.float32, device=dev)
@@ -115,17 +166,6 @@ def lmhead_leg(grpo, wl, cfg, d_model, dev, stream, reps):
                                       grad_hidden=dH, grad_weight=dW, loss_out=loss, logprobs_out=lp,
                                       counts_out=counts, workspace=ws_b, stream=stream)
 
-    def timed(fn):
-        fn()
-        evs = []
-        for _ in range(reps):
-            a, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record(stream)
-            fn()
-            e.record(stream)
-            evs.append((a, e))
-        torch.cuda.synchronize()
-        return sum(a.elapsed_time(e) for a, e in evs) / reps
     ref = wl.make_old_logprobs(cfg, lp, seed=cfg.index + 77).to(dev)
     loss4 = torch.empty(4, dtype=torch.float32, device=dev)
 
@@ -135,10 +175,10 @@ def lmhead_leg(grpo, wl, cfg, d_model, dev, stream, reps):
                                           0.0, 1.0, grad_hidden=dH, grad_weight=dW, loss_out=loss4,
                                           logprobs_out=lp, want_entropy=False, counts_out=counts,
                                           workspace=ws_b, stream=stream)
-    ms_f = timed(fwd)
-    ms_x = timed(fwd_bwd_aux)
+    ms_f = timed_calls(fwd, stream, reps, warmup)["mean"]
+    ms_x = timed_calls(fwd_bwd_aux, stream, reps, max(2, warmup // 2))["mean"]
     aux_vals = loss4.cpu().tolist()
-    ms_b = timed(fwd_bwd)
+    ms_b = timed_calls(fwd_bwd, stream, reps, max(2, warmup // 2))["mean"]
     c = counts.cpu().tolist()
     n_unmasked = c[0]
     zero_adv = int(((adv_tok == 0) & (b["mask"] != 0)).sum())
@@ -147,10 +187,13 @@ def lmhead_leg(grpo, wl, cfg, d_model, dev, stream, reps):
     # twice that again per row with a gradient for dL/dH and dL/dW)
     flops_f = 2.0 * n_unmasked * V * d_model
     flops_b = flops_f + 4.0 * n_grad * V * d_model
+    traffic, stamp = traffic_from_profile("lm_gemm_nt_%s_hbm_traffic" % cfg.name, "lm_gemm_nt")
     return {"note": "grpo_lmhead_logprobs_fwd / grpo_lmhead_loss_fwd_bwd: hidden [N, d] and head "
                     "weights [V, d] in bf16, logits formed on the matrix cores; tokens/s count all N rows, "
                     "flops only the rows that take part",
             "d_model": d_model, "rows": N, "rows_unmasked": n_unmasked, "rows_with_gradient": n_grad,
+            "workspace_bytes_fwd": ws_f_bytes, "workspace_bytes_fwd_bwd": ws_b_bytes,
+            "workspace_bytes_per_logit_fwd_bwd": ws_b_bytes / (float(N) * V),
             "fwd_ms": ms_f, "fwd_tokens_per_s": N / (ms_f * 1e-3),
             "fwd_bwd_ms": ms_b, "fwd_bwd_tokens_per_s": N / (ms_b * 1e-3), "loss": float(loss.cpu()),
             "aux": {"note": "grpo_lmhead_loss_aux_fwd_bwd, KL 0.001 and entropy 1e-4: every unmasked row has a "
@@ -158,67 +201,30 @@ def lmhead_leg(grpo, wl, cfg, d_model, dev, stream, reps):
                     "tflops": (flops_f + 4.0 * n_unmasked * V * d_model) / (ms_x * 1e-3) / 1e12,
                     "total": aux_vals[0], "policy": aux_vals[1], "mean_kl": aux_vals[2],
                     "mean_entropy": aux_vals[3]},
-            "roofline": {"bound": "mfma", "achieved": flops_f / (ms_f * 1e-3) / 1e12, "peak": 2500.0,
-                         "unit": "TFLOP/s", "frac": flops_f / (ms_f * 1e-3) / 1e12 / 2500.0,
+            "roofline": {"bound": "mfma", "achieved": flops_f / (ms_f * 1e-3) / 1e12,
+                         "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": flops_f / (ms_f * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS,
                          "kernel": "lm_gemm_nt (forward: logits + softmax partials)",
-                         "algorithmic_flops": flops_f, "traffic": None},
+                         "algorithmic_flops": flops_f, "traffic": traffic, "traffic_profile": stamp},
             "roofline_fwd_bwd": {"bound": "mfma", "achieved": flops_b / (ms_b * 1e-3) / 1e12,
-                                 "peak": 2500.0, "unit": "TFLOP/s",
-                                 "frac": flops_b / (ms_b * 1e-3) / 1e12 / 2500.0,
+                                 "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                 "frac": flops_b / (ms_b * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS,
                                  "algorithmic_flops": flops_b}}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="qwen_short")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-lmhead", action="store_true",
-                    help="skip the fused language-model-head leg (hidden states and head weights in)")
-    ap.add_argument("--d-model", type=int, default=5120,
-                    help="hidden size of the language-model-head leg (5120: a 32B Qwen-family model)")
-    ap.add_argument("--vocab", type=int, default=0,
-                    help="another vocabulary size for the workload's recipe (rows scaled to keep the "
-                         "bytes of logits); not the headline configuration, no language-model-head leg")
-    ap.add_argument("--logits-dtype", choices=["bf16", "f32"], default=None,
-                    help="another storage type for the logits, as --vocab")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run plain 1 GiB device copies (reference for HBM counters)")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU only (rows are independent; a multi-GPU run "
-              "would be this same kernel per rank plus a 40-byte all-reduce); use --gpus 1",
-              file=sys.stderr)
-        sys.exit(2)
-
+def run_workload(grpo, wl, cfg, args, dev, variant="", headline=False):
+    """Generates one batch, times the whole step and the side legs on it, frees it.
+    Returns (record, headline extras)."""
     import torch
-    import paper_2505_07291_amd as grpo
-    from paper_2505_07291_amd import workloads as wl
-
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
-    dev = "cuda:0"
-    cfg = wl.CONFIGS[args.workload]
-    variant = ""
-    if args.vocab or args.logits_dtype:
-        # the same recipe at another row width: the sequence length takes up the difference
-        import dataclasses
-        esz0 = 2 if cfg.dtype == "bf16" else 4
-        dt = args.logits_dtype or cfg.dtype
-        vocab = args.vocab or cfg.vocab
-        L = max(1, round(cfg.seq_len * cfg.vocab * esz0 / (vocab * (2 if dt == "bf16" else 4))))
-        cfg = dataclasses.replace(cfg.scaled(seq_len=L, vocab=vocab), dtype=dt)
-        variant = "@V=%d,%s" % (vocab, dt)
-        args.no_lmhead = True
     N, V = cfg.n_tokens, cfg.vocab
     log("[bench] generating %s: N=%d V=%d %s (%.2f GB of logits)" %
         (cfg.name, N, V, cfg.dtype, N * V * (2 if cfg.dtype == "bf16" else 4) / 1e9))
     batch = wl.make_batch(cfg, dev)
     esz = batch["logits"].element_size()
+    stream = torch.cuda.current_stream()
+    lp_ws = torch.empty(grpo.grpo_workspace_bytes(0), dtype=torch.uint8, device=dev)
     # old-policy log-probs: the library's own forward pass plus the recipe's staleness noise
-    new_lp = grpo.grpo_logprobs_fwd(batch["logits"], batch["tokens"], None, cfg.temperature)
+    new_lp = grpo.grpo_logprobs_fwd(batch["logits"], batch["tokens"], None, cfg.temperature, workspace=lp_ws)
     torch.cuda.synchronize()
     old = wl.make_old_logprobs(cfg, new_lp).to(dev)
 
@@ -229,7 +235,6 @@ def main():
     lp = torch.empty(N, dtype=torch.float32, device=dev)
     counts = torch.empty(5, dtype=torch.int64, device=dev)
     ws = torch.empty(grpo.grpo_workspace_bytes(N), dtype=torch.uint8, device=dev)
-    stream = torch.cuda.current_stream()
 
     def step(ev=None, mask=batch["mask"], oldlp=old, advantages=None):
         a_tok = adv_tok
@@ -260,13 +265,11 @@ def main():
         torch.cuda.synchronize()
         wall = (time.perf_counter() - t0) / K
         per_step = sorted(a.elapsed_time(b) for a, b in evs)
-        timed.last = {"median": per_step[len(per_step) // 2], "min": per_step[0], "max": per_step[-1]}
-        kern = sum(per_step) / K * 1e-3
-        return wall, kern
+        spread = {"median": per_step[len(per_step) // 2], "min": per_step[0], "max": per_step[-1]}
+        return wall, sum(per_step) / K * 1e-3, spread
 
-    log("[bench] timing %d steps after %d warm-up steps" % (args.steps, args.warmup))
-    wall, kern = timed(args.steps, args.warmup)
-    kern_spread = dict(timed.last)
+    log("[bench] %s: timing %d steps after %d warm-up steps" % (cfg.name, args.steps, args.warmup))
+    wall, kern, kern_spread = timed(args.steps, args.warmup)
     assert grpo.grpo_workspace_error(ws) == 0
     c = counts.cpu().tolist()
     loss_value = float(loss.cpu())
@@ -279,110 +282,203 @@ def main():
     # cut 1 read + 1 zero-fill, masked rows 1 zero-fill; plus 29 B of per-token scalars
     alg_bytes = row_bytes * (3 * n_full + 2 * n_zero_coeff + 1 * n_masked) + 29 * N
     conv_bytes = 3 * N * row_bytes
-    # what this design has to move through HBM: live rows are read once (kept in registers)
-    design_bytes = row_bytes * (2 * n_full + 2 * n_zero_coeff + 1 * n_masked) + 29 * N
+    # what this design moves through HBM: live rows are read once (kept in registers)
+    moved_bytes = row_bytes * (2 * n_full + 2 * n_zero_coeff + 1 * n_masked) + 29 * N
 
+    side_reps, side_warm = max(10, args.steps // 2), max(6, args.warmup)
     # worst case for the kernel: every row unmasked and live (ratio 1, non-zero advantage)
     ones = torch.ones(N, dtype=torch.uint8, device=dev)
     adv_ones = torch.full((N,), 0.5, dtype=torch.float32, device=dev)
-    wall_full, kern_full = timed(max(5, args.steps // 3), 2, mask=ones, oldlp=new_lp, advantages=adv_ones)
+    wall_full, kern_full, full_spread = timed(side_reps, side_warm, mask=ones, oldlp=new_lp, advantages=adv_ones)
     full_counts = counts.cpu().tolist()
 
     # the old-policy log-probs pass (one read of the logits), every row unmasked
-    fwd_ws = torch.empty(grpo.grpo_workspace_bytes(0), dtype=torch.uint8, device=dev)
-    fwd_evs = []
-    for i in range(3 + max(5, args.steps // 3)):
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record(stream)
-        grpo.grpo_logprobs_fwd(batch["logits"], batch["tokens"], ones, cfg.temperature,
-                               logprobs_out=lp, workspace=fwd_ws, stream=stream)
-        b.record(stream)
-        fwd_evs.append((a, b))
-    torch.cuda.synchronize()
-    fwd_ms = sum(a.elapsed_time(b) for a, b in fwd_evs[3:]) / len(fwd_evs[3:])
+    fwd = timed_calls(lambda: grpo.grpo_logprobs_fwd(batch["logits"], batch["tokens"], ones, cfg.temperature,
+                                                     logprobs_out=lp, workspace=lp_ws, stream=stream),
+                      stream, side_reps, side_warm)
 
-    # the objective with the KL and entropy terms fused in (section 4.1 coefficients),
-    # on the benchmark's own batch
+    # the objective with the KL and entropy terms fused in (section 4.1 coefficients), same batch
     ref = wl.make_old_logprobs(cfg, new_lp, seed=cfg.index + 77).to(dev)
     loss4 = torch.empty(4, dtype=torch.float32, device=dev)
     ent = torch.empty(N, dtype=torch.float32, device=dev)
-    aux_evs = []
-    for i in range(3 + max(5, args.steps // 3)):
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record(stream)
-        grpo.grpo_loss_aux_fwd_bwd(batch["logits"], batch["tokens"], old, ref, adv_tok, batch["mask"],
-                                   cfg.eps_low, cfg.eps_high, cfg.delta, cfg.temperature, 0.001, 1e-4,
-                                   0.0, 1.0, grad_logits=grad, loss_out=loss4, logprobs_out=lp,
-                                   entropy_out=ent, counts_out=counts, workspace=ws, stream=stream)
-        b.record(stream)
-        aux_evs.append((a, b))
-    torch.cuda.synchronize()
-    aux_ms = sum(a.elapsed_time(b) for a, b in aux_evs[3:]) / len(aux_evs[3:])
+    aux = timed_calls(lambda: grpo.grpo_loss_aux_fwd_bwd(
+        batch["logits"], batch["tokens"], old, ref, adv_tok, batch["mask"], cfg.eps_low, cfg.eps_high,
+        cfg.delta, cfg.temperature, 0.001, 1e-4, 0.0, 1.0, grad_logits=grad, loss_out=loss4,
+        logprobs_out=lp, entropy_out=ent, counts_out=counts, workspace=ws, stream=stream),
+        stream, side_reps, side_warm)
     aux_vals = loss4.cpu().tolist()
     # with an entropy term every unmasked row gets a gradient: 2 reads + 1 write each
     aux_alg = row_bytes * (3 * M + 1 * n_masked) + 37 * N
+    aux_moved = row_bytes * (2 * M + 1 * n_masked) + 37 * N
 
+    traffic, stamp = (None, {"profile": None}) if variant else \
+        traffic_from_profile("hbm_traffic_%s" % cfg.name, "grpo_rows_cached")
+    gb = lambda nbytes, sec: nbytes / sec / 1e9
+    rec = {
+        "workload": cfg.name + variant, "n_tokens": N, "vocab": V, "logits_dtype": cfg.dtype,
+        "rows_live": n_full, "rows_zero_coeff": n_zero_coeff, "rows_masked": n_masked,
+        "ms_per_step": wall * 1e3, "tokens_per_s": N / wall, "tokens_per_s_unmasked": M / wall,
+        "kernel_ms": kern * 1e3, "kernel_ms_median": kern_spread["median"],
+        "kernel_ms_min": kern_spread["min"], "kernel_ms_max": kern_spread["max"],
+        "algorithmic_bytes": alg_bytes, "achieved_gbps": gb(alg_bytes, kern),
+        "frac": gb(alg_bytes, kern) / HBM_PEAK_GBPS,
+        "moved_bytes": moved_bytes, "moved_gbps": gb(moved_bytes, kern),
+        "frac_moved": gb(moved_bytes, kern) / HBM_PEAK_GBPS,
+        "gbps_2r1w_all_rows_convention": gb(conv_bytes, kern),
+        "traffic": traffic, "traffic_profile": stamp,
+        "counts": dict(zip(grpo.COUNT_NAMES, c)), "loss": loss_value,
+        "full_rows": {"note": "same logits, every row unmasked and live: the kernel's worst case",
+                      "tokens_per_s": N / wall_full, "kernel_ms": kern_full * 1e3,
+                      "kernel_ms_median": full_spread["median"], "kernel_ms_min": full_spread["min"],
+                      "kernel_ms_max": full_spread["max"],
+                      "frac": gb(conv_bytes, kern_full) / HBM_PEAK_GBPS,
+                      "moved_gbps": gb(2 * N * row_bytes, kern_full),
+                      "frac_moved": gb(2 * N * row_bytes, kern_full) / HBM_PEAK_GBPS,
+                      "rows_live": full_counts[0]},
+        "logprobs_fwd": {"note": "grpo_logprobs_fwd, every row unmasked: one read of the logits",
+                         "tokens_per_s": N / (fwd["mean"] * 1e-3), "kernel_ms": fwd["mean"],
+                         "kernel_ms_median": fwd["median"], "kernel_ms_min": fwd["min"],
+                         "moved_gbps": gb(N * row_bytes, fwd["mean"] * 1e-3),
+                         "frac_moved": gb(N * row_bytes, fwd["mean"] * 1e-3) / HBM_PEAK_GBPS},
+        "aux_loss": {"note": "grpo_loss_aux_fwd_bwd on the same batch, KL 0.001 and entropy 1e-4 fused in",
+                     "tokens_per_s": N / (aux["mean"] * 1e-3), "kernel_ms": aux["mean"],
+                     "frac": gb(aux_alg, aux["mean"] * 1e-3) / HBM_PEAK_GBPS,
+                     "frac_moved": gb(aux_moved, aux["mean"] * 1e-3) / HBM_PEAK_GBPS,
+                     "total": aux_vals[0], "policy": aux_vals[1], "mean_kl": aux_vals[2],
+                     "mean_entropy": aux_vals[3]},
+    }
+    extras = {}
+    if headline:
+        extras["row_kernel"] = grpo.grpo_row_kernel_plan(
+            grpo.GRPO_BF16 if cfg.dtype == "bf16" else grpo.GRPO_F32, V)
+        if not args.no_lmhead and cfg.logits in ("normal", "normal_boost") and cfg.dtype == "bf16":
+            # the leg needs its own operands, gradients and two workspaces next to the batch
+            need = (grpo.grpo_lmhead_workspace_bytes(N, V, args.d_model, True) +
+                    grpo.grpo_lmhead_workspace_bytes(N, V, args.d_model, False) +
+                    6 * V * args.d_model + 4 * N * args.d_model)
+            free = torch.cuda.mem_get_info()[0]
+            if need < 0.9 * free:
+                extras["lmhead"] = lmhead_leg(grpo, wl, cfg, args.d_model, dev, stream,
+                                              max(3, args.steps // 6), max(5, args.warmup))
+            else:
+                extras["lmhead"] = {"skipped": "needs %.0f GB of device memory, %.0f GB free" % (need / 1e9, free / 1e9)}
+        if not args.no_cpu_baseline:
+            log("[bench] timing the fp64 oracle on a sample of the batch (about 12 s)")
+            step()
+            torch.cuda.synchronize()
+            extras["cpu_baseline"] = cpu_baseline(batch, old, adv_tok)
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
         for _ in range(3):
             dst.copy_(src)
         torch.cuda.synchronize()
+        del src, dst
+    return rec, extras
 
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="all",
+                    help="all (default): qwen_short as the headline plus the other three 152064-vocabulary "
+                         "batches; or one workload by name")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-lmhead", action="store_true",
+                    help="skip the fused language-model-head leg (hidden states and head weights in)")
+    ap.add_argument("--d-model", type=int, default=5120,
+                    help="hidden size of the language-model-head leg (5120: a 32B Qwen-family model)")
+    ap.add_argument("--vocab", type=int, default=0,
+                    help="another vocabulary size for the workload's recipe (rows scaled to keep the "
+                         "bytes of logits); not the headline configuration, no language-model-head leg")
+    ap.add_argument("--logits-dtype", choices=["bf16", "f32"], default=None,
+                    help="another storage type for the logits, as --vocab")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run plain 1 GiB device copies (reference for HBM counters)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (rows are independent; a multi-GPU run "
+              "would be this same kernel per rank plus a 40-byte all-reduce); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2505_07291_amd as grpo
+    from paper_2505_07291_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+    names = QWEN_WORKLOADS if args.workload == "all" else [args.workload]
+    variant = ""
+    if args.vocab or args.logits_dtype:
+        if args.workload == "all":
+            names = ["qwen_short"]
+        args.no_lmhead = True
+
+    records, head, head_extras, head_cfg = {}, None, {}, None
+    for i, name in enumerate(names):
+        cfg = wl.CONFIGS[name]
+        if args.vocab or args.logits_dtype:
+            # the same recipe at another row width: the sequence length takes up the difference
+            import dataclasses
+            esz0 = 2 if cfg.dtype == "bf16" else 4
+            dt = args.logits_dtype or cfg.dtype
+            vocab = args.vocab or cfg.vocab
+            L = max(1, round(cfg.seq_len * cfg.vocab * esz0 / (vocab * (2 if dt == "bf16" else 4))))
+            cfg = dataclasses.replace(cfg.scaled(seq_len=L, vocab=vocab), dtype=dt)
+            variant = "@V=%d,%s" % (vocab, dt)
+        rec, extras = run_workload(grpo, wl, cfg, args, dev, variant, headline=(i == 0))
+        gc.collect()                 # the batch died with run_workload's frame: hand its memory back
+        torch.cuda.empty_cache()
+        records[name] = rec
+        if i == 0:
+            head, head_extras, head_cfg = rec, extras, cfg
+
+    V = head["vocab"]
+    worst = min(records.values(), key=lambda r: r["frac"])
+    worst_moved = min(records.values(), key=lambda r: r["frac_moved"])
+    worst_full = min(records.values(), key=lambda r: r["full_rows"]["frac_moved"])
     out = {
-        "metric": "GRPO loss fwd+bwd tokens/s (V=152064 bf16)" if V == 152064 and cfg.dtype == "bf16" else
-                  "GRPO loss fwd+bwd tokens/s (V=%d %s)" % (V, cfg.dtype),
-        "value": N / wall, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": wall * 1e3, "higher_is_better": True,
+        "metric": "GRPO loss fwd+bwd tokens/s (V=152064 bf16)" if V == 152064 and head["logits_dtype"] == "bf16" else
+                  "GRPO loss fwd+bwd tokens/s (V=%d %s)" % (V, head["logits_dtype"]),
+        "value": head["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": head["ms_per_step"], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": cfg.name + variant, "n_tokens": N, "vocab": V, "logits_dtype": cfg.dtype,
-                   "group_size": cfg.group_size, "n_rollouts": cfg.n_rollouts,
-                   "rows_live": n_full, "rows_zero_coeff": n_zero_coeff, "rows_masked": n_masked,
-                   "eps_low": cfg.eps_low, "eps_high": cfg.eps_high, "delta": cfg.delta,
-                   "temperature": cfg.temperature,
-                   "row_kernel": grpo.grpo_row_kernel_plan(grpo.GRPO_BF16 if cfg.dtype == "bf16" else grpo.GRPO_F32, V)},
-        "counts": dict(zip(grpo.COUNT_NAMES, c)), "loss": loss_value,
-        "roofline": {"bound": "hbm", "achieved": alg_bytes / kern / 1e9, "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": alg_bytes / kern / 1e9 / HBM_PEAK_GBPS,
-                     "traffic": None if variant else traffic_from_profiles(cfg.name),
+        "config": {"workload": head["workload"], "n_tokens": head["n_tokens"], "vocab": V,
+                   "logits_dtype": head["logits_dtype"], "group_size": head_cfg.group_size,
+                   "n_rollouts": head_cfg.n_rollouts, "rows_live": head["rows_live"],
+                   "rows_zero_coeff": head["rows_zero_coeff"], "rows_masked": head["rows_masked"],
+                   "eps_low": head_cfg.eps_low, "eps_high": head_cfg.eps_high, "delta": head_cfg.delta,
+                   "temperature": head_cfg.temperature, "row_kernel": head_extras.get("row_kernel"),
+                   "also_timed": [n for n in names[1:]]},
+        "value_unmasked_tokens_per_s": head["tokens_per_s_unmasked"],
+        "counts": head["counts"], "loss": head["loss"],
+        "roofline": {"bound": "hbm", "achieved": head["achieved_gbps"], "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": head["frac"],
+                     "traffic": head["traffic"], "traffic_profile": head["traffic_profile"],
                      "kernel": "grpo_rows_cached (inside grpo_loss_fwd_bwd)",
-                     "kernel_ms": kern * 1e3, "kernel_ms_median": kern_spread["median"],
-                     "kernel_ms_min": kern_spread["min"], "kernel_ms_max": kern_spread["max"],
-                     "algorithmic_bytes": alg_bytes,
-                     "gbps_2r1w_all_rows_convention": conv_bytes / kern / 1e9,
-                     "gbps_design_traffic_1r1w": design_bytes / kern / 1e9},
-        "full_rows": {"note": "same logits, every row unmasked and live: the kernel's worst case",
-                      "tokens_per_s": N / wall_full, "kernel_ms": kern_full * 1e3,
-                      "gbps_2r1w": conv_bytes / kern_full / 1e9,
-                      "frac_2r1w": conv_bytes / kern_full / 1e9 / HBM_PEAK_GBPS,
-                      "gbps_design_traffic_1r1w": 2 * N * row_bytes / kern_full / 1e9,
-                      "rows_live": full_counts[0]},
-        "aux_loss": {"note": "grpo_loss_aux_fwd_bwd on the same batch, KL 0.001 and entropy 1e-4 fused in",
-                     "tokens_per_s": N / (aux_ms * 1e-3), "kernel_ms": aux_ms,
-                     "achieved_gbps": aux_alg / (aux_ms * 1e-3) / 1e9,
-                     "frac": aux_alg / (aux_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                     "total": aux_vals[0], "policy": aux_vals[1], "mean_kl": aux_vals[2],
-                     "mean_entropy": aux_vals[3]},
-        "logprobs_fwd": {"note": "grpo_logprobs_fwd, every row unmasked: one read of the logits",
-                         "tokens_per_s": N / (fwd_ms * 1e-3), "kernel_ms": fwd_ms,
-                         "gbps": N * row_bytes / (fwd_ms * 1e-3) / 1e9,
-                         "frac": N * row_bytes / (fwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS},
+                     "kernel_ms": head["kernel_ms"], "kernel_ms_median": head["kernel_ms_median"],
+                     "kernel_ms_min": head["kernel_ms_min"], "kernel_ms_max": head["kernel_ms_max"],
+                     "algorithmic_bytes": head["algorithmic_bytes"],
+                     "note": "achieved/frac count ALGORITHMIC bytes (a live row 2 reads + 1 write); the kernel "
+                             "keeps a row in registers and moves 1 read + 1 write: achieved_moved/frac_moved "
+                             "are the physical share of the 8 TB/s peak",
+                     "moved_bytes": head["moved_bytes"], "achieved_moved": head["moved_gbps"],
+                     "frac_moved": head["frac_moved"],
+                     "effective_gbps_2r1w_all_rows_convention": head["gbps_2r1w_all_rows_convention"],
+                     "worst_frac": worst["frac"], "worst_frac_workload": worst["workload"],
+                     "worst_frac_moved": worst_moved["frac_moved"],
+                     "worst_frac_moved_workload": worst_moved["workload"],
+                     "worst_full_rows_frac_moved": worst_full["full_rows"]["frac_moved"],
+                     "worst_full_rows_frac_moved_workload": worst_full["workload"]},
+        "workloads": records,
     }
-    if not args.no_lmhead and cfg.logits in ("normal", "normal_boost") and cfg.dtype == "bf16":
-        # the leg needs its own operands, gradients and two workspaces next to the batch
-        need = (grpo.grpo_lmhead_workspace_bytes(N, V, args.d_model, True) +
-                grpo.grpo_lmhead_workspace_bytes(N, V, args.d_model, False) +
-                6 * V * args.d_model + 4 * N * args.d_model)
-        free = torch.cuda.mem_get_info()[0]
-        if need < 0.9 * free:
-            out["lmhead"] = lmhead_leg(grpo, wl, cfg, args.d_model, dev, stream, max(3, args.steps // 6))
-        else:
-            out["lmhead"] = {"skipped": "needs %.0f GB of device memory, %.0f GB free" % (need / 1e9, free / 1e9)}
-    if not args.no_cpu_baseline:
-        log("[bench] timing the fp64 oracle on a sample of the batch (about 12 s)")
-        step()
-        torch.cuda.synchronize()
-        out["cpu_baseline"] = cpu_baseline(batch, old, adv_tok)
+    for key in ("lmhead", "cpu_baseline"):
+        if key in head_extras:
+            out[key] = head_extras[key]
     print(json.dumps(out), flush=True)
 
 
