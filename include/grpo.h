@@ -17,7 +17,8 @@
  * Conventions shared by every entry point
  *  - All data pointers are DEVICE pointers owned by the caller.  The library
  *    allocates nothing, frees nothing and keeps no per-call state; scratch comes
- *    from the caller's workspace.
+ *    from the caller's workspace (one entry point, grpo_loss_fwd_bwd_noalloc, uses an
+ *    array built into the library instead; see there).
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
  *    work is enqueued on it; nothing synchronises with the host, so results are
  *    device-resident and valid once the stream has reached that point.
@@ -48,7 +49,9 @@ typedef enum {
     GRPO_ERR_ALIGN = 4,     /* logits/grad base or row pitch not 16-byte aligned       */
     GRPO_ERR_PARAM = 5,     /* temperature <= 0, eps out of range, delta <= 1+eps_high */
     GRPO_ERR_WORKSPACE = 6, /* workspace NULL, misaligned or too small                 */
-    GRPO_ERR_HIP = 7        /* the HIP runtime reported an error at launch             */
+    GRPO_ERR_HIP = 7,       /* the HIP runtime reported an error at launch             */
+    GRPO_ERR_CAPACITY = 8   /* more rows than the library's built-in scratch array holds
+                               (grpo_loss_fwd_bwd_noalloc only)                         */
 } grpo_status;
 
 typedef enum {
@@ -260,6 +263,39 @@ grpo_status grpo_loss_fwd_bwd(const void *logits, grpo_dtype dtype, int64_t n_to
                               float grad_scale, float *loss_out, float *logprobs_out,
                               int64_t *counts_out, void *grad_logits, void *workspace,
                               size_t workspace_bytes, void *stream);
+
+/*
+ * grpo_loss_fwd_bwd for callers that cannot allocate device memory or size a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same computation, same kernels and bit-identical outputs, but the per-row scratch
+ * (objective terms, indicator bits, row queue, denominator) lives in an array built into
+ * the library's device image instead of a caller-supplied workspace, so the call takes
+ * no workspace and neither it nor anything it calls allocates or frees memory.
+ *
+ *  All arguments as in grpo_loss_fwd_bwd, without workspace / workspace_bytes, plus
+ *  error_out    [1] i32, device, written, or NULL: the sticky data-error word that
+ *               grpo_workspace_error reads for the workspace variant (0 = none, bit 0 =
+ *               an unmasked row had a token id outside [0, vocab)).
+ *  Limit:       n_tokens <= GRPO_NOALLOC_MAX_TOKENS, else GRPO_ERR_CAPACITY (nothing is
+ *               launched).  The array takes about 6.5 MiB of every GPU the library is
+ *               used on, for the life of the process.
+ *  Concurrency: all calls on one GPU share that GPU's array (each GPU has its own).  A
+ *               call clears what it needs at its start; two calls that overlap in time
+ *               on the same GPU (different streams, or host threads) race and give
+ *               undefined results.  Calls on one stream, or otherwise ordered, are fine.
+ *  The address of the array is looked up once per device, on the first call made with
+ *  that device current (hipGetSymbolAddress: a query, not an allocation); a failure of
+ *  that lookup returns GRPO_ERR_HIP.
+ */
+#define GRPO_NOALLOC_MAX_TOKENS 524288
+grpo_status grpo_loss_fwd_bwd_noalloc(const void *logits, grpo_dtype dtype, int64_t n_tokens,
+                                      int64_t vocab, int64_t row_stride, const int64_t *tokens,
+                                      const float *old_logprobs, const float *advantages,
+                                      const uint8_t *mask, float eps_low, float eps_high,
+                                      float delta, float temperature, double denom,
+                                      float grad_scale, float *loss_out, float *logprobs_out,
+                                      int64_t *counts_out, void *grad_logits, int32_t *error_out,
+                                      void *stream);
 
 /*
  * The same objective with the trainer's two auxiliary terms fused into the same pass

@@ -49,6 +49,9 @@ def lib():
         L.grpo_loss_fwd_bwd.restype = i32
         L.grpo_loss_fwd_bwd.argtypes = [vp, i32, i64, i64, i64, vp, vp, vp, vp, f32, f32, f32, f32,
                                         f64, f32, vp, vp, vp, vp, vp, sz, vp]
+        L.grpo_loss_fwd_bwd_noalloc.restype = i32
+        L.grpo_loss_fwd_bwd_noalloc.argtypes = [vp, i32, i64, i64, i64, vp, vp, vp, vp, f32, f32, f32, f32,
+                                                f64, f32, vp, vp, vp, vp, vp, vp]
         L.grpo_loss_aux_fwd_bwd.restype = i32
         L.grpo_loss_aux_fwd_bwd.argtypes = [vp, i32, i64, i64, i64, vp, vp, vp, vp, vp, vp, f32, f32, f32,
                                             f32, f32, f32, f64, f32, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -227,6 +230,41 @@ def grpo_loss_fwd_bwd(logits, tokens, old_logprobs, advantages, mask=None, eps_l
     if rc != GRPO_OK:
         raise GrpoError(rc, "grpo_loss_fwd_bwd")
     return loss_out, logprobs_out, counts_out, grad_logits
+
+
+NOALLOC_MAX_TOKENS = 524288  # GRPO_NOALLOC_MAX_TOKENS of grpo.h
+
+
+def grpo_loss_fwd_bwd_noalloc(logits, tokens, old_logprobs, advantages, mask, eps_low, eps_high, delta,
+                              temperature, denom, grad_scale, *, grad_logits, loss_out, logprobs_out=None,
+                              counts_out=None, error_out=None, vocab=None, stream=None):
+    """grpo_loss_fwd_bwd without a workspace; see grpo_loss_fwd_bwd_noalloc in grpo.h.  This wrapper
+    allocates nothing either: every output tensor is the caller's (grad_logits may be the logits
+    tensor itself).  Returns None; results are in the tensors passed."""
+    dt, n, v, stride = _logits_args(logits, vocab)
+    dev = logits.device
+    _check(tokens, torch.int64, n, "tokens", dev)
+    _check(old_logprobs, torch.float32, n, "old_logprobs", dev)
+    _check(advantages, torch.float32, n, "advantages", dev)
+    if mask is not None:
+        _check(mask, torch.uint8, n, "mask", dev)
+    if grad_logits.dtype != logits.dtype or grad_logits.shape != logits.shape or \
+            grad_logits.stride() != logits.stride():
+        raise ValueError("grad_logits must match logits in dtype, shape and strides")
+    _check(loss_out, torch.float32, 1, "loss_out", dev)
+    if logprobs_out is not None:
+        _check(logprobs_out, torch.float32, n, "logprobs_out", dev)
+    if counts_out is not None:
+        _check(counts_out, torch.int64, 5, "counts_out", dev)
+    if error_out is not None:
+        _check(error_out, torch.int32, 1, "error_out", dev)
+    rc = lib().grpo_loss_fwd_bwd_noalloc(_ptr(logits), dt, n, v, stride, _ptr(tokens), _ptr(old_logprobs),
+                                         _ptr(advantages), _ptr(mask), float(eps_low), float(eps_high),
+                                         float(delta), float(temperature), float(denom), float(grad_scale),
+                                         _ptr(loss_out), _ptr(logprobs_out), _ptr(counts_out),
+                                         _ptr(grad_logits), _ptr(error_out), _stream(stream))
+    if rc != GRPO_OK:
+        raise GrpoError(rc, "grpo_loss_fwd_bwd_noalloc")
 
 
 def grpo_loss_aux_fwd_bwd(logits, tokens, old_logprobs, ref_logprobs, advantages, mask=None,

@@ -1338,7 +1338,7 @@ __global__ void __launch_bounds__(1024) grpo_finalize(const float *J_ws, const f
                                                       const unsigned char *flags_ws, long long n,
                                                       const WsHeader *hdr, float kl_coef,
                                                       float ent_coef, float *loss_out,
-                                                      long long *counts_out)
+                                                      long long *counts_out, int *error_out)
 {
     __shared__ double lds_j[16][3];
     __shared__ long long lds_c[16][4];
@@ -1414,6 +1414,7 @@ __global__ void __launch_bounds__(1024) grpo_finalize(const float *J_ws, const f
         } else {
             loss_out[0] = (float)policy;
         }
+        if (error_out) *error_out = hdr->error;  // every row kernel has finished: the word is final
         if (counts_out) {
             counts_out[GRPO_COUNT_TOKENS] = hdr->M;
             counts_out[GRPO_COUNT_CLIP_HIGH] = t[0];
@@ -1717,7 +1718,8 @@ grpo_status loss_impl(bool aux, const void *logits, grpo_dtype dtype, int64_t n_
                       float temperature, float kl_coef,
                       float entropy_coef, double denom, float grad_scale, float *loss_out,
                       float *logprobs_out, float *entropy_out, int64_t *counts_out,
-                      void *grad_logits, void *workspace, size_t workspace_bytes, void *stream)
+                      void *grad_logits, void *workspace, size_t workspace_bytes, void *stream,
+                      int32_t *error_out = nullptr)
 {
     grpo_status rc = check_logits_args(logits, dtype, n_tokens, vocab, row_stride, tokens, temperature);
     if (rc != GRPO_OK) return rc;
@@ -1787,8 +1789,40 @@ grpo_status loss_impl(bool aux, const void *logits, grpo_dtype dtype, int64_t n_
     }
     hipLaunchKernelGGL(grpo_finalize, dim3(1), dim3(1024), 0, st, J_ws,
                        aux ? KL_ws : (const float *)nullptr, H_ws, flags_ws, (long long)n_tokens, hdr,
-                       kl_coef, entropy_coef, loss_out, (long long *)counts_out);
+                       kl_coef, entropy_coef, loss_out, (long long *)counts_out, (int *)error_out);
     return hipGetLastError() == hipSuccess ? GRPO_OK : GRPO_ERR_HIP;
+}
+
+// ---------------------------------------------------------------------------
+// Built-in scratch for grpo_loss_fwd_bwd_noalloc: the workspace of grpo_loss_fwd_bwd for
+// GRPO_NOALLOC_MAX_TOKENS rows as an array in the device image, so that callers that cannot
+// allocate (graph capture, serving loops) need not bring one.  Every GPU that loads the
+// library holds its own copy at its own address.
+// ---------------------------------------------------------------------------
+constexpr size_t noalloc_scratch_bytes(long long n)
+{
+    return kHeaderBytes + 3 * (((size_t)n * 4 + 255) / 256 * 256) + ((size_t)n + 255) / 256 * 256;
+}
+constexpr size_t kScratchBytes = noalloc_scratch_bytes(GRPO_NOALLOC_MAX_TOKENS);
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+// The device address of `scratch` on the current device.  In host code the array's name is
+// only a handle for the runtime, not an address a kernel can use: the address comes from
+// hipGetSymbolAddress, once per device, with that device current, and is kept per device.
+void *scratch_address()
+{
+    static std::atomic<void *> cached[64];  // zero-initialised; racing host threads store the same value
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    void *ptr = cached[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();  // leave no sticky error behind for the caller's next HIP call
+            return nullptr;
+        }
+        cached[dev].store(ptr, std::memory_order_release);
+    }
+    return ptr;
 }
 
 }  // namespace
@@ -1808,6 +1842,8 @@ const char *grpo_status_string(grpo_status status)
                    "delta > 1 + eps_high, eps_std >= 0, ddof in {0,1}";
         case GRPO_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned or too small";
         case GRPO_ERR_HIP: return "HIP runtime error at kernel launch";
+        case GRPO_ERR_CAPACITY:
+            return "n_tokens exceeds GRPO_NOALLOC_MAX_TOKENS, the rows the library's built-in scratch array holds";
     }
     return "unknown status";
 }
@@ -1984,6 +2020,40 @@ grpo_status grpo_loss_fwd_bwd(const void *logits, grpo_dtype dtype, int64_t n_to
                      advantages, mask, nullptr, eps_low, eps_high, delta, temperature, 0.f, 0.f, denom,
                      grad_scale, loss_out, logprobs_out, nullptr, counts_out, grad_logits, workspace,
                      workspace_bytes, stream);
+}
+
+grpo_status grpo_loss_fwd_bwd_noalloc(const void *logits, grpo_dtype dtype, int64_t n_tokens,
+                                      int64_t vocab, int64_t row_stride, const int64_t *tokens,
+                                      const float *old_logprobs, const float *advantages,
+                                      const uint8_t *mask, float eps_low, float eps_high,
+                                      float delta, float temperature, double denom,
+                                      float grad_scale, float *loss_out, float *logprobs_out,
+                                      int64_t *counts_out, void *grad_logits, int32_t *error_out,
+                                      void *stream)
+{
+    // the size limit first: it needs no device, and nothing may be launched beyond it
+    if (n_tokens > (int64_t)GRPO_NOALLOC_MAX_TOKENS) return GRPO_ERR_CAPACITY;
+    static_assert(kScratchBytes % 256 == 0, "the scratch array is a whole number of 256-byte lines");
+    // Validate everything else against a stand-in address before the device is asked for the
+    // real one, so that argument errors are reported the same way with or without a GPU.
+    // (loss_impl launches nothing when validation fails, and fails here only on arguments.)
+    if (n_tokens >= 0 && grpo_workspace_bytes(n_tokens) > kScratchBytes) return GRPO_ERR_CAPACITY;
+    {
+        const grpo_status rc = check_logits_args(logits, dtype, n_tokens, vocab, row_stride, tokens, temperature);
+        if (rc != GRPO_OK) return rc;
+        if (!(eps_low >= 0.f && eps_low <= 1.f) || !(eps_high >= 0.f) || !std::isfinite(eps_high) ||
+            !(delta > 1.f + eps_high) || std::isnan(denom) || std::isnan(grad_scale))
+            return GRPO_ERR_PARAM;
+        if (!loss_out) return GRPO_ERR_NULL;
+        if (n_tokens > 0 && (!old_logprobs || !advantages || !grad_logits)) return GRPO_ERR_NULL;
+        if (n_tokens > 0 && ((uintptr_t)grad_logits & 15u) != 0) return GRPO_ERR_ALIGN;
+    }
+    void *ws = scratch_address();
+    if (!ws) return GRPO_ERR_HIP;
+    return loss_impl(false, logits, dtype, n_tokens, vocab, row_stride, tokens, old_logprobs, nullptr,
+                     advantages, mask, nullptr, eps_low, eps_high, delta, temperature, 0.f, 0.f, denom,
+                     grad_scale, loss_out, logprobs_out, nullptr, counts_out, grad_logits, ws,
+                     kScratchBytes, stream, error_out);
 }
 
 grpo_status grpo_loss_aux_fwd_bwd(const void *logits, grpo_dtype dtype, int64_t n_tokens,

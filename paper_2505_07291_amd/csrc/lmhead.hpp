@@ -1142,7 +1142,7 @@ grpo_status lm_impl(bool bwd, bool aux, const void *hidden, int64_t hidden_strid
     if (bwd)
         hipLaunchKernelGGL(grpo_finalize, dim3(1), dim3(1024), 0, st, J_ws, aux ? KL_ws : (const float *)nullptr, H_ws,
                            flags_ws, (long long)n_tokens, hdr, kl_coef, entropy_coef, loss_out,
-                           (long long *)counts_out);
+                           (long long *)counts_out, (int *)nullptr);
     return hipGetLastError() == hipSuccess ? GRPO_OK : GRPO_ERR_HIP;
 }
 

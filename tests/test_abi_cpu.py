@@ -10,7 +10,7 @@ import pytest
 import paper_2505_07291_amd as grpo
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-OK, NULL, SHAPE, DTYPE, ALIGN, PARAM, WORKSPACE, HIP = range(8)
+OK, NULL, SHAPE, DTYPE, ALIGN, PARAM, WORKSPACE, HIP, CAPACITY = range(9)
 P = 0x7F0000001000  # a fake, 256-byte aligned, non-null "device pointer": validation never dereferences
 
 
@@ -31,7 +31,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_status_strings_and_workspace_size():
-    for code in range(8):
+    for code in range(9):
         assert len(grpo.status_string(code)) > 1
     assert grpo.status_string(99) == "unknown status"
     assert grpo.grpo_workspace_bytes(-1) == 0
@@ -113,6 +113,33 @@ def loss_args(**over):
 ])
 def test_loss_fwd_bwd_rejects_bad_arguments_before_any_launch(over, expect):
     assert grpo.lib().grpo_loss_fwd_bwd(*loss_args(**over)) == expect
+
+
+def noalloc_args(**over):
+    a = dict(logits=P, dtype=1, n=16, V=1024, stride=1024, tokens=P, old=P, adv=P, mask=P,
+             el=0.2, eh=0.2, delta=4.0, T=1.0, denom=0.0, gs=1.0, loss=P, lp=P, counts=P, grad=P,
+             err=P, stream=None)
+    a.update(over)
+    return [a[k] for k in ("logits", "dtype", "n", "V", "stride", "tokens", "old", "adv", "mask",
+                           "el", "eh", "delta", "T", "denom", "gs", "loss", "lp", "counts", "grad",
+                           "err", "stream")]
+
+
+@pytest.mark.parametrize("over,expect", [
+    (dict(n=grpo.NOALLOC_MAX_TOKENS + 1), CAPACITY), (dict(n=1 << 40), CAPACITY),
+    (dict(logits=None), NULL), (dict(old=None), NULL), (dict(loss=None), NULL), (dict(grad=None), NULL),
+    (dict(n=-1), SHAPE), (dict(V=0), SHAPE), (dict(stride=1000), SHAPE), (dict(dtype=2), DTYPE),
+    (dict(logits=P + 8), ALIGN), (dict(grad=P + 2), ALIGN),
+    (dict(T=0.0), PARAM), (dict(el=1.5), PARAM), (dict(delta=1.2), PARAM), (dict(denom=float("nan")), PARAM),
+])
+def test_noalloc_variant_rejects_bad_arguments_before_any_launch(over, expect):
+    """The entry point without a workspace: the row limit of its built-in scratch array is checked
+    first and by itself (no device is needed to refuse), then the same argument checks as the
+    workspace variant."""
+    assert grpo.lib().grpo_loss_fwd_bwd_noalloc(*noalloc_args(**over)) == expect
+    assert "GRPO_NOALLOC_MAX_TOKENS" in grpo.status_string(CAPACITY)
+    hdr = open(os.path.join(ROOT, "include", "grpo.h")).read()
+    assert "#define GRPO_NOALLOC_MAX_TOKENS %d" % grpo.NOALLOC_MAX_TOKENS in hdr
 
 
 def test_logprobs_and_advantages_reject_bad_arguments():
