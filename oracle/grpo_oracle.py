@@ -440,19 +440,43 @@ def lmhead_grad_weight(G, hidden, vocab_rows=None):
     return out
 
 
+def widen(a):
+    """Stored values as fp64, exactly: uint16 arrays are bf16 bit patterns (a bf16 is the upper
+    half of a binary32), float32 / float64 arrays are taken as they are."""
+    a = np.asarray(a)
+    if a.dtype == np.uint16:
+        return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    return a.astype(np.float64)
+
+
+def lmhead_products(products):
+    """The three matrix products of the head, z = h W^T, dL/dh = G W, dL/dW = G^T h, either as
+    the plain loops of grpo_oracle.c ("loops") or as numpy's fp64 matrix product of the exactly
+    widened operands ("library": the same sums, in the order the library picks; what sizes too
+    large for the loops are checked with).  Returns (logits, grad_hidden, grad_weight)."""
+    if products == "loops":
+        return lmhead_logits, lmhead_grad_hidden, lmhead_grad_weight
+    if products == "library":
+        return (lambda hidden, weight: widen(hidden) @ widen(weight).T,
+                lambda G, weight: np.asarray(G, dtype=np.float64) @ widen(weight),
+                lambda G, hidden: np.asarray(G, dtype=np.float64).T @ widen(hidden))
+    raise ValueError("products must be 'loops' or 'library'")
+
+
 def lmhead_loss_fwd_bwd(hidden, weight, tokens, old_logprobs, advantages, mask=None, *,
                         eps_low=0.2, eps_high=0.2, delta=4.0, temperature=1.0, denom=0.0,
-                        grad_scale=1.0, want_grads=True):
+                        grad_scale=1.0, want_grads=True, products="loops"):
     """The objective of ``loss_fwd_bwd`` on logits z = h W^T that are never rounded,
     and its gradient with respect to the hidden states and the head's weights."""
-    z = lmhead_logits(hidden, weight)
+    logits_of, grad_hidden_of, grad_weight_of = lmhead_products(products)
+    z = logits_of(hidden, weight)
     res = loss_fwd_bwd(z, tokens, old_logprobs, advantages, mask, eps_low=eps_low,
                        eps_high=eps_high, delta=delta, temperature=temperature, denom=denom,
                        grad_scale=grad_scale, grad_rows="all" if want_grads else None)
     res["logits"] = z
     if want_grads:
-        res["grad_hidden"] = lmhead_grad_hidden(res["grad"], weight)
-        res["grad_weight"] = lmhead_grad_weight(res["grad"], hidden)
+        res["grad_hidden"] = grad_hidden_of(res["grad"], weight)
+        res["grad_weight"] = grad_weight_of(res["grad"], hidden)
     return res
 
 

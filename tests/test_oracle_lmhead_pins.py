@@ -45,6 +45,28 @@ def test_contractions_match_library_products(dtype):
     assert np.abs(orc.lmhead_grad_weight(G, h, [18, 3]) - (G.T @ H)[[18, 3]]).max() < 1e-13
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_composition_with_library_products_equals_the_one_with_plain_loops(dtype):
+    """lmhead_loss_fwd_bwd(products="library") swaps the three plain-loop products for numpy's
+    fp64 matrix product of the exactly widened operands (what the GPU tests use at sizes the
+    loops would take minutes for): every output agrees with the plain-loop composition to
+    fp64 rounding, on non-square shapes, with clipped, capped and masked rows present."""
+    rng, h, w, tokens, adv, mask = _problem(11, N=23, d=17, V=31, dtype=dtype)
+    assert np.array_equal(orc.widen(h), _wide(h)) and orc.widen(h).dtype == np.float64
+    lp = orc.logprobs(orc.lmhead_logits(h, w), tokens, mask)
+    old = (lp + rng.uniform(-2.0, 2.0, lp.shape)).astype(np.float32)     # ratios e^-2 .. e^2
+    kw = dict(eps_low=0.2, eps_high=0.3, delta=3.0, temperature=0.8, denom=7.5, grad_scale=1.7)
+    a = orc.lmhead_loss_fwd_bwd(h, w, tokens, old, adv, mask, products="loops", **kw)
+    b = orc.lmhead_loss_fwd_bwd(h, w, tokens, old, adv, mask, products="library", **kw)
+    assert a["counts"].tolist() == b["counts"].tolist() and min(a["counts"][1:3]) > 0
+    assert abs(a["loss"] - b["loss"]) <= 1e-13 * abs(a["loss"])
+    for key in ("logits", "logprobs", "grad", "grad_hidden", "grad_weight"):
+        scale = np.abs(a[key]).max()
+        assert scale > 0 and np.abs(a[key] - b[key]).max() <= 1e-13 * scale, key
+    with pytest.raises(ValueError):
+        orc.lmhead_loss_fwd_bwd(h, w, tokens, old, adv, mask, products="fast")
+
+
 def test_row_strides_are_honoured():
     rng = np.random.default_rng(2)
     hb = rng.standard_normal((4, 16)).astype(np.float32)
