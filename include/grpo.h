@@ -366,15 +366,27 @@ grpo_status grpo_workspace_error(const void *workspace, int32_t *flag_out, void 
  *  tokens, mask, temperature, old_logprobs, advantages, eps_low, eps_high, delta,
  *  denom, grad_scale, loss_out, logprobs_out, counts_out: as in
  *           grpo_logprobs_fwd / grpo_loss_fwd_bwd.
- *  workspace  device, 256-byte aligned, at least
- *           grpo_lmhead_workspace_bytes(n_tokens, vocab, d_model, with_backward)
- *           bytes.  Forward only it holds a compacted copy of the hidden states
- *           of the rows that take part and 8 bytes per token and 256 vocabulary
- *           entries; with the backward it also holds the logits in fp32, the
- *           gradient with respect to them in bf16 (twice: row-major and
- *           transposed) and transposed copies of W and h, about
- *           8 * n_tokens * vocab + 2 * vocab * d_model bytes.  Contents on entry are
+ *  workspace  device, 256-byte aligned.  Forward only: at least
+ *           grpo_lmhead_workspace_bytes(n_tokens, vocab, d_model, 0) bytes; it holds a
+ *           compacted copy of the hidden states of the rows that take part and 8 bytes
+ *           per token and 256 vocabulary entries.  With the backward the rows that take
+ *           part are worked through in chunks, and per chunk row the workspace also holds
+ *           the logits in fp32 and their gradient in bf16 (twice: row-major and
+ *           transposed), 8 bytes per chunk row and vocabulary entry, next to transposed
+ *           copies of W and of the chunk's hidden states: its size follows the chunk, not
+ *           the number of tokens.  grpo_lmhead_workspace_bytes(.., 1) is the size for
+ *           the default chunk of 8192 rows (about 10.3 GB at vocab 152064, d_model 5120,
+ *           for any n_tokens >= 8192); grpo_lmhead_workspace_bytes_for_chunk gives the
+ *           size for another chunk.  The call uses the largest chunk (a multiple of 256
+ *           rows, at most n_tokens rounded up to 256) that fits into workspace_bytes:
+ *           a caller short of memory brings less, down to a chunk of 256 rows, a caller
+ *           with memory to spare brings more and gets fewer, larger chunks.  Less than
+ *           the 256-row size is GRPO_ERR_WORKSPACE.  Contents on entry are
  *           ignored; the error word is read with grpo_workspace_error.
+ *  Results do not depend on the chunk except for dL/dW, whose sum over the rows is taken
+ *  chunk by chunk in fp32 (the same as accumulating micro-batches).
+ *  With the backward vocab may not exceed 8388544 (byte offsets inside an operand tile of
+ *  the two gradient products are 32-bit): larger values are GRPO_ERR_SHAPE.
  * Rows with mask 0 cost no matrix work, and neither do, in the backward, rows whose
  * objective has no gradient (clipped, delta-capped, zero advantage): the rows that
  * take part are compacted on the device first.
@@ -383,8 +395,11 @@ grpo_status grpo_workspace_error(const void *workspace, int32_t *flag_out, void 
  * `stream`; nothing is allocated.
  * ------------------------------------------------------------------------- */
 
-/* Pure host function; 0 for invalid sizes. */
+/* Pure host functions; 0 for invalid sizes.  The second: the backward's workspace for chunks of
+ * chunk_rows rows (rounded up to a multiple of 256, at most n_tokens rounded up likewise). */
 size_t grpo_lmhead_workspace_bytes(int64_t n_tokens, int64_t vocab, int64_t d_model, int with_backward);
+size_t grpo_lmhead_workspace_bytes_for_chunk(int64_t n_tokens, int64_t vocab, int64_t d_model,
+                                             int64_t chunk_rows);
 
 /*
  * logprobs_out[t] = log softmax(W h_t / T)[y_t] for rows with mask 1 (0 at masked
@@ -432,8 +447,7 @@ grpo_status grpo_lmhead_loss_fwd_bwd(const void *hidden, int64_t hidden_stride, 
  * loss_out exactly as documented for grpo_loss_aux_fwd_bwd; G = grad_scale * dtotal/dz as
  * defined there, rounded to bf16 before the two products.  A row with weight 0 is treated
  * like a masked row and costs no matrix work.  With entropy_coef != 0 every row that takes
- * part has a gradient.  The same workspace size as grpo_lmhead_loss_fwd_bwd
- * (grpo_lmhead_workspace_bytes with with_backward != 0).
+ * part has a gradient.  The same workspace rules as grpo_lmhead_loss_fwd_bwd.
  */
 grpo_status grpo_lmhead_loss_aux_fwd_bwd(const void *hidden, int64_t hidden_stride, const void *weight,
                                          int64_t weight_stride, int64_t n_tokens, int64_t vocab,

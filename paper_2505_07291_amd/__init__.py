@@ -8,7 +8,7 @@ from .binding import (COUNT_NAMES, GRPO_BF16, GRPO_F32, GrpoError, grpo_filter_g
                       grpo_loss_fwd_bwd_noalloc, NOALLOC_MAX_TOKENS,
                       grpo_workspace_bytes, grpo_row_kernel_plan,
                       grpo_workspace_error, lib, status_string,
-                      grpo_lmhead_workspace_bytes, grpo_lmhead_logprobs_fwd, grpo_lmhead_loss_fwd_bwd,
+                      grpo_lmhead_workspace_bytes, grpo_lmhead_workspace_bytes_for_chunk, grpo_lmhead_logprobs_fwd, grpo_lmhead_loss_fwd_bwd,
                       grpo_lmhead_loss_aux_fwd_bwd)
 from .build import build_library  # noqa: F401
 from . import workloads  # noqa: F401

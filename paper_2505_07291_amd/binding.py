@@ -65,6 +65,8 @@ def lib():
         L.grpo_workspace_error.argtypes = [vp, vp, vp]
         L.grpo_lmhead_workspace_bytes.restype = sz
         L.grpo_lmhead_workspace_bytes.argtypes = [i64, i64, i64, i32]
+        L.grpo_lmhead_workspace_bytes_for_chunk.restype = sz
+        L.grpo_lmhead_workspace_bytes_for_chunk.argtypes = [i64, i64, i64, i64]
         L.grpo_lmhead_logprobs_fwd.restype = i32
         L.grpo_lmhead_logprobs_fwd.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, vp, f32, vp, vp, sz, vp]
         L.grpo_lmhead_loss_fwd_bwd.restype = i32
@@ -167,11 +169,29 @@ def grpo_group_advantages(rewards, group_size=None, group_offsets=None, eps_std=
     return adv_out, adv_tok_out
 
 
+_queue_workspaces = {}
+
+
+def _queue_workspace(device, stream):
+    """The small workspace grpo_logprobs_fwd's row queue lives in, one per device and stream, made
+    on first use and kept: calls on one stream run one after the other, so they can share it, and
+    the call does not allocate again (calls on different streams may overlap and must not)."""
+    if stream is None:
+        stream = torch.cuda.current_stream(device)
+    key = (device.index if device.index is not None else torch.cuda.current_device(), stream.cuda_stream)
+    ws = _queue_workspaces.get(key)
+    if ws is None:
+        ws = torch.empty(grpo_workspace_bytes(0), dtype=torch.uint8, device=device)
+        if not torch.cuda.is_current_stream_capturing():   # memory made under capture belongs to that graph
+            _queue_workspaces[key] = ws
+    return ws
+
+
 def grpo_logprobs_fwd(logits, tokens, mask=None, temperature=1.0, vocab=None, logprobs_out=None,
                       workspace=None, use_queue=True, stream=None):
     """log softmax(logits / T)[tokens] per row; see grpo_logprobs_fwd in grpo.h.
-    A small workspace for the row queue is allocated unless one is passed or
-    ``use_queue`` is False."""
+    Unless a workspace is passed or ``use_queue`` is False, the row queue uses a small
+    workspace this module keeps per device and stream."""
     dt, n, v, stride = _logits_args(logits, vocab)
     dev = logits.device
     _check(tokens, torch.int64, n, "tokens", dev)
@@ -180,7 +200,7 @@ def grpo_logprobs_fwd(logits, tokens, mask=None, temperature=1.0, vocab=None, lo
     if logprobs_out is None:
         logprobs_out = torch.empty(n, dtype=torch.float32, device=dev)
     if workspace is None and use_queue and n > 0:
-        workspace = torch.empty(grpo_workspace_bytes(0), dtype=torch.uint8, device=dev)
+        workspace = _queue_workspace(dev, stream)
     rc = lib().grpo_logprobs_fwd(_ptr(logits), dt, n, v, stride, _ptr(tokens), _ptr(mask),
                                  float(temperature), _ptr(logprobs_out), _ptr(workspace),
                                  0 if workspace is None else workspace.numel(), _stream(stream))
@@ -385,6 +405,12 @@ def grpo_workspace_error(workspace, stream=None) -> int:
 def grpo_lmhead_workspace_bytes(n_tokens: int, vocab: int, d_model: int, with_backward: bool) -> int:
     return int(lib().grpo_lmhead_workspace_bytes(int(n_tokens), int(vocab), int(d_model),
                                                  1 if with_backward else 0))
+
+
+def grpo_lmhead_workspace_bytes_for_chunk(n_tokens: int, vocab: int, d_model: int, chunk_rows: int) -> int:
+    """Workspace of the backward when it works through the rows in chunks of ``chunk_rows``."""
+    return int(lib().grpo_lmhead_workspace_bytes_for_chunk(int(n_tokens), int(vocab), int(d_model),
+                                                           int(chunk_rows)))
 
 
 def _lmhead_args(hidden, weight):

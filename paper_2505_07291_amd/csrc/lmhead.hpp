@@ -13,6 +13,14 @@
 // and H^T are transposed copies, so every operand of every product is K-contiguous and
 // one kernel serves all three.
 //
+// The backward works through the rows that take part in chunks of at most `cap` rows (a
+// multiple of 256 chosen from the size of the caller's workspace): logits, G, G^T and H^T
+// exist for one chunk at a time, dL/dH rows of different chunks are disjoint and dL/dW is
+// accumulated in fp32 from chunk to chunk.  The workspace is therefore bounded by the
+// chunk, not by the number of tokens.  The live rows are dealt evenly over the chunks
+// that are needed (lm_chunk_range, computed on the device from the live count), so no
+// chunk is a small remainder.
+//
 // Kernel shape (gfx950): 512 lanes = 8 wavefronts per workgroup (two per SIMD), one
 // 256 x 256 tile of C per workgroup, K in steps of 64.  Each wavefront owns a 128 x 64 part
 // as 4 x 2 blocks of v_mfma_f32_32x32x16_bf16 (128 accumulator registers per lane).  Eight
@@ -26,6 +34,8 @@
 // quarter of a ds_read_b128 fragment read) fall on 16 different groups of four banks.
 // After the last K step the same LDS serves the epilogue: the accumulators are turned round
 // through it so that the per-row softmax partials are plain loops, one row per lane.
+
+#include <algorithm>
 
 namespace {
 
@@ -56,6 +66,9 @@ struct GemmParams {
     long long lda, ldb;  // elements; rows 16-byte aligned
     int M, N, K;         // host-side sizes: M and K are upper bounds when the device values below are given
     const int *M_dev;    // optional: number of rows of A actually present (<= M)
+    int chunk, chunk_cap;  // chunk_cap > 0: *M_dev counts the rows of ALL chunks and this launch works on chunk
+                           // number `chunk` of them (lm_chunk_range): A, tokens32 and zy start at the
+                           // chunk's first row, the partials and Z are the chunk's own
     const int *K_dev;    // optional: length of the contraction actually present, rounded up to LM_BK
                          // in the kernel (the padding must hold zeros); 0 gives a zero result
     int tiles_n;
@@ -81,6 +94,22 @@ struct GemmParams {
     float *Z;                // optional fp32 copy of the logits, [M][ldz]
     long long ldz;
 };
+
+// Which of n_live rows chunk number `chunk` covers when no chunk may hold more than cap rows
+// (cap a multiple of 256): the fewest chunks that can hold them, each of the same size rounded
+// up to whole 256-row tiles.  Chunks beyond those are empty (count 0).
+__host__ __device__ inline void lm_chunk_range(int n_live, int cap, int chunk, int &base, int &count)
+{
+    const int needed = (n_live + cap - 1) / cap;
+    if (chunk >= needed) {
+        base = n_live;
+        count = 0;
+        return;
+    }
+    const int per = ((n_live + needed - 1) / needed + 255) / 256 * 256;  // <= cap
+    base = chunk * per;  // < n_live: (needed - 1) cap < n_live and per <= cap
+    count = n_live - base < per ? n_live - base : per;
+}
 
 // Workgroup -> tile.  The hardware deals consecutive workgroups to the 8 XCDs in turn;
 // each XCD has its own L2.  Workgroups of one XCD are given a contiguous run of the
@@ -184,8 +213,15 @@ template <int EPI, bool STORE_Z, bool AUX = false>
 __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
 {
     extern __shared__ __attribute__((aligned(1024))) char lm_smem[];
-    const int M = p.M_dev ? min(*p.M_dev, p.M) : p.M;
+    int M = p.M_dev ? min(*p.M_dev, p.M) : p.M;
+    int chunk_base = 0;  // first row of this launch's chunk in A, tokens32 and zy
+    if (p.chunk_cap > 0) {
+        int count;
+        lm_chunk_range(*p.M_dev, p.chunk_cap, p.chunk, chunk_base, count);
+        M = min(count, p.M);
+    }
     const int K = p.K_dev ? min((*p.K_dev + LM_BK - 1) / LM_BK * LM_BK, p.K) : p.K;
+    if (EPI == LM_EPI_F32 && p.accumulate && K == 0) return;  // nothing to add (an empty chunk)
     int tm, tn, part = 0, parts = 1, rest_index = -1;
     {
         const int tiles_m = (M + LM_BM - 1) / LM_BM;
@@ -220,7 +256,7 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
     // this workgroup's part of the contraction: K steps [kt0, kt0 + KT)
     const int kt0 = (int)((long long)(K / LM_BK) * part / parts);
     const int KT = (int)((long long)(K / LM_BK) * (part + 1) / parts) - kt0;
-    const char *a_tile = (const char *)p.A + ((long long)row0 * p.lda + (long long)kt0 * LM_BK) * 2;
+    const char *a_tile = (const char *)p.A + ((long long)(chunk_base + row0) * p.lda + (long long)kt0 * LM_BK) * 2;
     const char *b_tile = (const char *)p.B + ((long long)col0 * p.ldb + (long long)kt0 * LM_BK) * 2;
 
     // LDS is a ring of five 32 KB slots that operand tiles pass through in the order
@@ -403,7 +439,7 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
         const int r = row0 + tid;
         int yc = -1;
         if (r < M) {
-            const int y = p.tokens32[r];
+            const int y = p.tokens32[chunk_base + r];
             if (y >= col0 && y < col0 + LM_BN && y < p.N) yc = y - col0;
         }
         ycol_s[tid] = yc;
@@ -438,7 +474,7 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
         float *myrow = stage + lane * LM_EPI_PITCH;
         const int yc = ycol_s[rbase + lane] - wcol;
         if (yc >= 0 && yc < 64) {
-            p.zy[row0 + rbase + lane] = myrow[yc];
+            p.zy[chunk_base + row0 + rbase + lane] = myrow[yc];
             myrow[yc] = -INFINITY;
         }
         if (ncols < 64)
@@ -518,9 +554,10 @@ struct LmRows {
     float *gy;     // gradient at the sampled token: q (1 - p_y), from the sum without y
     // with the auxiliary terms: g_j = p_j (q2 + bq a_j), a_j = (z_j - mx) k - log2s = log2 p_j
     float *mx, *log2s, *q2, *bq;
-    float *part_m, *part_s, *part_w;
+    float *part_m, *part_s, *part_w;  // [tiles_n][part_stride], by row inside the chunk
     long long part_stride;
     int tiles_n;
+    int chunk, chunk_cap;  // the chunk of compact rows the per-chunk kernels work on (lm_chunk_range)
 };
 
 // Ordered compaction by one workgroup: keeps the indices i < n with keep(i), in order.
@@ -589,14 +626,17 @@ __global__ void __launch_bounds__(1024) lm_select_rows(RowParams p, LmRows w)
     if (threadIdx.x == 0) *w.n_live = total;
 }
 
-// Compact rows with a gradient -> rows2[], orig2[], *n_grad.
+// Compact rows of the current chunk with a gradient -> rows2[] (compact row), orig2[] (original
+// row), *n_grad.
 __global__ void __launch_bounds__(1024) lm_select_grad_rows(LmRows w)
 {
+    int base, count;
+    lm_chunk_range(*w.n_live, w.chunk_cap, w.chunk, base, count);
     const int total = lm_ordered_select(
-        *w.n_live, [&](long long i) { return w.q[i] != 0.f || (w.bq && w.bq[i] != 0.f); },
-        [&](int pos, long long i) {
-            w.rows2[pos] = (int)i;
-            w.orig2[pos] = w.rows[i];
+        count, [&](long long j) { return w.q[base + j] != 0.f || (w.bq && w.bq[base + j] != 0.f); },
+        [&](int pos, long long j) {
+            w.rows2[pos] = base + (int)j;
+            w.orig2[pos] = w.rows[base + j];
         });
     if (threadIdx.x == 0) *w.n_grad = total;
 }
@@ -623,11 +663,14 @@ __global__ void __launch_bounds__(LM_CMB_ROWS * LM_CMB_LANES) lm_combine(RowPara
     __shared__ float sh_m[LM_CMB_LANES][LM_CMB_ROWS + 1], sh_s[LM_CMB_LANES][LM_CMB_ROWS + 1];
     __shared__ float sh_w[LM_CMB_LANES][LM_CMB_ROWS + 1];
     const int rl = threadIdx.x % LM_CMB_ROWS, tl = threadIdx.x / LM_CMB_ROWS;
-    const long long i = (long long)blockIdx.x * LM_CMB_ROWS + rl;
-    const bool live = i < *w.n_live;
+    int base, count;
+    lm_chunk_range(*w.n_live, w.chunk_cap, w.chunk, base, count);
+    const long long il = (long long)blockIdx.x * LM_CMB_ROWS + rl;  // row inside the chunk: the partials' index
+    const long long i = base + il;                                  // compact row: the per-row arrays' index
+    const bool live = il < count;
     float mz = -INFINITY;  // maximum over the tiles, in units of z
     if (live)
-        for (int t = tl; t < w.tiles_n; t += LM_CMB_LANES) mz = fmaxf(mz, w.part_m[(long long)t * w.part_stride + i]);
+        for (int t = tl; t < w.tiles_n; t += LM_CMB_LANES) mz = fmaxf(mz, w.part_m[(long long)t * w.part_stride + il]);
     sh_m[tl][rl] = mz;
     __syncthreads();
 #pragma unroll
@@ -638,14 +681,14 @@ __global__ void __launch_bounds__(LM_CMB_ROWS * LM_CMB_LANES) lm_combine(RowPara
     float s = 0.f, ws = 0.f;
     if (live)
         for (int t = tl; t < w.tiles_n; t += LM_CMB_LANES) {
-            const float mt = w.part_m[(long long)t * w.part_stride + i];
+            const float mt = w.part_m[(long long)t * w.part_stride + il];
             if (mt == -INFINITY) continue;
-            const float st = w.part_s[(long long)t * w.part_stride + i];
+            const float st = w.part_s[(long long)t * w.part_stride + il];
             if constexpr (AUX) {
                 const float d = (mt - mx) * p.k;
                 const float f = __builtin_amdgcn_exp2f(d);
                 s = fmaf(st, f, s);
-                ws = fmaf(f, fmaf(d, st, w.part_w[(long long)t * w.part_stride + i]), ws);
+                ws = fmaf(f, fmaf(d, st, w.part_w[(long long)t * w.part_stride + il]), ws);
             } else {
                 s = fmaf(st, __builtin_amdgcn_exp2f(fmaf(mt, p.k, -mk)), s);
             }
@@ -699,6 +742,8 @@ __global__ void __launch_bounds__(256) lm_grad_logits(const float *Z, long long 
     const int n2 = *w.n_grad;
     const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
     if (r0 >= (n2 + 63) / 64 * 64) return;
+    int zbase, zcount;  // Z holds the current chunk's rows only
+    lm_chunk_range(*w.n_live, w.chunk_cap, w.chunk, zbase, zcount);
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;  // 16 x 4 columns, 16 rows per pass
     const int c = c0 + tx * 4;
 #pragma unroll
@@ -714,7 +759,7 @@ __global__ void __launch_bounds__(256) lm_grad_logits(const float *Z, long long 
                 q = w.q[ci], sh = w.shift[ci];
             }
             const int y = w.tokens32[ci];
-            const float *zrow = Z + (long long)ci * ldz + c;
+            const float *zrow = Z + (long long)(ci - zbase) * ldz + c;
             float z[4];
             if (c + 3 < V) {
                 const f32x4 zv = *(const f32x4 *)zrow;
@@ -770,7 +815,8 @@ __global__ void __launch_bounds__(256) lm_transpose(const __bf16 *in, long long 
 {
     __shared__ unsigned short tile[64][66];
     if (R_dev) R = min(R, *R_dev);
-    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+    // x walks the rows of `in` (the vocabulary for W: the y extent of a grid ends at 65535)
+    const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;  // 16 lanes x 4 elements across, 16 down
     const unsigned short *src = (const unsigned short *)in;
     unsigned short *dst = (unsigned short *)out;
@@ -871,16 +917,27 @@ hipError_t lm_launch_gemm(GemmParams p, hipStream_t st)
 struct LmLayout {
     size_t rows, tokens32, rows2, orig2, counts, zy, shift, q, gy, mx, log2s, q2, bq, part_m, part_s, part_w, Hc, Z, G, Gt,
         Wt, Ht, total;
-    long long ldz, ldg, ldgt;  // vocab and token counts rounded up to whole K steps
+    long long ldz, ldg, ldgt;  // vocab and chunk rows rounded up to whole K steps
     int tiles_n;
+    int cap;  // rows per chunk: what the partials, Z, G, G^T and H^T are sized for
 };
 
-LmLayout lm_layout(int64_t n, int64_t V, int64_t d, bool bwd)
+// Default limit of a chunk of the backward: 8192 rows keep the workspace at V = 152064 near
+// 10 GB whatever the number of tokens, and a chunk still fills the chip (32 tile rows: 19008 tiles
+// of the logits product, 640 of dL/dH).  A caller that brings more gets larger chunks.
+constexpr int64_t kLmChunkRows = 8192;
+constexpr int64_t kLmChunkMax = 1 << 20;  // rows; keeps every per-chunk grid extent and 32-bit offset in range
+
+int64_t lm_cap_limit(int64_t n) { return std::min<int64_t>(kLmChunkMax, std::max<int64_t>(256, (n + 255) / 256 * 256)); }
+
+// cap: rows per chunk, a multiple of 256 in [256, lm_cap_limit(n)] (the forward alone is one chunk)
+LmLayout lm_layout(int64_t n, int64_t V, int64_t d, bool bwd, int64_t cap)
 {
     LmLayout L = {};
+    L.cap = (int)cap;
     L.tiles_n = (int)((V + LM_BN - 1) / LM_BN);
     L.ldz = L.ldg = (long long)align_up((size_t)V, 64);  // whole K steps, 128-byte rows
-    L.ldgt = (long long)align_up((size_t)n, 64);
+    L.ldgt = (long long)align_up((size_t)cap, 64);
     size_t off = align_up(grpo_workspace_bytes(n), 256);
     auto take = [&](size_t bytes) {
         const size_t at = off;
@@ -891,12 +948,12 @@ LmLayout lm_layout(int64_t n, int64_t V, int64_t d, bool bwd)
     L.rows = take((size_t)n * 4);
     L.tokens32 = take((size_t)n * 4);
     L.zy = take((size_t)n * 4);
-    L.part_m = take((size_t)L.tiles_n * n * 4);
-    L.part_s = take((size_t)L.tiles_n * n * 4);
+    L.part_m = take((size_t)L.tiles_n * cap * 4);
+    L.part_s = take((size_t)L.tiles_n * cap * 4);
     L.Hc = take((size_t)n * d * 2);
     if (bwd) {
-        L.rows2 = take((size_t)n * 4);
-        L.orig2 = take((size_t)n * 4);
+        L.rows2 = take((size_t)cap * 4);
+        L.orig2 = take((size_t)cap * 4);
         L.shift = take((size_t)n * 4);
         L.q = take((size_t)n * 4);
         L.gy = take((size_t)n * 4);
@@ -904,9 +961,9 @@ LmLayout lm_layout(int64_t n, int64_t V, int64_t d, bool bwd)
         L.log2s = take((size_t)n * 4);
         L.q2 = take((size_t)n * 4);
         L.bq = take((size_t)n * 4);
-        L.part_w = take((size_t)L.tiles_n * n * 4);
-        L.Z = take((size_t)n * L.ldz * 4);
-        L.G = take((size_t)n * L.ldg * 2);
+        L.part_w = take((size_t)L.tiles_n * cap * 4);
+        L.Z = take((size_t)cap * L.ldz * 4);
+        L.G = take((size_t)cap * L.ldg * 2);
         L.Gt = take((size_t)V * L.ldgt * 2);
         L.Wt = take((size_t)d * L.ldg * 2);
         L.Ht = take((size_t)d * L.ldgt * 2);
@@ -915,13 +972,36 @@ LmLayout lm_layout(int64_t n, int64_t V, int64_t d, bool bwd)
     return L;
 }
 
+// The largest chunk (multiple of 256 rows) whose workspace fits `bytes`; 0 if not even 256 rows do.
+int64_t lm_cap_for_workspace(int64_t n, int64_t V, int64_t d, size_t bytes)
+{
+    int64_t lo = 0, hi = lm_cap_limit(n) / 256;  // in units of 256 rows; the size grows with the chunk
+    while (lo < hi) {
+        const int64_t mid = (lo + hi + 1) / 2;
+        if (lm_layout(n, V, d, true, mid * 256).total <= bytes)
+            lo = mid;
+        else
+            hi = mid - 1;
+    }
+    return lo * 256;
+}
+
+bool lm_sizes_ok(int64_t n_tokens, int64_t vocab, int64_t d_model)
+{
+    return n_tokens >= 0 && n_tokens <= 0x7fffff00ll && vocab > 0 && vocab <= kMaxVocab && d_model > 0 &&
+           d_model <= (1 << 20) && d_model % LM_BK == 0;
+}
+// With the backward G and W^T are operands whose rows are align64(vocab) elements long: the byte offset
+// of row 255 of an operand tile must fit 32 bits.
+bool lm_bwd_vocab_ok(int64_t vocab) { return (int64_t)align_up((size_t)vocab, 64) * 2 * LM_BM < (1ll << 32); }
+
 grpo_status lm_check_common(const void *hidden, int64_t hidden_stride, const void *weight,
                             int64_t weight_stride, int64_t n_tokens, int64_t vocab, int64_t d_model,
-                            const int64_t *tokens, float temperature)
+                            const int64_t *tokens, float temperature, bool bwd)
 {
-    if (n_tokens < 0 || n_tokens > 0x7fffff00ll || vocab <= 0 || vocab > kMaxVocab || d_model <= 0 ||
-        d_model > (1 << 20) || d_model % LM_BK != 0 || hidden_stride < d_model || weight_stride < d_model)
+    if (!lm_sizes_ok(n_tokens, vocab, d_model) || hidden_stride < d_model || weight_stride < d_model)
         return GRPO_ERR_SHAPE;
+    if (bwd && !lm_bwd_vocab_ok(vocab)) return GRPO_ERR_SHAPE;
     if (!(temperature > 0.f) || !std::isfinite(temperature)) return GRPO_ERR_PARAM;
     if (n_tokens == 0) return GRPO_OK;
     if (!hidden || !weight || !tokens) return GRPO_ERR_NULL;
@@ -944,7 +1024,7 @@ grpo_status lm_impl(bool bwd, bool aux, const void *hidden, int64_t hidden_strid
                     void *workspace, size_t workspace_bytes, void *stream)
 {
     grpo_status rc = lm_check_common(hidden, hidden_stride, weight, weight_stride, n_tokens, vocab,
-                                     d_model, tokens, temperature);
+                                     d_model, tokens, temperature, bwd);
     if (rc != GRPO_OK) return rc;
     if (bwd) {
         if (!(eps_low >= 0.f && eps_low <= 1.f) || !(eps_high >= 0.f) || !std::isfinite(eps_high) ||
@@ -960,9 +1040,13 @@ grpo_status lm_impl(bool bwd, bool aux, const void *hidden, int64_t hidden_strid
         if (n_tokens == 0) return GRPO_OK;
         if (!logprobs_out) return GRPO_ERR_NULL;
     }
-    const LmLayout L = lm_layout(n_tokens, vocab, d_model, bwd);
-    if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < L.total)
-        return GRPO_ERR_WORKSPACE;
+    if (!workspace || ((uintptr_t)workspace & 255u) != 0) return GRPO_ERR_WORKSPACE;
+    // the forward alone keeps nothing per logit and takes the largest chunk there is (one chunk up
+    // to 2^20 tokens); the backward takes the largest chunk the caller's workspace holds
+    const int64_t cap = bwd ? lm_cap_for_workspace(n_tokens, vocab, d_model, workspace_bytes) : lm_cap_limit(n_tokens);
+    if (cap == 0) return GRPO_ERR_WORKSPACE;
+    const LmLayout L = lm_layout(n_tokens, vocab, d_model, bwd, cap);
+    if (workspace_bytes < L.total) return GRPO_ERR_WORKSPACE;
 
     char *ws = (char *)workspace;
     hipStream_t st = (hipStream_t)stream;
@@ -972,12 +1056,15 @@ grpo_status lm_impl(bool bwd, bool aux, const void *hidden, int64_t hidden_strid
     float *KL_ws = (float *)(ws + kHeaderBytes + col);
     float *H_ws = (float *)(ws + kHeaderBytes + 2 * col);
     unsigned char *flags_ws = (unsigned char *)(ws + kHeaderBytes + 3 * col);
+    FinPartial *partials = (FinPartial *)(ws + kHeaderBytes + 3 * col + align_up((size_t)n_tokens, 256));
 
     if (bwd)
         hipLaunchKernelGGL(grpo_prepare, dim3(1), dim3(1024), 0, st, mask, aux ? token_weights : (const float *)nullptr,
                            (long long)n_tokens, denom, hdr);
     if (n_tokens > 0) {
         const int M = (int)n_tokens, V = (int)vocab, D = (int)d_model;
+        const int Mc = (int)std::min<int64_t>(cap, n_tokens);  // most rows a chunk can have
+        const int n_chunks = (int)((n_tokens + cap - 1) / cap);
         LmRows w = {};
         w.n_live = (int *)(ws + L.counts);
         w.n_grad = w.n_live + 1;
@@ -986,8 +1073,9 @@ grpo_status lm_impl(bool bwd, bool aux, const void *hidden, int64_t hidden_strid
         w.zy = (float *)(ws + L.zy);
         w.part_m = (float *)(ws + L.part_m);
         w.part_s = (float *)(ws + L.part_s);
-        w.part_stride = n_tokens;
+        w.part_stride = cap;
         w.tiles_n = L.tiles_n;
+        w.chunk_cap = (int)cap;
         if (aux) {
             w.part_w = (float *)(ws + L.part_w);
             w.mx = (float *)(ws + L.mx);
@@ -1038,64 +1126,73 @@ grpo_status lm_impl(bool bwd, bool aux, const void *hidden, int64_t hidden_strid
         hipLaunchKernelGGL(lm_gather_rows, dim3((unsigned)(M < 8192 ? M : 8192)), dim3(256), 0, st,
                            (const __bf16 *)hidden, (long long)hidden_stride, (const int *)w.rows,
                            (const int *)w.n_live, D, Hc, (long long)d_model);
-
-        GemmParams g = {};  // logits of the compact rows: softmax partials, z_y, fp32 copy for the backward
-        g.A = Hc;
-        g.lda = d_model;
-        g.B = (const __bf16 *)weight;
-        g.ldb = weight_stride;
-        g.M = M;
-        g.M_dev = w.n_live;
-        g.N = V;
-        g.K = D;
-        g.tokens32 = w.tokens32;
-        g.k = k;
-        g.part_m = w.part_m;
-        g.part_s = w.part_s;
-        g.part_w = w.part_w;
-        g.part_stride = n_tokens;
-        g.zy = w.zy;
-        g.Z = bwd ? (float *)(ws + L.Z) : nullptr;
-        g.ldz = L.ldz;
-        hipError_t e = aux   ? lm_launch_gemm<LM_EPI_LSE, true, true>(g, st)
-                       : bwd ? lm_launch_gemm<LM_EPI_LSE, true>(g, st)
-                             : lm_launch_gemm<LM_EPI_LSE, false>(g, st);
-        if (e != hipSuccess) return GRPO_ERR_HIP;
-
-        const dim3 cmb_grid((unsigned)((n_tokens + LM_CMB_ROWS - 1) / LM_CMB_ROWS));
-        if (aux)
-            hipLaunchKernelGGL(lm_combine<true>, cmb_grid, dim3(LM_CMB_ROWS * LM_CMB_LANES), 0, st, p, w);
-        else
-            hipLaunchKernelGGL(lm_combine<false>, cmb_grid, dim3(LM_CMB_ROWS * LM_CMB_LANES), 0, st, p, w);
-
+        __bf16 *G = nullptr, *Gt = nullptr, *Wt = nullptr, *Ht = nullptr;
+        const int n_cu = cu_count();
         if (bwd) {
-            __bf16 *G = (__bf16 *)(ws + L.G), *Gt = (__bf16 *)(ws + L.Gt);
-            __bf16 *Wt = (__bf16 *)(ws + L.Wt), *Ht = (__bf16 *)(ws + L.Ht);
+            G = (__bf16 *)(ws + L.G), Gt = (__bf16 *)(ws + L.Gt);
+            Wt = (__bf16 *)(ws + L.Wt), Ht = (__bf16 *)(ws + L.Ht);
+            // W^T [d][ldg], once for all chunks
+            hipLaunchKernelGGL(lm_transpose, dim3((unsigned)(L.ldg / 64), (unsigned)((D + 63) / 64)), dim3(256), 0,
+                               st, (const __bf16 *)weight, (long long)weight_stride, V, (const int *)nullptr,
+                               (const int *)nullptr, D, Wt, L.ldg);
+            // rows without gradient keep the zeros written here
+            hipLaunchKernelGGL(lm_zero<unsigned short>, dim3(2048), dim3(256), 0, st, (unsigned short *)grad_hidden,
+                               (long long)n_tokens, (long long)d_model, (long long)grad_hidden_stride);
+        }
+
+        for (int c = 0; c < n_chunks; ++c) {
+            w.chunk = c;
+            GemmParams g = {};  // logits of the chunk's rows: softmax partials, z_y, fp32 copy for the backward
+            g.A = Hc;
+            g.lda = d_model;
+            g.B = (const __bf16 *)weight;
+            g.ldb = weight_stride;
+            g.M = Mc;
+            g.M_dev = w.n_live;
+            g.chunk = c;
+            g.chunk_cap = (int)cap;
+            g.N = V;
+            g.K = D;
+            g.tokens32 = w.tokens32;
+            g.k = k;
+            g.part_m = w.part_m;
+            g.part_s = w.part_s;
+            g.part_w = w.part_w;
+            g.part_stride = cap;
+            g.zy = w.zy;
+            g.Z = bwd ? (float *)(ws + L.Z) : nullptr;
+            g.ldz = L.ldz;
+            hipError_t e = aux   ? lm_launch_gemm<LM_EPI_LSE, true, true>(g, st)
+                           : bwd ? lm_launch_gemm<LM_EPI_LSE, true>(g, st)
+                                 : lm_launch_gemm<LM_EPI_LSE, false>(g, st);
+            if (e != hipSuccess) return GRPO_ERR_HIP;
+
+            const dim3 cmb_grid((unsigned)((Mc + LM_CMB_ROWS - 1) / LM_CMB_ROWS));
+            if (aux)
+                hipLaunchKernelGGL(lm_combine<true>, cmb_grid, dim3(LM_CMB_ROWS * LM_CMB_LANES), 0, st, p, w);
+            else
+                hipLaunchKernelGGL(lm_combine<false>, cmb_grid, dim3(LM_CMB_ROWS * LM_CMB_LANES), 0, st, p, w);
+            if (!bwd) continue;
+
             hipLaunchKernelGGL(lm_select_grad_rows, dim3(1), dim3(1024), 0, st, w);
-            const dim3 gl_grid((unsigned)(L.ldg / 64), (unsigned)(L.ldgt / 64));
+            const dim3 gl_grid((unsigned)(L.ldg / 64), (unsigned)((Mc + 63) / 64));
             if (aux)
                 hipLaunchKernelGGL(lm_grad_logits<true>, gl_grid, dim3(256), 0, st, (const float *)(ws + L.Z), L.ldz,
                                    V, w, k, G, L.ldg, Gt, L.ldgt);
             else
                 hipLaunchKernelGGL(lm_grad_logits<false>, gl_grid, dim3(256), 0, st, (const float *)(ws + L.Z), L.ldz,
                                    V, w, k, G, L.ldg, Gt, L.ldgt);
-            // W^T [d][ldg]; H^T of the gradient rows [d][ldgt]
-            hipLaunchKernelGGL(lm_transpose, dim3((unsigned)((D + 63) / 64), (unsigned)(L.ldg / 64)), dim3(256), 0,
-                               st, (const __bf16 *)weight, (long long)weight_stride, V, (const int *)nullptr,
-                               (const int *)nullptr, D, Wt, L.ldg);
-            hipLaunchKernelGGL(lm_transpose, dim3((unsigned)((D + 63) / 64), (unsigned)(L.ldgt / 64)), dim3(256), 0,
+            // H^T of the chunk's gradient rows [d][ldgt]
+            hipLaunchKernelGGL(lm_transpose, dim3((unsigned)(L.ldgt / 64), (unsigned)((D + 63) / 64)), dim3(256), 0,
                                st, (const __bf16 *)hidden, (long long)hidden_stride, M, (const int *)w.n_grad,
                                (const int *)w.orig2, D, Ht, L.ldgt);
-            // rows without gradient keep the zeros written here
-            hipLaunchKernelGGL(lm_zero<unsigned short>, dim3(2048), dim3(256), 0, st, (unsigned short *)grad_hidden,
-                               (long long)n_tokens, (long long)d_model, (long long)grad_hidden_stride);
 
             GemmParams gh = {};  // dL/dH [gradient rows][d] = G . W, scattered to the original rows
             gh.A = G;
             gh.lda = L.ldg;
             gh.B = Wt;
             gh.ldb = L.ldg;
-            gh.M = M;
+            gh.M = Mc;
             gh.M_dev = w.n_grad;
             gh.N = D;
             gh.K = (int)L.ldg;
@@ -1105,20 +1202,19 @@ grpo_status lm_impl(bool bwd, bool aux, const void *hidden, int64_t hidden_strid
             gh.group_m = LM_GM_BWD;
             // The fp32 logits are no longer needed: their space takes the partial results (blocks of
             // 256 x 256 fp32) of the tiles whose contraction over the vocabulary is cut into parts.
-            const size_t z_blocks = (size_t)n_tokens * (size_t)L.ldz * 4 / ((size_t)LM_BM * LM_BN * 4);
+            const size_t z_blocks = (size_t)cap * (size_t)L.ldz * 4 / ((size_t)LM_BM * LM_BN * 4);
             gh.split_items = (int)(z_blocks < 0x7fffffffu ? z_blocks : 0x7fffffffu);
             gh.split_ws = (float *)(ws + L.Z);
-            const int n_cu = cu_count();
             gh.n_cu = n_cu;
             e = lm_launch_gemm<LM_EPI_BF16, false>(gh, st);
             if (e != hipSuccess) return GRPO_ERR_HIP;
             if (gh.split_items > 0)
                 hipLaunchKernelGGL(lm_split_reduce, dim3(2048), dim3(256), 0, st, (const float *)gh.split_ws,
-                                   (const int *)w.n_grad, M, D, (D + LM_BN - 1) / LM_BN, (int)(L.ldg / LM_BK),
+                                   (const int *)w.n_grad, Mc, D, (D + LM_BN - 1) / LM_BN, (int)(L.ldg / LM_BK),
                                    gh.split_items, n_cu, LM_GM_BWD, (const int *)w.orig2, (__bf16 *)grad_hidden,
                                    (long long)grad_hidden_stride);
 
-            GemmParams gw = {};  // dL/dW [V][d] = G^T . H over the gradient rows
+            GemmParams gw = {};  // dL/dW [V][d] (+)= G^T . H over the chunk's gradient rows
             gw.A = Gt;
             gw.lda = L.ldgt;
             gw.B = Ht;
@@ -1129,7 +1225,7 @@ grpo_status lm_impl(bool bwd, bool aux, const void *hidden, int64_t hidden_strid
             gw.K_dev = w.n_grad;
             gw.C = grad_weight;
             gw.ldc = grad_weight_stride;
-            gw.accumulate = accumulate_grad_weight ? 1 : 0;
+            gw.accumulate = (accumulate_grad_weight || c > 0) ? 1 : 0;  // the first chunk starts the sum
             gw.group_m = LM_GM_BWD;
             e = lm_launch_gemm<LM_EPI_F32, false>(gw, st);
             if (e != hipSuccess) return GRPO_ERR_HIP;
@@ -1140,9 +1236,9 @@ grpo_status lm_impl(bool bwd, bool aux, const void *hidden, int64_t hidden_strid
                            (long long)d_model, (long long)grad_weight_stride);
     }
     if (bwd)
-        hipLaunchKernelGGL(grpo_finalize, dim3(1), dim3(1024), 0, st, J_ws, aux ? KL_ws : (const float *)nullptr, H_ws,
-                           flags_ws, (long long)n_tokens, hdr, kl_coef, entropy_coef, loss_out,
-                           (long long *)counts_out, (int *)nullptr);
+        hipLaunchKernelGGL(grpo_finalize, dim3(fin_blocks(n_tokens)), dim3(1024), 0, st, J_ws,
+                           aux ? KL_ws : (const float *)nullptr, H_ws, flags_ws, (long long)n_tokens, hdr, partials,
+                           kl_coef, entropy_coef, loss_out, (long long *)counts_out, (int *)nullptr);
     return hipGetLastError() == hipSuccess ? GRPO_OK : GRPO_ERR_HIP;
 }
 
@@ -1152,8 +1248,16 @@ extern "C" {
 
 size_t grpo_lmhead_workspace_bytes(int64_t n_tokens, int64_t vocab, int64_t d_model, int with_backward)
 {
-    if (n_tokens < 0 || vocab <= 0 || d_model <= 0) return 0;
-    return lm_layout(n_tokens, vocab, d_model, with_backward != 0).total;
+    if (!lm_sizes_ok(n_tokens, vocab, d_model) || (with_backward && !lm_bwd_vocab_ok(vocab))) return 0;
+    const int64_t cap = with_backward ? std::min<int64_t>(lm_cap_limit(n_tokens), kLmChunkRows) : lm_cap_limit(n_tokens);
+    return lm_layout(n_tokens, vocab, d_model, with_backward != 0, cap).total;
+}
+
+size_t grpo_lmhead_workspace_bytes_for_chunk(int64_t n_tokens, int64_t vocab, int64_t d_model, int64_t chunk_rows)
+{
+    if (!lm_sizes_ok(n_tokens, vocab, d_model) || !lm_bwd_vocab_ok(vocab) || chunk_rows <= 0) return 0;
+    const int64_t cap = std::min<int64_t>(lm_cap_limit(n_tokens), (std::min<int64_t>(chunk_rows, kLmChunkMax) + 255) / 256 * 256);
+    return lm_layout(n_tokens, vocab, d_model, true, cap).total;
 }
 
 grpo_status grpo_lmhead_logprobs_fwd(const void *hidden, int64_t hidden_stride, const void *weight,

@@ -223,15 +223,25 @@ def make_old_logprobs(cfg: Workload, new_logprobs, seed=None, guard=1e-3):
 def make_lmhead_batch(cfg: Workload, d_model: int, device="cpu", seed=None, chunk_rows=4096):
     """The inputs of the fused language-model-head path for the recipe of ``cfg``: final
     hidden states [N, d_model] and head weights [vocab, d_model] in bf16 instead of logits.
+    Tokens (Zipf recipe aside), mask, rewards and lengths are the ones ``make_batch`` draws for
+    the same seed.  Logits cannot be set element by element here, only through h and W:
 
-    hidden ~ N(0, 1) and weight ~ N(0, logit_std^2 / d_model), so the logits h W^T have the
-    configured standard deviation; for "normal_boost" each row's hidden state is moved along
-    its sampled token's weight row so that this one logit rises by 8 (the other logits
-    move by 8 cos(w_v, w_y), a few tenths).  Tokens, mask, rewards and lengths are the
-    ones ``make_batch`` draws for the same seed.  Only the "normal" recipes exist here.
+    normal / normal_boost: hidden ~ N(0, 1), weight ~ N(0, logit_std^2 / d_model), so the logits
+        h W^T have the configured standard deviation; for "normal_boost" each row's hidden
+        state is moved along its sampled token's weight row so that this one logit rises by 8
+        (the other logits move by 8 cos(w_v, w_y), a few tenths).
+    spike: as normal, then every row's hidden state is moved along ONE weight row so that this
+        logit rises by 40 (near-one-hot softmax): the sampled token's on even rows, another
+        entry's on odd rows; 1 % of the rows get h = 0, i.e. all logits equal.
+    zipf_gumbel: the last coordinate of every weight row holds the log-frequency of its entry
+        under Zipf(1.1) over a random permutation of ranks and every hidden state has 1 there, so
+        z = log-frequency + Gaussian noise of unit standard deviation from the other coordinates
+        (Gaussian where ``make_batch`` has Gumbel noise: a product cannot carry element-wise
+        noise of another law); tokens are drawn from that Zipf law; stored unscaled, the
+        recipe's temperature is applied by the kernel.
     """
-    if cfg.logits not in ("normal", "normal_boost"):
-        raise ValueError("make_lmhead_batch supports the normal and normal_boost recipes")
+    if cfg.logits not in ("normal", "normal_boost", "spike", "zipf_gumbel"):
+        raise ValueError("unknown logits recipe %r" % cfg.logits)
     device = torch.device(device)
     seed = BASE_SEED + cfg.index if seed is None else seed
     N, V, R, L = cfg.n_tokens, cfg.vocab, cfg.n_rollouts, cfg.seq_len
@@ -256,13 +266,28 @@ def make_lmhead_batch(cfg: Workload, d_model: int, device="cpu", seed=None, chun
         rewards = torch.randint(0, 3, (R,), generator=small).to(torch.float32) * 0.5
     for g in range(min(cfg.forced_zero_groups, cfg.n_prompts)):
         rewards[g * cfg.group_size:(g + 1) * cfg.group_size] = 0.0
-    tokens = torch.randint(0, V, (N,), generator=small, dtype=torch.int64).to(device)
+    tokens_cpu = torch.randint(0, V, (N,), generator=small, dtype=torch.int64)
+    spike_other = torch.randint(1, max(V, 2), (N,), generator=small, dtype=torch.int64)
+    const_rows = torch.rand(N, generator=small) < 0.01
+    logfreq = None
+    if cfg.logits == "zipf_gumbel":
+        perm = torch.randperm(V, generator=small)
+        ranks = torch.empty(V, dtype=torch.float64)
+        ranks[perm] = torch.arange(1, V + 1, dtype=torch.float64)
+        logfreq = -1.1 * torch.log(ranks)
+        logfreq = logfreq - torch.logsumexp(logfreq, 0)
+        tokens_cpu = torch.multinomial(torch.exp(logfreq), N, replacement=True, generator=small)
+    tokens = tokens_cpu.to(device)
 
+    noise_dims = d_model - 1 if cfg.logits == "zipf_gumbel" else d_model
+    w_std = cfg.logit_std / math.sqrt(max(noise_dims, 1))
     weight = torch.empty((V, d_model), dtype=torch.bfloat16, device=device)
     for v0 in range(0, V, chunk_rows):
         v1 = min(V, v0 + chunk_rows)
-        w = torch.randn((v1 - v0, d_model), generator=big, device=device, dtype=torch.float32)
-        weight[v0:v1] = (w * (cfg.logit_std / math.sqrt(d_model))).to(torch.bfloat16)
+        w = torch.randn((v1 - v0, d_model), generator=big, device=device, dtype=torch.float32) * w_std
+        if logfreq is not None:
+            w[:, d_model - 1] = logfreq[v0:v1].to(torch.float32).to(device)
+        weight[v0:v1] = w.to(torch.bfloat16)
     hidden = torch.empty((N, d_model), dtype=torch.bfloat16, device=device)
     for r0 in range(0, N, chunk_rows):
         r1 = min(N, r0 + chunk_rows)
@@ -270,6 +295,15 @@ def make_lmhead_batch(cfg: Workload, d_model: int, device="cpu", seed=None, chun
         if cfg.logits == "normal_boost":
             wy = weight[tokens[r0:r1]].to(torch.float32)
             h += 8.0 * wy / (wy * wy).sum(dim=1, keepdim=True).clamp_min(1e-20)
+        elif cfg.logits == "spike":
+            y = tokens[r0:r1]
+            other = (y + spike_other[r0:r1].to(device)) % V
+            on_y = (torch.arange(r0, r1, device=device) % 2) == 0
+            wt = weight[torch.where(on_y, y, other)].to(torch.float32)
+            h += 40.0 * wt / (wt * wt).sum(dim=1, keepdim=True).clamp_min(1e-20)
+            h[const_rows[r0:r1].to(device)] = 0.0
+        elif cfg.logits == "zipf_gumbel":
+            h[:, d_model - 1] = 1.0
         hidden[r0:r1] = h.to(torch.bfloat16)
     return dict(cfg=cfg, hidden=hidden, weight=weight, d_model=d_model, tokens=tokens,
                 mask=mask.to(device), rewards=rewards.to(device),

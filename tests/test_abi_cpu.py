@@ -267,16 +267,34 @@ def test_lmhead_logprobs_rejects_bad_arguments_and_sizes_its_workspace():
     assert call(ws=None) == WORKSPACE and call(ws_bytes=64) == WORKSPACE
     assert call(hs=130) == ALIGN
     # workspace sizes: forward holds a compacted copy of the hidden states and 8 bytes per token
-    # and 256 vocabulary entries; backward also the logits (fp32), their gradient (bf16, twice)
-    # and the transposed operands
+    # and 256 vocabulary entries; the backward works in chunks of rows and holds, per chunk row, the
+    # logits (fp32) and their gradient (bf16, twice), next to the transposed operands: its size
+    # follows the chunk (8192 rows by default), not the number of tokens
     n, V, d = 16384, 152064, 5120
     fwd = grpo.grpo_lmhead_workspace_bytes(n, V, d, False)
     bwd = grpo.grpo_lmhead_workspace_bytes(n, V, d, True)
     assert fwd % 256 == 0 and bwd % 256 == 0
     assert fwd < 300 << 20 and fwd >= grpo.grpo_workspace_bytes(n) + 8 * n * ((V + 255) // 256) + 2 * n * d
-    assert bwd >= 8 * n * V + 2 * V * d and bwd < 9 * n * V + 4 * V * d
+    chunk = 8192
+    assert bwd >= 8 * chunk * V + 2 * V * d and bwd < 9 * chunk * V + 4 * V * d + 64 * n
+    assert bwd <= 4 * n * V + 4 * V * d                    # at most 4 bytes per logit of this batch
+    by_chunk = grpo.grpo_lmhead_workspace_bytes_for_chunk
+    assert by_chunk(n, V, d, chunk) == bwd and by_chunk(n, V, d, 8000) == bwd      # rounded up to 256 rows
+    assert by_chunk(n, V, d, 256) < by_chunk(n, V, d, 512) < bwd < by_chunk(n, V, d, n) == by_chunk(n, V, d, 10 ** 9)
+    big = grpo.grpo_lmhead_workspace_bytes(131072, V, d, True)                     # eight times the tokens:
+    assert big - bwd < 64 * (131072 - n) + 2 * (131072 - n) * d + 4096             # only per-row arrays grow
+    assert grpo.grpo_lmhead_workspace_bytes(300, V, d, True) == by_chunk(300, V, d, 512)   # fewer rows than a chunk
     assert grpo.grpo_lmhead_workspace_bytes(-1, V, d, True) == 0
     assert grpo.grpo_lmhead_workspace_bytes(n, 0, d, True) == 0
+    assert by_chunk(n, V, d, 0) == 0 and by_chunk(n, V, 100, 256) == 0
+    # with the backward the vocabulary is limited by 32-bit offsets inside an operand tile
+    assert grpo.grpo_lmhead_workspace_bytes(16, 8388544, 64, True) > 0
+    assert grpo.grpo_lmhead_workspace_bytes(16, 8388545, 64, True) == 0
+    assert grpo.grpo_lmhead_workspace_bytes(16, 8388545, 64, False) > 0
+    assert L.grpo_lmhead_loss_fwd_bwd(*lmhead_args(V=8388545, ws_bytes=1 << 60)) == SHAPE
+    # a workspace below the 256-row size is refused, anything from there on is taken
+    need = by_chunk(16, 1000, 128, 256)
+    assert L.grpo_lmhead_loss_fwd_bwd(*lmhead_args(ws_bytes=need - 256)) == WORKSPACE
 
 
 def lmhead_aux_args(**over):
