@@ -180,6 +180,15 @@ def lmhead_leg(grpo, wl, cfg, d_model, dev, stream, reps, warmup):
     aux_vals = loss4.cpu().tolist()
     ms_b = timed_calls(fwd_bwd, stream, reps, max(2, warmup // 2))["mean"]
     c = counts.cpu().tolist()
+    # the same call with a workspace large enough for all rows in one chunk (the default workspace
+    # bounds the chunk at 8192 rows, whatever N)
+    one = {"skipped": "not enough free device memory"}
+    ws_1_bytes = grpo.grpo_lmhead_workspace_bytes_for_chunk(N, V, d_model, N)
+    if ws_1_bytes > ws_b_bytes and ws_1_bytes < 0.9 * torch.cuda.mem_get_info()[0]:
+        ws_b = torch.empty(ws_1_bytes, dtype=torch.uint8, device=dev)
+        ms_1 = timed_calls(fwd_bwd, stream, reps, max(2, warmup // 2))["mean"]
+        one = {"fwd_bwd_ms": ms_1, "workspace_bytes": ws_1_bytes,
+               "workspace_bytes_per_logit": ws_1_bytes / (float(N) * V)}
     n_unmasked = c[0]
     zero_adv = int(((adv_tok == 0) & (b["mask"] != 0)).sum())
     n_grad = n_unmasked - (c[1] + c[2] + c[3] + zero_adv)   # rows whose objective has a gradient
@@ -196,6 +205,7 @@ def lmhead_leg(grpo, wl, cfg, d_model, dev, stream, reps, warmup):
             "workspace_bytes_per_logit_fwd_bwd": ws_b_bytes / (float(N) * V),
             "fwd_ms": ms_f, "fwd_tokens_per_s": N / (ms_f * 1e-3),
             "fwd_bwd_ms": ms_b, "fwd_bwd_tokens_per_s": N / (ms_b * 1e-3), "loss": float(loss.cpu()),
+            "fwd_bwd_one_chunk": one,
             "aux": {"note": "grpo_lmhead_loss_aux_fwd_bwd, KL 0.001 and entropy 1e-4: every unmasked row has a "
                             "gradient", "fwd_bwd_ms": ms_x, "fwd_bwd_tokens_per_s": N / (ms_x * 1e-3),
                     "tflops": (flops_f + 4.0 * n_unmasked * V * d_model) / (ms_x * 1e-3) / 1e12,
@@ -326,6 +336,10 @@ def run_workload(grpo, wl, cfg, args, dev, variant="", headline=False):
         "frac_moved": gb(moved_bytes, kern) / HBM_PEAK_GBPS,
         "gbps_2r1w_all_rows_convention": gb(conv_bytes, kern),
         "traffic": traffic, "traffic_profile": stamp,
+        # launches of the row kernel in this workload's part of the run, in order (for reading a kernel trace)
+        "row_kernel_launches": [["grpo_logprobs_fwd (setup)", 1], ["workload", args.warmup + args.steps],
+                                ["every row live", side_warm + side_reps], ["grpo_logprobs_fwd", side_warm + side_reps],
+                                ["grpo_loss_aux_fwd_bwd (its own instantiation)", side_warm + side_reps]],
         "counts": dict(zip(grpo.COUNT_NAMES, c)), "loss": loss_value,
         "full_rows": {"note": "same logits, every row unmasked and live: the kernel's worst case",
                       "tokens_per_s": N / wall_full, "kernel_ms": kern_full * 1e3,

@@ -37,7 +37,7 @@ struct WsHeader {
     double inv_D;  // 1 / D, or 0 when D == 0
     long long M;   // rows with mask != 0
     int error;     // sticky data-error word (bit 0: token id out of range)
-    int pad;
+    unsigned fin_ticket;  // blocks of grpo_finalize that have delivered their partial sums
 };
 // The row queue: up to kQueueParts counters, each on a 128-byte line of its own, follow
 // the 256-byte header.  With P counters in use, counter q hands out the rows q, q + P,
@@ -406,7 +406,12 @@ __device__ __forceinline__ RowScalars row_scalars(const RowParams &p, long long 
 {
     RowScalars o = {};
     const float ay = fmaf(zy, p.k, -mk);
-    const float s = s_excl + __builtin_amdgcn_exp2f(ay);
+    // A logit of +inf must poison its row wherever it sits.  The bf16 reference maximum reads the
+    // upper element of a 32-bit word together with the lower element's bits, so +inf there looks
+    // like NaN and is skipped: the maximum stays finite and the sum becomes +inf instead of NaN
+    // (everywhere else inf - inf has already made it NaN).  A sum that is not finite has no logarithm.
+    const float s0 = s_excl + __builtin_amdgcn_exp2f(ay);
+    const float s = s0 < INFINITY ? s0 : NAN;
     const float log2s = __builtin_amdgcn_logf(s);
     o.s = s;
     o.s_excl = s_excl;
@@ -1317,7 +1322,7 @@ __global__ void __launch_bounds__(1024) grpo_prepare(const unsigned char *mask,
         hdr->inv_D = D > 0.0 ? 1.0 / D : 0.0;
         hdr->M = M;
         hdr->error = 0;
-        hdr->pad = 0;
+        hdr->fin_ticket = 0u;
     }
 }
 
@@ -1333,16 +1338,64 @@ __global__ void grpo_reset_queue(WsHeader *hdr)
 // loss = -(1/D) sum_t J_t in fp64 and a fixed order; indicator counts.  With the
 // auxiliary arrays (KL_ws, H_ws non-NULL) loss_out has four entries:
 // total = policy + kl_coef * mean kl - ent_coef * mean H, policy, mean kl, mean H.
+//
+// One workgroup per segment of kFinSegment rows: it sums its rows (a fixed assignment of rows to
+// lanes, wavefronts combined in order), leaves the partial sums in the workspace and draws a
+// ticket; the workgroup that draws the last ticket adds the partials in segment order and writes
+// the results.  Which workgroup that is varies from run to run, what it computes does not: the
+// sums are bitwise reproducible.  (A single workgroup took 13 us for 16384 rows and 0.1 ms for
+// 131072; the segments take about as long as one of them.)
+constexpr int kFinSegment = 4096;  // rows per segment: four per lane
+struct FinPartial {
+    double s[3];
+    long long c[4];
+    long long pad;
+};
+static_assert(sizeof(FinPartial) == 64, "one partial per 64 bytes");
+constexpr size_t fin_partials_bytes(long long n)
+{
+    return (((size_t)((n + kFinSegment - 1) / kFinSegment) * sizeof(FinPartial)) + 255) / 256 * 256;
+}
+
 __global__ void __launch_bounds__(1024) grpo_finalize(const float *J_ws, const float *KL_ws,
                                                       const float *H_ws,
                                                       const unsigned char *flags_ws, long long n,
-                                                      const WsHeader *hdr, float kl_coef,
+                                                      WsHeader *hdr, FinPartial *partials, float kl_coef,
                                                       float ent_coef, float *loss_out,
                                                       long long *counts_out, int *error_out)
 {
     __shared__ double lds_j[16][3];
     __shared__ long long lds_c[16][4];
+    __shared__ unsigned lds_ticket;
     const bool aux = KL_ws != nullptr;
+    const long long nseg = (n + kFinSegment - 1) / kFinSegment;  // 0 for an empty batch: one block, no rows
+    // sums x over the block in a fixed order: lanes inside a wavefront, then the wavefronts in turn
+    auto block_totals = [&](double (&sj)[3], long long (&c)[4]) {
+#pragma unroll
+        for (int q = 0; q < 3; ++q) sj[q] = wave_sum(sj[q]);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) c[q] = wave_sum(c[q]);
+        __syncthreads();  // the arrays may still be read from the previous use
+        if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+            for (int q = 0; q < 3; ++q) lds_j[threadIdx.x >> 6][q] = sj[q];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) lds_c[threadIdx.x >> 6][q] = c[q];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < 3; ++q) sj[q] = 0.0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) c[q] = 0;
+#pragma unroll 2  // all 16 at once would read 224 registers' worth of partial sums first, and spill
+        for (int w = 0; w < 16; ++w) {  // wavefront by wavefront, in order
+#pragma unroll
+            for (int q = 0; q < 3; ++q) sj[q] += lds_j[w][q];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) c[q] += lds_c[w][q];
+        }
+    };
+
     double sj[3] = {0.0, 0.0, 0.0};
     long long c[4] = {0, 0, 0, 0};
     auto count = [&](int fl) {
@@ -1351,10 +1404,12 @@ __global__ void __launch_bounds__(1024) grpo_finalize(const float *J_ws, const f
         c[2] += (fl & kFlagDelta) ? 1 : 0;
         c[3] += (fl & kFlagOutOfBand) ? 1 : 0;
     };
-    // four rows per lane and step (the arrays start on 256-byte boundaries), then the last n % 4
-    // rows one by one: a fixed assignment of rows to lanes, so the sums are reproducible
-    const long long n4 = n & ~3ll;
-    for (long long i = threadIdx.x * 4ll; i < n4; i += 4096) {
+    // this block's segment: four rows per lane (the arrays start on 256-byte boundaries and a
+    // segment is a multiple of four rows), the batch's last n % 4 rows one by one
+    const long long seg0 = (long long)blockIdx.x * kFinSegment;
+    const long long seg1 = seg0 + kFinSegment < n ? seg0 + kFinSegment : n;
+    const long long i = seg0 + threadIdx.x * 4ll;
+    if (i + 3 < seg1) {
         const float4 j = *(const float4 *)(J_ws + i);
         sj[0] += (double)j.x;
         sj[0] += (double)j.y;
@@ -1374,39 +1429,49 @@ __global__ void __launch_bounds__(1024) grpo_finalize(const float *J_ws, const f
         const unsigned fl4 = *(const unsigned *)(flags_ws + i);
 #pragma unroll
         for (int b = 0; b < 4; ++b) count((int)((fl4 >> (8 * b)) & 0xffu));
-    }
-    for (long long i = n4 + threadIdx.x; i < n; i += 1024) {
-        sj[0] += (double)J_ws[i];
-        if (aux) {
-            sj[1] += (double)KL_ws[i];
-            sj[2] += (double)H_ws[i];
+    } else {
+        for (long long r = i; r < seg1; ++r) {  // at most three rows, in one lane of the last segment
+            sj[0] += (double)J_ws[r];
+            if (aux) {
+                sj[1] += (double)KL_ws[r];
+                sj[2] += (double)H_ws[r];
+            }
+            count(flags_ws[r]);
         }
-        count(flags_ws[i]);
     }
+    block_totals(sj, c);
+    if (nseg > 1) {
+        if (threadIdx.x == 0) {
+            FinPartial pt;
 #pragma unroll
-    for (int q = 0; q < 3; ++q) sj[q] = wave_sum(sj[q]);
+            for (int q = 0; q < 3; ++q) pt.s[q] = sj[q];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) c[q] = wave_sum(c[q]);
-    if ((threadIdx.x & 63) == 0) {
+            for (int q = 0; q < 4; ++q) pt.c[q] = c[q];
+            pt.pad = 0;
+            partials[blockIdx.x] = pt;
+            __threadfence();  // the partial is visible before the ticket is
+            lds_ticket = atomicAdd(&hdr->fin_ticket, 1u);
+        }
+        __syncthreads();
+        if (lds_ticket != (unsigned)(nseg - 1)) return;  // whole workgroup alike
+        __threadfence();  // the last ticket: every partial has been delivered; read them afresh
 #pragma unroll
-        for (int q = 0; q < 3; ++q) lds_j[threadIdx.x >> 6][q] = sj[q];
+        for (int q = 0; q < 3; ++q) sj[q] = 0.0;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) lds_c[threadIdx.x >> 6][q] = c[q];
+        for (int q = 0; q < 4; ++q) c[q] = 0;
+        for (long long sgm = threadIdx.x; sgm < nseg; sgm += 1024) {  // lane l: segments l, l + 1024, ...
+            const volatile FinPartial *pp = partials + sgm;
+#pragma unroll
+            for (int q = 0; q < 3; ++q) sj[q] += pp->s[q];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) c[q] += pp->c[q];
+        }
+        block_totals(sj, c);
     }
-    __syncthreads();
     if (threadIdx.x == 0) {
-        double tot[3] = {0.0, 0.0, 0.0};
-        long long t[4] = {0, 0, 0, 0};
-#pragma unroll 2  // all 16 at once would read 224 registers' worth of partial sums first, and spill
-        for (int w = 0; w < 16; ++w) {  // wavefront by wavefront, in order
-#pragma unroll
-            for (int q = 0; q < 3; ++q) tot[q] += lds_j[w][q];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) t[q] += lds_c[w][q];
-        }
-        const double policy = 0.0 - tot[0] * hdr->inv_D;
+        const double policy = 0.0 - sj[0] * hdr->inv_D;
         if (aux) {
-            const double klm = tot[1] * hdr->inv_D, hm = tot[2] * hdr->inv_D;
+            const double klm = sj[1] * hdr->inv_D, hm = sj[2] * hdr->inv_D;
             loss_out[0] = (float)(policy + (double)kl_coef * klm - (double)ent_coef * hm);
             loss_out[1] = (float)policy;
             loss_out[2] = (float)klm;
@@ -1417,10 +1482,10 @@ __global__ void __launch_bounds__(1024) grpo_finalize(const float *J_ws, const f
         if (error_out) *error_out = hdr->error;  // every row kernel has finished: the word is final
         if (counts_out) {
             counts_out[GRPO_COUNT_TOKENS] = hdr->M;
-            counts_out[GRPO_COUNT_CLIP_HIGH] = t[0];
-            counts_out[GRPO_COUNT_CLIP_LOW] = t[1];
-            counts_out[GRPO_COUNT_DELTA] = t[2];
-            counts_out[GRPO_COUNT_OUT_OF_BAND] = t[3];
+            counts_out[GRPO_COUNT_CLIP_HIGH] = c[0];
+            counts_out[GRPO_COUNT_CLIP_LOW] = c[1];
+            counts_out[GRPO_COUNT_DELTA] = c[2];
+            counts_out[GRPO_COUNT_OUT_OF_BAND] = c[3];
         }
     }
 }
@@ -1710,6 +1775,12 @@ grpo_status check_logits_args(const void *logits, grpo_dtype dtype, int64_t n_to
 }
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+unsigned fin_blocks(int64_t n) { return (unsigned)(n > 0 ? (n + kFinSegment - 1) / kFinSegment : 1); }
+// header | J, KL estimate, entropy per row (f32 each) | indicator bits per row (u8) | partial sums per segment
+constexpr size_t loss_workspace_bytes(long long n)
+{
+    return kHeaderBytes + 3 * (((size_t)n * 4 + 255) / 256 * 256) + ((size_t)n + 255) / 256 * 256 + fin_partials_bytes(n);
+}
 
 grpo_status loss_impl(bool aux, const void *logits, grpo_dtype dtype, int64_t n_tokens, int64_t vocab,
                       int64_t row_stride, const int64_t *tokens, const float *old_logprobs,
@@ -1742,6 +1813,7 @@ grpo_status loss_impl(bool aux, const void *logits, grpo_dtype dtype, int64_t n_
     float *KL_ws = (float *)(ws + kHeaderBytes + col);
     float *H_ws = (float *)(ws + kHeaderBytes + 2 * col);
     unsigned char *flags_ws = (unsigned char *)(ws + kHeaderBytes + 3 * col);
+    FinPartial *partials = (FinPartial *)(ws + kHeaderBytes + 3 * col + align_up((size_t)n_tokens, 256));
     hipStream_t st = (hipStream_t)stream;
 
     hipLaunchKernelGGL(grpo_prepare, dim3(1), dim3(1024), 0, st, mask, aux ? token_weights : nullptr,
@@ -1787,8 +1859,8 @@ grpo_status loss_impl(bool aux, const void *logits, grpo_dtype dtype, int64_t n_
                 launch_rows<GRPO_F32, false>(p, st);
         }
     }
-    hipLaunchKernelGGL(grpo_finalize, dim3(1), dim3(1024), 0, st, J_ws,
-                       aux ? KL_ws : (const float *)nullptr, H_ws, flags_ws, (long long)n_tokens, hdr,
+    hipLaunchKernelGGL(grpo_finalize, dim3(fin_blocks(n_tokens)), dim3(1024), 0, st, J_ws,
+                       aux ? KL_ws : (const float *)nullptr, H_ws, flags_ws, (long long)n_tokens, hdr, partials,
                        kl_coef, entropy_coef, loss_out, (long long *)counts_out, (int *)error_out);
     return hipGetLastError() == hipSuccess ? GRPO_OK : GRPO_ERR_HIP;
 }
@@ -1799,11 +1871,7 @@ grpo_status loss_impl(bool aux, const void *logits, grpo_dtype dtype, int64_t n_
 // allocate (graph capture, serving loops) need not bring one.  Every GPU that loads the
 // library holds its own copy at its own address.
 // ---------------------------------------------------------------------------
-constexpr size_t noalloc_scratch_bytes(long long n)
-{
-    return kHeaderBytes + 3 * (((size_t)n * 4 + 255) / 256 * 256) + ((size_t)n + 255) / 256 * 256;
-}
-constexpr size_t kScratchBytes = noalloc_scratch_bytes(GRPO_NOALLOC_MAX_TOKENS);
+constexpr size_t kScratchBytes = loss_workspace_bytes(GRPO_NOALLOC_MAX_TOKENS);
 static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
 // The device address of `scratch` on the current device.  In host code the array's name is
@@ -1882,8 +1950,7 @@ grpo_status grpo_row_kernel_plan(grpo_dtype dtype, int64_t vocab, grpo_row_plan 
 size_t grpo_workspace_bytes(int64_t n_tokens)
 {
     if (n_tokens < 0) return 0;
-    // header | J, KL estimate, entropy per row (f32 each) | indicator bits per row (u8)
-    return kHeaderBytes + 3 * align_up((size_t)n_tokens * 4, 256) + align_up((size_t)n_tokens, 256);
+    return loss_workspace_bytes(n_tokens);
 }
 
 grpo_status grpo_group_advantages(const float *rewards, int64_t n_rollouts,

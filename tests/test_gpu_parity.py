@@ -420,6 +420,21 @@ def test_edge_cases(V):
     assert int(torch.isnan(lp3).sum()) == 1 and bool(torch.isnan(grad3[7].float()).all())
     assert not bool(torch.isnan(grad3[6].float()).any())
 
+    say("[case] edge: +inf or NaN at an even or an odd position of the row poisons that row, and only that row")
+    # (a bf16 at an odd position is the upper half of a 32-bit word; the position must not matter)
+    inf, nan = float("inf"), float("nan")
+    for pos, val in ((V - 100, inf), (V - 99, inf), (V - 99, nan), (2, inf), (3, inf), (int(tokens[7]), inf)):
+        z5 = logits.clone()
+        z5[7, pos] = val
+        loss5, lp5, counts5, grad5 = grpo.grpo_loss_fwd_bwd(z5, tokens, old, adv, ones)
+        lpf5 = grpo.grpo_logprobs_fwd(z5, tokens)
+        torch.cuda.synchronize()
+        what = "%s at %d" % (val, pos)
+        assert bool(torch.isnan(loss5)) and bool(torch.isnan(lp5[7])) and int(torch.isnan(lp5).sum()) == 1, what
+        assert bool(torch.isnan(grad5[7].float()).all()), what
+        assert not bool(torch.isnan(grad5[6].float()).any()) and not bool(torch.isnan(grad5[8].float()).any()), what
+        assert bool(torch.isnan(lpf5[7])) and int(torch.isnan(lpf5).sum()) == 1, what
+
     say("[case] edge: -inf logits (vocabulary masking) are legal")
     z4 = logits.clone()
     z4[:, V // 4:3 * V // 4] = float("-inf")
