@@ -406,10 +406,8 @@ __device__ __forceinline__ RowScalars row_scalars(const RowParams &p, long long 
 {
     RowScalars o = {};
     const float ay = fmaf(zy, p.k, -mk);
-    // A logit of +inf must poison its row wherever it sits.  The bf16 reference maximum reads the
-    // upper element of a 32-bit word together with the lower element's bits, so +inf there looks
-    // like NaN and is skipped: the maximum stays finite and the sum becomes +inf instead of NaN
-    // (everywhere else inf - inf has already made it NaN).  A sum that is not finite has no logarithm.
+    // A sum that is not finite has no logarithm: NaN, so that the row is poisoned whatever way
+    // a +inf logit came in (with +inf as the row's maximum inf - inf has already made it NaN).
     const float s0 = s_excl + __builtin_amdgcn_exp2f(ay);
     const float s = s0 < INFINITY ? s0 : NAN;
     const float log2s = __builtin_amdgcn_logf(s);
@@ -505,25 +503,33 @@ __device__ __forceinline__ void set_neg_inf(u32x4 &v, int e)
     }
 }
 
-// A reference maximum of one vector for the softmax shift.  For bf16 the upper
-// element of each 32-bit word is compared as the raw word, i.e. with the lower
-// element's bits as extra mantissa: that moves it by less than one bf16 ulp, which is
-// immaterial for a shift (any value near the maximum does) and saves the masking.
-// A raw word whose upper half is +-inf reads as NaN and is skipped by fmaxf.
-// With EXACT the upper elements are masked and the result is the true maximum: the
-// entropy gradient of a near-one-hot row is a difference a_max - Abar of order 1e-8,
-// which survives in fp32 only if a_max itself is (nearly) zero.
-template <grpo_dtype DT, bool EXACT>
-__device__ __forceinline__ float vec_max_ref(const u32x4 &z)
+// max(a, b, c) as one v_max3_f32.  fmaxf() costs more than it looks: the compiler must first
+// quiet a possible signalling NaN in every operand it knows nothing about (one v_max_f32 x, x, x
+// each), which doubled the instructions of the maximum pass.  The instruction itself skips quiet
+// NaNs like fmaxf and turns a signalling NaN into a quiet NaN result; both are fine here, a
+// NaN logit poisons its row in the sum pass in any case.  The operands are never results of
+// transcendental instructions (those need a wait state the compiler does not insert for
+// inline assembly).
+__device__ __forceinline__ float max3_f32(float a, float b, float c)
 {
-    float m;
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
+// The running maximum m joined with the elements of one vector: one v_max3_f32 per 32-bit word
+// (two bf16, each widened exactly: the upper one by masking, the lower one by a shift), or per
+// two fp32 values.  The maximum is exact, which the entropy gradient of a near-one-hot row needs
+// (a difference a_max - Abar of order 1e-8 survives in fp32 only if a_max is exactly zero).
+template <grpo_dtype DT>
+__device__ __forceinline__ float vec_max_into(float m, const u32x4 &z)
+{
     if constexpr (DT == GRPO_BF16) {
-        constexpr unsigned hi_mask = EXACT ? 0xffff0000u : 0xffffffffu;
-        m = fmaxf(as_f32(z[0] & hi_mask), as_f32(z[0] << 16));
 #pragma unroll
-        for (int d = 1; d < 4; ++d) m = fmaxf(m, fmaxf(as_f32(z[d] & hi_mask), as_f32(z[d] << 16)));
+        for (int d = 0; d < 4; ++d) m = max3_f32(m, as_f32(z[d] & 0xffff0000u), as_f32(z[d] << 16));
     } else {
-        m = fmaxf(fmaxf(as_f32(z[0]), as_f32(z[1])), fmaxf(as_f32(z[2]), as_f32(z[3])));
+        m = max3_f32(m, as_f32(z[0]), as_f32(z[1]));
+        m = max3_f32(m, as_f32(z[2]), as_f32(z[3]));
     }
     return m;
 }
@@ -727,7 +733,8 @@ __device__ __forceinline__ void online_vec(const u32x4 &z, bool has_y, int ey, f
     unpack<DT>(z, f);
     float vm = f[0];
 #pragma unroll
-    for (int e = 1; e < EPV; ++e) vm = fmaxf(vm, f[e]);
+    for (int e = 1; e + 1 < EPV; e += 2) vm = max3_f32(vm, f[e], f[e + 1]);
+    vm = max3_f32(vm, f[EPV - 1], f[EPV - 1]);  // EPV is even: the last element is still to come
     if (vm > m) {
         // new reference: every exponent so far moves by dlt, every term by 2^dlt
         const float dlt = (m - vm) * k;  // -inf the first time: s and w are 0 and stay 0
@@ -790,6 +797,11 @@ constexpr int row_reg_stash_slots(int block, int nv) { return nv > 19 ? GRPO_ROW
 #define GRPO_WIDE_RST 0
 #endif
 constexpr int kWideRegSlots = GRPO_WIDE_NV;
+// 1: the lane's number is opaque at every use also where the row fits the registers (the per-slot
+// in-range masks are then recomputed instead of kept in scalar registers and spilled to lanes)
+#ifndef GRPO_OPAQUE_LANE
+#define GRPO_OPAQUE_LANE 1
+#endif
 #ifndef GRPO_REM_NV
 #define GRPO_REM_NV 48
 #endif
@@ -922,12 +934,12 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
     // registers of their own across the whole row loop, and the row spills.
     auto lane = [&]() __attribute__((always_inline)) {
         int t = tid;
-        if constexpr (NL > 0) asm volatile("" : "+v"(t));
+        if constexpr (NL > 0 || GRPO_OPAQUE_LANE) asm volatile("" : "+v"(t));
         return t;
     };
     auto lane_off = [&]() __attribute__((always_inline)) {
         unsigned o = toff;
-        if constexpr (NL > 0) asm volatile("" : "+v"(o));
+        if constexpr (NL > 0 || GRPO_OPAQUE_LANE) asm volatile("" : "+v"(o));
         return o;
     };
     unsigned noff = toff;  // byte offset of this lane inside a slab, as used by the refills
@@ -1010,7 +1022,7 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
             forget(buf[i]);
-            mx = fmaxf(mx, vec_max_ref<DT, AUX>(buf[i]));
+            mx = vec_max_into<DT>(mx, buf[i]);
             VECTOR_FENCE();
         }
         if constexpr (NL > 0) {
@@ -1018,12 +1030,12 @@ __global__ void __launch_bounds__(BLOCK, NV > 19 ? 2 : 4) grpo_rows_cached(RowPa
 #pragma unroll
             for (int j = 0; j < NL; ++j) {
                     const u32x4 z = lds_slot(j, vy, ey);
-                mx = fmaxf(mx, vec_max_ref<DT, AUX>(z));
+                mx = vec_max_into<DT>(mx, z);
                 asm volatile("" : "+v"(mx));  // done with this slot before the next one is read
                 VECTOR_FENCE();
             }
         }
-        if (tail_wave) mx = fmaxf(mx, vec_max_ref<DT, AUX>(tbuf));
+        if (tail_wave) mx = vec_max_into<DT>(mx, tbuf);
         // the part of the row that is not resident: online statistics, first read
         const char *zrow_cur = (const char *)p.logits + row * p.row_stride * BYTES;
         float rem_m = -INFINITY, rem_s = 0.f, rem_w = 0.f;
