@@ -1773,7 +1773,19 @@ void launch_rows(const RowParams &p_in, hipStream_t st)
     }
 }
 
-grpo_status check_logits_args(const void *logits, grpo_dtype dtype, int64_t n_tokens, int64_t vocab,
+// The integer a C caller put into an enum parameter.  The C ABI passes enums as ints and a C caller
+// may pass any int; in C++ merely reading an enum object that holds no enumerator's value is
+// undefined, so the boundary reads the bytes instead and validates the integer.
+template <typename E>
+int raw_enum(const E &e)
+{
+    static_assert(sizeof(E) == sizeof(int), "enums of the C ABI are ints");
+    int v;
+    __builtin_memcpy(&v, &e, sizeof v);
+    return v;
+}
+
+grpo_status check_logits_args(const void *logits, int dtype, int64_t n_tokens, int64_t vocab,
                               int64_t row_stride, const int64_t *tokens, float temperature)
 {
     if (dtype != GRPO_F32 && dtype != GRPO_BF16) return GRPO_ERR_DTYPE;
@@ -1794,7 +1806,7 @@ constexpr size_t loss_workspace_bytes(long long n)
     return kHeaderBytes + 3 * (((size_t)n * 4 + 255) / 256 * 256) + ((size_t)n + 255) / 256 * 256 + fin_partials_bytes(n);
 }
 
-grpo_status loss_impl(bool aux, const void *logits, grpo_dtype dtype, int64_t n_tokens, int64_t vocab,
+grpo_status loss_impl(bool aux, const void *logits, int dtype, int64_t n_tokens, int64_t vocab,
                       int64_t row_stride, const int64_t *tokens, const float *old_logprobs,
                       const float *ref_logprobs, const float *advantages, const uint8_t *mask,
                       const float *token_weights, float eps_low, float eps_high, float delta,
@@ -1911,7 +1923,7 @@ extern "C" {
 
 const char *grpo_status_string(grpo_status status)
 {
-    switch (status) {
+    switch (raw_enum(status)) {
         case GRPO_OK: return "ok";
         case GRPO_ERR_NULL: return "a required pointer is NULL";
         case GRPO_ERR_SHAPE: return "bad shape: negative size, vocab outside [1, 2^28] or row_stride < vocab";
@@ -1928,8 +1940,9 @@ const char *grpo_status_string(grpo_status status)
     return "unknown status";
 }
 
-grpo_status grpo_row_kernel_plan(grpo_dtype dtype, int64_t vocab, grpo_row_plan *plan_out)
+grpo_status grpo_row_kernel_plan(grpo_dtype dtype_arg, int64_t vocab, grpo_row_plan *plan_out)
 {
+    const int dtype = raw_enum(dtype_arg);
     if (dtype != GRPO_F32 && dtype != GRPO_BF16) return GRPO_ERR_DTYPE;
     if (vocab <= 0 || vocab > kMaxVocab) return GRPO_ERR_SHAPE;
     if (!plan_out) return GRPO_ERR_NULL;
@@ -2055,11 +2068,12 @@ grpo_status grpo_packed_layout(const int64_t *cu_seqlens, int64_t n_rollouts, in
     return hipGetLastError() == hipSuccess ? GRPO_OK : GRPO_ERR_HIP;
 }
 
-grpo_status grpo_logprobs_fwd(const void *logits, grpo_dtype dtype, int64_t n_tokens, int64_t vocab,
+grpo_status grpo_logprobs_fwd(const void *logits, grpo_dtype dtype_arg, int64_t n_tokens, int64_t vocab,
                               int64_t row_stride, const int64_t *tokens, const uint8_t *mask,
                               float temperature, float *logprobs_out, void *workspace,
                               size_t workspace_bytes, void *stream)
 {
+    const int dtype = raw_enum(dtype_arg);
     grpo_status rc = check_logits_args(logits, dtype, n_tokens, vocab, row_stride, tokens, temperature);
     if (rc != GRPO_OK) return rc;
     if (workspace && (((uintptr_t)workspace & 255u) != 0 || workspace_bytes < kHeaderBytes))
@@ -2087,7 +2101,7 @@ grpo_status grpo_logprobs_fwd(const void *logits, grpo_dtype dtype, int64_t n_to
     return hipGetLastError() == hipSuccess ? GRPO_OK : GRPO_ERR_HIP;
 }
 
-grpo_status grpo_loss_fwd_bwd(const void *logits, grpo_dtype dtype, int64_t n_tokens, int64_t vocab,
+grpo_status grpo_loss_fwd_bwd(const void *logits, grpo_dtype dtype_arg, int64_t n_tokens, int64_t vocab,
                               int64_t row_stride, const int64_t *tokens, const float *old_logprobs,
                               const float *advantages, const uint8_t *mask, float eps_low,
                               float eps_high, float delta, float temperature, double denom,
@@ -2095,13 +2109,14 @@ grpo_status grpo_loss_fwd_bwd(const void *logits, grpo_dtype dtype, int64_t n_to
                               int64_t *counts_out, void *grad_logits, void *workspace,
                               size_t workspace_bytes, void *stream)
 {
+    const int dtype = raw_enum(dtype_arg);
     return loss_impl(false, logits, dtype, n_tokens, vocab, row_stride, tokens, old_logprobs, nullptr,
                      advantages, mask, nullptr, eps_low, eps_high, delta, temperature, 0.f, 0.f, denom,
                      grad_scale, loss_out, logprobs_out, nullptr, counts_out, grad_logits, workspace,
                      workspace_bytes, stream);
 }
 
-grpo_status grpo_loss_fwd_bwd_noalloc(const void *logits, grpo_dtype dtype, int64_t n_tokens,
+grpo_status grpo_loss_fwd_bwd_noalloc(const void *logits, grpo_dtype dtype_arg, int64_t n_tokens,
                                       int64_t vocab, int64_t row_stride, const int64_t *tokens,
                                       const float *old_logprobs, const float *advantages,
                                       const uint8_t *mask, float eps_low, float eps_high,
@@ -2110,6 +2125,7 @@ grpo_status grpo_loss_fwd_bwd_noalloc(const void *logits, grpo_dtype dtype, int6
                                       int64_t *counts_out, void *grad_logits, int32_t *error_out,
                                       void *stream)
 {
+    const int dtype = raw_enum(dtype_arg);
     // the size limit first: it needs no device, and nothing may be launched beyond it
     if (n_tokens > (int64_t)GRPO_NOALLOC_MAX_TOKENS) return GRPO_ERR_CAPACITY;
     static_assert(kScratchBytes % 256 == 0, "the scratch array is a whole number of 256-byte lines");
@@ -2135,7 +2151,7 @@ grpo_status grpo_loss_fwd_bwd_noalloc(const void *logits, grpo_dtype dtype, int6
                      kScratchBytes, stream, error_out);
 }
 
-grpo_status grpo_loss_aux_fwd_bwd(const void *logits, grpo_dtype dtype, int64_t n_tokens,
+grpo_status grpo_loss_aux_fwd_bwd(const void *logits, grpo_dtype dtype_arg, int64_t n_tokens,
                                   int64_t vocab, int64_t row_stride, const int64_t *tokens,
                                   const float *old_logprobs, const float *ref_logprobs,
                                   const float *advantages, const uint8_t *mask,
@@ -2146,6 +2162,7 @@ grpo_status grpo_loss_aux_fwd_bwd(const void *logits, grpo_dtype dtype, int64_t 
                                   int64_t *counts_out, void *grad_logits, void *workspace,
                                   size_t workspace_bytes, void *stream)
 {
+    const int dtype = raw_enum(dtype_arg);
     return loss_impl(true, logits, dtype, n_tokens, vocab, row_stride, tokens, old_logprobs,
                      ref_logprobs, advantages, mask, token_weights, eps_low, eps_high, delta,
                      temperature, kl_coef,
