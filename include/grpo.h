@@ -277,7 +277,7 @@ grpo_status grpo_loss_fwd_bwd(const void *logits, grpo_dtype dtype, int64_t n_to
  *               grpo_workspace_error reads for the workspace variant (0 = none, bit 0 =
  *               an unmasked row had a token id outside [0, vocab)).
  *  Limit:       n_tokens <= GRPO_NOALLOC_MAX_TOKENS, else GRPO_ERR_CAPACITY (nothing is
- *               launched).  The array takes about 6.5 MiB of every GPU the library is
+ *               launched).  The array takes about 8.5 MiB of every GPU the library is
  *               used on, for the life of the process.
  *  Concurrency: all calls on one GPU share that GPU's array (each GPU has its own).  A
  *               call clears what it needs at its start; two calls that overlap in time
