@@ -163,7 +163,7 @@ def test_zero_coefficients_match_the_plain_head_call_and_rows_without_gradient_s
 
 
 def test_full_size_qwen_short_sampled_rows():
-    """BASELINE configs[1] with a 5120-wide head and the coefficients of section 4.1: log-probs,
+    """The benchmark's headline batch (16384 tokens, vocabulary 152064) with a 5120-wide head and the coefficients of section 4.1: log-probs,
     entropies and dL/dH rows against the oracle on sampled rows, the two scalars that need every
     row (mean KL, mean entropy) against the library's own per-token outputs summed in fp64, dL/dW
     through properties that hold at any size."""

@@ -372,7 +372,7 @@ def test_edge_cases():
 
 
 def test_full_size_qwen_short_sampled_rows():
-    """BASELINE configs[1] with a 5120-wide head (the hidden size of the paper's 32B model):
+    """The benchmark's headline batch (16384 tokens, vocabulary 152064) with a 5120-wide head (the hidden size of the paper's 32B model):
     log-probs and dL/dH rows against the oracle on sampled rows of every class, dL/dW through
     properties that hold at any size."""
     cfg = wl.CONFIGS["qwen_short"]
