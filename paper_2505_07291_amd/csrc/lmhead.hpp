@@ -388,6 +388,34 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
     // row 8 (v / 4) + 4 (l / 32) + v % 4.
     const int cl = lane & 31, g = lane >> 5;
     const int wrow = wm * (LM_FA * 32), wcol = wn * (LM_FB * 32);
+    if (EPI == LM_EPI_F32 && p.accumulate) {
+        // C += result.  All loads of a block row first, then the sums and stores: element by element the
+        // dependent load in front of every store made this epilogue take 2 ms longer than the plain store
+        // (dL/dW of the second and later chunks).
+#pragma unroll
+        for (int i = 0; i < LM_FA; ++i) {
+            float old[16][LM_FB];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = row0 + wrow + i * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+#pragma unroll
+                for (int j = 0; j < LM_FB; ++j) {
+                    const int col = col0 + wcol + j * 32 + cl;
+                    old[v][j] = (row < M && col < p.N) ? ((const float *)p.C)[(long long)row * p.ldc + col] : 0.f;
+                }
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = row0 + wrow + i * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+#pragma unroll
+                for (int j = 0; j < LM_FB; ++j) {
+                    const int col = col0 + wcol + j * 32 + cl;
+                    if (row < M && col < p.N) ((float *)p.C)[(long long)row * p.ldc + col] = old[v][j] + acc[i][j][v];
+                }
+            }
+        }
+        return;
+    }
     if (EPI == LM_EPI_BF16 || EPI == LM_EPI_F32) {
 #pragma unroll
         for (int i = 0; i < LM_FA; ++i)
@@ -406,8 +434,7 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
                     } else if (EPI == LM_EPI_BF16) {
                         ((__bf16 *)p.C)[orow * p.ldc + col] = (__bf16)acc[i][j][v];
                     } else {
-                        float *c = (float *)p.C + orow * p.ldc + col;
-                        *c = p.accumulate ? *c + acc[i][j][v] : acc[i][j][v];
+                        ((float *)p.C)[orow * p.ldc + col] = acc[i][j][v];
                     }
                 }
             }
