@@ -371,11 +371,11 @@ grpo_status grpo_workspace_error(const void *workspace, int32_t *flag_out, void 
  *           compacted copy of the hidden states of the rows that take part and 8 bytes
  *           per token and 256 vocabulary entries.  With the backward the rows that take
  *           part are worked through in chunks, and per chunk row the workspace also holds
- *           the logits in fp32 and their gradient in bf16 (twice: row-major and
- *           transposed), 8 bytes per chunk row and vocabulary entry, next to transposed
- *           copies of W and of the chunk's hidden states: its size follows the chunk, not
+ *           the logits in fp32 and their gradient in bf16, 6 bytes per chunk row and
+ *           vocabulary entry, next to a transposed copy of the chunk's hidden states (W is
+ *           never copied): its size follows the chunk, not
  *           the number of tokens.  grpo_lmhead_workspace_bytes(.., 1) is the size for
- *           the default chunk of 8192 rows (about 10.3 GB at vocab 152064, d_model 5120,
+ *           the default chunk of 8192 rows (about 7.6 GB at vocab 152064, d_model 5120,
  *           for any n_tokens >= 8192); grpo_lmhead_workspace_bytes_for_chunk gives the
  *           size for another chunk.  The call uses the largest chunk (a multiple of 256
  *           rows, at most n_tokens rounded up to 256) that fits into workspace_bytes:

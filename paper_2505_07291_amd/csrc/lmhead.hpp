@@ -4,17 +4,20 @@
 // and uses the row arithmetic, the workspace header and the small kernels defined there).
 //
 // Everything heavy is one bf16 MFMA kernel, lm_gemm_nt: C[M x N] = A[M x K] B[N x K]^T with
-// both operands contiguous along K, fp32 accumulation.  It runs three times:
-//   logits   z  = H W^T        (K = d_model)  epilogue: per-row softmax partials in fp32
+// fp32 accumulation.  An operand is either contiguous along K ([M][K], the plain case) or
+// "K-major" ([K][M], read from LDS with the transposing reads of gfx950).  It runs three times:
+//   logits   z  = H W^T        (K = d_model)  A = H, B = W, both plain
+//                                             epilogue: per-row softmax partials in fp32
 //                                             from the accumulators, z_y, optional fp32 z
-//   dL/dH       = G  (W^T)^T   (K = vocab)    epilogue: bf16 store
-//   dL/dW       = G^T (H^T)^T  (K = tokens)   epilogue: fp32 store or accumulate
-// G = dL/dz is formed once, in bf16, by an elementwise kernel that also writes G^T; W^T
-// and H^T are transposed copies, so every operand of every product is K-contiguous and
-// one kernel serves all three.
+//   dL/dH       = G W          (K = vocab)    A = G plain, B = W K-major; epilogue: bf16 store
+//   dL/dW       = G^T H        (K = tokens)   A = G K-major, B = H^T plain; epilogue: fp32 store
+//                                             or accumulate
+// G = dL/dz is formed once, in bf16, by an elementwise kernel and serves both gradient
+// products as it lies; W is never copied; H^T (the chunk's gradient rows, [d][rows]) is the
+// one transposed copy, 1/30 of G's size.
 //
 // The backward works through the rows that take part in chunks of at most `cap` rows (a
-// multiple of 256 chosen from the size of the caller's workspace): logits, G, G^T and H^T
+// multiple of 256 chosen from the size of the caller's workspace): logits, G and H^T
 // exist for one chunk at a time, dL/dH rows of different chunks are disjoint and dL/dW is
 // accumulated in fp32 from chunk to chunk.  The workspace is therefore bounded by the
 // chunk, not by the number of tokens.  The live rows are dealt evenly over the chunks
@@ -54,7 +57,7 @@ constexpr int LM_SLOTS = 5;                          // operand tiles resident i
 constexpr int LM_LPT = LM_BM * LM_CPR / LM_THREADS;  // 16-byte loads per lane and operand tile: 4
 constexpr int LM_LDS_BYTES = LM_SLOTS * LM_TILE_BYTES;
 constexpr int LM_GROUP_M = 8;                        // tile rows that share a sweep along N
-constexpr int LM_GM_BWD = 4;                         // the same for the two gradient products: their A panels (G, G^T)
+constexpr int LM_GM_BWD = 4;                         // the same for the two gradient products: their A panels (of G)
                                                      // come from HBM, and a lower group re-reads them less often
 constexpr int LM_SPLIT_MAX = 32;                     // parts the contraction of one tile of dL/dH may be cut into
 
@@ -93,6 +96,13 @@ struct GemmParams {
     float *zy;               // [M]: the accumulator at the sampled token's column
     float *Z;                // optional fp32 copy of the logits, [M][ldz]
     long long ldz;
+    // K-major operands (AKM / BKM: stored [K][M] resp. [K][N], contiguous along M resp. N, lda / ldb between
+    // k rows): how many elements of a k row exist (a multiple of 8; chunks past them re-read the last one)
+    int a_cols, b_cols;
+    // K-major B: how many k rows exist when that is fewer than K (0: all of them).  The rows past them read
+    // as zeros: the buffer descriptor of the last K step ends with the last row that exists, and a load
+    // past a descriptor's end puts zeros into LDS (measured on gfx950).
+    int b_rows;
 };
 
 // Which of n_live rows chunk number `chunk` covers when no chunk may hold more than cap rows
@@ -184,6 +194,12 @@ __device__ __forceinline__ bool lm_map_tile(int tiles_m, int tiles_n, const LmSp
     return true;
 }
 
+// A K-major operand tile in LDS is [64 k][256 m] bf16, 512 bytes per k row.  The 16-byte chunk at
+// position pc of row k holds logical chunk pc ^ lm_km_swizzle(k) (applied on the global-address side):
+// a transposing fragment read touches rows k .. k + 3 (and k + 8 .. k + 11 in the other half of the
+// wavefront), 64 bytes of each, and with the swizzle those land on different banks.
+__device__ __forceinline__ int lm_km_swizzle(int k) { return (4 * (k & 3)) ^ (2 * ((k >> 3) & 1)); }
+
 template <int CTRL>
 __device__ __forceinline__ float lm_dpp(float v)
 {
@@ -209,7 +225,7 @@ __device__ __forceinline__ float lm_row32_sum(float v)
     return v + __shfl_xor(v, 16, 64);
 }
 
-template <int EPI, bool STORE_Z, bool AUX = false>
+template <int EPI, bool STORE_Z, bool AUX = false, bool AKM = false, bool BKM = false>
 __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
 {
     extern __shared__ __attribute__((aligned(1024))) char lm_smem[];
@@ -250,14 +266,29 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
         const int lc = pc ^ ((r >> 1) & (LM_CPR - 1));
         const int ra = min(row0 + r, M - 1) - row0;
         const int rb = min(col0 + r, p.N - 1) - col0;
-        a_off[i] = (unsigned)(((long long)ra * p.lda + lc * 8) * 2);
-        b_off[i] = (unsigned)(((long long)rb * p.ldb + lc * 8) * 2);
+        // K-major: chunk c of the tile is k row c / 32, position c % 32
+        const int kk = c >> 5, lck = (c & 31) ^ lm_km_swizzle(kk);
+        if constexpr (AKM) {
+            const int ch = min((row0 >> 3) + lck, (p.a_cols >> 3) - 1) - (row0 >> 3);
+            a_off[i] = (unsigned)((long long)kk * p.lda * 2 + ch * 16);
+        } else {
+            a_off[i] = (unsigned)(((long long)ra * p.lda + lc * 8) * 2);
+        }
+        if constexpr (BKM) {
+            const int ch = min((col0 >> 3) + lck, (p.b_cols >> 3) - 1) - (col0 >> 3);
+            b_off[i] = (unsigned)((long long)kk * p.ldb * 2 + ch * 16);
+        } else {
+            b_off[i] = (unsigned)(((long long)rb * p.ldb + lc * 8) * 2);
+        }
     }
     // this workgroup's part of the contraction: K steps [kt0, kt0 + KT)
     const int kt0 = (int)((long long)(K / LM_BK) * part / parts);
     const int KT = (int)((long long)(K / LM_BK) * (part + 1) / parts) - kt0;
-    const char *a_tile = (const char *)p.A + ((long long)(chunk_base + row0) * p.lda + (long long)kt0 * LM_BK) * 2;
-    const char *b_tile = (const char *)p.B + ((long long)col0 * p.ldb + (long long)kt0 * LM_BK) * 2;
+    const char *a_tile = AKM ? (const char *)p.A + ((long long)kt0 * LM_BK * p.lda + row0) * 2
+                             : (const char *)p.A + ((long long)(chunk_base + row0) * p.lda + (long long)kt0 * LM_BK) * 2;
+    const char *b_tile = BKM ? (const char *)p.B + ((long long)kt0 * LM_BK * p.ldb + col0) * 2
+                             : (const char *)p.B + ((long long)col0 * p.ldb + (long long)kt0 * LM_BK) * 2;
+    const long long a_kstep = (long long)LM_BK * p.lda * 2, b_kstep = (long long)LM_BK * p.ldb * 2;  // K-major only
 
     // LDS is a ring of five 32 KB slots that operand tiles pass through in the order
     // A(0), B(0), A(1), B(1), ...: entry q = 2 kt + (0 for A, 1 for B) lives in slot q % 5.
@@ -273,9 +304,26 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
     // clamped above and K steps below, so every address is inside the operand).
     const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)a_tile, 0, -1, 0x00020000);
     const __amdgpu_buffer_rsrc_t b_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)b_tile, 0, -1, 0x00020000);
+    // A K-major operand moves by whole k rows from step to step, further than a 32-bit offset reaches:
+    // its descriptor is made again for every step (scalar arithmetic).
     auto issue_half = [&](int q, bool b_operand, int half) {
-        const int k0 = min(q >> 1, KT - 1) * (LM_BK * 2);
+        const int kt = min(q >> 1, KT - 1);
         char *sd = slot_of(q) + wave * 1024;
+        if (b_operand ? BKM : AKM) {
+            const char *base = b_operand ? b_tile + kt * b_kstep : a_tile + kt * a_kstep;
+            unsigned bytes = 0xffffffffu;  // range check wide open, except for a ragged last step of B
+            const int k0 = (kt0 + kt) * LM_BK;
+            if (b_operand && p.b_rows > 0 && k0 + LM_BK > p.b_rows)
+                bytes = (unsigned)((long long)(p.b_rows - k0 - 1) * p.ldb * 2 + (long long)(p.b_cols - col0) * 2);
+            const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, (int)bytes, 0x00020000);
+#pragma unroll
+            for (int i = half * (LM_LPT / 2); i < (half + 1) * (LM_LPT / 2); ++i)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc,
+                                                         (__attribute__((address_space(3))) void *)(sd + i * (LM_THREADS * 16)),
+                                                         16, (int)(b_operand ? b_off[i] : a_off[i]), 0, 0, 0);
+            return;
+        }
+        const int k0 = kt * (LM_BK * 2);
 #pragma unroll
         for (int i = half * (LM_LPT / 2); i < (half + 1) * (LM_LPT / 2); ++i)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(b_operand ? b_rsrc : a_rsrc,
@@ -292,6 +340,39 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
         frag_off[ks] = (unsigned)((fr * LM_CPR + ((2 * ks + fh) ^ ((fr >> 1) & (LM_CPR - 1)))) * 16);
     const unsigned a_wave = (unsigned)(wm * (LM_FA * 32) * LM_BK * 2);
     const unsigned b_wave = (unsigned)(wn * (LM_FB * 32) * LM_BK * 2);
+    // K-major tiles are read with the transposing 64-bit LDS read: lane i of a group of 16 lanes gives the
+    // address of 4 consecutive m at k row i / 4 (piece i % 4 of 16 m) and receives the 4 k values of m = i.
+    // Two such reads (k rows +0..3 and +4..7) make the 8 consecutive k of m = lane % 32 that a lane holds
+    // for the 32 x 32 x 16 product: lanes 0-15 and 16-31 cover m 0-15 and 16-31, lanes 32-63 the k rows + 8.
+    unsigned akm_off[LM_FA], bkm_off[LM_FB];
+    {
+        const int kh = lane >> 5, mg = (lane >> 4) & 1, i16 = lane & 15;
+        const int kkl = 8 * kh + (i16 >> 2), sw = lm_km_swizzle(kkl);
+#pragma unroll
+        for (int i = 0; i < LM_FA; ++i) {
+            const int ml = wm * (LM_FA * 32) + i * 32 + 16 * mg + 4 * (i16 & 3);
+            akm_off[i] = (unsigned)(kkl * (LM_BM * 2) + (((ml >> 3) ^ sw) * 16) + (ml & 7) * 2);
+        }
+#pragma unroll
+        for (int j = 0; j < LM_FB; ++j) {
+            const int nl = wn * (LM_FB * 32) + j * 32 + 16 * mg + 4 * (i16 & 3);
+            bkm_off[j] = (unsigned)(kkl * (LM_BN * 2) + (((nl >> 3) ^ sw) * 16) + (nl & 7) * 2);
+        }
+    }
+    // Written as assembly: the compiler holds the builtin form of this read back behind every outstanding
+    // load to LDS (s_waitcnt vmcnt(0) in front of each k-step's reads), which the pipeline below exists to
+    // avoid.  The results arrive asynchronously; every use sits behind the explicit lgkmcnt(0) of lds_landed().
+    auto tr_frag = [&](const char *s) {
+        typedef short s16x4 __attribute__((ext_vector_type(4)));
+        s16x4 lo, hi;
+        const unsigned at = (unsigned)(uintptr_t)(__attribute__((address_space(3))) const char *)s;
+        asm volatile("ds_read_b64_tr_b16 %0, %2\n\tds_read_b64_tr_b16 %1, %2 offset:2048"
+                     : "=&v"(lo), "=&v"(hi)
+                     : "v"(at)
+                     : "memory");
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    static_assert(4 * (LM_BM * 2) == 2048, "the second read's offset is written into the assembly");
 
     f32x16 acc[LM_FA][LM_FB];
 #pragma unroll
@@ -309,11 +390,19 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
     auto read_frags = [&](bf16x8 (&f)[LM_FA + LM_FB], int kt, int ks) {
         const char *sa = slot_of(2 * kt), *sb = slot_of(2 * kt + 1);
 #pragma unroll
-        for (int i = 0; i < LM_FA; ++i)
-            f[i] = *(const bf16x8 *)(sa + a_wave + i * (32 * LM_BK * 2) + frag_off[ks]);
+        for (int i = 0; i < LM_FA; ++i) {
+            if constexpr (AKM)
+                f[i] = tr_frag(sa + akm_off[i] + ks * (16 * LM_BM * 2));
+            else
+                f[i] = *(const bf16x8 *)(sa + a_wave + i * (32 * LM_BK * 2) + frag_off[ks]);
+        }
 #pragma unroll
-        for (int j = 0; j < LM_FB; ++j)
-            f[LM_FA + j] = *(const bf16x8 *)(sb + b_wave + j * (32 * LM_BK * 2) + frag_off[ks]);
+        for (int j = 0; j < LM_FB; ++j) {
+            if constexpr (BKM)
+                f[LM_FA + j] = tr_frag(sb + bkm_off[j] + ks * (16 * LM_BN * 2));
+            else
+                f[LM_FA + j] = *(const bf16x8 *)(sb + b_wave + j * (32 * LM_BK * 2) + frag_off[ks]);
+        }
     };
     auto products = [&](const bf16x8 (&f)[LM_FA + LM_FB]) {
 #pragma unroll
@@ -332,7 +421,7 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
         __builtin_amdgcn_sched_barrier(0);
     };
     auto interleave = [&]() {
-        __builtin_amdgcn_sched_group_barrier(0x100, LM_FA + LM_FB, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, (AKM ? 2 : 1) * LM_FA + (BKM ? 2 : 1) * LM_FB, 0);
 #pragma unroll
         for (int i = 0; i < LM_LPT / 2; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
@@ -341,6 +430,7 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
         __builtin_amdgcn_sched_group_barrier(0x008, LM_FA * LM_FB - LM_LPT, 0);
         __builtin_amdgcn_sched_barrier(0);
     };
+    static_assert(LM_BM == 256 && LM_BN == 256, "K-major tiles: 32 chunks per k row");
     static_assert(LM_BK / 16 == 4 && LM_SLOTS == 5 && LM_LPT == 4 && LM_FA * LM_FB >= LM_LPT,
                   "the pipeline and its wait counts are written for 4 k-steps, 5 slots, 4 loads per operand tile");
 
@@ -755,28 +845,28 @@ __global__ void __launch_bounds__(LM_CMB_ROWS * LM_CMB_LANES) lm_combine(RowPara
     }
 }
 
-// G = dL/dz in bf16 for the gradient rows, row-major [n_grad][ldg] and transposed
-// [V][ldgt], from the fp32 logits: g_j = -q p_j, g_y = q (1 - p_y).  64 x 64 tiles, four
-// consecutive elements per lane on both sides.  Padding (columns V .. ldg of G, columns
-// n_grad .. the next multiple of 64 of G^T) is written as zeros so that the products can
-// run over whole K steps.
+// G = dL/dz in bf16 for the chunk's gradient rows, row-major [n_grad][ldg], from the fp32 logits:
+// g_j = -q p_j, g_y = q (1 - p_y).  A wavefront takes 512 consecutive entries of a row, eight per lane
+// (two 16-byte reads, one 16-byte write); a workgroup 16 rows of them.  Padding is written as zeros: the
+// columns V .. ldg (dL/dH runs over whole K steps of the vocabulary) and the rows n_grad .. the next
+// multiple of 64 (dL/dW runs over whole K steps of rows).
+constexpr int LM_GL_COLS = 512, LM_GL_ROWS = 16;
 template <bool AUX>
 __global__ void __launch_bounds__(256) lm_grad_logits(const float *Z, long long ldz, int V, LmRows w,
-                                                      float k, __bf16 *G, long long ldg, __bf16 *Gt,
-                                                      long long ldgt)
+                                                      float k, __bf16 *G, long long ldg, int col_groups)
 {
-    __shared__ float tile[64][65];
-    const int n2 = *w.n_grad;
-    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
-    if (r0 >= (n2 + 63) / 64 * 64) return;
+    const int n2 = *w.n_grad, n2_pad = (n2 + 63) / 64 * 64;
+    const int r0 = (int)(blockIdx.x / (unsigned)col_groups) * LM_GL_ROWS;
+    if (r0 >= n2_pad) return;  // LM_GL_ROWS divides 64: a workgroup's rows are all inside or all outside
     int zbase, zcount;  // Z holds the current chunk's rows only
     lm_chunk_range(*w.n_live, w.chunk_cap, w.chunk, zbase, zcount);
-    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;  // 16 x 4 columns, 16 rows per pass
-    const int c = c0 + tx * 4;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int c = (int)(blockIdx.x % (unsigned)col_groups) * LM_GL_COLS + lane * 8;
+    if (c >= ldg) return;  // ldg is a multiple of 64: whole groups of eight
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int rl = ty + 16 * i, r = r0 + rl;
-        float gv[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < LM_GL_ROWS / 4; ++i) {
+        const int r = r0 + wv + 4 * i;
+        float gv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         if (r < n2 && c < V) {
             const int ci = w.rows2[r];
             float q = 0.f, sh = 0.f, mxr = 0.f, l2s = 0.f, q2 = 0.f, bq = 0.f;
@@ -787,16 +877,17 @@ __global__ void __launch_bounds__(256) lm_grad_logits(const float *Z, long long 
             }
             const int y = w.tokens32[ci];
             const float *zrow = Z + (long long)(ci - zbase) * ldz + c;
-            float z[4];
-            if (c + 3 < V) {
-                const f32x4 zv = *(const f32x4 *)zrow;
-                z[0] = zv[0], z[1] = zv[1], z[2] = zv[2], z[3] = zv[3];
+            float z[8];
+            if (c + 7 < V) {
+                const f32x4 z0 = *(const f32x4 *)zrow, z1 = *(const f32x4 *)(zrow + 4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) z[e] = z0[e], z[4 + e] = z1[e];
             } else {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) z[e] = c + e < V ? zrow[e] : -INFINITY;
+                for (int e = 0; e < 8; ++e) z[e] = c + e < V ? zrow[e] : -INFINITY;
             }
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
+            for (int e = 0; e < 8; ++e) {
                 if constexpr (AUX) {
                     // g_j = p_j (q2 + bq log2 p_j): policy, KL and entropy parts in one (see grad_vec_aux)
                     const float a = fmaxf(fmaf(z[e] - mxr, k, -l2s), kExpFloor);
@@ -808,28 +899,11 @@ __global__ void __launch_bounds__(256) lm_grad_logits(const float *Z, long long 
                 if (c + e >= V) gv[e] = 0.f;
             }
         }
-        if (r < n2 && c < ldg) {  // ldg is a multiple of 64: whole groups of four
-            bf16x2 lo = __builtin_convertvector((f32x2){gv[0], gv[1]}, bf16x2);
-            bf16x2 hi = __builtin_convertvector((f32x2){gv[2], gv[3]}, bf16x2);
-            unsigned *dst = (unsigned *)(G + (long long)r * ldg + c);
-            dst[0] = __builtin_bit_cast(unsigned, lo);
-            dst[1] = __builtin_bit_cast(unsigned, hi);
-        }
+        u32x4 out;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) tile[rl][tx * 4 + e] = gv[e];
-    }
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int cl2 = ty + 16 * i, cc = c0 + cl2;  // vocabulary entry: a row of G^T
-        const int r = r0 + tx * 4;                   // four consecutive gradient rows
-        if (cc < V && r < ldgt) {
-            bf16x2 lo = __builtin_convertvector((f32x2){tile[tx * 4][cl2], tile[tx * 4 + 1][cl2]}, bf16x2);
-            bf16x2 hi = __builtin_convertvector((f32x2){tile[tx * 4 + 2][cl2], tile[tx * 4 + 3][cl2]}, bf16x2);
-            unsigned *dst = (unsigned *)(Gt + (long long)cc * ldgt + r);
-            dst[0] = __builtin_bit_cast(unsigned, lo);
-            dst[1] = __builtin_bit_cast(unsigned, hi);
-        }
+        for (int e = 0; e < 4; ++e)
+            out[e] = __builtin_bit_cast(unsigned, __builtin_convertvector((f32x2){gv[2 * e], gv[2 * e + 1]}, bf16x2));
+        *(u32x4 *)(G + (long long)r * ldg + c) = out;
     }
 }
 
@@ -917,7 +991,7 @@ __global__ void __launch_bounds__(256) lm_zero(T *out, long long rows, long long
 // Host side
 // ---------------------------------------------------------------------------
 
-template <int EPI, bool STORE_Z, bool AUX = false>
+template <int EPI, bool STORE_Z, bool AUX = false, bool AKM = false, bool BKM = false>
 hipError_t lm_launch_gemm(GemmParams p, hipStream_t st)
 {
     static std::atomic<bool> attr_done[64];      // setting the attribute twice is harmless
@@ -925,7 +999,7 @@ hipError_t lm_launch_gemm(GemmParams p, hipStream_t st)
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     if (dev >= 0 && dev < 64 && !attr_done[dev].load()) {
-        e = hipFuncSetAttribute((const void *)lm_gemm_nt<EPI, STORE_Z, AUX>,
+        e = hipFuncSetAttribute((const void *)lm_gemm_nt<EPI, STORE_Z, AUX, AKM, BKM>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, LM_LDS_BYTES);
         if (e != hipSuccess) return e;
         attr_done[dev].store(true);
@@ -937,16 +1011,16 @@ hipError_t lm_launch_gemm(GemmParams p, hipStream_t st)
     const long long items = EPI == LM_EPI_BF16 && p.split_items > 0
                                 ? (long long)(p.n_cu > 0 ? p.n_cu : 256) * LM_SPLIT_MAX : 0;
     const long long grid = ((tiles + 7) / 8 + (items + 7) / 8) * 8;
-    hipLaunchKernelGGL((lm_gemm_nt<EPI, STORE_Z, AUX>), dim3((unsigned)grid), dim3(LM_THREADS), LM_LDS_BYTES, st, p);
+    hipLaunchKernelGGL((lm_gemm_nt<EPI, STORE_Z, AUX, AKM, BKM>), dim3((unsigned)grid), dim3(LM_THREADS), LM_LDS_BYTES, st, p);
     return hipGetLastError();
 }
 
 struct LmLayout {
-    size_t rows, tokens32, rows2, orig2, counts, zy, shift, q, gy, mx, log2s, q2, bq, part_m, part_s, part_w, Hc, Z, G, Gt,
-        Wt, Ht, total;
+    size_t rows, tokens32, rows2, orig2, counts, zy, shift, q, gy, mx, log2s, q2, bq, part_m, part_s, part_w, Hc, Z, G, Ht,
+        total;
     long long ldz, ldg, ldgt;  // vocab and chunk rows rounded up to whole K steps
     int tiles_n;
-    int cap;  // rows per chunk: what the partials, Z, G, G^T and H^T are sized for
+    int cap;  // rows per chunk: what the partials, Z, G and H^T are sized for
 };
 
 // Default limit of a chunk of the backward: 8192 rows keep the workspace at V = 152064 near
@@ -991,8 +1065,6 @@ LmLayout lm_layout(int64_t n, int64_t V, int64_t d, bool bwd, int64_t cap)
         L.part_w = take((size_t)L.tiles_n * cap * 4);
         L.Z = take((size_t)cap * L.ldz * 4);
         L.G = take((size_t)cap * L.ldg * 2);
-        L.Gt = take((size_t)V * L.ldgt * 2);
-        L.Wt = take((size_t)d * L.ldg * 2);
         L.Ht = take((size_t)d * L.ldgt * 2);
     }
     L.total = off;
@@ -1018,7 +1090,7 @@ bool lm_sizes_ok(int64_t n_tokens, int64_t vocab, int64_t d_model)
     return n_tokens >= 0 && n_tokens <= 0x7fffff00ll && vocab > 0 && vocab <= kMaxVocab && d_model > 0 &&
            d_model <= (1 << 20) && d_model % LM_BK == 0;
 }
-// With the backward G and W^T are operands whose rows are align64(vocab) elements long: the byte offset
+// With the backward G is an operand whose rows are align64(vocab) elements long: the byte offset
 // of row 255 of an operand tile must fit 32 bits.
 bool lm_bwd_vocab_ok(int64_t vocab) { return (int64_t)align_up((size_t)vocab, 64) * 2 * LM_BM < (1ll << 32); }
 
@@ -1153,15 +1225,10 @@ grpo_status lm_impl(bool bwd, bool aux, const void *hidden, int64_t hidden_strid
         hipLaunchKernelGGL(lm_gather_rows, dim3((unsigned)(M < 8192 ? M : 8192)), dim3(256), 0, st,
                            (const __bf16 *)hidden, (long long)hidden_stride, (const int *)w.rows,
                            (const int *)w.n_live, D, Hc, (long long)d_model);
-        __bf16 *G = nullptr, *Gt = nullptr, *Wt = nullptr, *Ht = nullptr;
+        __bf16 *G = nullptr, *Ht = nullptr;
         const int n_cu = cu_count();
         if (bwd) {
-            G = (__bf16 *)(ws + L.G), Gt = (__bf16 *)(ws + L.Gt);
-            Wt = (__bf16 *)(ws + L.Wt), Ht = (__bf16 *)(ws + L.Ht);
-            // W^T [d][ldg], once for all chunks
-            hipLaunchKernelGGL(lm_transpose, dim3((unsigned)(L.ldg / 64), (unsigned)((D + 63) / 64)), dim3(256), 0,
-                               st, (const __bf16 *)weight, (long long)weight_stride, V, (const int *)nullptr,
-                               (const int *)nullptr, D, Wt, L.ldg);
+            G = (__bf16 *)(ws + L.G), Ht = (__bf16 *)(ws + L.Ht);
             // rows without gradient keep the zeros written here
             hipLaunchKernelGGL(lm_zero<unsigned short>, dim3(2048), dim3(256), 0, st, (unsigned short *)grad_hidden,
                                (long long)n_tokens, (long long)d_model, (long long)grad_hidden_stride);
@@ -1202,23 +1269,28 @@ grpo_status lm_impl(bool bwd, bool aux, const void *hidden, int64_t hidden_strid
             if (!bwd) continue;
 
             hipLaunchKernelGGL(lm_select_grad_rows, dim3(1), dim3(1024), 0, st, w);
-            const dim3 gl_grid((unsigned)(L.ldg / 64), (unsigned)((Mc + 63) / 64));
+            const int gl_cols = (int)((L.ldg + LM_GL_COLS - 1) / LM_GL_COLS);
+            // rows up to the next multiple of 64: the padding rows are written too (G has cap >= 256 rows)
+            const dim3 gl_grid((unsigned)((long long)gl_cols * ((Mc + 63) / 64 * (64 / LM_GL_ROWS))));
             if (aux)
                 hipLaunchKernelGGL(lm_grad_logits<true>, gl_grid, dim3(256), 0, st, (const float *)(ws + L.Z), L.ldz,
-                                   V, w, k, G, L.ldg, Gt, L.ldgt);
+                                   V, w, k, G, L.ldg, gl_cols);
             else
                 hipLaunchKernelGGL(lm_grad_logits<false>, gl_grid, dim3(256), 0, st, (const float *)(ws + L.Z), L.ldz,
-                                   V, w, k, G, L.ldg, Gt, L.ldgt);
+                                   V, w, k, G, L.ldg, gl_cols);
             // H^T of the chunk's gradient rows [d][ldgt]
             hipLaunchKernelGGL(lm_transpose, dim3((unsigned)(L.ldgt / 64), (unsigned)((D + 63) / 64)), dim3(256), 0,
                                st, (const __bf16 *)hidden, (long long)hidden_stride, M, (const int *)w.n_grad,
                                (const int *)w.orig2, D, Ht, L.ldgt);
 
-            GemmParams gh = {};  // dL/dH [gradient rows][d] = G . W, scattered to the original rows
+            GemmParams gh = {};  // dL/dH [gradient rows][d] = G . W, scattered to the original rows; W is read as it
+                                 // lies, [vocab][d]: K-major, its rows past the vocabulary read as zeros
             gh.A = G;
             gh.lda = L.ldg;
-            gh.B = Wt;
-            gh.ldb = L.ldg;
+            gh.B = (const __bf16 *)weight;
+            gh.ldb = weight_stride;
+            gh.b_cols = D;
+            gh.b_rows = V;
             gh.M = Mc;
             gh.M_dev = w.n_grad;
             gh.N = D;
@@ -1233,7 +1305,7 @@ grpo_status lm_impl(bool bwd, bool aux, const void *hidden, int64_t hidden_strid
             gh.split_items = (int)(z_blocks < 0x7fffffffu ? z_blocks : 0x7fffffffu);
             gh.split_ws = (float *)(ws + L.Z);
             gh.n_cu = n_cu;
-            e = lm_launch_gemm<LM_EPI_BF16, false>(gh, st);
+            e = lm_launch_gemm<LM_EPI_BF16, false, false, false, true>(gh, st);
             if (e != hipSuccess) return GRPO_ERR_HIP;
             if (gh.split_items > 0)
                 hipLaunchKernelGGL(lm_split_reduce, dim3(2048), dim3(256), 0, st, (const float *)gh.split_ws,
@@ -1241,9 +1313,11 @@ grpo_status lm_impl(bool bwd, bool aux, const void *hidden, int64_t hidden_strid
                                    gh.split_items, n_cu, LM_GM_BWD, (const int *)w.orig2, (__bf16 *)grad_hidden,
                                    (long long)grad_hidden_stride);
 
-            GemmParams gw = {};  // dL/dW [V][d] (+)= G^T . H over the chunk's gradient rows
-            gw.A = Gt;
-            gw.lda = L.ldgt;
+            GemmParams gw = {};  // dL/dW [V][d] (+)= G^T . H over the chunk's gradient rows; G is read as it lies,
+                                 // [rows][ldg]: K-major
+            gw.A = G;
+            gw.lda = L.ldg;
+            gw.a_cols = (int)L.ldg;
             gw.B = Ht;
             gw.ldb = L.ldgt;
             gw.M = V;
@@ -1254,7 +1328,7 @@ grpo_status lm_impl(bool bwd, bool aux, const void *hidden, int64_t hidden_strid
             gw.ldc = grad_weight_stride;
             gw.accumulate = (accumulate_grad_weight || c > 0) ? 1 : 0;  // the first chunk starts the sum
             gw.group_m = LM_GM_BWD;
-            e = lm_launch_gemm<LM_EPI_F32, false>(gw, st);
+            e = lm_launch_gemm<LM_EPI_F32, false, false, true, false>(gw, st);
             if (e != hipSuccess) return GRPO_ERR_HIP;
         }
     } else if (bwd && !accumulate_grad_weight && vocab > 0) {
