@@ -180,15 +180,14 @@ def lmhead_leg(grpo, wl, cfg, d_model, dev, stream, reps, warmup):
     aux_vals = loss4.cpu().tolist()
     ms_b = timed_calls(fwd_bwd, stream, reps, max(2, warmup // 2))["mean"]
     c = counts.cpu().tolist()
-    # the same call with a workspace large enough for all rows in one chunk (the default workspace
-    # bounds the chunk at 8192 rows, whatever N)
-    one = {"skipped": "not enough free device memory"}
-    ws_1_bytes = grpo.grpo_lmhead_workspace_bytes_for_chunk(N, V, d_model, N)
-    if ws_1_bytes > ws_b_bytes and ws_1_bytes < 0.9 * torch.cuda.mem_get_info()[0]:
-        ws_b = torch.empty(ws_1_bytes, dtype=torch.uint8, device=dev)
-        ms_1 = timed_calls(fwd_bwd, stream, reps, max(2, warmup // 2))["mean"]
-        one = {"fwd_bwd_ms": ms_1, "workspace_bytes": ws_1_bytes,
-               "workspace_bytes_per_logit": ws_1_bytes / (float(N) * V)}
+    # the same call with a workspace for chunks of half the default (the default workspace bounds the
+    # chunk at 10240 rows, whatever N): what working through the rows in more, smaller chunks costs
+    half_rows = 5120
+    ws_h_bytes = grpo.grpo_lmhead_workspace_bytes_for_chunk(N, V, d_model, half_rows)
+    ws_b = torch.empty(ws_h_bytes, dtype=torch.uint8, device=dev)
+    ms_h = timed_calls(fwd_bwd, stream, reps, max(2, warmup // 2))["mean"]
+    half = {"chunk_rows": half_rows, "fwd_bwd_ms": ms_h, "workspace_bytes": ws_h_bytes,
+            "workspace_bytes_per_logit": ws_h_bytes / (float(N) * V)}
     n_unmasked = c[0]
     zero_adv = int(((adv_tok == 0) & (b["mask"] != 0)).sum())
     n_grad = n_unmasked - (c[1] + c[2] + c[3] + zero_adv)   # rows whose objective has a gradient
@@ -205,7 +204,7 @@ def lmhead_leg(grpo, wl, cfg, d_model, dev, stream, reps, warmup):
             "workspace_bytes_per_logit_fwd_bwd": ws_b_bytes / (float(N) * V),
             "fwd_ms": ms_f, "fwd_tokens_per_s": N / (ms_f * 1e-3),
             "fwd_bwd_ms": ms_b, "fwd_bwd_tokens_per_s": N / (ms_b * 1e-3), "loss": float(loss.cpu()),
-            "fwd_bwd_one_chunk": one,
+            "fwd_bwd_half_chunks": half,
             "aux": {"note": "grpo_lmhead_loss_aux_fwd_bwd, KL 0.001 and entropy 1e-4: every unmasked row has a "
                             "gradient", "fwd_bwd_ms": ms_x, "fwd_bwd_tokens_per_s": N / (ms_x * 1e-3),
                     "tflops": (flops_f + 4.0 * n_unmasked * V * d_model) / (ms_x * 1e-3) / 1e12,

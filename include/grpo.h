@@ -375,8 +375,8 @@ grpo_status grpo_workspace_error(const void *workspace, int32_t *flag_out, void 
  *           vocabulary entry, next to a transposed copy of the chunk's hidden states (W is
  *           never copied): its size follows the chunk, not
  *           the number of tokens.  grpo_lmhead_workspace_bytes(.., 1) is the size for
- *           the default chunk of 8192 rows (about 7.6 GB at vocab 152064, d_model 5120,
- *           for any n_tokens >= 8192); grpo_lmhead_workspace_bytes_for_chunk gives the
+ *           the default chunk of 10240 rows (about 9.6 GB at vocab 152064, d_model 5120,
+ *           for any n_tokens >= 10240); grpo_lmhead_workspace_bytes_for_chunk gives the
  *           size for another chunk.  The call uses the largest chunk (a multiple of 256
  *           rows, at most n_tokens rounded up to 256) that fits into workspace_bytes:
  *           a caller short of memory brings less, down to a chunk of 256 rows, a caller

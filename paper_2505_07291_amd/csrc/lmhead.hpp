@@ -1023,10 +1023,11 @@ struct LmLayout {
     int cap;  // rows per chunk: what the partials, Z, G and H^T are sized for
 };
 
-// Default limit of a chunk of the backward: 8192 rows keep the workspace at V = 152064 near
-// 10 GB whatever the number of tokens, and a chunk still fills the chip (32 tile rows: 19008 tiles
-// of the logits product, 640 of dL/dH).  A caller that brings more gets larger chunks.
-constexpr int64_t kLmChunkRows = 8192;
+// Default limit of a chunk of the backward: 10240 rows keep the workspace at V = 152064 under
+// 10 GB whatever the number of tokens (6 bytes per chunk row and vocabulary entry), and a chunk
+// still fills the chip (40 tile rows: 23760 tiles of the logits product, 800 of dL/dH).  A caller
+// that brings more gets larger chunks.
+constexpr int64_t kLmChunkRows = 10240;
 constexpr int64_t kLmChunkMax = 1 << 20;  // rows; keeps every per-chunk grid extent and 32-bit offset in range
 
 int64_t lm_cap_limit(int64_t n) { return std::min<int64_t>(kLmChunkMax, std::max<int64_t>(256, (n + 255) / 256 * 256)); }

@@ -268,18 +268,18 @@ def test_lmhead_logprobs_rejects_bad_arguments_and_sizes_its_workspace():
     assert call(hs=130) == ALIGN
     # workspace sizes: forward holds a compacted copy of the hidden states and 8 bytes per token
     # and 256 vocabulary entries; the backward works in chunks of rows and holds, per chunk row, the
-    # logits (fp32) and their gradient (bf16): its size follows the chunk (8192 rows by default), not the
+    # logits (fp32) and their gradient (bf16): its size follows the chunk (10240 rows by default), not the
     # number of tokens, and no copy of the weights is part of it
     n, V, d = 16384, 152064, 5120
     fwd = grpo.grpo_lmhead_workspace_bytes(n, V, d, False)
     bwd = grpo.grpo_lmhead_workspace_bytes(n, V, d, True)
     assert fwd % 256 == 0 and bwd % 256 == 0
     assert fwd < 300 << 20 and fwd >= grpo.grpo_workspace_bytes(n) + 8 * n * ((V + 255) // 256) + 2 * n * d
-    chunk = 8192
+    chunk = 10240
     assert bwd >= 6 * chunk * V and bwd < 7 * chunk * V + 64 * n + 8 * n * d
     assert bwd <= 4 * n * V + 4 * V * d                    # at most 4 bytes per logit of this batch
     by_chunk = grpo.grpo_lmhead_workspace_bytes_for_chunk
-    assert by_chunk(n, V, d, chunk) == bwd and by_chunk(n, V, d, 8000) == bwd      # rounded up to 256 rows
+    assert by_chunk(n, V, d, chunk) == bwd and by_chunk(n, V, d, 10000) == bwd      # rounded up to 256 rows
     assert by_chunk(n, V, d, 256) < by_chunk(n, V, d, 512) < bwd < by_chunk(n, V, d, n) == by_chunk(n, V, d, 10 ** 9)
     big = grpo.grpo_lmhead_workspace_bytes(131072, V, d, True)                     # eight times the tokens:
     assert big - bwd < 64 * (131072 - n) + 2 * (131072 - n) * d + 4096             # only per-row arrays grow
