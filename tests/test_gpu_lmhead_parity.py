@@ -157,6 +157,15 @@ def test_random_shapes_and_parameters(seed):
     run_case(cfg, d, denom=denom, grad_scale=f32(rng.uniform(0.2, 3.0)), label="random %d" % seed)
 
 
+@pytest.mark.parametrize("vocab,d_model", [(2, 64), (40, 64), (63, 192), (64, 128), (65, 64), (255, 320), (257, 64)])
+def test_vocabularies_around_one_step_of_the_contraction(vocab, d_model):
+    """dL/dH contracts over the vocabulary in steps of 64 and reads the weights as they lie: fewer entries
+    than one step, exactly one, one more, and the same around one 256-column tile; every element compared."""
+    cfg = wl.CONFIGS["qwen_short"].scaled(n_prompts=2, seq_len=33, vocab=vocab, group_size=4)
+    say("\n[case] lmhead small vocabulary V=%d d=%d N=%d" % (vocab, d_model, cfg.n_tokens))
+    run_case(cfg, d_model, label="V=%d" % vocab)
+
+
 def test_denominator_grad_scale_accumulate_and_determinism():
     cfg = wl.CONFIGS["qwen_short"].scaled(n_prompts=2, seq_len=40, vocab=1500, group_size=4)
     batch, old, adv_tok, out = run_case(cfg, 128, denom=1000.0, grad_scale=2.5, label="denom/scale")
