@@ -285,7 +285,8 @@ grpo_status grpo_loss_fwd_bwd(const void *logits, grpo_dtype dtype, int64_t n_to
  *               undefined results.  Calls on one stream, or otherwise ordered, are fine.
  *  The address of the array is looked up once per device, on the first call made with
  *  that device current (hipGetSymbolAddress: a query, not an allocation); a failure of
- *  that lookup returns GRPO_ERR_HIP.
+ *  that lookup returns GRPO_ERR_HIP.  A caller that captures the call into a graph makes
+ *  one call on that device before the capture begins, so that the lookup is not part of it.
  */
 #define GRPO_NOALLOC_MAX_TOKENS 524288
 grpo_status grpo_loss_fwd_bwd_noalloc(const void *logits, grpo_dtype dtype, int64_t n_tokens,

@@ -8,6 +8,7 @@ from paper_2505_07291_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
+KW = (0.2, 0.2, 4.0, 1.0, 0.0, 1.0)   # eps_low, eps_high, delta, temperature, denom, grad_scale: the binding's defaults
 
 
 def _setup():
@@ -71,6 +72,43 @@ def test_graph_capture_and_replay():
         torch.cuda.synchronize()
         for k, v in ref.items():
             assert torch.equal(v, bufs[k]), "%s differs on replay %d" % (k, i)
+
+
+def test_noalloc_entry_point_in_a_captured_graph():
+    """The entry point without a workspace exists for callers that cannot allocate, graph capture first of all:
+    after one eager call (which looks the built-in scratch array's address up) it is captured and replayed,
+    with eager work in between, and gives the bits of the workspace variant every time."""
+    cfg, b, old, bufs = _setup()
+    _step(cfg, b, old, bufs, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    ref = _snapshot(bufs)
+    err = torch.full((1,), 7, dtype=torch.int32, device=DEV)
+
+    def step(stream):
+        grpo.grpo_loss_fwd_bwd_noalloc(b["logits"], b["tokens"], old, bufs["adv_tok"], b["mask"], *KW,
+                                       grad_logits=bufs["grad"], loss_out=bufs["loss"], logprobs_out=bufs["lp"],
+                                       counts_out=bufs["counts"], error_out=err, stream=stream)
+    step(torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for k in ("loss", "lp", "counts", "grad"):
+        assert torch.equal(ref[k], bufs[k]), "%s differs in the eager call" % k
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step(side)
+    torch.cuda.synchronize()
+    for i in range(3):
+        for k in ("loss", "lp", "counts", "grad"):
+            bufs[k].zero_()                                   # eager work between the replays
+        err.fill_(7)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in ("loss", "lp", "counts", "grad"):
+            assert torch.equal(ref[k], bufs[k]), "%s differs on replay %d" % (k, i)
+        assert int(err) == 0
 
 
 def _lm_setup():
