@@ -266,7 +266,9 @@ __global__ void __launch_bounds__(LM_THREADS) lm_gemm_nt(GemmParams p)
         const int lc = pc ^ ((r >> 1) & (LM_CPR - 1));
         const int ra = min(row0 + r, M - 1) - row0;
         const int rb = min(col0 + r, p.N - 1) - col0;
-        // K-major: chunk c of the tile is k row c / 32, position c % 32
+        // K-major operand: the tile is [64 k rows][256 m]; chunk c is k row c / 32 at position c % 32 and holds
+        // logical chunk (c % 32) ^ lm_km_swizzle(k row); chunks past the end of the operand's k row re-read
+        // its last chunk (they belong to rows or columns of C that are never stored)
         const int kk = c >> 5, lck = (c & 31) ^ lm_km_swizzle(kk);
         if constexpr (AKM) {
             const int ch = min((row0 >> 3) + lck, (p.a_cols >> 3) - 1) - (row0 >> 3);
