@@ -380,10 +380,14 @@ def test_edge_cases():
         grpo.grpo_lmhead_logprobs_fwd(h, w, tok, workspace=torch.empty(256, dtype=torch.uint8, device=DEV))
 
 
-def test_full_size_qwen_short_sampled_rows():
-    """The benchmark's headline batch (16384 tokens, vocabulary 152064) with a 5120-wide head (the hidden size of the paper's 32B model):
-    log-probs and dL/dH rows against the oracle on sampled rows of every class, dL/dW through
-    properties that hold at any size."""
+def test_full_size_qwen_short():
+    """The benchmark's headline batch (16384 tokens, vocabulary 152064) with a 5120-wide head (the hidden size
+    of the paper's 32B model), in the launch configuration bench.py times.  The oracle forms the fp64 logits of
+    every unmasked row (its library products, pinned against its loops), so every input of the call and every
+    expected value is the oracle's: log-probs of all rows, loss and counters; dL/dH element by element on 1024
+    sampled rows and every row without a gradient; dL/dW element by element on 600 sampled vocabulary entries
+    (every gradient row contributes to each of them), among them sampled tokens; and the two identities that tie
+    the whole of dL/dW to dL/dH."""
     cfg = wl.CONFIGS["qwen_short"]
     d = 5120
     batch = wl.make_lmhead_batch(cfg, d, device=DEV)
@@ -392,50 +396,66 @@ def test_full_size_qwen_short_sampled_rows():
     kw = dict(eps_low=f32(cfg.eps_low), eps_high=f32(cfg.eps_high), delta=f32(cfg.delta))
     mask_np = batch["mask"].cpu().numpy()
     tokens_np = batch["tokens"].cpu().numpy()
-    rng = np.random.default_rng(11)
-    live_rows = np.flatnonzero(mask_np == 1)
-    rows = np.sort(np.concatenate([rng.choice(live_rows, 20, replace=False),
-                                   rng.choice(np.flatnonzero(mask_np == 0), 4, replace=False)]))
+    unm = np.flatnonzero(mask_np != 0)
     hb, wb = bits(batch["hidden"]), bits(batch["weight"])
-    say("[gpu] full-size lmhead: oracle logits for %d sampled rows" % len(rows))
-    z_rows = orc.lmhead_logits(hb, wb, rows=rows)
-    lp_rows = orc.logprobs(z_rows, tokens_np[rows], mask_np[rows], temperature=T)
-    # old log-probs for every row come from a cheap stand-in (the sampled rows get the oracle's)
+    logits_of, grad_hidden_of, grad_weight_of = orc.lmhead_products("library")
+    say("[gpu] full-size lmhead: oracle logits of the %d unmasked rows" % len(unm))
+    z = logits_of(hb[unm], wb)                                         # [unmasked, V] fp64
+    lp_orc = np.zeros(N)
+    lp_orc[unm] = orc.logprobs(z, tokens_np[unm], None, temperature=T)
+    old = wl.make_old_logprobs(cfg, lp_orc)
     adv = orc.group_advantages(batch["rewards"].cpu().numpy(), group_size=batch["group_size"])
     adv_tok = orc.broadcast_advantages(adv, batch["rollout_of_token"].cpu().numpy()).astype(np.float32)
+    obj = orc.objective_from_logprobs(lp_orc, old.numpy(), adv_tok, mask_np, **kw)
+
     say("[gpu] full-size lmhead: grpo_lmhead_logprobs_fwd N=%d V=%d d=%d" % (N, V, d))
     lp_g = grpo.grpo_lmhead_logprobs_fwd(batch["hidden"], batch["weight"], batch["tokens"], batch["mask"], T)
     torch.cuda.synchronize()
-    err = np.abs(lp_g.cpu().numpy().astype(np.float64)[rows] - lp_rows).max()
-    say("[gpu] full-size lmhead: log-prob err on sampled rows %.3e" % err)
+    err = np.abs(lp_g.cpu().numpy().astype(np.float64) - lp_orc).max()
+    say("[gpu] full-size lmhead: log-prob err over all rows %.3e" % err)
     assert err <= TOL_LOGP
-    # old = fixed offsets from a host generator; sampled rows use the oracle's log-probs, the
-    # others the library's: the objective at the sampled rows then depends on oracle values only
-    gen = torch.Generator().manual_seed(77)
-    noise = (torch.randn(N, generator=gen) * 0.1).clamp(-0.15, 0.15)
-    base = lp_g.cpu().double()
-    base[torch.as_tensor(rows)] = torch.as_tensor(lp_rows)
-    old = (base + noise.double()).float()
-    M = int(mask_np.sum())
-    say("[gpu] full-size lmhead: grpo_lmhead_loss_fwd_bwd")
+    say("[gpu] full-size lmhead: grpo_lmhead_loss_fwd_bwd (default workspace)")
     loss, lp, counts, dH, dW = grpo.grpo_lmhead_loss_fwd_bwd(
         batch["hidden"], batch["weight"], batch["tokens"], old.to(DEV), torch.as_tensor(adv_tok, device=DEV),
         batch["mask"], temperature=T, **kw)
     torch.cuda.synchronize()
     assert torch.equal(lp, lp_g)
-    assert int(counts[0]) == M
-    obj = orc.objective_from_logprobs(lp_rows, old.numpy()[rows], adv_tok[rows], mask_np[rows],
-                                      denom=float(M), **kw)
-    G_rows = orc.grad_rows(z_rows, tokens_np[rows], obj["coeff"], temperature=T)
-    dH_o = orc.lmhead_grad_hidden(G_rows, wb)
-    Ww_max = float(np.abs(wide(wb[:4096])).max())
-    bound = np.abs(G_rows) @ np.abs(wide(wb))
-    eH = np.abs(dH.cpu().double().numpy()[rows] - dH_o)
-    floor = (2.0 ** -22) * np.abs(obj["coeff"] / T)[:, None] * Ww_max
-    say("[gpu] full-size lmhead: dH err max %.3e (max|dH| %.3e)" % (eH.max(), np.abs(dH_o).max()))
+    assert counts.cpu().numpy().tolist() == obj["counts"].tolist()
+    say("[gpu] full-size lmhead: loss %.8g vs %.8g, counts %s" % (loss.item(), obj["loss"], counts.tolist()))
+    assert abs(loss.item() - obj["loss"]) <= TOL_LOSS_REL * abs(obj["loss"]) + 1e-7
+
+    # the gradient with respect to the logits of every unmasked row (rows with coefficient 0: zeros)
+    coeff = obj["coeff"]
+    G = orc.grad_rows(z, tokens_np[unm], coeff[unm], temperature=T)     # [unmasked, V] fp64
+    del z
+    Wd, Hd = wide(wb), wide(hb[unm])
+    rng = np.random.default_rng(11)
+    # dL/dH: 1024 sampled unmasked rows, element by element
+    pick = np.sort(rng.choice(len(unm), 1024, replace=False))
+    dH_o = G[pick] @ Wd
+    bound = np.abs(G[pick]) @ np.abs(Wd)
+    dH_np = dH.cpu().double().numpy()
+    eH = np.abs(dH_np[unm[pick]] - dH_o)
+    floor = (2.0 ** -22) * np.abs(coeff[unm[pick]] / T)[:, None] * float(np.abs(Wd).max())
+    say("[gpu] full-size lmhead: dH err max %.3e (max|dH| %.3e) on %d rows" % (eH.max(), np.abs(dH_o).max(), len(pick)))
     assert np.all(eH <= 1.05 * U * (bound + np.abs(dH_o)) + floor)
-    assert np.all(dH.cpu().float().numpy()[rows][obj["coeff"] == 0] == 0.0)
-    # dL/dW: (1) <dW, W> = <G, Z> = <dH, H> ties the two products to each other;
+    assert np.linalg.norm(eH) <= 0.6 * U * np.linalg.norm(bound + np.abs(dH_o)) + np.linalg.norm(floor)
+    no_grad = np.ones(N, dtype=bool)
+    no_grad[unm[coeff[unm] != 0]] = False
+    assert not dH_np[no_grad].any()                                    # masked rows and rows whose gradient is cut
+    # dL/dW: 600 vocabulary entries, half of them tokens that were sampled in a gradient row
+    used = np.unique(tokens_np[unm[coeff[unm] != 0]])
+    vs = np.unique(np.concatenate([rng.choice(used, 300, replace=False), rng.choice(V, 300, replace=False)]))
+    Gs = np.ascontiguousarray(G[:, vs])
+    dW_o = Gs.T @ Hd
+    bound_w = np.abs(Gs).T @ np.abs(Hd)
+    eW = np.abs(dW.cpu().double().numpy()[vs] - dW_o)
+    say("[gpu] full-size lmhead: dW err max %.3e (max|dW| %.3e) on %d vocabulary entries" %
+        (eW.max(), np.abs(dW_o).max(), len(vs)))
+    assert np.all(eW <= 1.05 * U * bound_w + 1e-30)
+    assert np.linalg.norm(eW) <= 0.6 * U * np.linalg.norm(bound_w)
+    del G, Gs
+    # the whole of dL/dW: (1) <dW, W> = <G, Z> = <dH, H> ties the two products to each other;
     # (2) its column sums vanish up to the bf16 rounding of G, because every row of G sums to 0
     inner_W = (dW.double() * batch["weight"].double()).sum().item()
     inner_H = (dH.double() * batch["hidden"].double()).sum().item()
